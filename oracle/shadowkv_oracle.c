@@ -1,0 +1,341 @@
+/*
+ * ShadowKV CPU oracle -- TEST INFRASTRUCTURE, NOT PRODUCT CODE.
+ *
+ * A plain, slow, obviously-correct implementation of the two operations the
+ * GPU library exports: landmark/outlier construction (pre-filling algorithm,
+ * Alg. 1 of the paper, every step after the SVD) and one sparse decode step
+ * (decoding algorithm, Alg. 2, followed by the standard attention over the
+ * selected set described in the "Theoretical Equivalent Bandwidth" section).
+ *
+ * Rules this file keeps:
+ *   - it shares nothing with the HIP path (no header, no helper, no table);
+ *   - inputs are the same bf16 bit patterns the GPU gets, widened exactly to
+ *     fp64; every sum, norm, exponential and angle is fp64; nothing is rounded
+ *     on the way except the bf16 outputs (round-to-nearest-even from fp64);
+ *   - the steps run in the paper's order with its notation, no blocking and
+ *     no fusion, so it can be checked against the paper by eye;
+ *   - only tests, the smoke check and the benchmark's cpu_baseline leg may
+ *     build or call it.
+ *
+ * Pins (tests/test_oracle_*.py): brute-force re-implementation on tiny
+ * shapes, dense softmax attention when the budget covers every chunk, exact
+ * reconstruction at full rank, RoPE group identities, chunk-size-1 reduction
+ * to token top-k, closed forms for the cosine criterion.  What is NOT pinned
+ * anywhere ("parity unpinned"): how well the method approximates dense
+ * attention on a trained model -- that needs weights and evaluation suites.
+ *
+ * Notation (paper): b batch, h_q / h_kv query / key-value heads, G = h_q/h_kv,
+ * d head dim, s chunked context length, c chunk size, n_ch = s/c, o outlier
+ * chunks, n_c = n_ch - o landmarks, k selected chunks, w resident recent
+ * tokens, r rank.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+typedef struct oracle_params {
+  int32_t batch, n_q_heads, n_kv_heads, head_dim;
+  int32_t ctx_len, chunk_size, rank;
+  int32_t n_outlier_chunks, topk_chunks, local_len;
+  double rope_theta;      /* base of the rotary frequencies */
+  const float *inv_freq;  /* optional [d/2]; replaces theta^(-2i/d) */
+  double softmax_scale;   /* 0 => 1/sqrt(d) */
+} oracle_params;
+
+int oracle_num_threads(void) {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}
+
+/* ---- bf16 <-> fp64 ------------------------------------------------------ */
+
+static double bf16_to_f64(uint16_t h) {
+  uint32_t u = (uint32_t)h << 16;
+  float f;
+  memcpy(&f, &u, sizeof f);
+  return (double)f;
+}
+
+/* Round an fp64 value to the nearest bf16 (ties to even) in ONE rounding. */
+uint16_t oracle_f64_to_bf16(double x) {
+  if (isnan(x)) return 0x7fc0;
+  uint16_t sign = signbit(x) ? 0x8000 : 0;
+  double a = fabs(x);
+  if (a == 0.0) return sign;
+  if (isinf(a)) return sign | 0x7f80;
+  int e;
+  (void)frexp(a, &e); /* a = m * 2^e, m in [0.5, 1) => floor(log2 a) = e-1 */
+  int E = e - 1;
+  if (E < -126) E = -126;              /* subnormal range: fixed spacing */
+  double ulp = ldexp(1.0, E - 7);      /* bf16 keeps 7 fraction bits */
+  double q = nearbyint(a / ulp);       /* default mode: ties to even */
+  double r = q * ulp;                  /* exactly representable in fp32 */
+  float f = (float)r;
+  if (isinf(f)) return sign | 0x7f80;
+  uint32_t u;
+  memcpy(&u, &f, sizeof u);
+  return sign | (uint16_t)(u >> 16);
+}
+
+/* ---- rotary position embedding ------------------------------------------
+ * Rotate-half pairing over the full head dimension: coordinate i < d/2 is
+ * paired with i + d/2, frequency theta^(-2i/d), angle = position * frequency
+ * (the RoPE the decoding algorithm applies to the rebuilt keys).            */
+static double rope_freq(const oracle_params *p, int i) {
+  if (p->inv_freq) return (double)p->inv_freq[i];
+  return pow(p->rope_theta, -2.0 * (double)i / (double)p->head_dim);
+}
+
+static void rope_inplace(const oracle_params *p, double *x, double pos) {
+  int half = p->head_dim / 2;
+  for (int i = 0; i < half; ++i) {
+    double phi = pos * rope_freq(p, i);
+    double cs = cos(phi), sn = sin(phi);
+    double x0 = x[i], x1 = x[i + half];
+    x[i] = x0 * cs - x1 * sn;
+    x[i + half] = x1 * cs + x0 * sn;
+  }
+}
+
+/* Exposed for the identity tests: y[n,:] = RoPE(x[n,:], pos[n]). */
+void oracle_rope(const oracle_params *p, const double *x, const double *pos,
+                 int64_t n_rows, double *y) {
+  int d = p->head_dim;
+  for (int64_t n = 0; n < n_rows; ++n) {
+    memcpy(y + n * d, x + n * d, sizeof(double) * d);
+    rope_inplace(p, y + n * d, pos[n]);
+  }
+}
+
+/* ---- ArgTopK with the lower-index-wins tie rule ------------------------- */
+typedef struct { double key; int32_t idx; } keyed;
+
+static int cmp_desc(const void *a, const void *b) {
+  const keyed *x = a, *y = b;
+  if (x->key > y->key) return -1;
+  if (x->key < y->key) return 1;
+  return (x->idx > y->idx) - (x->idx < y->idx);
+}
+
+/* ---- Alg. 1 (after the SVD line): landmarks and outliers ----------------
+ * k_rope, v: [b, h_kv, s, d] bf16.  Outputs per (b, h_kv):
+ *   landmarks [n_c, d] bf16, landmark_chunk_ids [n_c] ascending,
+ *   outlier_chunk_ids [o] most-outlying first, k_outlier/v_outlier [o*c, d].
+ * Optional fp64 diagnostics: chunk_min_cos [b,h_kv,n_ch], chunk_mean
+ * [b,h_kv,n_ch,d] (pass NULL to skip).  v / v_outlier may be NULL.         */
+int oracle_build_landmarks(const oracle_params *p, const uint16_t *k_rope,
+                           const uint16_t *v, uint16_t *landmarks,
+                           int32_t *landmark_chunk_ids,
+                           int32_t *outlier_chunk_ids, uint16_t *k_outlier,
+                           uint16_t *v_outlier, double *chunk_min_cos,
+                           double *chunk_mean) {
+  const int d = p->head_dim, c = p->chunk_size, o = p->n_outlier_chunks;
+  const int64_t s = p->ctx_len;
+  if (d <= 0 || c <= 0 || s % c) return -1;
+  const int64_t n_ch = s / c, n_c = n_ch - o;
+  if (o < 0 || n_c < 0) return -1;
+  const int64_t units = (int64_t)p->batch * p->n_kv_heads;
+  const double eps = 1e-8;
+  int fail = 0;
+
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int64_t u = 0; u < units; ++u) {
+    const uint16_t *K = k_rope + u * s * d;
+    double *C = malloc(sizeof(double) * n_ch * d);      /* chunk means */
+    keyed *m = malloc(sizeof(keyed) * (n_ch ? n_ch : 1)); /* -min cos   */
+    char *is_out = calloc(n_ch ? n_ch : 1, 1);
+    if (!C || !m || !is_out) {
+      fail = 1; free(C); free(m); free(is_out); continue;
+    }
+    /* C <- Reduce(K^RoPE): mean over the c tokens of each chunk */
+    for (int64_t j = 0; j < n_ch; ++j)
+      for (int x = 0; x < d; ++x) {
+        double acc = 0.0;
+        for (int t = 0; t < c; ++t) acc += bf16_to_f64(K[(j * c + t) * d + x]);
+        C[j * d + x] = acc / (double)c;
+      }
+    /* S <- CosineSimilarity(C, K^RoPE); Min over the chunk's tokens */
+    for (int64_t j = 0; j < n_ch; ++j) {
+      double cn = 0.0;
+      for (int x = 0; x < d; ++x) cn += C[j * d + x] * C[j * d + x];
+      cn = sqrt(cn);
+      double mn = INFINITY;
+      for (int t = 0; t < c; ++t) {
+        double dot = 0.0, kn = 0.0;
+        for (int x = 0; x < d; ++x) {
+          double kv = bf16_to_f64(K[(j * c + t) * d + x]);
+          dot += C[j * d + x] * kv;
+          kn += kv * kv;
+        }
+        kn = sqrt(kn);
+        double cs = dot / (fmax(cn, eps) * fmax(kn, eps));
+        if (cs < mn) mn = cs;
+      }
+      m[j].key = -mn; /* ArgTopK(-Min(S), o) */
+      m[j].idx = (int32_t)j;
+      if (chunk_min_cos) chunk_min_cos[u * n_ch + j] = mn;
+    }
+    if (chunk_mean) memcpy(chunk_mean + u * n_ch * d, C, sizeof(double) * n_ch * d);
+    qsort(m, n_ch, sizeof(keyed), cmp_desc);
+    /* Gather the outlier chunks' exact keys and values */
+    for (int i = 0; i < o; ++i) {
+      int64_t j = m[i].idx;
+      is_out[j] = 1;
+      outlier_chunk_ids[u * o + i] = (int32_t)j;
+      memcpy(k_outlier + (u * o + i) * c * d, K + j * c * d, sizeof(uint16_t) * c * d);
+      if (v && v_outlier)
+        memcpy(v_outlier + (u * o + i) * c * d, v + (u * s + j * c) * d,
+               sizeof(uint16_t) * c * d);
+    }
+    /* L <- C without the outlier rows, in ascending chunk order */
+    int64_t slot = 0;
+    for (int64_t j = 0; j < n_ch; ++j) {
+      if (is_out[j]) continue;
+      landmark_chunk_ids[u * n_c + slot] = (int32_t)j;
+      for (int x = 0; x < d; ++x)
+        landmarks[(u * n_c + slot) * d + x] = oracle_f64_to_bf16(C[j * d + x]);
+      ++slot;
+    }
+    free(C); free(m); free(is_out);
+  }
+  return fail ? -2 : 0;
+}
+
+/* ---- Alg. 2 + sparse attention: one decode step -------------------------
+ * q [b,h_q,d]; A [b,s,r]; B [b,h_kv,r,d]; landmarks [b,h_kv,n_c,d];
+ * landmark_chunk_ids [b,h_kv,n_c]; k_outlier/v_outlier [b,h_kv,o*c,d];
+ * k_local/v_local [b,h_kv,w,d]; value_store [b,h_kv,s,d]; pos_offset [b] or
+ * NULL.  All bf16 except ids.  Outputs: out_bf16 [b,h_q,d]; optional:
+ * out_f64 [b,h_q,d], chunk_ids [b,h_kv,k] (true chunk ids, best first),
+ * z2 [b,h_kv,n_c] (log-domain group score per landmark slot),
+ * k_sparse [b,h_kv,k*c,d] fp64 (rebuilt, rotated keys in chunk_ids order).   */
+int oracle_decode_step(const oracle_params *p, const uint16_t *q,
+                       const uint16_t *A, const uint16_t *B,
+                       const uint16_t *landmarks,
+                       const int32_t *landmark_chunk_ids,
+                       const uint16_t *k_outlier, const uint16_t *v_outlier,
+                       const uint16_t *k_local, const uint16_t *v_local,
+                       const uint16_t *value_store, const int32_t *pos_offset,
+                       uint16_t *out_bf16, double *out_f64, int32_t *chunk_ids,
+                       double *z2_out, double *k_sparse_out) {
+  const int d = p->head_dim, c = p->chunk_size, r = p->rank;
+  const int o = p->n_outlier_chunks, k = p->topk_chunks, w = p->local_len;
+  const int hq = p->n_q_heads, hkv = p->n_kv_heads;
+  const int64_t s = p->ctx_len;
+  if (d <= 0 || (d & 1) || c <= 0 || s % c || hkv <= 0 || hq % hkv) return -1;
+  const int G = hq / hkv;
+  const int64_t n_ch = s / c, n_c = n_ch - o;
+  if (k < 0 || k > n_c) return -1;
+  const int64_t T = (int64_t)o * c + (int64_t)k * c + w;
+  const double scale = p->softmax_scale != 0.0 ? p->softmax_scale : 1.0 / sqrt((double)d);
+  const int64_t units = (int64_t)p->batch * hkv;
+  int fail = 0;
+
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int64_t u = 0; u < units; ++u) {
+    const int64_t bi = u / hkv, h = u % hkv;
+    const uint16_t *L = landmarks + u * n_c * d;
+    const int32_t *Lid = landmark_chunk_ids + u * n_c;
+    double *P = malloc(sizeof(double) * (size_t)G * (n_c ? n_c : 1));
+    keyed *z2 = malloc(sizeof(keyed) * (n_c ? n_c : 1));
+    double *Kt = malloc(sizeof(double) * (T ? T : 1) * d); /* attended keys   */
+    double *Vt = malloc(sizeof(double) * (T ? T : 1) * d); /* attended values */
+    double *a = malloc(sizeof(double) * (T ? T : 1));
+    if (!P || !z2 || !Kt || !Vt || !a) {
+      fail = 1; free(P); free(z2); free(Kt); free(Vt); free(a); continue;
+    }
+    /* P <- Q L^T, scaled by 1/sqrt(d); S <- Softmax over the landmarks.
+     * Kept in the log domain: log S = P - logsumexp(P) per query head.
+     * (The sum over the s_q query positions is the identity for s_q = 1.) */
+    for (int g = 0; g < G; ++g) {
+      const uint16_t *qg = q + (bi * hq + h * G + g) * d;
+      double mx = -INFINITY;
+      for (int64_t j = 0; j < n_c; ++j) {
+        double dot = 0.0;
+        for (int x = 0; x < d; ++x) dot += bf16_to_f64(qg[x]) * bf16_to_f64(L[j * d + x]);
+        P[g * n_c + j] = dot * scale;
+        if (P[g * n_c + j] > mx) mx = P[g * n_c + j];
+      }
+      double se = 0.0;
+      for (int64_t j = 0; j < n_c; ++j) se += exp(P[g * n_c + j] - mx);
+      double lse = mx + log(se);
+      for (int64_t j = 0; j < n_c; ++j) P[g * n_c + j] -= lse;
+    }
+    /* S2 <- max over the query heads of the KV group */
+    for (int64_t j = 0; j < n_c; ++j) {
+      double best = -INFINITY;
+      for (int g = 0; g < G; ++g)
+        if (P[g * n_c + j] > best) best = P[g * n_c + j];
+      z2[j].key = best;
+      z2[j].idx = (int32_t)j;
+      if (z2_out) z2_out[u * n_c + j] = best;
+    }
+    /* I <- ArgTopK(S2, k): landmark slots; ties go to the lower slot */
+    qsort(z2, n_c, sizeof(keyed), cmp_desc);
+
+    /* K <- [K_outlier ; RoPE(Gather(A, I) B) ; K_new],
+     * V <- [V_outlier ; Gather(V_store, I) ; V_new]                       */
+    int64_t row = 0;
+    for (int64_t i = 0; i < (int64_t)o * c; ++i, ++row)
+      for (int x = 0; x < d; ++x) {
+        Kt[row * d + x] = bf16_to_f64(k_outlier[(u * o * c + i) * d + x]);
+        Vt[row * d + x] = bf16_to_f64(v_outlier[(u * o * c + i) * d + x]);
+      }
+    const double pos0 = pos_offset ? (double)pos_offset[bi] : 0.0;
+    for (int i = 0; i < k; ++i) {
+      const int64_t ch = Lid[z2[i].idx];
+      if (chunk_ids) chunk_ids[u * k + i] = (int32_t)ch;
+      for (int t = 0; t < c; ++t, ++row) {
+        const int64_t n = ch * c + t; /* token index inside the context */
+        const uint16_t *Arow = A + (bi * s + n) * r;
+        for (int x = 0; x < d; ++x) {
+          double acc = 0.0;
+          for (int rho = 0; rho < r; ++rho)
+            acc += bf16_to_f64(Arow[rho]) * bf16_to_f64(B[((u * r) + rho) * d + x]);
+          Kt[row * d + x] = acc;
+        }
+        rope_inplace(p, Kt + row * d, pos0 + (double)n);
+        if (k_sparse_out)
+          memcpy(k_sparse_out + ((u * k + i) * c + t) * d, Kt + row * d, sizeof(double) * d);
+        for (int x = 0; x < d; ++x)
+          Vt[row * d + x] = bf16_to_f64(value_store[(u * s + n) * d + x]);
+      }
+    }
+    for (int64_t i = 0; i < w; ++i, ++row)
+      for (int x = 0; x < d; ++x) {
+        Kt[row * d + x] = bf16_to_f64(k_local[(u * w + i) * d + x]);
+        Vt[row * d + x] = bf16_to_f64(v_local[(u * w + i) * d + x]);
+      }
+
+    /* standard softmax attention of each query head of the group over K, V */
+    for (int g = 0; g < G; ++g) {
+      const uint16_t *qg = q + (bi * hq + h * G + g) * d;
+      double mx = -INFINITY;
+      for (int64_t i = 0; i < T; ++i) {
+        double dot = 0.0;
+        for (int x = 0; x < d; ++x) dot += bf16_to_f64(qg[x]) * Kt[i * d + x];
+        a[i] = dot * scale;
+        if (a[i] > mx) mx = a[i];
+      }
+      double se = 0.0;
+      for (int64_t i = 0; i < T; ++i) { a[i] = exp(a[i] - mx); se += a[i]; }
+      for (int x = 0; x < d; ++x) {
+        double acc = 0.0;
+        for (int64_t i = 0; i < T; ++i) acc += a[i] * Vt[i * d + x];
+        double ov = T ? acc / se : 0.0;
+        int64_t oi = (bi * hq + h * G + g) * d + x;
+        if (out_f64) out_f64[oi] = ov;
+        out_bf16[oi] = oracle_f64_to_bf16(ov);
+      }
+    }
+    free(P); free(z2); free(Kt); free(Vt); free(a);
+  }
+  return fail ? -2 : 0;
+}

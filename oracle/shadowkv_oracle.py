@@ -1,0 +1,208 @@
+"""ctypes front end of the ShadowKV CPU oracle -- TEST INFRASTRUCTURE ONLY.
+
+Builds ``shadowkv_oracle.c`` with gcc (``-O2 -fopenmp``, no intrinsics) into
+``liboracle_shadowkv.so`` beside it and exposes the two operations as numpy
+functions.  bf16 tensors travel as ``uint16`` arrays holding the raw bits.
+
+Only tests, the smoke check and the benchmark's ``cpu_baseline`` leg may import
+this module; the GPU library never does.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "shadowkv_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle_shadowkv.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle if the library is missing or older than its source."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        cmd = ["gcc", "-std=c99", "-O2", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+class _Params(C.Structure):
+    _fields_ = [
+        ("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+        ("head_dim", C.c_int32), ("ctx_len", C.c_int32), ("chunk_size", C.c_int32),
+        ("rank", C.c_int32), ("n_outlier_chunks", C.c_int32), ("topk_chunks", C.c_int32),
+        ("local_len", C.c_int32), ("rope_theta", C.c_double), ("inv_freq", C.c_void_p),
+        ("softmax_scale", C.c_double),
+    ]
+
+
+@dataclass
+class OracleParams:
+    batch: int
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    ctx_len: int
+    chunk_size: int
+    rank: int
+    n_outlier_chunks: int
+    topk_chunks: int
+    local_len: int
+    rope_theta: float = 5e5
+    inv_freq: Optional[np.ndarray] = None  # float32 [head_dim/2]
+    softmax_scale: float = 0.0
+
+    @property
+    def n_chunks(self) -> int:
+        return self.ctx_len // self.chunk_size
+
+    @property
+    def n_landmarks(self) -> int:
+        return self.n_chunks - self.n_outlier_chunks
+
+    def _c(self):
+        inv = None
+        if self.inv_freq is not None:
+            inv = np.ascontiguousarray(self.inv_freq, dtype=np.float32)
+            assert inv.shape == (self.head_dim // 2,)
+        st = _Params(self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim, self.ctx_len,
+                     self.chunk_size, self.rank, self.n_outlier_chunks, self.topk_chunks,
+                     self.local_len, float(self.rope_theta),
+                     inv.ctypes.data if inv is not None else None, float(self.softmax_scale))
+        return st, inv  # keep `inv` alive while the struct is in use
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = C.CDLL(_LIB)
+        _lib.oracle_num_threads.restype = C.c_int
+        _lib.oracle_f64_to_bf16.restype = C.c_uint16
+        _lib.oracle_f64_to_bf16.argtypes = [C.c_double]
+        _lib.oracle_rope.restype = None
+        _lib.oracle_rope.argtypes = [C.c_void_p] * 3 + [C.c_int64, C.c_void_p]
+        _lib.oracle_build_landmarks.restype = C.c_int
+        _lib.oracle_build_landmarks.argtypes = [C.c_void_p] * 10
+        _lib.oracle_decode_step.restype = C.c_int
+        _lib.oracle_decode_step.argtypes = [C.c_void_p] * 17
+    return _lib
+
+
+def num_threads() -> int:
+    return int(_load().oracle_num_threads())
+
+
+def as_bits(x) -> np.ndarray:
+    """bf16 torch tensor (CPU) or uint16 ndarray -> contiguous uint16 ndarray of raw bits."""
+    if isinstance(x, np.ndarray):
+        assert x.dtype == np.uint16, x.dtype
+        return np.ascontiguousarray(x)
+    import torch
+    assert x.dtype == torch.bfloat16 and x.device.type == "cpu"
+    return x.contiguous().view(torch.int16).numpy().view(np.uint16)
+
+
+def bits_to_f64(bits: np.ndarray) -> np.ndarray:
+    """Exact widening of bf16 bit patterns to float64."""
+    return (bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def f64_to_bits(x: np.ndarray) -> np.ndarray:
+    """Single-rounding (nearest-even) fp64 -> bf16 bits, elementwise through the C routine."""
+    lib = _load()
+    flat = np.asarray(x, dtype=np.float64).ravel()
+    out = np.fromiter((lib.oracle_f64_to_bf16(float(v)) for v in flat), dtype=np.uint16, count=flat.size)
+    return out.reshape(np.shape(x))
+
+
+def _ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data
+
+
+def rope(p: OracleParams, x: np.ndarray, pos: np.ndarray) -> np.ndarray:
+    """y[n] = RoPE(x[n], pos[n]) in fp64; x [n, d]."""
+    lib = _load()
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    pos = np.ascontiguousarray(pos, dtype=np.float64)
+    assert x.ndim == 2 and x.shape[1] == p.head_dim and pos.shape == (x.shape[0],)
+    y = np.empty_like(x)
+    st, keep = p._c()
+    lib.oracle_rope(C.addressof(st), x.ctypes.data, pos.ctypes.data, x.shape[0], y.ctypes.data)
+    del keep
+    return y
+
+
+def build_landmarks(p: OracleParams, k_rope, v=None, diagnostics: bool = False) -> dict:
+    """Alg. 1 after the SVD.  k_rope, v: [b, h_kv, s, d] bf16 bits."""
+    lib = _load()
+    b, h, s, d, c, o = p.batch, p.n_kv_heads, p.ctx_len, p.head_dim, p.chunk_size, p.n_outlier_chunks
+    n_ch, n_c = p.n_chunks, p.n_landmarks
+    k_rope = as_bits(k_rope)
+    assert k_rope.shape == (b, h, s, d), k_rope.shape
+    if v is not None:
+        v = as_bits(v)
+        assert v.shape == (b, h, s, d)
+    res = {
+        "landmarks": np.zeros((b, h, n_c, d), np.uint16),
+        "landmark_chunk_ids": np.zeros((b, h, n_c), np.int32),
+        "outlier_chunk_ids": np.zeros((b, h, o), np.int32),
+        "k_outlier": np.zeros((b, h, o * c, d), np.uint16),
+        "v_outlier": np.zeros((b, h, o * c, d), np.uint16) if v is not None else None,
+        "chunk_min_cos": np.zeros((b, h, n_ch), np.float64) if diagnostics else None,
+        "chunk_mean": np.zeros((b, h, n_ch, d), np.float64) if diagnostics else None,
+    }
+    st, keep = p._c()
+    rc = lib.oracle_build_landmarks(C.addressof(st), _ptr(k_rope), _ptr(v), _ptr(res["landmarks"]),
+                                    _ptr(res["landmark_chunk_ids"]), _ptr(res["outlier_chunk_ids"]),
+                                    _ptr(res["k_outlier"]), _ptr(res["v_outlier"]),
+                                    _ptr(res["chunk_min_cos"]), _ptr(res["chunk_mean"]))
+    del keep
+    if rc != 0:
+        raise ValueError(f"oracle_build_landmarks rejected its arguments (rc={rc})")
+    return res
+
+
+def decode_step(p: OracleParams, q, A, B, landmarks, landmark_chunk_ids, k_outlier, v_outlier,
+                k_local, v_local, value_store, pos_offset=None, diagnostics: bool = True) -> dict:
+    """Alg. 2 followed by softmax attention over [outliers ; selected chunks ; recent tokens]."""
+    lib = _load()
+    b, hq, h, s, d = p.batch, p.n_q_heads, p.n_kv_heads, p.ctx_len, p.head_dim
+    c, r, o, k, w, n_c = p.chunk_size, p.rank, p.n_outlier_chunks, p.topk_chunks, p.local_len, p.n_landmarks
+    q, A, B = as_bits(q), as_bits(A), as_bits(B)
+    landmarks, value_store = as_bits(landmarks), as_bits(value_store)
+    k_outlier, v_outlier = as_bits(k_outlier), as_bits(v_outlier)
+    k_local, v_local = as_bits(k_local), as_bits(v_local)
+    ids = np.ascontiguousarray(landmark_chunk_ids, dtype=np.int32)
+    assert q.shape == (b, hq, d) and A.shape == (b, s, r) and B.shape == (b, h, r, d)
+    assert landmarks.shape == (b, h, n_c, d) and ids.shape == (b, h, n_c)
+    assert k_outlier.shape == (b, h, o * c, d) and v_outlier.shape == (b, h, o * c, d)
+    assert k_local.shape == (b, h, w, d) and v_local.shape == (b, h, w, d)
+    assert value_store.shape == (b, h, s, d)
+    pos = None
+    if pos_offset is not None:
+        pos = np.ascontiguousarray(pos_offset, dtype=np.int32)
+        assert pos.shape == (b,)
+    res = {
+        "out": np.zeros((b, hq, d), np.uint16),
+        "out_f64": np.zeros((b, hq, d), np.float64),
+        "chunk_ids": np.zeros((b, h, k), np.int32),
+        "z2": np.zeros((b, h, n_c), np.float64) if diagnostics else None,
+        "k_sparse": np.zeros((b, h, k * c, d), np.float64) if diagnostics else None,
+    }
+    st, keep = p._c()
+    rc = lib.oracle_decode_step(C.addressof(st), _ptr(q), _ptr(A), _ptr(B), _ptr(landmarks), _ptr(ids),
+                                _ptr(k_outlier), _ptr(v_outlier), _ptr(k_local), _ptr(v_local),
+                                _ptr(value_store), _ptr(pos), _ptr(res["out"]), _ptr(res["out_f64"]),
+                                _ptr(res["chunk_ids"]), _ptr(res["z2"]), _ptr(res["k_sparse"]))
+    del keep
+    if rc != 0:
+        raise ValueError(f"oracle_decode_step rejected its arguments (rc={rc})")
+    return res

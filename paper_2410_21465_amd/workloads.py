@@ -1,0 +1,223 @@
+"""Seeded synthetic inputs shaped like the paper's decode workloads.
+
+This module only *draws inputs*; it implements no step of the method.  Both
+the CPU oracle and the HIP library are fed the tensors made here, bit for bit,
+and neither of them calls anything in this file.
+
+What it makes (all from one ``torch.Generator`` seeded per workload, fixed draw
+order):
+
+* pre-RoPE keys ``K_pre [b, s, h_kv*d]`` with a decaying spectrum: a
+  token-correlated latent ``U`` (first-order autoregression along tokens,
+  correlation ``rho``), singular values ``exp(-i/40)``, a random mixing matrix
+  and N(0, 0.02) noise, scaled so that attention logits are peaked rather than
+  flat;
+* the rank-``r`` factors ``A [b, s, r]``, ``B [b, h_kv, r, d]`` of ``K_pre``
+  (top eigenvectors of its Gram matrix through ``torch.linalg.eigh``) -- the
+  first line of the paper's pre-filling algorithm, which is an *input* of the
+  decode path;
+* post-RoPE keys ``k_rope [b, h_kv, s, d]`` (``K_pre`` rotated at positions
+  0..s-1; also an input of the pre-filling algorithm), optional planted outlier
+  or needle chunks;
+* values, recent-token keys/values, and a pool of queries.
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass, replace
+from typing import Dict, Optional
+
+import torch
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    batch: int
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    ctx_len: int
+    chunk_size: int = 8
+    rank: int = 160
+    n_outlier_chunks: int = 48
+    topk_chunks: int = 256
+    local_len: int = 32
+    rope_theta: float = 5e5
+    seed: int = 0
+    value_location: str = "hbm"      # "hbm" | "host" (pinned, device-readable)
+    plant: str = "none"              # "none" | "outliers" | "needles"
+    rho: float = 0.9                 # adjacent-token correlation of the latent
+    n_queries: int = 16              # size of the query pool
+    needle_gain: float = 8.0
+
+    @property
+    def group(self) -> int:
+        return self.n_q_heads // self.n_kv_heads
+
+    @property
+    def key_width(self) -> int:
+        return self.n_kv_heads * self.head_dim
+
+    @property
+    def n_chunks(self) -> int:
+        return self.ctx_len // self.chunk_size
+
+    @property
+    def n_landmarks(self) -> int:
+        return self.n_chunks - self.n_outlier_chunks
+
+    @property
+    def units(self) -> int:
+        return self.batch * self.n_kv_heads
+
+    def scaled(self, **kw) -> "Workload":
+        return replace(self, **kw)
+
+
+# The five benchmark configurations (names c1..c5) and the HBM twin of c3.
+CONFIGS: Dict[str, Workload] = {
+    "c1": Workload("c1", 1, 32, 8, 128, 4096, topk_chunks=64, n_outlier_chunks=8, seed=0),
+    "c2": Workload("c2", 8, 32, 8, 128, 32768, seed=1, value_location="host"),
+    "c3-host": Workload("c3-host", 16, 32, 8, 128, 131072, seed=2, value_location="host", plant="outliers"),
+    "c3-hbm": Workload("c3-hbm", 16, 32, 8, 128, 131072, seed=2, value_location="hbm", plant="outliers"),
+    "c4": Workload("c4", 1, 32, 2, 128, 1048576, seed=3, value_location="host", plant="needles"),
+    "c5": Workload("c5", 8, 32, 32, 96, 131072, rope_theta=1e4, seed=4, value_location="hbm"),
+}
+
+_LATENT = 320          # latent width; singular values beyond are far below the noise floor
+_NOISE = 0.02
+_TARGET_STD = 3.0      # per-element std of K_pre: makes q.k/sqrt(d) have std ~3 (peaked softmax)
+_AR_TAPS = 128
+
+
+def _rotate(x: torch.Tensor, pos: torch.Tensor, theta: float, inverse: bool = False) -> torch.Tensor:
+    """Rotate pairs (i, i+d/2) of the last axis of ``x [..., n, d]`` by ``pos[n] * theta^(-2i/d)``.
+
+    Input synthesis only: it turns drawn pre-RoPE keys into the post-RoPE keys
+    a model would hand to the pre-filling algorithm.
+    """
+    d = x.shape[-1]
+    half = d // 2
+    inv = theta ** (-torch.arange(half, dtype=torch.float64, device=x.device) * 2.0 / d)
+    ang = pos.to(torch.float64)[:, None] * inv[None, :]
+    cs, sn = torch.cos(ang).to(torch.float32), torch.sin(ang).to(torch.float32)
+    if inverse:
+        sn = -sn
+    x0, x1 = x[..., :half].float(), x[..., half:].float()
+    return torch.cat([x0 * cs - x1 * sn, x1 * cs + x0 * sn], dim=-1)
+
+
+def _latent(n: int, width: int, rho: float, gen: torch.Generator, device) -> torch.Tensor:
+    """[n, width] stationary AR(1) along tokens (unit variance), as a truncated moving average."""
+    eps = torch.randn(width, n + _AR_TAPS - 1, generator=gen, device=device, dtype=torch.float32)
+    if rho == 0.0:
+        return eps[:, _AR_TAPS - 1:].t().contiguous()
+    taps = math.sqrt(1.0 - rho * rho) * rho ** torch.arange(_AR_TAPS - 1, -1, -1, dtype=torch.float32, device=device)
+    u = torch.nn.functional.conv1d(eps[:, None, :], taps[None, None, :])[:, 0, :]
+    return u.t().contiguous()
+
+
+def _alloc(shape, dtype, device, pinned: bool) -> torch.Tensor:
+    if pinned:
+        return torch.empty(shape, dtype=dtype, device="cpu", pin_memory=torch.cuda.is_available())
+    return torch.empty(shape, dtype=dtype, device=device)
+
+
+def generate(wl: Workload, device: Optional[str] = None, want_prefill: bool = True,
+             value_device: Optional[str] = None) -> Dict[str, torch.Tensor]:
+    """Draw one workload.  Returns bf16 tensors (ids int32):
+
+    ``q_pool [n_queries, b, h_q, d]``, ``A [b, s, r]``, ``B [b, h_kv, r, d]``,
+    ``k_rope [b, h_kv, s, d]`` (only if ``want_prefill``), ``v [b, h_kv, s, d]``
+    (on ``value_device``; pinned host memory when the workload says "host"),
+    ``k_local, v_local [b, h_kv, w, d]``, ``pos_offset [b]`` (zeros),
+    ``needle_chunks [b, h_kv, 4]`` for the needle workload.
+    """
+    if device is None:
+        device = "cuda" if torch.cuda.is_available() else "cpu"
+    dev = torch.device(device)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(1000 + wl.seed)
+    b, hkv, hq, d, s, c, r, w = (wl.batch, wl.n_kv_heads, wl.n_q_heads, wl.head_dim, wl.ctx_len,
+                                 wl.chunk_size, wl.rank, wl.local_len)
+    D = wl.key_width
+    R = min(_LATENT, D)
+    bf = torch.bfloat16
+    sigma = torch.exp(-torch.arange(R, dtype=torch.float32, device=dev) / 40.0)
+    gain = _TARGET_STD * math.sqrt(D / float((sigma * sigma).sum()))
+
+    host_values = wl.value_location == "host"
+    if value_device is None:
+        value_device = "cpu" if host_values else device
+    out: Dict[str, torch.Tensor] = {
+        "A": torch.empty(b, s, r, dtype=bf, device=dev),
+        "B": torch.empty(b, hkv, r, d, dtype=bf, device=dev),
+        "k_local": torch.empty(b, hkv, w, d, dtype=bf, device=dev),
+        "v": _alloc((b, hkv, s, d), bf, value_device, pinned=(value_device == "cpu" and host_values)),
+        "pos_offset": torch.zeros(b, dtype=torch.int32, device=dev),
+    }
+    if want_prefill:
+        out["k_rope"] = torch.empty(b, hkv, s, d, dtype=bf, device=dev)
+    needle_dirs = None
+    if wl.plant == "needles":
+        out["needle_chunks"] = torch.empty(b, hkv, 4, dtype=torch.int32, device=dev)
+        needle_dirs = torch.empty(b, hkv, 4, d, dtype=torch.float32, device=dev)
+
+    pos_all = torch.arange(s + w, device=dev)
+    for bi in range(b):
+        # 1. low-rank pre-RoPE keys for the s context tokens and the w recent ones
+        W = torch.randn(D, R, generator=gen, device=dev, dtype=torch.float32) / math.sqrt(D)
+        U = _latent(s + w, R, wl.rho, gen, dev) * gain
+        k_pre = (U * sigma[None, :]) @ W.t()
+        del U
+        k_pre += _NOISE * torch.randn(s + w, D, generator=gen, device=dev, dtype=torch.float32)
+        kp_heads = k_pre.view(s + w, hkv, d).permute(1, 0, 2)          # [h_kv, s+w, d] view
+        if wl.plant == "needles":
+            # four chunks per KV head whose eight rows all equal one direction after rotation
+            med = kp_heads[:, :s].norm(dim=-1).median(dim=-1).values    # [h_kv]
+            ids = torch.stack([torch.randperm(s // c, generator=gen, device=dev)[:4] for _ in range(hkv)])
+            dirs = torch.randn(hkv, 4, d, generator=gen, device=dev, dtype=torch.float32)
+            dirs = dirs / dirs.norm(dim=-1, keepdim=True) * (3.0 * med)[:, None, None]
+            for h in range(hkv):
+                for j in range(4):
+                    tok = ids[h, j] * c + torch.arange(c, device=dev)
+                    rows = dirs[h, j].expand(c, d)
+                    kp_heads[h, tok] = _rotate(rows, tok, wl.rope_theta, inverse=True)
+            out["needle_chunks"][bi] = ids.to(torch.int32)
+            needle_dirs[bi] = dirs
+        # 2. rank-r factors of the context keys (pre-filling algorithm, SVD line)
+        ctx = k_pre[:s]
+        gram = (ctx.t() @ ctx).to(torch.float64)
+        evals, evecs = torch.linalg.eigh(gram)
+        psi = evecs[:, -r:].flip(-1).to(torch.float32)                  # [D, r], strongest first
+        out["A"][bi] = (ctx @ psi).to(bf)
+        out["B"][bi] = psi.t().reshape(r, hkv, d).permute(1, 0, 2).to(bf)
+        del gram, evals, evecs, psi
+        # 3. post-RoPE keys at positions 0..s+w-1
+        rot = _rotate(kp_heads, pos_all, wl.rope_theta)                 # [h_kv, s+w, d] fp32
+        out["k_local"][bi] = rot[:, s:].to(bf)
+        if want_prefill:
+            kr = rot[:, :s]
+            if wl.plant == "outliers":
+                n_plant = max(1, (s // c) // 100)
+                med = kr.norm(dim=-1).median(dim=-1).values
+                for h in range(hkv):
+                    ch = torch.randperm(s // c, generator=gen, device=dev)[:n_plant]
+                    tok = (ch[:, None] * c + torch.arange(c, device=dev)[None, :]).reshape(-1)
+                    g = torch.randn(tok.numel(), d, generator=gen, device=dev, dtype=torch.float32)
+                    kr[h, tok] = g / g.norm(dim=-1, keepdim=True) * (10.0 * med[h])
+            out["k_rope"][bi] = kr.to(bf)
+        del rot, k_pre
+        # 4. values
+        vb = torch.randn(hkv, s, d, generator=gen, device=dev, dtype=torch.float32).to(bf)
+        out["v"][bi].copy_(vb)
+        del vb
+    out["v_local"] = torch.randn(b, hkv, w, d, generator=gen, device=dev, dtype=torch.float32).to(bf)
+    # 5. queries
+    qp = torch.randn(wl.n_queries, b, hq, d, generator=gen, device=dev, dtype=torch.float32)
+    if needle_dirs is not None:
+        pull = (needle_dirs / needle_dirs.norm(dim=-1, keepdim=True)).sum(dim=2)   # [b, h_kv, d]
+        qp = qp + wl.needle_gain * pull.repeat_interleave(wl.group, dim=1)[None]
+    out["q_pool"] = qp.to(bf)
+    return out
