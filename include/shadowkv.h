@@ -1,0 +1,156 @@
+/*
+ * libshadowkv -- ShadowKV decode hot path on one MI355X (gfx950), C ABI.
+ *
+ * Two operations, both enqueue-only on caller-owned HIP streams:
+ *
+ *   shadowkv_build_landmarks  pre-filling algorithm (Alg. 1) after its SVD
+ *                             line: chunk means of the post-RoPE keys,
+ *                             per-chunk minimum cosine between mean and keys,
+ *                             the o lowest chunks become resident outliers,
+ *                             the other chunk means become landmarks.
+ *   shadowkv_decode_step      decoding algorithm (Alg. 2) plus the attention
+ *                             over the selected set ("Theoretical Equivalent
+ *                             Bandwidth" section): landmark scores, per-head
+ *                             softmax, max over the GQA group, top-k chunks;
+ *                             values of those chunks gathered, their keys
+ *                             rebuilt from the rank-r factors and rotated at
+ *                             their true positions; softmax attention over
+ *                             [outliers ; selected chunks ; recent tokens].
+ *
+ * Notation (paper): b batch, h_q / h_kv query / KV heads, G = h_q / h_kv,
+ * d head dim, s chunked context length, c chunk size, n_ch = s / c, o outlier
+ * chunks, n_c = n_ch - o landmarks, k selected chunks, w recent tokens, r rank.
+ *
+ * Conventions for every pointer argument:
+ *   - "dev"  = device (HBM) memory, "dev|pinned" = HBM or device-readable
+ *     pinned host memory.  All tensors are dense, row-major in the layout
+ *     written next to them, 16-byte aligned.  bf16 = raw 16-bit patterns.
+ *   - The caller owns every buffer (workspace included) and both streams.
+ *     The library allocates no device memory; it keeps two HIP events per
+ *     device for the side-stream fork/join, released by shadowkv_shutdown().
+ *   - Calls return after enqueuing; outputs are valid once `stream` has been
+ *     synchronised.  Work put on `side_stream` is joined back into `stream`
+ *     before the call returns.
+ *   - Return value: SHADOWKV_OK or a negative code.  Arguments are validated
+ *     on the host before anything is enqueued, so a rejected call has no
+ *     effect on the GPU (and can be exercised on a machine without one).
+ */
+#ifndef SHADOWKV_H
+#define SHADOWKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SHADOWKV_OK 0
+#define SHADOWKV_EINVAL (-1)     /* bad shape, null pointer, unsupported size */
+#define SHADOWKV_EWORKSPACE (-2) /* workspace missing, misaligned or too small */
+#define SHADOWKV_EHIP (-3)       /* HIP runtime / launch error (see last_error) */
+
+#define SHADOWKV_VALUES_DEVICE 0 /* value store in HBM: attention reads it in place */
+#define SHADOWKV_VALUES_HOST 1   /* pinned host store: staged by a gather kernel   */
+
+/* flags */
+#define SHADOWKV_FLAG_STAGE_VALUES 1u /* run the chunk gather even for an HBM store */
+
+typedef uint16_t shadowkv_bf16;
+
+typedef struct shadowkv_params {
+  int32_t batch;            /* b  >= 1 */
+  int32_t n_q_heads;        /* h_q, multiple of n_kv_heads, G <= 64 */
+  int32_t n_kv_heads;       /* h_kv >= 1 */
+  int32_t head_dim;         /* d in {64, 96, 128} */
+  int32_t ctx_len;          /* s: tokens covered by A / landmarks / value store; multiple of chunk_size */
+  int32_t chunk_size;       /* c in [1, 64] */
+  int32_t rank;             /* r: multiple of 8, 8 <= r <= 256 */
+  int32_t n_outlier_chunks; /* o >= 0, o <= 1024 */
+  int32_t topk_chunks;      /* k: 1 <= k <= n_c = s/c - o */
+  int32_t local_len;        /* w >= 0 resident recent tokens (the current token included) */
+  int32_t value_location;   /* SHADOWKV_VALUES_DEVICE | SHADOWKV_VALUES_HOST */
+  uint32_t flags;           /* SHADOWKV_FLAG_* */
+  double rope_theta;        /* RoPE base; frequency i is theta^(-2i/d), i < d/2, pairs (i, i + d/2) */
+  double softmax_scale;     /* 0 => 1/sqrt(d); used for landmark scores and for attention */
+  const float *inv_freq;    /* optional dev [d/2]: replaces theta^(-2i/d) (scaled-RoPE models) */
+} shadowkv_params;
+
+/*
+ * Alg. 1, every line after the SVD.  Per (batch, KV head):
+ *   C_j   = mean of the c post-RoPE keys of chunk j            (fp64 accumulate)
+ *   m_j   = min over the chunk's tokens of cos(C_j, key), each norm clamped at 1e-8
+ *   outliers = the o chunks with the smallest m_j (ties: lower chunk id)
+ *   landmarks = bf16(C_j) of the other chunks in ascending chunk order.
+ *
+ *   k_rope              dev        [b, h_kv, s, d] bf16   post-RoPE keys
+ *   v                   dev|pinned [b, h_kv, s, d] bf16   values; may be NULL (then v_outlier is untouched)
+ *   landmarks           dev  out   [b, h_kv, n_c, d] bf16
+ *   landmark_chunk_ids  dev  out   [b, h_kv, n_c] int32   true chunk id of each landmark slot, ascending
+ *   outlier_chunk_ids   dev  out   [b, h_kv, o] int32     ascending chunk id
+ *   k_outlier,v_outlier dev  out   [b, h_kv, o*c, d] bf16 exact copies, chunk order as outlier_chunk_ids
+ *   workspace           dev        >= shadowkv_build_workspace_bytes(), 256-byte aligned
+ * The fields rank, topk_chunks, local_len of params are ignored here.
+ */
+int shadowkv_build_landmarks(const shadowkv_params *params, const shadowkv_bf16 *k_rope,
+                             const shadowkv_bf16 *v, shadowkv_bf16 *landmarks,
+                             int32_t *landmark_chunk_ids, int32_t *outlier_chunk_ids,
+                             shadowkv_bf16 *k_outlier, shadowkv_bf16 *v_outlier, void *workspace,
+                             size_t workspace_bytes, void *stream);
+
+/*
+ * Alg. 2 followed by softmax attention over the selected set, for one new token per sequence.
+ *
+ *   q                   dev        [b, h_q, d] bf16       post-RoPE query; head g uses KV head g / G
+ *   A                   dev        [b, s, r] bf16         left low-rank factor of the pre-RoPE keys (no head axis)
+ *   B                   dev        [b, h_kv, r, d] bf16   right factor, per KV head
+ *   landmarks, landmark_chunk_ids  as produced by shadowkv_build_landmarks
+ *   k_outlier,v_outlier dev        [b, h_kv, o*c, d] bf16 (may be NULL when o == 0)
+ *   k_local, v_local    dev        [b, h_kv, w, d] bf16   post-RoPE keys / values of the w most recent tokens
+ *                                                          (may be NULL when w == 0)
+ *   value_store         dev|pinned [b, h_kv, s, d] bf16   per params->value_location
+ *   pos_offset          dev        [b] int32 or NULL      position of context token 0 (NULL => 0)
+ *   out                 dev  out   [b, h_q, d] bf16
+ *   out_chunk_ids       dev  out   [b, h_kv, k] int32 or NULL: the selected true chunk ids, ascending
+ *   workspace           dev        >= shadowkv_decode_workspace_bytes(), 256-byte aligned
+ *   stream              HIP stream all work is ordered on
+ *   side_stream         HIP stream for the value gather (overlaps the key rebuild); NULL => serial on `stream`
+ *
+ * Scores are ranked in the log domain: score(slot) = max over the group's heads of
+ * (scale * <q_g, L_slot> - logsumexp_g), which orders slots exactly like softmax-then-max;
+ * fp64 accumulation; ties go to the lower slot.
+ */
+int shadowkv_decode_step(const shadowkv_params *params, const shadowkv_bf16 *q,
+                         const shadowkv_bf16 *A, const shadowkv_bf16 *B,
+                         const shadowkv_bf16 *landmarks, const int32_t *landmark_chunk_ids,
+                         const shadowkv_bf16 *k_outlier, const shadowkv_bf16 *v_outlier,
+                         const shadowkv_bf16 *k_local, const shadowkv_bf16 *v_local,
+                         const shadowkv_bf16 *value_store, const int32_t *pos_offset,
+                         shadowkv_bf16 *out, int32_t *out_chunk_ids, void *workspace,
+                         size_t workspace_bytes, void *stream, void *side_stream);
+
+/* Workspace sizes in bytes for the given shape (0 if params are invalid). */
+size_t shadowkv_build_workspace_bytes(const shadowkv_params *params);
+size_t shadowkv_decode_workspace_bytes(const shadowkv_params *params);
+
+/* Host-only check of a parameter block: SHADOWKV_OK or SHADOWKV_EINVAL (reason via last_error). */
+int shadowkv_validate_params(const shadowkv_params *params, int for_decode);
+
+/*
+ * Intermediates of the last decode step inside `workspace` (for tests and profiling).
+ * which: 0 = rebuilt rotated keys, fp32 [b, h_kv, k*c, d], rows in out_chunk_ids order;
+ *        1 = staged values, bf16 [b, h_kv, k*c, d] (only when the gather ran);
+ *        2 = group scores of every landmark slot, fp64 [b, h_kv, n_c]... not kept: returns NULL.
+ * Returns a pointer into `workspace`, or NULL.
+ */
+void *shadowkv_decode_workspace_view(const shadowkv_params *params, void *workspace, int which);
+
+const char *shadowkv_status_string(int status); /* static string for a return code            */
+const char *shadowkv_last_error(void);          /* thread-local detail of the last failure     */
+int shadowkv_version(void);                     /* major*10000 + minor*100 + patch             */
+void shadowkv_shutdown(void);                   /* destroy cached events; safe to call twice   */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SHADOWKV_H */

@@ -1,0 +1,86 @@
+// Launch interfaces of the ShadowKV HIP kernels (internal; the public ABI is
+// include/shadowkv.h).  Every launcher only enqueues on the given stream and
+// returns hipGetLastError().
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "common.hpp"
+
+namespace skv {
+
+constexpr int kMaxHalfDim = 64;   // head_dim <= 128
+constexpr int kScoreTile = 256;   // landmark rows per scoring workgroup
+
+// Rotary frequencies, in revolutions per position (inv_freq / 2 pi), fp64, by value.
+struct RopeFreqs {
+  double rev[kMaxHalfDim];
+};
+
+// ---- landmark scoring (decoding algorithm, P = Q L^T / sqrt(d)) ----------------
+// logits [b*h_q, n_c] fp64; partials [b*h_q, n_tiles] (max, sum exp(p - max)) per tile.
+hipError_t launch_score(const bf16_t* q, const bf16_t* landmarks, double* logits, double2* partials,
+                        int batch, int hq, int hkv, int d, int n_c, double scale, hipStream_t st);
+
+// ---- ArgTopK -------------------------------------------------------------------
+constexpr int kSrcLogits = 0;  // key = max over the group of (logit - lse)
+constexpr int kSrcArray = 1;   // key = sign * scores[unit, j]
+
+struct SelectArgs {
+  const double* logits;     // kSrcLogits: [units*G, n]
+  const double2* partials;  //             [units*G, n_tiles]
+  int n_tiles, G;
+  const double* scores;     // kSrcArray: [units, n]
+  double sign;
+  int n, k, slice_len, n_slices, cand_stride;
+  uint64_t* cand_key;       // [units, cand_stride] survivors of the slices
+  int32_t* cand_idx;
+  const int32_t* id_map;    // optional [units, n]: index -> reported id
+  int32_t* out_ids;         // [units, k], ascending index order
+  int32_t* out_ids2;        // optional copy
+};
+struct SelectPlan {
+  int e, slice_len, n_slices, cand_stride, merge_e;
+};
+bool plan_select(int n, int k, SelectPlan* plan);
+hipError_t launch_select(const SelectArgs& a, const SelectPlan& plan, int src, int units, hipStream_t st);
+
+// ---- key reconstruction + RoPE (K_sparse = RoPE(Gather(A, I) B)) -----------------
+// k_sparse fp32 [units, k*c, d]; sel_ids [units, k] true chunk ids.
+hipError_t launch_recon(const bf16_t* A, const bf16_t* B, const int32_t* sel_ids, const int32_t* pos_offset,
+                        float* k_sparse, const RopeFreqs& freqs, const float* inv_freq_dev, int batch, int hkv,
+                        int d, int s, int r, int c, int k, hipStream_t st);
+
+// ---- value chunk gather (V_sparse = Gather(V_store, I)) -----------------------------
+hipError_t launch_gather_values(const bf16_t* store, const int32_t* sel_ids, bf16_t* v_sparse, int units, int d,
+                                int s, int c, int k, hipStream_t st);
+
+// ---- attention over [outliers ; selected ; recent] ------------------------------------
+struct AttnArgs {
+  const bf16_t* q;          // [b, h_q, d]
+  const bf16_t* k_outlier;  // [units, o*c, d]
+  const bf16_t* v_outlier;
+  const float* k_sparse;    // [units, k*c, d] fp32
+  const bf16_t* v_sparse;   // staged [units, k*c, d], or NULL: read the store through sel_ids
+  const bf16_t* v_store;    // [units, s, d]
+  const int32_t* sel_ids;   // [units, k]
+  const bf16_t* k_local;    // [units, w, d]
+  const bf16_t* v_local;
+  float* part_acc;          // [b*h_q, n_splits, d]
+  float2* part_ml;          // [b*h_q, n_splits] (max in log2 units, sum)
+  bf16_t* out;              // [b, h_q, d]
+  int batch, hq, hkv, d, s, c, o, k, w;
+  int split_len, n_splits;
+  float scale_log2;         // softmax scale * log2(e)
+};
+hipError_t launch_attention(const AttnArgs& a, hipStream_t st);
+
+// ---- pre-filling algorithm: chunk means, min cosine, compaction, outlier gather -------
+hipError_t launch_chunk_stats(const bf16_t* k_rope, bf16_t* chunk_mean, double* chunk_min_cos, int units, int d,
+                              int s, int c, hipStream_t st);
+hipError_t launch_compact_landmarks(const bf16_t* chunk_mean, const int32_t* outlier_ids, bf16_t* landmarks,
+                                    int32_t* landmark_chunk_ids, int units, int d, int n_ch, int o, hipStream_t st);
+hipError_t launch_gather_outliers(const bf16_t* k_rope, const bf16_t* v, const int32_t* outlier_ids,
+                                  bf16_t* k_outlier, bf16_t* v_outlier, int units, int d, int s, int c, int o,
+                                  hipStream_t st);
+
+}  // namespace skv

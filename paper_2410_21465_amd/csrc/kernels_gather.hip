@@ -1,0 +1,54 @@
+// Value chunk gather: V_sparse = Gather(V_store, I) (decoding algorithm, "gather value
+// cache" line).  The store may live in pinned host memory that the GPU reads over PCIe,
+// so the kernel is a zero-copy reader: every chunk is c*d*2 contiguous bytes, lanes take
+// 16 bytes each, and each thread keeps four independent loads in flight before it
+// stores, which is what keeps a high-latency link busy.  The same kernel serves an HBM
+// store when staging is requested.
+#include "kernels.hpp"
+
+namespace skv {
+
+constexpr int kGatherUnroll = 4;
+
+__global__ __launch_bounds__(256) void gather_values_kernel(const uint4* __restrict__ store,
+                                                            const int32_t* __restrict__ sel_ids,
+                                                            uint4* __restrict__ v_sparse, int k, int vec_per_chunk,
+                                                            size_t vec_per_unit_store) {
+  const int last_chunk = (int)(vec_per_unit_store / vec_per_chunk) - 1;
+  const int unit = blockIdx.y;
+  const int32_t* ids = sel_ids + (size_t)unit * k;
+  const uint4* src_u = store + (size_t)unit * vec_per_unit_store;
+  uint4* dst_u = v_sparse + (size_t)unit * k * vec_per_chunk;
+  const int total = k * vec_per_chunk;  // 16-byte vectors this unit moves
+  const int stride = gridDim.x * 256;
+  for (int v0 = blockIdx.x * 256 + threadIdx.x; v0 < total; v0 += stride * kGatherUnroll) {
+    uint4 buf[kGatherUnroll];
+#pragma unroll
+    for (int u = 0; u < kGatherUnroll; ++u) {
+      const int v = v0 + u * stride;
+      if (v < total) {
+        const int ch = v / vec_per_chunk, off = v - ch * vec_per_chunk;
+        buf[u] = src_u[(size_t)min(max(ids[ch], 0), last_chunk) * vec_per_chunk + off];
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kGatherUnroll; ++u) {
+      const int v = v0 + u * stride;
+      if (v < total) dst_u[v] = buf[u];
+    }
+  }
+}
+
+hipError_t launch_gather_values(const bf16_t* store, const int32_t* sel_ids, bf16_t* v_sparse, int units, int d,
+                                int s, int c, int k, hipStream_t st) {
+  const int vec_per_chunk = c * d * 2 / 16;
+  const int total = k * vec_per_chunk;
+  int gx = (total + 256 * kGatherUnroll - 1) / (256 * kGatherUnroll);
+  if (gx < 1) gx = 1;
+  dim3 grid(gx, units), block(256);
+  hipLaunchKernelGGL(gather_values_kernel, grid, block, 0, st, reinterpret_cast<const uint4*>(store), sel_ids,
+                     reinterpret_cast<uint4*>(v_sparse), k, vec_per_chunk, (size_t)s * d * 2 / 16);
+  return hipGetLastError();
+}
+
+}  // namespace skv

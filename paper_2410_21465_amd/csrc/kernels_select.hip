@@ -1,0 +1,172 @@
+// ArgTopK of the decoding algorithm (group score of every landmark slot -> k chunks)
+// and of the pre-filling algorithm (lowest minimum cosine -> o outlier chunks).
+//
+// Two kernels: `select_slices` ranks one slice of NT*E candidates per workgroup and
+// keeps min(k, slice) of them; `select_merge` ranks the survivors of all slices of a
+// unit.  With a single slice the first kernel writes the final ids itself.
+#include "kernels.hpp"
+#include "select.hpp"
+
+namespace skv {
+
+constexpr int kSelNT = 512;
+
+// Log-sum-exp of each query head of the unit from the per-tile (max, sum) pairs the
+// scoring kernel left behind; fp64 throughout.
+__device__ void unit_lse(const double2* __restrict__ part, int n_tiles, int G, double* lse_sm) {
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  for (int g = wave; g < G; g += kSelNT / kWave) {
+    const double2* p = part + (size_t)g * n_tiles;
+    double m = -INFINITY;
+    for (int t = lane; t < n_tiles; t += kWave) m = fmax(m, p[t].x);
+    m = wave_max_f64(m);
+    double s = 0.0;
+    for (int t = lane; t < n_tiles; t += kWave) s += p[t].y * exp(p[t].x - m);
+    s = wave_sum_f64(s);
+    if (lane == 0) lse_sm[g] = m + log(s);
+  }
+  __syncthreads();
+}
+
+template <int E, int SRC>
+__global__ __launch_bounds__(kSelNT) void select_slices(SelectArgs a) {
+  __shared__ SelectSmem<kSelNT> sm;
+  __shared__ double lse_sm[64];
+  const int unit = blockIdx.y, slice = blockIdx.x;
+  const int base = slice * a.slice_len;
+  const int n_here = min(a.slice_len, a.n - base);
+  const int k_here = min(a.k, n_here);
+
+  uint64_t key[E];
+  if constexpr (SRC == kSrcLogits) {
+    unit_lse(a.partials + (size_t)unit * a.G * a.n_tiles, a.n_tiles, a.G, lse_sm);
+    const double* lg = a.logits + (size_t)unit * a.G * a.n;
+#pragma unroll
+    for (int e = 0; e < E; ++e) key[e] = 0ull;
+    const int j0 = base + threadIdx.x * E;
+    for (int g = 0; g < a.G; ++g) {
+      const double l = lse_sm[g];
+      const double* row = lg + (size_t)g * a.n;
+#pragma unroll
+      for (int e = 0; e < E; ++e) {
+        const int j = j0 + e;
+        if (j < a.n) {
+          const uint64_t kk = f64_key(row[j] - l);
+          key[e] = kk > key[e] ? kk : key[e];   // max over the heads of the group
+        }
+      }
+    }
+  } else {
+    const double* sc = a.scores + (size_t)unit * a.n;
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+      const int j = base + threadIdx.x * E + e;
+      key[e] = j < a.n ? f64_key(a.sign * sc[j]) : 0ull;
+    }
+  }
+
+  uint32_t sel; int pos;
+  block_select_topk<kSelNT, E>(key, k_here, sm, sel, pos);
+
+  if (a.n_slices == 1) {
+#pragma unroll
+    for (int e = 0; e < E; ++e)
+      if ((sel & (1u << e)) && pos < k_here) {
+        const int j = base + threadIdx.x * E + e;
+        const int id = a.id_map ? a.id_map[(size_t)unit * a.n + j] : j;
+        a.out_ids[(size_t)unit * a.k + pos] = id;
+        if (a.out_ids2) a.out_ids2[(size_t)unit * a.k + pos] = id;
+        ++pos;
+      }
+  } else {
+    const size_t off = (size_t)unit * a.cand_stride + (size_t)slice * min(a.k, a.slice_len);
+#pragma unroll
+    for (int e = 0; e < E; ++e)
+      if ((sel & (1u << e)) && pos < k_here) {
+        a.cand_key[off + pos] = key[e];
+        a.cand_idx[off + pos] = base + threadIdx.x * E + e;
+        ++pos;
+      }
+  }
+}
+
+template <int E>
+__global__ __launch_bounds__(kSelNT) void select_merge(SelectArgs a) {
+  __shared__ SelectSmem<kSelNT> sm;
+  const int unit = blockIdx.x;
+  const int per = min(a.k, a.slice_len);
+  const int n_last = a.n - (a.n_slices - 1) * a.slice_len;
+  const int n_cand = (a.n_slices - 1) * per + min(a.k, n_last);
+  const uint64_t* ck = a.cand_key + (size_t)unit * a.cand_stride;
+  const int32_t* ci = a.cand_idx + (size_t)unit * a.cand_stride;
+  uint64_t key[E];
+  int idx[E];
+#pragma unroll
+  for (int e = 0; e < E; ++e) {
+    const int c = threadIdx.x * E + e;
+    key[e] = c < n_cand ? ck[c] : 0ull;
+    idx[e] = c < n_cand ? ci[c] : 0;
+  }
+  uint32_t sel; int pos;
+  block_select_topk<kSelNT, E>(key, a.k, sm, sel, pos);
+#pragma unroll
+  for (int e = 0; e < E; ++e)
+    if ((sel & (1u << e)) && pos < a.k) {
+      const int id = a.id_map ? a.id_map[(size_t)unit * a.n + idx[e]] : idx[e];
+      a.out_ids[(size_t)unit * a.k + pos] = id;
+      if (a.out_ids2) a.out_ids2[(size_t)unit * a.k + pos] = id;
+      ++pos;
+    }
+}
+
+// ---- host side ----------------------------------------------------------------
+// Smallest per-thread element count whose slice plan fits the merge kernel.
+bool plan_select(int n, int k, SelectPlan* plan) {
+  static const int es[] = {4, 8, 16, 32};
+  for (int e : es) {
+    const int slice_len = kSelNT * e;
+    const int n_slices = (n + slice_len - 1) / slice_len;
+    const long cand = (long)n_slices * (k < slice_len ? k : slice_len);
+    if (n_slices == 1 || cand <= (long)kSelNT * 32) {
+      plan->e = e; plan->slice_len = slice_len; plan->n_slices = n_slices;
+      plan->cand_stride = n_slices == 1 ? 0 : (int)cand;
+      int me = 1;
+      while ((long)kSelNT * me < cand) me *= 2;
+      plan->merge_e = n_slices == 1 ? 0 : me;
+      return true;
+    }
+  }
+  return false;
+}
+
+template <int SRC>
+static hipError_t launch_slices(const SelectArgs& a, int e, int units, hipStream_t st) {
+  dim3 grid(a.n_slices, units), block(kSelNT);
+  switch (e) {
+    case 4: hipLaunchKernelGGL((select_slices<4, SRC>), grid, block, 0, st, a); break;
+    case 8: hipLaunchKernelGGL((select_slices<8, SRC>), grid, block, 0, st, a); break;
+    case 16: hipLaunchKernelGGL((select_slices<16, SRC>), grid, block, 0, st, a); break;
+    case 32: hipLaunchKernelGGL((select_slices<32, SRC>), grid, block, 0, st, a); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_select(const SelectArgs& a, const SelectPlan& plan, int src, int units, hipStream_t st) {
+  hipError_t err = src == kSrcLogits ? launch_slices<kSrcLogits>(a, plan.e, units, st)
+                                     : launch_slices<kSrcArray>(a, plan.e, units, st);
+  if (err != hipSuccess || a.n_slices == 1) return err;
+  dim3 grid(units), block(kSelNT);
+  switch (plan.merge_e) {
+    case 1: hipLaunchKernelGGL((select_merge<1>), grid, block, 0, st, a); break;
+    case 2: hipLaunchKernelGGL((select_merge<2>), grid, block, 0, st, a); break;
+    case 4: hipLaunchKernelGGL((select_merge<4>), grid, block, 0, st, a); break;
+    case 8: hipLaunchKernelGGL((select_merge<8>), grid, block, 0, st, a); break;
+    case 16: hipLaunchKernelGGL((select_merge<16>), grid, block, 0, st, a); break;
+    case 32: hipLaunchKernelGGL((select_merge<32>), grid, block, 0, st, a); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+}  // namespace skv

@@ -1,0 +1,370 @@
+// C ABI of libshadowkv (see include/shadowkv.h): argument validation, workspace layout,
+// and the enqueue order of the kernels.  Nothing here touches the GPU before the
+// arguments have been accepted.
+#include "../../include/shadowkv.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+
+#include "kernels.hpp"
+
+using namespace skv;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+void set_err(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
+  va_end(ap);
+}
+
+int fail_inval(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
+  va_end(ap);
+  return SHADOWKV_EINVAL;
+}
+
+int fail_hip(const char* what, hipError_t e) {
+  set_err("%s: %s", what, hipGetErrorString(e));
+  return SHADOWKV_EHIP;
+}
+
+constexpr size_t kAlign = 256;
+size_t up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+struct Shape {
+  int b, hq, hkv, G, d, s, c, r, o, k, w, n_ch, n_c, units;
+  bool stage;
+};
+
+// Shape rules shared by both entry points.  Returns SHADOWKV_OK or EINVAL with a reason.
+int check_params(const shadowkv_params* p, bool decode, Shape* sh) {
+  if (!p) return fail_inval("params is NULL");
+  if (p->batch < 1 || p->n_q_heads < 1 || p->n_kv_heads < 1)
+    return fail_inval("batch, n_q_heads, n_kv_heads must be >= 1");
+  if (p->n_q_heads % p->n_kv_heads) return fail_inval("n_q_heads must be a multiple of n_kv_heads");
+  if (p->n_q_heads / p->n_kv_heads > 64) return fail_inval("group size above 64 is not supported");
+  if (p->head_dim != 64 && p->head_dim != 96 && p->head_dim != 128)
+    return fail_inval("head_dim must be 64, 96 or 128");
+  if (p->chunk_size < 1 || p->chunk_size > 64) return fail_inval("chunk_size must be in [1, 64]");
+  if (p->ctx_len < p->chunk_size || p->ctx_len % p->chunk_size)
+    return fail_inval("ctx_len must be a positive multiple of chunk_size");
+  const long n_ch = p->ctx_len / p->chunk_size;
+  if (p->n_outlier_chunks < 0 || p->n_outlier_chunks > 1024 || p->n_outlier_chunks > n_ch)
+    return fail_inval("n_outlier_chunks must be in [0, min(1024, ctx_len/chunk_size)]");
+  const long units = (long)p->batch * p->n_kv_heads;
+  if (units > 65535) return fail_inval("batch * n_kv_heads above 65535 is not supported");
+  if (p->value_location != SHADOWKV_VALUES_DEVICE && p->value_location != SHADOWKV_VALUES_HOST)
+    return fail_inval("value_location must be SHADOWKV_VALUES_DEVICE or SHADOWKV_VALUES_HOST");
+  sh->b = p->batch; sh->hq = p->n_q_heads; sh->hkv = p->n_kv_heads; sh->G = sh->hq / sh->hkv;
+  sh->d = p->head_dim; sh->s = p->ctx_len; sh->c = p->chunk_size; sh->o = p->n_outlier_chunks;
+  sh->n_ch = (int)n_ch; sh->n_c = (int)n_ch - sh->o; sh->units = (int)units;
+  sh->r = p->rank; sh->k = p->topk_chunks; sh->w = p->local_len;
+  sh->stage = p->value_location == SHADOWKV_VALUES_HOST || (p->flags & SHADOWKV_FLAG_STAGE_VALUES);
+  if (!decode) return SHADOWKV_OK;
+  if (p->rank < 8 || p->rank > 256 || p->rank % 8) return fail_inval("rank must be a multiple of 8 in [8, 256]");
+  if (p->local_len < 0) return fail_inval("local_len must be >= 0");
+  if (p->topk_chunks < 1 || p->topk_chunks > sh->n_c)
+    return fail_inval("topk_chunks must be in [1, ctx_len/chunk_size - n_outlier_chunks]");
+  if ((long)p->topk_chunks * p->chunk_size > (1l << 24)) return fail_inval("topk_chunks * chunk_size too large");
+  if (!(p->softmax_scale >= 0.0) || !std::isfinite(p->softmax_scale))
+    return fail_inval("softmax_scale must be finite and >= 0");
+  if (!p->inv_freq && !(p->rope_theta > 0.0 && std::isfinite(p->rope_theta)))
+    return fail_inval("rope_theta must be finite and > 0 when inv_freq is NULL");
+  SelectPlan plan;
+  if (!plan_select(sh->n_c, sh->k, &plan))
+    return fail_inval("topk_chunks / landmark count combination exceeds the selection kernels' capacity");
+  return SHADOWKV_OK;
+}
+
+struct AttnPlan {
+  int split_len, n_splits;
+};
+AttnPlan plan_attention(const Shape& sh) {
+  const int gh = (sh.G % 8 == 0) ? 8 : (sh.G % 4 == 0) ? 4 : (sh.G % 2 == 0) ? 2 : 1;
+  const long T = (long)sh.o * sh.c + (long)sh.k * sh.c + sh.w;
+  long want = T * sh.units * (sh.G / gh) / 2048;
+  want = (want + 15) / 16 * 16;
+  if (want < 32) want = 32;
+  if (want > 256) want = 256;
+  AttnPlan ap;
+  ap.split_len = (int)want;
+  ap.n_splits = (int)((T + want - 1) / want);
+  return ap;
+}
+
+struct DecodeLayout {
+  size_t logits, partials, cand_key, cand_idx, sel_ids, k_sparse, v_sparse, part_acc, part_ml, total;
+  SelectPlan sel;
+  AttnPlan attn;
+  int n_tiles;
+};
+DecodeLayout decode_layout(const Shape& sh) {
+  DecodeLayout L{};
+  plan_select(sh.n_c, sh.k, &L.sel);
+  L.attn = plan_attention(sh);
+  L.n_tiles = (sh.n_c + kScoreTile - 1) / kScoreTile;
+  const size_t heads = (size_t)sh.b * sh.hq, rows = (size_t)sh.units * sh.k * sh.c;
+  size_t off = 0;
+  L.logits = off; off += up(heads * sh.n_c * sizeof(double));
+  L.partials = off; off += up(heads * L.n_tiles * sizeof(double2));
+  L.cand_key = off; off += up((size_t)sh.units * L.sel.cand_stride * sizeof(uint64_t));
+  L.cand_idx = off; off += up((size_t)sh.units * L.sel.cand_stride * sizeof(int32_t));
+  L.sel_ids = off; off += up((size_t)sh.units * sh.k * sizeof(int32_t));
+  L.k_sparse = off; off += up(rows * sh.d * sizeof(float));
+  L.v_sparse = off; off += sh.stage ? up(rows * sh.d * sizeof(bf16_t)) : 0;
+  L.part_acc = off; off += up(heads * L.attn.n_splits * sh.d * sizeof(float));
+  L.part_ml = off; off += up(heads * L.attn.n_splits * sizeof(float2));
+  L.total = off;
+  return L;
+}
+
+struct BuildLayout {
+  size_t chunk_mean, min_cos, cand_key, cand_idx, total;
+  SelectPlan sel;
+};
+bool build_layout(const Shape& sh, BuildLayout* L) {
+  *L = BuildLayout{};
+  if (sh.o > 0 && !plan_select(sh.n_ch, sh.o, &L->sel)) return false;
+  size_t off = 0;
+  L->chunk_mean = off; off += up((size_t)sh.units * sh.n_ch * sh.d * sizeof(bf16_t));
+  L->min_cos = off; off += up((size_t)sh.units * sh.n_ch * sizeof(double));
+  L->cand_key = off; off += up((size_t)sh.units * L->sel.cand_stride * sizeof(uint64_t));
+  L->cand_idx = off; off += up((size_t)sh.units * L->sel.cand_stride * sizeof(int32_t));
+  L->total = off;
+  return true;
+}
+
+int check_workspace(void* ws, size_t have, size_t need) {
+  if (!ws) { set_err("workspace is NULL"); return SHADOWKV_EWORKSPACE; }
+  if (reinterpret_cast<uintptr_t>(ws) % kAlign) { set_err("workspace must be 256-byte aligned"); return SHADOWKV_EWORKSPACE; }
+  if (have < need) { set_err("workspace too small: %zu bytes given, %zu needed", have, need); return SHADOWKV_EWORKSPACE; }
+  return SHADOWKV_OK;
+}
+
+// Fork/join events, one pair per device, created on first use.
+std::mutex g_mu;
+constexpr int kMaxDev = 16;
+hipEvent_t g_fork[kMaxDev] = {}, g_join[kMaxDev] = {};
+bool g_have[kMaxDev] = {};
+
+int get_events(hipEvent_t* fork, hipEvent_t* join) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail_hip("hipGetDevice", e);
+  if (dev < 0 || dev >= kMaxDev) return fail_inval("device index %d out of range", dev);
+  if (!g_have[dev]) {
+    e = hipEventCreateWithFlags(&g_fork[dev], hipEventDisableTiming);
+    if (e != hipSuccess) return fail_hip("hipEventCreate", e);
+    e = hipEventCreateWithFlags(&g_join[dev], hipEventDisableTiming);
+    if (e != hipSuccess) { (void)hipEventDestroy(g_fork[dev]); return fail_hip("hipEventCreate", e); }
+    g_have[dev] = true;
+  }
+  *fork = g_fork[dev]; *join = g_join[dev];
+  return SHADOWKV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int shadowkv_version(void) { return 100; }
+
+const char* shadowkv_status_string(int status) {
+  switch (status) {
+    case SHADOWKV_OK: return "ok";
+    case SHADOWKV_EINVAL: return "invalid argument";
+    case SHADOWKV_EWORKSPACE: return "workspace missing, misaligned or too small";
+    case SHADOWKV_EHIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+const char* shadowkv_last_error(void) { return g_err; }
+
+void shadowkv_shutdown(void) {
+  std::lock_guard<std::mutex> lk(g_mu);
+  int cur = 0;
+  if (hipGetDevice(&cur) != hipSuccess) cur = -1;
+  for (int d = 0; d < kMaxDev; ++d)
+    if (g_have[d]) {
+      if (hipSetDevice(d) == hipSuccess) { (void)hipEventDestroy(g_fork[d]); (void)hipEventDestroy(g_join[d]); }
+      g_have[d] = false;
+    }
+  if (cur >= 0) (void)hipSetDevice(cur);
+}
+
+int shadowkv_validate_params(const shadowkv_params* params, int for_decode) {
+  Shape sh;
+  return check_params(params, for_decode != 0, &sh);
+}
+
+size_t shadowkv_decode_workspace_bytes(const shadowkv_params* params) {
+  Shape sh;
+  if (check_params(params, true, &sh) != SHADOWKV_OK) return 0;
+  return decode_layout(sh).total;
+}
+
+size_t shadowkv_build_workspace_bytes(const shadowkv_params* params) {
+  Shape sh;
+  BuildLayout L;
+  if (check_params(params, false, &sh) != SHADOWKV_OK || !build_layout(sh, &L)) return 0;
+  return L.total;
+}
+
+void* shadowkv_decode_workspace_view(const shadowkv_params* params, void* workspace, int which) {
+  Shape sh;
+  if (!workspace || check_params(params, true, &sh) != SHADOWKV_OK) return nullptr;
+  const DecodeLayout L = decode_layout(sh);
+  char* ws = static_cast<char*>(workspace);
+  switch (which) {
+    case 0: return ws + L.k_sparse;
+    case 1: return sh.stage ? ws + L.v_sparse : nullptr;
+    case 2: return ws + L.sel_ids;
+    case 3: return ws + L.logits;
+    default: return nullptr;
+  }
+}
+
+int shadowkv_build_landmarks(const shadowkv_params* params, const shadowkv_bf16* k_rope, const shadowkv_bf16* v,
+                             shadowkv_bf16* landmarks, int32_t* landmark_chunk_ids, int32_t* outlier_chunk_ids,
+                             shadowkv_bf16* k_outlier, shadowkv_bf16* v_outlier, void* workspace,
+                             size_t workspace_bytes, void* stream) {
+  Shape sh;
+  int rc = check_params(params, false, &sh);
+  if (rc != SHADOWKV_OK) return rc;
+  if (!k_rope) return fail_inval("k_rope is NULL");
+  if (sh.n_c > 0 && (!landmarks || !landmark_chunk_ids)) return fail_inval("landmarks / landmark_chunk_ids is NULL");
+  if (sh.o > 0 && (!outlier_chunk_ids || !k_outlier)) return fail_inval("outlier outputs are NULL with n_outlier_chunks > 0");
+  if (sh.o > 0 && v && !v_outlier) return fail_inval("v given but v_outlier is NULL");
+  if (!aligned16(k_rope) || !aligned16(v) || !aligned16(landmarks) || !aligned16(k_outlier) || !aligned16(v_outlier))
+    return fail_inval("tensor pointers must be 16-byte aligned");
+  BuildLayout L;
+  if (!build_layout(sh, &L)) return fail_inval("n_outlier_chunks / chunk count exceeds the selection kernels' capacity");
+  rc = check_workspace(workspace, workspace_bytes, L.total);
+  if (rc != SHADOWKV_OK) return rc;
+
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* ws = static_cast<char*>(workspace);
+  bf16_t* chunk_mean = reinterpret_cast<bf16_t*>(ws + L.chunk_mean);
+  double* min_cos = reinterpret_cast<double*>(ws + L.min_cos);
+  hipError_t e = launch_chunk_stats(k_rope, chunk_mean, min_cos, sh.units, sh.d, sh.s, sh.c, st);
+  if (e != hipSuccess) return fail_hip("chunk_stats", e);
+  if (sh.o > 0) {
+    SelectArgs a{};
+    a.scores = min_cos; a.sign = -1.0;  // ArgTopK(-Min(S), o)
+    a.n = sh.n_ch; a.k = sh.o;
+    a.slice_len = L.sel.slice_len; a.n_slices = L.sel.n_slices; a.cand_stride = L.sel.cand_stride;
+    a.cand_key = reinterpret_cast<uint64_t*>(ws + L.cand_key);
+    a.cand_idx = reinterpret_cast<int32_t*>(ws + L.cand_idx);
+    a.out_ids = outlier_chunk_ids;
+    e = launch_select(a, L.sel, kSrcArray, sh.units, st);
+    if (e != hipSuccess) return fail_hip("select outliers", e);
+    e = launch_gather_outliers(k_rope, v, outlier_chunk_ids, k_outlier, v_outlier, sh.units, sh.d, sh.s, sh.c, sh.o, st);
+    if (e != hipSuccess) return fail_hip("gather outliers", e);
+  }
+  e = launch_compact_landmarks(chunk_mean, outlier_chunk_ids, landmarks, landmark_chunk_ids, sh.units, sh.d, sh.n_ch,
+                               sh.o, st);
+  if (e != hipSuccess) return fail_hip("compact landmarks", e);
+  return SHADOWKV_OK;
+}
+
+int shadowkv_decode_step(const shadowkv_params* params, const shadowkv_bf16* q, const shadowkv_bf16* A,
+                         const shadowkv_bf16* B, const shadowkv_bf16* landmarks, const int32_t* landmark_chunk_ids,
+                         const shadowkv_bf16* k_outlier, const shadowkv_bf16* v_outlier,
+                         const shadowkv_bf16* k_local, const shadowkv_bf16* v_local,
+                         const shadowkv_bf16* value_store, const int32_t* pos_offset, shadowkv_bf16* out,
+                         int32_t* out_chunk_ids, void* workspace, size_t workspace_bytes, void* stream,
+                         void* side_stream) {
+  Shape sh;
+  int rc = check_params(params, true, &sh);
+  if (rc != SHADOWKV_OK) return rc;
+  if (!q || !A || !B || !landmarks || !landmark_chunk_ids || !value_store || !out)
+    return fail_inval("q, A, B, landmarks, landmark_chunk_ids, value_store and out must not be NULL");
+  if (sh.o > 0 && (!k_outlier || !v_outlier)) return fail_inval("k_outlier / v_outlier is NULL with n_outlier_chunks > 0");
+  if (sh.w > 0 && (!k_local || !v_local)) return fail_inval("k_local / v_local is NULL with local_len > 0");
+  if (!aligned16(q) || !aligned16(A) || !aligned16(B) || !aligned16(landmarks) || !aligned16(k_outlier) ||
+      !aligned16(v_outlier) || !aligned16(k_local) || !aligned16(v_local) || !aligned16(value_store) || !aligned16(out))
+    return fail_inval("tensor pointers must be 16-byte aligned");
+  const DecodeLayout L = decode_layout(sh);
+  rc = check_workspace(workspace, workspace_bytes, L.total);
+  if (rc != SHADOWKV_OK) return rc;
+
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  hipStream_t side = static_cast<hipStream_t>(side_stream);
+  const bool fork = sh.stage && side && side != st;
+  char* ws = static_cast<char*>(workspace);
+  double* logits = reinterpret_cast<double*>(ws + L.logits);
+  double2* partials = reinterpret_cast<double2*>(ws + L.partials);
+  int32_t* sel_ids = reinterpret_cast<int32_t*>(ws + L.sel_ids);
+  float* k_sparse = reinterpret_cast<float*>(ws + L.k_sparse);
+  bf16_t* v_sparse = sh.stage ? reinterpret_cast<bf16_t*>(ws + L.v_sparse) : nullptr;
+  const double scale = params->softmax_scale != 0.0 ? params->softmax_scale : 1.0 / std::sqrt((double)sh.d);
+
+  RopeFreqs freqs;
+  for (int i = 0; i < sh.d / 2; ++i)
+    freqs.rev[i] = std::pow(params->rope_theta, -2.0 * (double)i / (double)sh.d) / 6.283185307179586476925;
+  for (int i = sh.d / 2; i < kMaxHalfDim; ++i) freqs.rev[i] = 0.0;
+
+  std::lock_guard<std::mutex> lk(g_mu);  // one enqueue sequence at a time (the events are shared)
+  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+  if (fork) {
+    rc = get_events(&ev_fork, &ev_join);
+    if (rc != SHADOWKV_OK) return rc;
+  }
+
+  // 1. P = Q L^T / sqrt(d), per-tile softmax statistics
+  hipError_t e = launch_score(q, landmarks, logits, partials, sh.b, sh.hq, sh.hkv, sh.d, sh.n_c, scale, st);
+  if (e != hipSuccess) return fail_hip("score", e);
+  // 2. softmax normaliser per head, max over the group, ArgTopK -> true chunk ids
+  SelectArgs a{};
+  a.logits = logits; a.partials = partials; a.n_tiles = L.n_tiles; a.G = sh.G;
+  a.n = sh.n_c; a.k = sh.k;
+  a.slice_len = L.sel.slice_len; a.n_slices = L.sel.n_slices; a.cand_stride = L.sel.cand_stride;
+  a.cand_key = reinterpret_cast<uint64_t*>(ws + L.cand_key);
+  a.cand_idx = reinterpret_cast<int32_t*>(ws + L.cand_idx);
+  a.id_map = landmark_chunk_ids;
+  a.out_ids = sel_ids; a.out_ids2 = out_chunk_ids;
+  e = launch_select(a, L.sel, kSrcLogits, sh.units, st);
+  if (e != hipSuccess) return fail_hip("select chunks", e);
+  // 3. values of the selected chunks (side stream) while 4. keys are rebuilt and rotated
+  if (sh.stage) {
+    hipStream_t gs = st;
+    if (fork) {
+      if ((e = hipEventRecord(ev_fork, st)) != hipSuccess) return fail_hip("hipEventRecord", e);
+      if ((e = hipStreamWaitEvent(side, ev_fork, 0)) != hipSuccess) return fail_hip("hipStreamWaitEvent", e);
+      gs = side;
+    }
+    e = launch_gather_values(value_store, sel_ids, v_sparse, sh.units, sh.d, sh.s, sh.c, sh.k, gs);
+    if (e != hipSuccess) return fail_hip("gather values", e);
+    if (fork && (e = hipEventRecord(ev_join, side)) != hipSuccess) return fail_hip("hipEventRecord", e);
+  }
+  e = launch_recon(A, B, sel_ids, pos_offset, k_sparse, freqs, params->inv_freq, sh.b, sh.hkv, sh.d, sh.s, sh.r, sh.c,
+                   sh.k, st);
+  if (e != hipSuccess) return fail_hip("reconstruct keys", e);
+  if (fork && (e = hipStreamWaitEvent(st, ev_join, 0)) != hipSuccess) return fail_hip("hipStreamWaitEvent", e);
+  // 5. attention over [outliers ; selected ; recent]
+  AttnArgs t{};
+  t.q = q; t.k_outlier = k_outlier; t.v_outlier = v_outlier; t.k_sparse = k_sparse; t.v_sparse = v_sparse;
+  t.v_store = value_store; t.sel_ids = sel_ids; t.k_local = k_local; t.v_local = v_local;
+  t.part_acc = reinterpret_cast<float*>(ws + L.part_acc);
+  t.part_ml = reinterpret_cast<float2*>(ws + L.part_ml);
+  t.out = out;
+  t.batch = sh.b; t.hq = sh.hq; t.hkv = sh.hkv; t.d = sh.d; t.s = sh.s; t.c = sh.c; t.o = sh.o; t.k = sh.k; t.w = sh.w;
+  t.split_len = L.attn.split_len; t.n_splits = L.attn.n_splits;
+  t.scale_log2 = (float)(scale * 1.4426950408889634074);
+  e = launch_attention(t, st);
+  if (e != hipSuccess) return fail_hip("attention", e);
+  return SHADOWKV_OK;
+}
+
+}  // extern "C"

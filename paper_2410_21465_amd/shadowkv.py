@@ -1,0 +1,250 @@
+"""ctypes binding of libshadowkv.so: argument marshalling only.
+
+Every step of the path runs in the HIP library; this module turns torch tensors
+into pointers, sizes the workspace and picks the streams.  There is no fallback:
+if the library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libshadowkv.so")
+
+OK, EINVAL, EWORKSPACE, EHIP = 0, -1, -2, -3
+VALUES_DEVICE, VALUES_HOST = 0, 1
+FLAG_STAGE_VALUES = 1
+
+EXPORTS = (
+    "shadowkv_build_landmarks", "shadowkv_decode_step", "shadowkv_build_workspace_bytes",
+    "shadowkv_decode_workspace_bytes", "shadowkv_validate_params", "shadowkv_decode_workspace_view",
+    "shadowkv_status_string", "shadowkv_last_error", "shadowkv_version", "shadowkv_shutdown",
+)
+
+
+class CParams(C.Structure):
+    _fields_ = [
+        ("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+        ("ctx_len", C.c_int32), ("chunk_size", C.c_int32), ("rank", C.c_int32),
+        ("n_outlier_chunks", C.c_int32), ("topk_chunks", C.c_int32), ("local_len", C.c_int32),
+        ("value_location", C.c_int32), ("flags", C.c_uint32),
+        ("rope_theta", C.c_double), ("softmax_scale", C.c_double), ("inv_freq", C.c_void_p),
+    ]
+
+
+class ShadowKVError(RuntimeError):
+    def __init__(self, status: int, detail: str):
+        super().__init__(f"libshadowkv: {status_string(status)} ({status}): {detail}")
+        self.status = status
+        self.detail = detail
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load the HIP library (built beforehand by ``python -m paper_2410_21465_amd.build``)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2410_21465_amd.build` "
+                "(there is no non-HIP fallback)")
+        L = C.CDLL(LIB_PATH)
+        vp, sz, i32 = C.c_void_p, C.c_size_t, C.c_int
+        L.shadowkv_build_landmarks.restype = i32
+        L.shadowkv_build_landmarks.argtypes = [vp] * 9 + [sz, vp]
+        L.shadowkv_decode_step.restype = i32
+        L.shadowkv_decode_step.argtypes = [vp] * 15 + [sz, vp, vp]
+        L.shadowkv_build_workspace_bytes.restype = sz
+        L.shadowkv_build_workspace_bytes.argtypes = [vp]
+        L.shadowkv_decode_workspace_bytes.restype = sz
+        L.shadowkv_decode_workspace_bytes.argtypes = [vp]
+        L.shadowkv_validate_params.restype = i32
+        L.shadowkv_validate_params.argtypes = [vp, i32]
+        L.shadowkv_decode_workspace_view.restype = vp
+        L.shadowkv_decode_workspace_view.argtypes = [vp, vp, i32]
+        L.shadowkv_status_string.restype = C.c_char_p
+        L.shadowkv_status_string.argtypes = [i32]
+        L.shadowkv_last_error.restype = C.c_char_p
+        L.shadowkv_version.restype = i32
+        L.shadowkv_shutdown.restype = None
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().shadowkv_status_string(status).decode()
+
+
+def last_error() -> str:
+    return lib().shadowkv_last_error().decode()
+
+
+def version() -> int:
+    return int(lib().shadowkv_version())
+
+
+def _check(status: int) -> None:
+    if status != OK:
+        raise ShadowKVError(status, last_error())
+
+
+@dataclass
+class Params:
+    batch: int
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    ctx_len: int
+    chunk_size: int = 8
+    rank: int = 160
+    n_outlier_chunks: int = 48
+    topk_chunks: int = 256
+    local_len: int = 32
+    value_location: int = VALUES_DEVICE
+    flags: int = 0
+    rope_theta: float = 5e5
+    softmax_scale: float = 0.0
+    inv_freq: Optional[torch.Tensor] = None   # device float32 [head_dim/2]
+
+    @property
+    def n_chunks(self) -> int:
+        return self.ctx_len // self.chunk_size
+
+    @property
+    def n_landmarks(self) -> int:
+        return self.n_chunks - self.n_outlier_chunks
+
+    def c_struct(self) -> CParams:
+        inv = None
+        if self.inv_freq is not None:
+            assert self.inv_freq.dtype == torch.float32 and self.inv_freq.is_contiguous()
+            inv = self.inv_freq.data_ptr()
+        return CParams(self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim, self.ctx_len, self.chunk_size,
+                       self.rank, self.n_outlier_chunks, self.topk_chunks, self.local_len, self.value_location,
+                       self.flags, float(self.rope_theta), float(self.softmax_scale), inv)
+
+    @classmethod
+    def from_workload(cls, wl, **kw) -> "Params":
+        loc = VALUES_HOST if wl.value_location == "host" else VALUES_DEVICE
+        base = dict(batch=wl.batch, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads, head_dim=wl.head_dim,
+                    ctx_len=wl.ctx_len, chunk_size=wl.chunk_size, rank=wl.rank,
+                    n_outlier_chunks=wl.n_outlier_chunks, topk_chunks=wl.topk_chunks, local_len=wl.local_len,
+                    value_location=loc, rope_theta=wl.rope_theta)
+        base.update(kw)
+        return cls(**base)
+
+
+def validate_params(p: Params, for_decode: bool = True) -> int:
+    st = p.c_struct()
+    return int(lib().shadowkv_validate_params(C.addressof(st), 1 if for_decode else 0))
+
+
+def decode_workspace_bytes(p: Params) -> int:
+    st = p.c_struct()
+    return int(lib().shadowkv_decode_workspace_bytes(C.addressof(st)))
+
+
+def build_workspace_bytes(p: Params) -> int:
+    st = p.c_struct()
+    return int(lib().shadowkv_build_workspace_bytes(C.addressof(st)))
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    assert t.is_contiguous(), "tensors must be contiguous"
+    return t.data_ptr()
+
+
+def _stream_ptr(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def alloc_workspace(nbytes: int, device="cuda") -> torch.Tensor:
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+
+
+def build_landmarks(p: Params, k_rope: torch.Tensor, v: Optional[torch.Tensor] = None,
+                    workspace: Optional[torch.Tensor] = None, stream=None) -> dict:
+    """Pre-filling algorithm after its SVD line.  Returns the new device tensors."""
+    b, h, s, d, c, o = p.batch, p.n_kv_heads, p.ctx_len, p.head_dim, p.chunk_size, p.n_outlier_chunks
+    n_c = p.n_landmarks
+    dev = k_rope.device
+    assert k_rope.dtype == torch.bfloat16 and tuple(k_rope.shape) == (b, h, s, d)
+    if v is not None:
+        assert v.dtype == torch.bfloat16 and tuple(v.shape) == (b, h, s, d)
+    bf, i32 = torch.bfloat16, torch.int32
+    out = {
+        "landmarks": torch.empty(b, h, max(n_c, 0), d, dtype=bf, device=dev),
+        "landmark_chunk_ids": torch.empty(b, h, max(n_c, 0), dtype=i32, device=dev),
+        "outlier_chunk_ids": torch.empty(b, h, o, dtype=i32, device=dev),
+        "k_outlier": torch.empty(b, h, o * c, d, dtype=bf, device=dev),
+        "v_outlier": torch.empty(b, h, o * c, d, dtype=bf, device=dev) if v is not None else None,
+    }
+    st = p.c_struct()
+    if workspace is None:
+        workspace = alloc_workspace(int(lib().shadowkv_build_workspace_bytes(C.addressof(st))), dev)
+    rc = lib().shadowkv_build_landmarks(C.addressof(st), _ptr(k_rope), _ptr(v), _ptr(out["landmarks"]),
+                                        _ptr(out["landmark_chunk_ids"]), _ptr(out["outlier_chunk_ids"]),
+                                        _ptr(out["k_outlier"]), _ptr(out["v_outlier"]), _ptr(workspace),
+                                        workspace.numel(), _stream_ptr(stream))
+    _check(rc)
+    out["workspace"] = workspace
+    return out
+
+
+def decode_step(p: Params, q, A, B, landmarks, landmark_chunk_ids, k_outlier, v_outlier, k_local, v_local,
+                value_store, pos_offset=None, out=None, out_chunk_ids=None, workspace=None, stream=None,
+                side_stream=None):
+    """One decode step.  Returns ``(out [b,h_q,d] bf16, chunk_ids [b,h_kv,k] int32, workspace)``."""
+    dev = q.device
+    if out is None:
+        out = torch.empty(p.batch, p.n_q_heads, p.head_dim, dtype=torch.bfloat16, device=dev)
+    if out_chunk_ids is None:
+        out_chunk_ids = torch.empty(p.batch, p.n_kv_heads, p.topk_chunks, dtype=torch.int32, device=dev)
+    st = p.c_struct()
+    if workspace is None:
+        workspace = alloc_workspace(int(lib().shadowkv_decode_workspace_bytes(C.addressof(st))), dev)
+    rc = lib().shadowkv_decode_step(C.addressof(st), _ptr(q), _ptr(A), _ptr(B), _ptr(landmarks),
+                                    _ptr(landmark_chunk_ids), _ptr(k_outlier), _ptr(v_outlier), _ptr(k_local),
+                                    _ptr(v_local), _ptr(value_store), _ptr(pos_offset), _ptr(out),
+                                    _ptr(out_chunk_ids), _ptr(workspace), workspace.numel(), _stream_ptr(stream),
+                                    None if side_stream is None else _stream_ptr(side_stream))
+    _check(rc)
+    return out, out_chunk_ids, workspace
+
+
+def workspace_view(p: Params, workspace: torch.Tensor, which: str) -> Optional[torch.Tensor]:
+    """Intermediate of the last decode step as a tensor aliasing ``workspace``.
+
+    ``"k_sparse"`` fp32 [b,h_kv,k*c,d]; ``"v_sparse"`` bf16 (staged runs only); ``"logits"`` fp64 [b,h_q,n_c].
+    """
+    code = {"k_sparse": 0, "v_sparse": 1, "sel_ids": 2, "logits": 3}[which]
+    st = p.c_struct()
+    ptr = lib().shadowkv_decode_workspace_view(C.addressof(st), workspace.data_ptr(), code)
+    if not ptr:
+        return None
+    off = ptr - workspace.data_ptr()
+    rows = (p.batch, p.n_kv_heads, p.topk_chunks * p.chunk_size, p.head_dim)
+    if which == "k_sparse":
+        n = rows[0] * rows[1] * rows[2] * rows[3]
+        return workspace[off:off + 4 * n].view(torch.float32).view(rows)
+    if which == "v_sparse":
+        n = rows[0] * rows[1] * rows[2] * rows[3]
+        return workspace[off:off + 2 * n].view(torch.bfloat16).view(rows)
+    if which == "sel_ids":
+        n = p.batch * p.n_kv_heads * p.topk_chunks
+        return workspace[off:off + 4 * n].view(torch.int32).view(p.batch, p.n_kv_heads, p.topk_chunks)
+    n = p.batch * p.n_q_heads * p.n_landmarks
+    return workspace[off:off + 8 * n].view(torch.float64).view(p.batch, p.n_q_heads, p.n_landmarks)

@@ -1,0 +1,103 @@
+"""Host-only checks of the C ABI: the library loads, exports every declared symbol,
+and rejects bad arguments before touching a GPU (none is needed to run these)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2410_21465_amd import shadowkv as S
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "shadowkv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(shadowkv_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = S.lib()
+    names = declared_symbols()
+    assert "shadowkv_build_landmarks" in names and "shadowkv_decode_step" in names
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in shadowkv.h but not exported"
+    assert set(S.EXPORTS) <= set(names)
+    assert S.version() >= 100
+
+
+def test_status_strings():
+    assert S.status_string(S.OK) == "ok"
+    for code in (S.EINVAL, S.EWORKSPACE, S.EHIP, -99):
+        assert S.status_string(code)
+
+
+GOOD = dict(batch=2, n_q_heads=8, n_kv_heads=2, head_dim=128, ctx_len=4096, chunk_size=8, rank=160,
+            n_outlier_chunks=4, topk_chunks=16, local_len=8)
+
+
+def test_valid_params_and_workspace_sizes():
+    p = S.Params(**GOOD)
+    assert S.validate_params(p) == S.OK and S.validate_params(p, for_decode=False) == S.OK
+    w = S.decode_workspace_bytes(p)
+    assert w > 0 and w % 256 == 0
+    bigger = S.decode_workspace_bytes(S.Params(**{**GOOD, "topk_chunks": 32}))
+    assert bigger > w
+    staged = S.decode_workspace_bytes(S.Params(**{**GOOD, "value_location": S.VALUES_HOST}))
+    assert staged >= w + 2 * 8 * 16 * 128 * 2 * 2      # units * c * k * d bf16 values
+    assert S.build_workspace_bytes(p) >= 2 * 2 * 512 * (128 * 2 + 8)
+    # the five benchmark shapes are all accepted
+    from paper_2410_21465_amd.workloads import CONFIGS
+    for wl in CONFIGS.values():
+        assert S.validate_params(S.Params.from_workload(wl)) == S.OK, wl.name
+
+
+@pytest.mark.parametrize("bad", [
+    dict(batch=0), dict(n_q_heads=9), dict(head_dim=80), dict(head_dim=127), dict(chunk_size=0), dict(chunk_size=65),
+    dict(ctx_len=4100), dict(ctx_len=0), dict(rank=12), dict(rank=0), dict(rank=264), dict(topk_chunks=0),
+    dict(topk_chunks=509), dict(n_outlier_chunks=-1), dict(n_outlier_chunks=2000), dict(local_len=-1),
+    dict(value_location=7), dict(softmax_scale=-1.0), dict(rope_theta=0.0), dict(n_q_heads=2 * 65, n_kv_heads=2),
+])
+def test_invalid_params_are_rejected(bad):
+    p = S.Params(**{**GOOD, **bad})
+    assert S.validate_params(p) == S.EINVAL
+    assert S.last_error()
+    assert S.decode_workspace_bytes(p) == 0
+
+
+def test_build_ignores_decode_only_fields():
+    p = S.Params(**{**GOOD, "rank": 12, "topk_chunks": 0})
+    assert S.validate_params(p, for_decode=False) == S.OK
+    assert S.build_workspace_bytes(p) > 0
+
+
+def test_calls_reject_null_and_bad_workspace_without_a_gpu():
+    lib = S.lib()
+    st = S.Params(**GOOD).c_struct()
+    fake = C.c_void_p(0x1000)        # never dereferenced: validation fails first
+    args = [fake] * 11               # q .. pos_offset
+    # NULL q
+    rc = lib.shadowkv_decode_step(C.addressof(st), None, *args[1:], fake, None, fake, 1 << 40, None, None)
+    assert rc == S.EINVAL
+    # misaligned tensor pointer
+    rc = lib.shadowkv_decode_step(C.addressof(st), C.c_void_p(0x1008), *args[1:], fake, None, fake, 1 << 40, None, None)
+    assert rc == S.EINVAL and "aligned" in S.last_error()
+    # NULL workspace, misaligned workspace, short workspace
+    rc = lib.shadowkv_decode_step(C.addressof(st), *args, fake, None, None, 1 << 40, None, None)
+    assert rc == S.EWORKSPACE
+    rc = lib.shadowkv_decode_step(C.addressof(st), *args, fake, None, C.c_void_p(0x1010), 1 << 40, None, None)
+    assert rc == S.EWORKSPACE
+    rc = lib.shadowkv_decode_step(C.addressof(st), *args, fake, None, fake, 1024, None, None)
+    assert rc == S.EWORKSPACE and "too small" in S.last_error()
+    # NULL params
+    rc = lib.shadowkv_decode_step(None, *args, fake, None, fake, 1 << 40, None, None)
+    assert rc == S.EINVAL
+    # build: NULL k_rope, short workspace
+    rc = lib.shadowkv_build_landmarks(C.addressof(st), None, None, fake, fake, fake, fake, None, fake, 1 << 40, None)
+    assert rc == S.EINVAL
+    rc = lib.shadowkv_build_landmarks(C.addressof(st), fake, None, fake, fake, fake, fake, None, fake, 16, None)
+    assert rc == S.EWORKSPACE
+    # missing outlier tensors with o > 0
+    rc = lib.shadowkv_decode_step(C.addressof(st), *args[:5], None, None, *args[7:], fake, None, fake, 1 << 40, None, None)
+    assert rc == S.EINVAL

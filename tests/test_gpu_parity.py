@@ -1,0 +1,98 @@
+"""HIP library vs CPU oracle, element by element, on small seeded workloads that
+still span several tiles, ragged tails and every degenerate case (-m gpu)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2410_21465_amd import shadowkv as S
+from paper_2410_21465_amd.workloads import CONFIGS, Workload
+
+import parity_util as PU
+
+pytestmark = pytest.mark.gpu
+
+
+def small(name, **kw):
+    base = dict(batch=2, n_q_heads=8, n_kv_heads=2, head_dim=128, ctx_len=4096, chunk_size=8, rank=32,
+                n_outlier_chunks=4, topk_chunks=24, local_len=5, rope_theta=5e5, seed=7, n_queries=2)
+    base.update(kw)
+    return Workload(name, **base)
+
+
+CASES = [
+    small("tiny-d64", head_dim=64, ctx_len=512, chunk_size=4, rank=16, topk_chunks=5, n_outlier_chunks=3, local_len=3),
+    small("d128-g4"),
+    small("d96-mha", n_q_heads=4, n_kv_heads=4, head_dim=96, ctx_len=2048, rank=40, topk_chunks=17,
+          n_outlier_chunks=2, rope_theta=1e4),
+    small("g16", batch=1, n_q_heads=32, n_kv_heads=2, ctx_len=8192, rank=64, topk_chunks=40),
+    small("g3-odd", batch=1, n_q_heads=6, n_kv_heads=2, head_dim=64, ctx_len=1536, chunk_size=6, rank=24,
+          topk_chunks=9, n_outlier_chunks=1, local_len=1),
+    small("no-outliers-no-local", n_outlier_chunks=0, local_len=0, ctx_len=1024, topk_chunks=7),
+    small("full-budget", ctx_len=1024, topk_chunks=124, n_outlier_chunks=4),
+    small("chunk1", batch=1, chunk_size=1, ctx_len=700, topk_chunks=33, n_outlier_chunks=0, rank=16),
+    small("multi-slice", batch=1, n_q_heads=4, n_kv_heads=1, ctx_len=8 * 5003, topk_chunks=64, n_outlier_chunks=5,
+          rank=16),
+    small("rank160-k256", batch=1, n_q_heads=8, n_kv_heads=2, ctx_len=32768, rank=160, topk_chunks=256,
+          n_outlier_chunks=48, local_len=32),
+]
+
+
+@pytest.mark.parametrize("wl", CASES, ids=[c.name for c in CASES])
+def test_build_and_decode_small(wl):
+    print(f"\n[case] {wl}", flush=True)
+    t = PU.draw(wl)
+    ref_b, _ = PU.run_build_parity(wl, t)
+    for qi in range(wl.n_queries):
+        stats, _, _ = PU.run_decode_parity(wl, t, ref_b, qi=qi)
+        print(f"[decode] {wl.name} q{qi}: {stats}", flush=True)
+
+
+def test_config1_all_in_hbm():
+    wl = CONFIGS["c1"]
+    t = PU.draw(wl)
+    ref_b, _ = PU.run_build_parity(wl, t)
+    for qi in range(4):
+        stats, _, _ = PU.run_decode_parity(wl, t, ref_b, qi=qi)
+        print(f"[decode] c1 q{qi}: {stats}", flush=True)
+
+
+def test_host_value_store_and_streams():
+    """Pinned-host value store: staged by the gather kernel on a side stream; serial and forked runs agree bit for bit."""
+    wl = small("host-values", value_location="host", ctx_len=8192, topk_chunks=48)
+    t = PU.draw(wl)
+    assert t["v"].device.type == "cpu" and t["v"].is_pinned()
+    ref_b, _ = PU.run_build_parity(wl, t)
+    s1, _, (o1, i1, _) = PU.run_decode_parity(wl, t, ref_b, side_stream=True)
+    s2, _, (o2, i2, _) = PU.run_decode_parity(wl, t, ref_b, side_stream=False)
+    assert torch.equal(o1, o2) and torch.equal(i1, i2)
+    print(f"[decode] host-values: {s1}", flush=True)
+
+
+def test_staged_hbm_matches_in_place():
+    wl = small("stage-hbm", ctx_len=8192, topk_chunks=48)
+    t = PU.draw(wl)
+    ref_b, _ = PU.run_build_parity(wl, t)
+    _, _, (o1, i1, _) = PU.run_decode_parity(wl, t, ref_b, flags=S.FLAG_STAGE_VALUES)
+    _, _, (o2, i2, _) = PU.run_decode_parity(wl, t, ref_b, flags=0)
+    assert torch.equal(o1, o2) and torch.equal(i1, i2)
+
+
+def test_positions_beyond_one_million_and_inv_freq_override():
+    wl = small("far-positions", batch=2, ctx_len=2048, topk_chunks=16)
+    t = PU.draw(wl)
+    ref_b, _ = PU.run_build_parity(wl, t)
+    pos = torch.tensor([1_048_576 + 12_345, 3_999_999], dtype=torch.int32)
+    stats, _, _ = PU.run_decode_parity(wl, t, ref_b, pos_offset=pos)
+    print(f"[decode] far positions: {stats}", flush=True)
+    inv = (1e4 ** (-2.0 * np.arange(64) / 128.0) / 8.0).astype(np.float32)   # a scaled-RoPE style table
+    stats, _, _ = PU.run_decode_parity(wl, t, ref_b, pos_offset=pos, inv_freq=inv, softmax_scale=0.11)
+    print(f"[decode] inv_freq override: {stats}", flush=True)
+
+
+def test_repeated_calls_are_deterministic():
+    wl = small("determinism")
+    t = PU.draw(wl)
+    ref_b, _ = PU.run_build_parity(wl, t)
+    _, _, (o1, i1, _) = PU.run_decode_parity(wl, t, ref_b)
+    _, _, (o2, i2, _) = PU.run_decode_parity(wl, t, ref_b)
+    assert torch.equal(o1, o2) and torch.equal(i1, i2)
