@@ -1,0 +1,174 @@
+#!/usr/bin/env python3
+"""Decode-step benchmark of libshadowkv on one MI355X.
+
+One "step" = one shadowkv_decode_step (landmark scoring, selection, key rebuild + RoPE,
+value gather, attention) for the whole batch of a synthetic workload shaped like the
+paper's; the metric is decode tokens/s = batch / step time, inputs resident before the
+timed region.  Prints ONE JSON line (see the fields below) with a `roofline` object for
+the dominant kernel (landmark scoring, HBM-bound) and a `cpu_baseline` object (the CPU
+oracle timed on this host on a bounded sample).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E bandwidth
+
+
+def algorithmic_bytes(wl) -> dict:
+    """Bytes the method itself has to move per decode step (bf16 everywhere), by consumer."""
+    d, c, r, k, o, w, G = wl.head_dim, wl.chunk_size, wl.rank, wl.topk_chunks, wl.n_outlier_chunks, wl.local_len, wl.group
+    u = wl.units
+    per = {
+        "landmarks": 2 * d * wl.n_landmarks,            # read once for all G heads of the group
+        "A_rows": 2 * r * k * c,                        # gathered rows of the left factor
+        "B": 2 * r * d,
+        "values": 2 * d * k * c,                        # selected chunks' values, read once
+        "resident_kv": 2 * 2 * d * (o * c + w),         # outlier + recent keys and values
+        "q_out": 2 * 2 * d * G,
+    }
+    tot = {n: v * u for n, v in per.items()}
+    tot["total"] = sum(tot.values())
+    return tot
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="c3-hbm", help="c1 | c2 | c3-hbm | c3-host | c4 | c5")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU time budget of the oracle leg")
+    ap.add_argument("--no-side-stream", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2410_21465_amd import shadowkv as S
+    from paper_2410_21465_amd.workloads import CONFIGS, generate
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    wl = CONFIGS[args.workload]
+    dev = "cuda"
+    t0 = time.time()
+    t = generate(wl, device=dev)
+    p = S.Params.from_workload(wl)
+    # pre-filling algorithm (after the SVD) through the library itself
+    torch.cuda.synchronize()
+    tb = time.time()
+    bl = S.build_landmarks(p, t["k_rope"], t["v"])
+    torch.cuda.synchronize()
+    build_ms_first = (time.time() - tb) * 1e3
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for _ in range(3):
+        S.build_landmarks(p, t["k_rope"], t["v"], workspace=bl["workspace"])
+    ev1.record()
+    torch.cuda.synchronize()
+    build_ms = ev0.elapsed_time(ev1) / 3
+    setup_s = time.time() - t0
+
+    ws = S.alloc_workspace(S.decode_workspace_bytes(p))
+    out = torch.empty(wl.batch, wl.n_q_heads, wl.head_dim, dtype=torch.bfloat16, device=dev)
+    ids = torch.empty(wl.batch, wl.n_kv_heads, wl.topk_chunks, dtype=torch.int32, device=dev)
+    side = None if args.no_side_stream else torch.cuda.Stream()
+    pool = t["q_pool"]
+
+    def step(i: int):
+        S.decode_step(p, pool[i % pool.shape[0]], t["A"], t["B"], bl["landmarks"], bl["landmark_chunk_ids"],
+                      bl["k_outlier"], bl["v_outlier"], t["k_local"], t["v_local"], t["v"], t["pos_offset"],
+                      out=out, out_chunk_ids=ids, workspace=ws, side_stream=side)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    S.profile_begin(args.steps)
+    t1 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    prof = S.profile_end()
+    ms_per_step = (t2 - t1) * 1e3 / args.steps
+    value = wl.batch / (ms_per_step * 1e-3)
+
+    ab = algorithmic_bytes(wl)
+    score_ms = prof["ms"]["score"]
+    score_bytes = ab["landmarks"] + ab["q_out"] // 2
+    achieved = score_bytes / (score_ms * 1e-3) / 1e9
+    traffic = None
+    pmc = os.path.join(ROOT, "profiles", f"score_kernel_{wl.name}_pmc.json")
+    if os.path.exists(pmc):
+        with open(pmc) as f:
+            traffic = json.load(f).get("hbm_bytes_per_launch")
+    res = {
+        "metric": "decode_tokens_per_s", "value": value, "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: batch {wl.batch} x context {wl.ctx_len}, {wl.n_q_heads}q/{wl.n_kv_heads}kv "
+                               f"heads, d={wl.head_dim}, c={wl.chunk_size}, r={wl.rank}, k={wl.topk_chunks}, "
+                               f"o={wl.n_outlier_chunks}, w={wl.local_len}, values in {wl.value_location}",
+                   "layers": 1, "side_stream": side is not None},
+        "roofline": {"kernel": "score_kernel (landmark scoring, P = Q L^T)", "bound": "hbm", "achieved": achieved,
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
+                     "algorithmic_bytes_per_launch": score_bytes, "avg_launch_ms": score_ms},
+        "stage_ms": prof["ms"],
+        "step_algorithmic_bytes": ab["total"],
+        "step_hbm_gbps": ab["total"] / (ms_per_step * 1e-3) / 1e9,
+        "build_landmarks_ms": build_ms,
+        "setup_s": setup_s,
+    }
+    if wl.value_location == "host":
+        res["value_gather_pcie_bytes"] = ab["values"]
+
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(wl, t, args.cpu_seconds)
+    print(json.dumps(res), flush=True)
+    return 0
+
+
+def cpu_baseline(wl, t, budget_s: float) -> dict:
+    """The CPU oracle, as it stands, on the first sequences of the same workload."""
+    import numpy as np
+    from oracle import shadowkv_oracle as O
+
+    bs = min(wl.batch, 4)
+    sub = wl.scaled(batch=bs)
+    op = O.OracleParams(bs, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ctx_len, wl.chunk_size, wl.rank,
+                        wl.n_outlier_chunks, wl.topk_chunks, wl.local_len, rope_theta=wl.rope_theta)
+
+    def bits(x):
+        return O.as_bits(x[:bs].detach().cpu())
+
+    k_rope, v = bits(t["k_rope"]), bits(t["v"])
+    bl = O.build_landmarks(op, k_rope, v)
+    del k_rope
+    a = (bits(t["A"]), bits(t["B"]), bl["landmarks"], bl["landmark_chunk_ids"], bl["k_outlier"], bl["v_outlier"],
+         bits(t["k_local"]), bits(t["v_local"]), v, t["pos_offset"][:bs].cpu().numpy())
+    pool = t["q_pool"]
+    reps, spent = 0, 0.0
+    while reps < 3 or (spent < budget_s and reps < 1000):
+        q = O.as_bits(pool[reps % pool.shape[0]][:bs].detach().cpu())
+        t0 = time.perf_counter()
+        O.decode_step(op, q, *a, diagnostics=False)
+        spent += time.perf_counter() - t0
+        reps += 1
+    return {"value": bs * reps / spent, "unit": "tokens/s", "cores": O.num_threads(), "kind": "oracle",
+            "sample": f"first {bs} of {wl.batch} sequences of {sub.name}, {reps} decode steps, {spent:.1f} s",
+            "ms_per_step": spent / reps * 1e3}
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -138,12 +138,23 @@ int shadowkv_validate_params(const shadowkv_params *params, int for_decode);
 
 /*
  * Intermediates of the last decode step inside `workspace` (for tests and profiling).
- * which: 0 = rebuilt rotated keys, fp32 [b, h_kv, k*c, d], rows in out_chunk_ids order;
- *        1 = staged values, bf16 [b, h_kv, k*c, d] (only when the gather ran);
- *        2 = group scores of every landmark slot, fp64 [b, h_kv, n_c]... not kept: returns NULL.
+ * which: 0 = rebuilt rotated keys RoPE(Gather(A, I) B), fp32 [b, h_kv, k*c, d], rows in out_chunk_ids order;
+ *        1 = staged values Gather(V_store, I), bf16 [b, h_kv, k*c, d] (NULL when the gather did not run);
+ *        2 = selected true chunk ids, int32 [b, h_kv, k];
+ *        3 = scaled landmark logits P / sqrt(d), fp64 [b, h_q, n_c].
  * Returns a pointer into `workspace`, or NULL.
  */
 void *shadowkv_decode_workspace_view(const shadowkv_params *params, void *workspace, int which);
+
+/*
+ * Per-stage timing of decode steps with HIP events recorded on the caller's stream at the
+ * stage boundaries (measurement aid, not part of the method).  Between begin and end every
+ * decode step (up to max_steps) records 5 events; end synchronises, writes the summed
+ * milliseconds of the 4 stages -- landmark scoring | selection | key rebuild (+ forked value
+ * gather) | attention (+ join) -- to stage_ms[4] and the number of recorded steps to n_steps.
+ */
+int shadowkv_profile_begin(int max_steps);
+int shadowkv_profile_end(double *stage_ms, int *n_steps);
 
 const char *shadowkv_status_string(int status); /* static string for a return code            */
 const char *shadowkv_last_error(void);          /* thread-local detail of the last failure     */

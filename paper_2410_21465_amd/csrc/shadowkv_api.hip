@@ -8,6 +8,7 @@
 #include <cstdio>
 #include <cstring>
 #include <mutex>
+#include <vector>
 
 #include "kernels.hpp"
 
@@ -173,9 +174,62 @@ int get_events(hipEvent_t* fork, hipEvent_t* join) {
   return SHADOWKV_OK;
 }
 
+// Optional per-stage timing: HIP events recorded on the caller's stream at the stage
+// boundaries of every decode step between profile_begin and profile_end.
+constexpr int kStages = 4;  // score | select | rebuild keys (+ forked gather) | attention (+ join)
+struct Profile {
+  bool on = false;
+  int max_steps = 0, n_steps = 0;
+  std::vector<hipEvent_t> ev;  // [max_steps][kStages + 1]
+} g_prof;
+
+void prof_mark(hipStream_t st, int step, int boundary) {
+  if (step >= 0) (void)hipEventRecord(g_prof.ev[(size_t)step * (kStages + 1) + boundary], st);
+}
+
 }  // namespace
 
 extern "C" {
+
+int shadowkv_profile_begin(int max_steps) {
+  std::lock_guard<std::mutex> lk(g_mu);
+  if (g_prof.on) return fail_inval("profiling is already on");
+  if (max_steps < 1 || max_steps > 100000) return fail_inval("max_steps must be in [1, 100000]");
+  g_prof.ev.assign((size_t)max_steps * (kStages + 1), nullptr);
+  for (auto& e : g_prof.ev) {
+    hipError_t err = hipEventCreate(&e);
+    if (err != hipSuccess) {
+      for (auto& d : g_prof.ev) if (d) (void)hipEventDestroy(d);
+      g_prof.ev.clear();
+      return fail_hip("hipEventCreate", err);
+    }
+  }
+  g_prof.on = true; g_prof.max_steps = max_steps; g_prof.n_steps = 0;
+  return SHADOWKV_OK;
+}
+
+int shadowkv_profile_end(double* stage_ms, int* n_steps) {
+  std::lock_guard<std::mutex> lk(g_mu);
+  if (!g_prof.on) return fail_inval("profiling is not on");
+  int rc = SHADOWKV_OK;
+  if (stage_ms) for (int i = 0; i < kStages; ++i) stage_ms[i] = 0.0;
+  for (int s = 0; s < g_prof.n_steps && rc == SHADOWKV_OK; ++s) {
+    hipEvent_t* e = &g_prof.ev[(size_t)s * (kStages + 1)];
+    hipError_t err = hipEventSynchronize(e[kStages]);
+    if (err != hipSuccess) { rc = fail_hip("hipEventSynchronize", err); break; }
+    for (int i = 0; i < kStages; ++i) {
+      float ms = 0.f;
+      err = hipEventElapsedTime(&ms, e[i], e[i + 1]);
+      if (err != hipSuccess) { rc = fail_hip("hipEventElapsedTime", err); break; }
+      if (stage_ms) stage_ms[i] += ms;
+    }
+  }
+  if (n_steps) *n_steps = g_prof.n_steps;
+  for (auto& d : g_prof.ev) if (d) (void)hipEventDestroy(d);
+  g_prof.ev.clear();
+  g_prof.on = false;
+  return rc;
+}
 
 int shadowkv_version(void) { return 100; }
 
@@ -322,9 +376,12 @@ int shadowkv_decode_step(const shadowkv_params* params, const shadowkv_bf16* q, 
     if (rc != SHADOWKV_OK) return rc;
   }
 
+  const int pstep = (g_prof.on && g_prof.n_steps < g_prof.max_steps) ? g_prof.n_steps++ : -1;
+  prof_mark(st, pstep, 0);
   // 1. P = Q L^T / sqrt(d), per-tile softmax statistics
   hipError_t e = launch_score(q, landmarks, logits, partials, sh.b, sh.hq, sh.hkv, sh.d, sh.n_c, scale, st);
   if (e != hipSuccess) return fail_hip("score", e);
+  prof_mark(st, pstep, 1);
   // 2. softmax normaliser per head, max over the group, ArgTopK -> true chunk ids
   SelectArgs a{};
   a.logits = logits; a.partials = partials; a.n_tiles = L.n_tiles; a.G = sh.G;
@@ -336,6 +393,7 @@ int shadowkv_decode_step(const shadowkv_params* params, const shadowkv_bf16* q, 
   a.out_ids = sel_ids; a.out_ids2 = out_chunk_ids;
   e = launch_select(a, L.sel, kSrcLogits, sh.units, st);
   if (e != hipSuccess) return fail_hip("select chunks", e);
+  prof_mark(st, pstep, 2);
   // 3. values of the selected chunks (side stream) while 4. keys are rebuilt and rotated
   if (sh.stage) {
     hipStream_t gs = st;
@@ -351,6 +409,7 @@ int shadowkv_decode_step(const shadowkv_params* params, const shadowkv_bf16* q, 
   e = launch_recon(A, B, sel_ids, pos_offset, k_sparse, freqs, params->inv_freq, sh.b, sh.hkv, sh.d, sh.s, sh.r, sh.c,
                    sh.k, st);
   if (e != hipSuccess) return fail_hip("reconstruct keys", e);
+  prof_mark(st, pstep, 3);
   if (fork && (e = hipStreamWaitEvent(st, ev_join, 0)) != hipSuccess) return fail_hip("hipStreamWaitEvent", e);
   // 5. attention over [outliers ; selected ; recent]
   AttnArgs t{};
@@ -364,6 +423,7 @@ int shadowkv_decode_step(const shadowkv_params* params, const shadowkv_bf16* q, 
   t.scale_log2 = (float)(scale * 1.4426950408889634074);
   e = launch_attention(t, st);
   if (e != hipSuccess) return fail_hip("attention", e);
+  prof_mark(st, pstep, 4);
   return SHADOWKV_OK;
 }
 

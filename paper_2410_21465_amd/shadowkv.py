@@ -24,7 +24,9 @@ EXPORTS = (
     "shadowkv_build_landmarks", "shadowkv_decode_step", "shadowkv_build_workspace_bytes",
     "shadowkv_decode_workspace_bytes", "shadowkv_validate_params", "shadowkv_decode_workspace_view",
     "shadowkv_status_string", "shadowkv_last_error", "shadowkv_version", "shadowkv_shutdown",
+    "shadowkv_profile_begin", "shadowkv_profile_end",
 )
+STAGES = ("score", "select", "rebuild_keys", "attention")
 
 
 class CParams(C.Structure):
@@ -74,6 +76,10 @@ def lib() -> C.CDLL:
         L.shadowkv_last_error.restype = C.c_char_p
         L.shadowkv_version.restype = i32
         L.shadowkv_shutdown.restype = None
+        L.shadowkv_profile_begin.restype = i32
+        L.shadowkv_profile_begin.argtypes = [i32]
+        L.shadowkv_profile_end.restype = i32
+        L.shadowkv_profile_end.argtypes = [vp, vp]
         _lib = L
     return _lib
 
@@ -88,6 +94,19 @@ def last_error() -> str:
 
 def version() -> int:
     return int(lib().shadowkv_version())
+
+
+def profile_begin(max_steps: int) -> None:
+    _check(lib().shadowkv_profile_begin(int(max_steps)))
+
+
+def profile_end() -> dict:
+    """Stops stage timing; returns {"steps": n, "ms": {stage: mean milliseconds per step}}."""
+    ms = (C.c_double * 4)()
+    n = C.c_int(0)
+    _check(lib().shadowkv_profile_end(ms, C.byref(n)))
+    steps = max(n.value, 1)
+    return {"steps": n.value, "ms": {name: ms[i] / steps for i, name in enumerate(STAGES)}}
 
 
 def _check(status: int) -> None:

@@ -132,7 +132,8 @@ def generate(wl: Workload, device: Optional[str] = None, want_prefill: bool = Tr
     ``k_rope [b, h_kv, s, d]`` (only if ``want_prefill``), ``v [b, h_kv, s, d]``
     (on ``value_device``; pinned host memory when the workload says "host"),
     ``k_local, v_local [b, h_kv, w, d]``, ``pos_offset [b]`` (zeros),
-    ``needle_chunks [b, h_kv, 4]`` for the needle workload.
+    ``needle_chunks [b, h_kv, 4]`` for the needle workload, ``planted_chunks
+    [b, h_kv, n_ch/100]`` for the planted-outlier workload.
     """
     if device is None:
         device = "cuda" if torch.cuda.is_available() else "cpu"
@@ -160,6 +161,9 @@ def generate(wl: Workload, device: Optional[str] = None, want_prefill: bool = Tr
     if want_prefill:
         out["k_rope"] = torch.empty(b, hkv, s, d, dtype=bf, device=dev)
     needle_dirs = None
+    n_plant = max(1, (s // c) // 100)
+    if wl.plant == "outliers" and want_prefill:
+        out["planted_chunks"] = torch.empty(b, hkv, n_plant, dtype=torch.int32, device=dev)
     if wl.plant == "needles":
         out["needle_chunks"] = torch.empty(b, hkv, 4, dtype=torch.int32, device=dev)
         needle_dirs = torch.empty(b, hkv, 4, d, dtype=torch.float32, device=dev)
@@ -200,13 +204,13 @@ def generate(wl: Workload, device: Optional[str] = None, want_prefill: bool = Tr
         if want_prefill:
             kr = rot[:, :s]
             if wl.plant == "outliers":
-                n_plant = max(1, (s // c) // 100)
                 med = kr.norm(dim=-1).median(dim=-1).values
                 for h in range(hkv):
                     ch = torch.randperm(s // c, generator=gen, device=dev)[:n_plant]
                     tok = (ch[:, None] * c + torch.arange(c, device=dev)[None, :]).reshape(-1)
                     g = torch.randn(tok.numel(), d, generator=gen, device=dev, dtype=torch.float32)
                     kr[h, tok] = g / g.norm(dim=-1, keepdim=True) * (10.0 * med[h])
+                    out["planted_chunks"][bi, h] = ch.to(torch.int32)
             out["k_rope"][bi] = kr.to(bf)
         del rot, k_pre
         # 4. values
