@@ -208,8 +208,14 @@ def generate(wl: Workload, device: Optional[str] = None, want_prefill: bool = Tr
                 for h in range(hkv):
                     ch = torch.randperm(s // c, generator=gen, device=dev)[:n_plant]
                     tok = (ch[:, None] * c + torch.arange(c, device=dev)[None, :]).reshape(-1)
-                    g = torch.randn(tok.numel(), d, generator=gen, device=dev, dtype=torch.float32)
-                    kr[h, tok] = g / g.norm(dim=-1, keepdim=True) * (10.0 * med[h])
+                    # rows alternate between +u and -u (10x the median norm) plus a little noise: the
+                    # chunk mean nearly cancels, so the minimum cosine is far below any natural chunk's
+                    u = torch.randn(n_plant, 1, d, generator=gen, device=dev, dtype=torch.float32)
+                    u = u / u.norm(dim=-1, keepdim=True) * (10.0 * med[h])
+                    sign = 1.0 - 2.0 * (torch.arange(c, device=dev) % 2).to(torch.float32)
+                    g = (u * sign[None, :, None]).reshape(-1, d)
+                    g = g + 0.05 * med[h] / math.sqrt(d) * torch.randn(tok.numel(), d, generator=gen, device=dev)
+                    kr[h, tok] = g
                     out["planted_chunks"][bi, h] = ch.to(torch.int32)
             out["k_rope"][bi] = kr.to(bf)
         del rot, k_pre
