@@ -1,120 +1,119 @@
 // Landmark scoring: P = Q L^T * scale for every landmark slot (first line of the
-// decoding algorithm), streamed once from HBM for all heads of a KV group.
+// decoding algorithm), streamed once from HBM for up to four heads of a KV group.
 //
-// The scores decide an index set that has to match an fp64 reference, so products
-// (exact in fp32 for bf16 inputs) are accumulated in fp64 -- v_fma_f64 issues at the
-// same rate as scalar fp32 FMA on this chip, and the kernel stays bound by the L read.
+// The scores decide an index set that has to match an fp64 reference to within
+// 1e-6, so the bf16 inputs are widened to fp64 and contracted on the fp64 matrix
+// pipe (v_mfma_f64_4x4x4f64: four independent 4x4x4 blocks per wave, 256 FMAs per
+// issue, no cross-lane reduction needed).  The vector ALU only unpacks and converts,
+// which leaves the kernel bound by the HBM read of L.
 //
-// Layout: 16 lanes share one landmark row (D/16 contiguous elements each), a wave
-// covers 4 rows per load and 64 rows in all, a workgroup 256 rows.  Besides the
-// logits the kernel leaves, per (head, tile), the pair (max, sum exp(p - max)) from
-// which the selection kernel forms each head's log-sum-exp.
+// Operand layout of the instruction, as measured on gfx950: input lane
+// = 16*k + 4*block + (i for A | j for B), result lane = 16*i + 4*block + j.
+// Here i = query head (4), j = landmark row inside the block (4 blocks = 16 rows),
+// k = which 16-byte piece of each 64-byte row segment the lane loads.  A wave covers
+// 64 rows (four 16-row tiles, all loads issued before the first MFMA), a workgroup 256.
+// Result lane 16*i + r holds the logit of head i, row r of the tile: it stores it
+// (16 consecutive doubles per head) and folds it into its running (max, sum exp),
+// from which the selection kernel forms each head's log-sum-exp.
 #include "kernels.hpp"
 
 namespace skv {
 
-template <int D, int GH>
+// (m, s) <- (m, s) (+) (m2, s2) for s = sum exp(p - m)
+__device__ __forceinline__ void lse_merge(double& m, double& s, double m2, double s2) {
+  if (m2 == -INFINITY) return;
+  if (m == -INFINITY) { m = m2; s = s2; return; }
+  const double e = exp(-fabs(m - m2));
+  if (m2 > m) { s = s * e + s2; m = m2; } else { s += s2 * e; }
+}
+
+template <int D>
 __global__ __launch_bounds__(256) void score_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ L,
                                                     double* __restrict__ logits, double2* __restrict__ partials,
                                                     int hq, int hkv, int G, int n_c, int n_tiles, double scale) {
-  constexpr int EPL = D / 16;
-  __shared__ double sp[4][GH][kWave];
-  __shared__ double2 wred[4][GH];
-  const int unit = blockIdx.y, tile = blockIdx.x, g0 = blockIdx.z * GH;
+  constexpr int NI = D / 32;  // 16-byte pieces per lane per row
+  __shared__ double2 wred[4][4];
+  const int unit = blockIdx.y, tile = blockIdx.x, g0 = blockIdx.z * 4;
   const int b = unit / hkv, h = unit % hkv;
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-  const int sub = lane & 15, rg = lane >> 4;
+  const int kq = lane >> 4, blk = (lane >> 2) & 3, ij = lane & 3;
   const size_t head0 = (size_t)b * hq + (size_t)h * G + g0;
 
-  double qv[GH][EPL];
+  // A operand: q of head g0 + ij, the elements this lane's k-slot meets, as fp64
+  double qa[NI][8];
+  {
+    const bool hv = g0 + ij < G;
+    const bf16_t* qp = q + (head0 + (hv ? ij : 0)) * D + 8 * kq;
 #pragma unroll
-  for (int g = 0; g < GH; ++g) {
-    float x[EPL];
-    load_bf16_row<EPL>(q + (head0 + g) * D + sub * EPL, x);
+    for (int i = 0; i < NI; ++i) {
+      float x[8];
+      load_bf16_row<8>(qp + 32 * i, x);
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) qv[g][e] = (double)x[e];
+      for (int e = 0; e < 8; ++e) qa[i][e] = hv ? (double)x[e] : 0.0;
+    }
   }
 
   const bf16_t* Lu = L + (size_t)unit * n_c * D;
   const int row0 = tile * kScoreTile + wave * kWave;
-#pragma unroll 4
-  for (int it = 0; it < 16; ++it) {
-    const int rw = it * 4 + rg;
-    const int row = row0 + rw;
-    double acc[GH];
+  uint4 w[4][NI];
 #pragma unroll
-    for (int g = 0; g < GH; ++g) acc[g] = 0.0;
-    if (row < n_c) {
-      float x[EPL];
-      load_bf16_row<EPL>(Lu + (size_t)row * D + sub * EPL, x);
+  for (int t = 0; t < 4; ++t) {
+    const int r = row0 + t * 16 + blk * 4 + ij;
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) {
-        const double xd = (double)x[e];
+    for (int i = 0; i < NI; ++i) {
+      w[t][i] = make_uint4(0u, 0u, 0u, 0u);
+      if (r < n_c) w[t][i] = *reinterpret_cast<const uint4*>(Lu + (size_t)r * D + 32 * i + 8 * kq);
+    }
+  }
+
+  const int hd = g0 + (lane >> 4);  // head of this lane's results
+  double m = -INFINITY, s = 0.0;
 #pragma unroll
-        for (int g = 0; g < GH; ++g) acc[g] = fma(xd, qv[g][e], acc[g]);
+  for (int t = 0; t < 4; ++t) {
+    double acc = 0.0;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const uint32_t u4[4] = {w[t][i].x, w[t][i].y, w[t][i].z, w[t][i].w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        acc = __builtin_amdgcn_mfma_f64_4x4x4f64(qa[i][2 * e], (double)bf16_lo(u4[e]), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f64_4x4x4f64(qa[i][2 * e + 1], (double)bf16_hi(u4[e]), acc, 0, 0, 0);
       }
     }
-#pragma unroll
-    for (int g = 0; g < GH; ++g) {
-      const double t = sum16_f64(acc[g]);
-      if (sub == g) sp[wave][g][rw] = row < n_c ? t * scale : -INFINITY;
+    const int r = row0 + t * 16 + (lane & 15);
+    if (r < n_c && hd < G) {
+      const double p = acc * scale;
+      logits[(head0 + (lane >> 4)) * n_c + r] = p;
+      lse_merge(m, s, p, 1.0);
     }
   }
-  __syncthreads();
 
-  // one lane per row from here on: coalesced logit stores, wave-wide (max, sum exp)
-  const int row = row0 + lane;
+  // (max, sum) of each head over the workgroup's 256 rows
 #pragma unroll
-  for (int g = 0; g < GH; ++g) {
-    const double p = sp[wave][g][lane];
-    if (row < n_c) logits[(head0 + g) * n_c + row] = p;
-    const double m = wave_max_f64(p);
-    const double e = (row < n_c) ? exp(p - m) : 0.0;
-    const double s = wave_sum_f64(e);
-    if (lane == 0) wred[wave][g] = make_double2(m, s);
-  }
+  for (int x = 8; x >= 1; x >>= 1) lse_merge(m, s, shfl_xor_f64(m, x), shfl_xor_f64(s, x));
+  if ((lane & 15) == 0) wred[wave][lane >> 4] = make_double2(m, s);
   __syncthreads();
-  if (threadIdx.x < GH) {
+  if (threadIdx.x < 4 && g0 + (int)threadIdx.x < G) {
     const int g = threadIdx.x;
-    double M = -INFINITY;
+    double M = -INFINITY, S = 0.0;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) M = fmax(M, wred[w][g].x);
-    double S = 0.0;
-#pragma unroll
-    for (int w = 0; w < 4; ++w)
-      if (wred[w][g].x != -INFINITY) S += wred[w][g].y * exp(wred[w][g].x - M);
+    for (int wv = 0; wv < 4; ++wv) lse_merge(M, S, wred[wv][g].x, wred[wv][g].y);
     partials[(head0 + g) * n_tiles + tile] = make_double2(M, S);
   }
 }
 
-template <int D>
-static hipError_t launch_score_d(const bf16_t* q, const bf16_t* L, double* logits, double2* partials, int batch,
-                                 int hq, int hkv, int n_c, double scale, hipStream_t st) {
-  const int G = hq / hkv;
-  const int n_tiles = (n_c + kScoreTile - 1) / kScoreTile;
-  const int gh = (G % 8 == 0) ? 8 : (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1;
-  dim3 grid(n_tiles, batch * hkv, G / gh), block(256);
-#define SKV_SCORE(GH_)                                                                                   \
-  hipLaunchKernelGGL((score_kernel<D, GH_>), grid, block, 0, st, q, L, logits, partials, hq, hkv, G, n_c, \
-                     n_tiles, scale)
-  switch (gh) {
-    case 8: SKV_SCORE(8); break;
-    case 4: SKV_SCORE(4); break;
-    case 2: SKV_SCORE(2); break;
-    default: SKV_SCORE(1); break;
-  }
-#undef SKV_SCORE
-  return hipGetLastError();
-}
-
 hipError_t launch_score(const bf16_t* q, const bf16_t* landmarks, double* logits, double2* partials, int batch,
                         int hq, int hkv, int d, int n_c, double scale, hipStream_t st) {
+  const int G = hq / hkv;
+  const int n_tiles = (n_c + kScoreTile - 1) / kScoreTile;
+  dim3 grid(n_tiles, batch * hkv, (G + 3) / 4), block(256);
   switch (d) {
-    case 64: return launch_score_d<64>(q, landmarks, logits, partials, batch, hq, hkv, n_c, scale, st);
-    case 96: return launch_score_d<96>(q, landmarks, logits, partials, batch, hq, hkv, n_c, scale, st);
-    case 128: return launch_score_d<128>(q, landmarks, logits, partials, batch, hq, hkv, n_c, scale, st);
+    case 64: hipLaunchKernelGGL((score_kernel<64>), grid, block, 0, st, q, landmarks, logits, partials, hq, hkv, G, n_c, n_tiles, scale); break;
+    case 96: hipLaunchKernelGGL((score_kernel<96>), grid, block, 0, st, q, landmarks, logits, partials, hq, hkv, G, n_c, n_tiles, scale); break;
+    case 128: hipLaunchKernelGGL((score_kernel<128>), grid, block, 0, st, q, landmarks, logits, partials, hq, hkv, G, n_c, n_tiles, scale); break;
     default: return hipErrorInvalidValue;
   }
+  return hipGetLastError();
 }
 
 }  // namespace skv
