@@ -54,7 +54,8 @@ extern "C" {
 #define SHADOWKV_VALUES_HOST 1   /* pinned host store: staged by a gather kernel   */
 
 /* flags */
-#define SHADOWKV_FLAG_STAGE_VALUES 1u /* run the chunk gather even for an HBM store */
+#define SHADOWKV_FLAG_STAGE_VALUES 1u      /* run the chunk gather even for an HBM store            */
+#define SHADOWKV_FLAG_KEEP_REBUILT_KEYS 2u /* also write RoPE(Gather(A,I) B) to the workspace (tests) */
 
 typedef uint16_t shadowkv_bf16;
 
@@ -138,7 +139,8 @@ int shadowkv_validate_params(const shadowkv_params *params, int for_decode);
 
 /*
  * Intermediates of the last decode step inside `workspace` (for tests and profiling).
- * which: 0 = rebuilt rotated keys RoPE(Gather(A, I) B), fp32 [b, h_kv, k*c, d], rows in out_chunk_ids order;
+ * which: 0 = rebuilt rotated keys RoPE(Gather(A, I) B), fp32 [b, h_kv, k*c, d], rows in out_chunk_ids order
+ *            (only with SHADOWKV_FLAG_KEEP_REBUILT_KEYS; the keys normally live in registers only);
  *        1 = staged values Gather(V_store, I), bf16 [b, h_kv, k*c, d] (NULL when the gather did not run);
  *        2 = selected true chunk ids, int32 [b, h_kv, k];
  *        3 = scaled landmark logits P / sqrt(d), fp64 [b, h_q, n_c].
@@ -150,8 +152,8 @@ void *shadowkv_decode_workspace_view(const shadowkv_params *params, void *worksp
  * Per-stage timing of decode steps with HIP events recorded on the caller's stream at the
  * stage boundaries (measurement aid, not part of the method).  Between begin and end every
  * decode step (up to max_steps) records 5 events; end synchronises, writes the summed
- * milliseconds of the 4 stages -- landmark scoring | selection | key rebuild (+ forked value
- * gather) | attention (+ join) -- to stage_ms[4] and the number of recorded steps to n_steps.
+ * milliseconds of the 4 stages -- landmark scoring | selection | staged value gather (zero when
+ * values are read in place) | attention with key rebuild -- to stage_ms[4] and the number of recorded steps to n_steps.
  */
 int shadowkv_profile_begin(int max_steps);
 int shadowkv_profile_end(double *stage_ms, int *n_steps);

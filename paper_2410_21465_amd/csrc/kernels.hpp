@@ -44,34 +44,36 @@ struct SelectPlan {
 bool plan_select(int n, int k, SelectPlan* plan);
 hipError_t launch_select(const SelectArgs& a, const SelectPlan& plan, int src, int units, hipStream_t st);
 
-// ---- key reconstruction + RoPE (K_sparse = RoPE(Gather(A, I) B)) -----------------
-// k_sparse fp32 [units, k*c, d]; sel_ids [units, k] true chunk ids.
-hipError_t launch_recon(const bf16_t* A, const bf16_t* B, const int32_t* sel_ids, const int32_t* pos_offset,
-                        float* k_sparse, const RopeFreqs& freqs, const float* inv_freq_dev, int batch, int hkv,
-                        int d, int s, int r, int c, int k, hipStream_t st);
-
 // ---- value chunk gather (V_sparse = Gather(V_store, I)) -----------------------------
 hipError_t launch_gather_values(const bf16_t* store, const int32_t* sel_ids, bf16_t* v_sparse, int units, int d,
                                 int s, int c, int k, hipStream_t st);
 
-// ---- attention over [outliers ; selected ; recent] ------------------------------------
+// ---- attention over [outliers ; recent] and [selected chunks], keys rebuilt in-kernel ----
+// K_sparse = RoPE(Gather(A, I) B) is formed per 32-row block on the matrix cores and consumed
+// from registers.  Splits 0 .. n_res_splits-1 cover the resident rows, the rest the selected rows.
 struct AttnArgs {
   const bf16_t* q;          // [b, h_q, d]
+  const bf16_t* A;          // [b, s, r]
+  const bf16_t* B;          // [units, r, d]
   const bf16_t* k_outlier;  // [units, o*c, d]
   const bf16_t* v_outlier;
-  const float* k_sparse;    // [units, k*c, d] fp32
-  const bf16_t* v_sparse;   // staged [units, k*c, d], or NULL: read the store through sel_ids
-  const bf16_t* v_store;    // [units, s, d]
-  const int32_t* sel_ids;   // [units, k]
   const bf16_t* k_local;    // [units, w, d]
   const bf16_t* v_local;
+  const bf16_t* v_sparse;   // staged [units, k*c, d], or NULL: read v_store through sel_ids
+  const bf16_t* v_store;    // [units, s, d] (HBM, or device-readable pinned host memory)
+  const int32_t* sel_ids;   // [units, k] true chunk ids
+  const int32_t* pos_offset;  // [b] or NULL
+  const float* inv_freq_dev;  // optional [d/2]
+  float* k_sparse_out;      // optional [units, k*c, d]: copy of the rebuilt keys (diagnostics)
   float* part_acc;          // [b*h_q, n_splits, d]
   float2* part_ml;          // [b*h_q, n_splits] (max in log2 units, sum)
   bf16_t* out;              // [b, h_q, d]
-  int batch, hq, hkv, d, s, c, o, k, w;
-  int split_len, n_splits;
+  int batch, hq, hkv, d, s, c, o, k, w, r, r32, rp;
+  int res_split_len, n_res_splits, sparse_split_len, n_splits;
   float scale_log2;         // softmax scale * log2(e)
+  RopeFreqs freqs;
 };
+inline int attention_heads_per_group(int G) { return (G % 8 == 0) ? 8 : (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1; }
 hipError_t launch_attention(const AttnArgs& a, hipStream_t st);
 
 // ---- pre-filling algorithm: chunk means, min cosine, compaction, outlier gather -------

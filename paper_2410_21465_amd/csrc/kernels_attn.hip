@@ -1,38 +1,105 @@
-// Softmax attention of each query head over K = [K_outlier ; RoPE(K_sparse) ; K_recent],
-// V = [V_outlier ; V_sparse ; V_recent] (last lines of the decoding algorithm and the
-// "standard attention computation for the top-k chunks and predefined outliers").
+// Sparse attention of the decode step, fused with the key rebuild:
+//   K = [K_outlier ; RoPE(Gather(A, I) B) ; K_recent],  V = [V_outlier ; Gather(V, I) ; V_recent],
+//   out_g = softmax(q_g K^T * scale) V      (last lines of the decoding algorithm and the "standard
+//   attention computation for the top-k chunks and predefined outliers").
 //
-// Split-K flash-decode: the T attended tokens of a (batch, KV head) unit are cut into
-// splits; one workgroup streams one split for up to 8 query heads of the GQA group at a
-// time, so K and V rows are read once per group rather than once per head.  16 lanes
-// share a token row (d/16 contiguous elements each); every lane keeps an online-softmax
-// state (running max in log2 units, sum, d/16 output columns) per head, merged across
-// the row groups by shuffles, across waves through LDS, and across splits by the small
-// combine kernel.  Rebuilt keys arrive as fp32 (their bf16 rounding alone would use up
-// most of the output tolerance); values of the selected chunks are read either from the
-// staging buffer or in place from the HBM value store through the chunk ids.
+// Split-K flash-decode.  The attended tokens of a (batch, KV head) unit are cut into splits; one
+// workgroup streams one split for up to 8 query heads of the GQA group, so K and V are touched
+// once per group.  Two kinds of split:
+//   * resident splits (outlier and recent tokens): K rows are read as stored (bf16);
+//   * sparse splits (selected chunks): the keys never exist in memory.  Each wave gathers 32 rows
+//     of A straight into MFMA operand layout, multiplies by B^T staged in LDS
+//     (v_mfma_f32_16x16x32_bf16, fp32 accumulate), rotates the accumulators in registers (the
+//     RoPE partner i + d/2 of a column sits in the same lane, d/32 column blocks away), and forms
+//     q.K from the same registers; a 16-lane reduction gives every lane the logit of its rows.
+// In both kinds 16 lanes share a V row (d/16 columns each) and every lane keeps an online-softmax
+// state (running max in log2 units, sum, its output columns) per head; states are merged across
+// the four row groups of a wave by shuffles, across waves through LDS, and across splits by the
+// combine kernel.  Keeping the rebuilt keys in fp32 registers matters: rounding them to bf16
+// alone would use up most of the output tolerance.
+// RoPE angle: position * frequency in fp64 revolutions, reduced to [-0.5, 0.5), then fp32
+// sin/cos of 2*pi*x -- accurate at positions beyond 2^20.
 #include "kernels.hpp"
 
 namespace skv {
 
-template <int ELEMS>
-__device__ __forceinline__ void load_f32_row(const float* __restrict__ p, float (&x)[ELEMS]) {
-  if constexpr (ELEMS == 8) {
-    const float4 a = reinterpret_cast<const float4*>(p)[0], b = reinterpret_cast<const float4*>(p)[1];
-    x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
-  } else if constexpr (ELEMS == 6) {
-    const float2 a = reinterpret_cast<const float2*>(p)[0], b = reinterpret_cast<const float2*>(p)[1],
-                 c = reinterpret_cast<const float2*>(p)[2];
-    x[0] = a.x; x[1] = a.y; x[2] = b.x; x[3] = b.y; x[4] = c.x; x[5] = c.y;
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+
+// Sum over the 16 lanes of a DPP row, result in every lane: four rotate-and-add steps, each a
+// single VALU instruction with a DPP operand (row_ror:n), no LDS traffic.
+template <int N>
+__device__ __forceinline__ float row_ror_f32(float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x120 + N, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float allsum16_f32(float v) {
+  v += row_ror_f32<8>(v);
+  v += row_ror_f32<4>(v);
+  v += row_ror_f32<2>(v);
+  v += row_ror_f32<1>(v);
+  return v;
+}
+
+// The same for GH independent values, interleaved so that no DPP operand was written by the
+// instruction just before it.
+template <int GH>
+__device__ __forceinline__ void allsum16_vec(float (&v)[GH]) {
+#pragma unroll
+  for (int g = 0; g < GH; ++g) v[g] += row_ror_f32<8>(v[g]);
+#pragma unroll
+  for (int g = 0; g < GH; ++g) v[g] += row_ror_f32<4>(v[g]);
+#pragma unroll
+  for (int g = 0; g < GH; ++g) v[g] += row_ror_f32<2>(v[g]);
+#pragma unroll
+  for (int g = 0; g < GH; ++g) v[g] += row_ror_f32<1>(v[g]);
+}
+
+template <int GH, int EPL>
+struct OnlineSoftmax {
+  float m[GH], l[GH], acc[GH][EPL];
+  __device__ __forceinline__ void init() {
+#pragma unroll
+    for (int g = 0; g < GH; ++g) {
+      m[g] = -INFINITY; l[g] = 0.f;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
+    }
+  }
+  __device__ __forceinline__ void update(int g, float logit2, const float (&vx)[EPL]) {
+    const float mn = fmaxf(m[g], logit2);
+    const float corr = __builtin_amdgcn_exp2f(m[g] - mn);
+    const float p = __builtin_amdgcn_exp2f(logit2 - mn);
+    l[g] = l[g] * corr + p;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[g][e] = fmaf(p, vx[e], acc[g][e] * corr);
+    m[g] = mn;
+  }
+};
+
+template <int EPL>
+__device__ __forceinline__ void unpack_bf16(const uint32_t (&w)[EPL / 2], float (&x)[EPL]) {
+#pragma unroll
+  for (int i = 0; i < EPL / 2; ++i) { x[2 * i] = bf16_lo(w[i]); x[2 * i + 1] = bf16_hi(w[i]); }
+}
+template <int EPL>
+__device__ __forceinline__ void load_raw(const bf16_t* __restrict__ p, uint32_t (&w)[EPL / 2]) {
+  if constexpr (EPL == 8) {
+    const uint4 v = *reinterpret_cast<const uint4*>(p);
+    w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
+  } else if constexpr (EPL == 6) {
+    const uint32_t* q = reinterpret_cast<const uint32_t*>(p);
+    w[0] = q[0]; w[1] = q[1]; w[2] = q[2];
   } else {
-    const float4 a = reinterpret_cast<const float4*>(p)[0];
-    x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
+    const uint2 v = *reinterpret_cast<const uint2*>(p);
+    w[0] = v.x; w[1] = v.y;
   }
 }
 
-template <int D, int GH>
-__global__ __launch_bounds__(256) void attn_split_kernel(AttnArgs a) {
-  constexpr int EPL = D / 16;
+// KSMAX = number of 32-wide rank steps the A prefetch buffer is sized for (5: r <= 160, 8: r <= 256)
+template <int D, int GH, int KSMAX, bool FAST4>
+__global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
+  constexpr int EPL = D / 16, NB = D / 16, HB = NB / 2;
+  extern __shared__ __align__(16) bf16_t Bt[];  // [D][rp], element (n, kk) = B[kk][n]
   __shared__ float sm_acc[4][GH][D];
   __shared__ float sm_m[4][GH], sm_l[4][GH];
   const int unit = blockIdx.y, split = blockIdx.x, g0 = blockIdx.z * GH;
@@ -40,86 +107,263 @@ __global__ __launch_bounds__(256) void attn_split_kernel(AttnArgs a) {
   const size_t head0 = (size_t)b * a.hq + (size_t)h * G + g0;
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int sub = lane & 15, rg = lane >> 4;
-  const int oc = a.o * a.c, kc = a.k * a.c, T = oc + kc + a.w;
-  const int i_begin = split * a.split_len;
-  const int i_end = min(T, i_begin + a.split_len);
+  const int oc = a.o * a.c, kc = a.k * a.c;
 
-  float qv[GH][EPL];
-#pragma unroll
-  for (int g = 0; g < GH; ++g) {
-    float x[EPL];
-    load_bf16_row<EPL>(a.q + (head0 + g) * D + sub * EPL, x);
-#pragma unroll
-    for (int e = 0; e < EPL; ++e) qv[g][e] = x[e] * a.scale_log2;
-  }
-  float m[GH], l[GH], acc[GH][EPL];
-#pragma unroll
-  for (int g = 0; g < GH; ++g) {
-    m[g] = -INFINITY; l[g] = 0.f;
-#pragma unroll
-    for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
-  }
+  OnlineSoftmax<GH, EPL> st;
+  st.init();
 
-  const int n_iter = (i_end - i_begin + 15) / 16;
-  for (int it = 0; it < n_iter; ++it) {
-    const int i = i_begin + it * 16 + wave * 4 + rg;
-    const bool ok = i < i_end;
-    float kx[EPL], vx[EPL];
-#pragma unroll
-    for (int e = 0; e < EPL; ++e) { kx[e] = 0.f; vx[e] = 0.f; }
-    if (ok) {
-      if (i < oc) {
-        const size_t row = (size_t)unit * oc + i;
-        load_bf16_row<EPL>(a.k_outlier + row * D + sub * EPL, kx);
-        load_bf16_row<EPL>(a.v_outlier + row * D + sub * EPL, vx);
-      } else if (i < oc + kc) {
-        const int j = i - oc;
-        const size_t row = (size_t)unit * kc + j;
-        load_f32_row<EPL>(a.k_sparse + row * D + sub * EPL, kx);
-        if (a.v_sparse) {
-          load_bf16_row<EPL>(a.v_sparse + row * D + sub * EPL, vx);
-        } else {
-          const int ch = j / a.c, t = j - ch * a.c;
-          const int id = min(max(a.sel_ids[(size_t)unit * a.k + ch], 0), a.s / a.c - 1);
-          const size_t tok = (size_t)id * a.c + t;
-          load_bf16_row<EPL>(a.v_store + ((size_t)unit * a.s + tok) * D + sub * EPL, vx);
-        }
-      } else {
-        const size_t row = (size_t)unit * a.w + (i - oc - kc);
-        load_bf16_row<EPL>(a.k_local + row * D + sub * EPL, kx);
-        load_bf16_row<EPL>(a.v_local + row * D + sub * EPL, vx);
-      }
-    }
+  if (split < a.n_res_splits) {
+    // ---------------- resident tokens: [outliers ; recent] ----------------
+    float qv[GH][EPL];
 #pragma unroll
     for (int g = 0; g < GH; ++g) {
-      float dot = 0.f;
+      float x[EPL];
+      load_bf16_row<EPL>(a.q + (head0 + g) * D + sub * EPL, x);
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) dot = fmaf(kx[e], qv[g][e], dot);
-      dot = sum16_f32(dot);
+      for (int e = 0; e < EPL; ++e) qv[g][e] = x[e] * a.scale_log2;
+    }
+    const int n_res = oc + a.w;
+    const int i_begin = split * a.res_split_len;
+    const int i_end = min(n_res, i_begin + a.res_split_len);
+    const int n_iter = (i_end - i_begin + 15) / 16;
+    for (int it = 0; it < n_iter; ++it) {
+      const int i = i_begin + it * 16 + wave * 4 + rg;
+      const bool ok = i < i_end;
+      float kx[EPL], vx[EPL];
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) { kx[e] = 0.f; vx[e] = 0.f; }
       if (ok) {
-        const float mn = fmaxf(m[g], dot);
-        const float corr = exp2f(m[g] - mn);
-        const float p = exp2f(dot - mn);
-        l[g] = l[g] * corr + p;
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) acc[g][e] = fmaf(p, vx[e], acc[g][e] * corr);
-        m[g] = mn;
+        const bf16_t *kp, *vp;
+        if (i < oc) {
+          kp = a.k_outlier + ((size_t)unit * oc + i) * D;
+          vp = a.v_outlier + ((size_t)unit * oc + i) * D;
+        } else {
+          kp = a.k_local + ((size_t)unit * a.w + (i - oc)) * D;
+          vp = a.v_local + ((size_t)unit * a.w + (i - oc)) * D;
+        }
+        load_bf16_row<EPL>(kp + sub * EPL, kx);
+        load_bf16_row<EPL>(vp + sub * EPL, vx);
       }
+#pragma unroll
+      for (int g = 0; g < GH; ++g) {
+        float dot = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) dot = fmaf(kx[e], qv[g][e], dot);
+        dot = allsum16_f32(dot);
+        if (ok) st.update(g, dot, vx);
+      }
+    }
+  } else {
+    // ---------------- selected chunks: rebuild keys on the matrix cores ----------------
+    const int last_chunk = a.s / a.c - 1;  // ids are clamped: a bad id can never address outside A or V
+    const int32_t* ids = a.sel_ids + (size_t)unit * a.k;
+    const int r = a.r, rp = a.rp, r32 = a.r32;
+    {  // stage B^T, zero beyond rank r
+      const bf16_t* Bu = a.B + (size_t)unit * r * D;
+      for (int idx = threadIdx.x; idx < r32 * (D / 8); idx += 256) {
+        const int kk = idx % r32, n8 = idx / r32;
+        uint4 wv = make_uint4(0u, 0u, 0u, 0u);
+        if (kk < r) wv = *reinterpret_cast<const uint4*>(Bu + (size_t)kk * D + n8 * 8);
+        const uint32_t w4[4] = {wv.x, wv.y, wv.z, wv.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          Bt[(n8 * 8 + 2 * i) * rp + kk] = (bf16_t)(w4[i] & 0xffffu);
+          Bt[(n8 * 8 + 2 * i + 1) * rp + kk] = (bf16_t)(w4[i] >> 16);
+        }
+      }
+    }
+    // q in accumulator-column layout (column nb*16 + sub), pre-scaled to log2 units
+    float qc[GH][NB];
+#pragma unroll
+    for (int g = 0; g < GH; ++g)
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) qc[g][nb] = bf16_to_f32(a.q[(head0 + g) * D + nb * 16 + sub]) * a.scale_log2;
+    double frev[HB];
+#pragma unroll
+    for (int nb = 0; nb < HB; ++nb) {
+      const int f = nb * 16 + sub;
+      frev[nb] = a.inv_freq_dev ? (double)a.inv_freq_dev[f] * 0.15915494309189533577 : a.freqs.rev[f];
+    }
+    const double pos0 = a.pos_offset ? (double)a.pos_offset[b] : 0.0;
+    __syncthreads();
+
+    const int s_begin = (split - a.n_res_splits) * a.sparse_split_len;
+    const int s_end = min(kc, s_begin + a.sparse_split_len);
+    const int ksteps = r32 / 32;
+    const bool ragged_rank = (r & 31) != 0;  // last rank step only partly backed by A
+    // FAST4 (chunk size a multiple of 4): the 4 rows a lane holds per tile are consecutive tokens,
+    // so one accurate angle per tile and frequency is stepped by one position three times.
+    float cd[HB], sd[HB];
+    if constexpr (FAST4) {
+#pragma unroll
+      for (int nb = 0; nb < HB; ++nb) {
+        double rv = frev[nb];
+        rv -= rint(rv);
+        cd[nb] = __builtin_amdgcn_cosf((float)rv);
+        sd[nb] = __builtin_amdgcn_sinf((float)rv);
+      }
+    }
+    for (int row0 = s_begin + wave * 32; row0 < s_end; row0 += 128) {
+      // -- this lane's A rows (operand layout: row = lane % 16 of each 16-row tile), all loads up front.
+      //    Rows past the end of the split are clamped onto its last row; their logits are masked below.
+      bf16x8 af[KSMAX][2];
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt) {
+        const int i = min(row0 + mt * 16 + sub, s_end - 1);
+        const int ch = i / a.c, t = i - ch * a.c;
+        const size_t n = (size_t)min(max(ids[ch], 0), last_chunk) * a.c + t;
+        const bf16_t* arow = a.A + ((size_t)b * a.s + n) * r + rg * 8;
+#pragma unroll
+        for (int ks = 0; ks < KSMAX; ++ks) {
+          uint4 wv = make_uint4(0u, 0u, 0u, 0u);
+          if (ks < ksteps && (!ragged_rank || ks * 32 + rg * 8 < r)) wv = *reinterpret_cast<const uint4*>(arow + ks * 32);
+          af[ks][mt] = *reinterpret_cast<bf16x8*>(&wv);
+        }
+      }
+      // -- rows whose logits this lane will hold (accumulator layout: rows 4*(lane/16)+j), their V slices
+      uint32_t vraw[2][4][EPL / 2];
+      int tok[2][FAST4 ? 1 : 4];
+      bool okr[2][FAST4 ? 1 : 4];
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt) {
+        if constexpr (FAST4) {
+          const int i0 = row0 + mt * 16 + rg * 4;
+          okr[mt][0] = i0 < s_end;
+          const int ic = min(i0, s_end - 4);
+          const int ch = ic / a.c, t = ic - ch * a.c;
+          const int n0 = min(max(ids[ch], 0), last_chunk) * a.c + t;
+          tok[mt][0] = n0;
+          const bf16_t* vp = (a.v_sparse ? a.v_sparse + ((size_t)unit * kc + ic) * D
+                                         : a.v_store + ((size_t)unit * a.s + n0) * D) + sub * EPL;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) load_raw<EPL>(vp + (size_t)j * D, vraw[mt][j]);
+        } else {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const int i = row0 + mt * 16 + rg * 4 + j;
+            okr[mt][j] = i < s_end;
+            const int ic = min(i, s_end - 1);
+            const int ch = ic / a.c, t = ic - ch * a.c;
+            const int n = min(max(ids[ch], 0), last_chunk) * a.c + t;
+            tok[mt][j] = n;
+            const bf16_t* vp = a.v_sparse ? a.v_sparse + ((size_t)unit * kc + ic) * D
+                                          : a.v_store + ((size_t)unit * a.s + n) * D;
+            load_raw<EPL>(vp + sub * EPL, vraw[mt][j]);
+          }
+        }
+      }
+      // -- K tile = A_sel * B on the matrix cores
+      f32x4 acc[2][NB];
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) acc[mt][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < KSMAX; ++ks) {
+        if (ks < ksteps) {
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb) {
+            const bf16x8 bfrag = *reinterpret_cast<const bf16x8*>(&Bt[(nb * 16 + sub) * rp + ks * 32 + rg * 8]);
+            acc[0][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[ks][0], bfrag, acc[0][nb], 0, 0, 0);
+            acc[1][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[ks][1], bfrag, acc[1][nb], 0, 0, 0);
+          }
+        }
+      }
+      // -- RoPE and q.K row by row (logits of the 8 rows x GH heads stay in registers) ...
+      float lg[2][4][GH];
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt) {
+        float cs[HB], sn[HB];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const bool ok = okr[mt][FAST4 ? 0 : j];
+          if (!FAST4 || j == 0) {
+            const double pos = pos0 + (double)tok[mt][FAST4 ? 0 : j];
+#pragma unroll
+            for (int nb = 0; nb < HB; ++nb) {
+              double rev = pos * frev[nb];
+              rev -= rint(rev);
+              const float rv = (float)rev;  // revolutions in [-0.5, 0.5]
+              sn[nb] = __builtin_amdgcn_sinf(rv);
+              cs[nb] = __builtin_amdgcn_cosf(rv);
+            }
+          } else {
+#pragma unroll
+            for (int nb = 0; nb < HB; ++nb) {
+              const float c1 = cs[nb] * cd[nb] - sn[nb] * sd[nb];
+              sn[nb] = sn[nb] * cd[nb] + cs[nb] * sd[nb];
+              cs[nb] = c1;
+            }
+          }
+          float kr[NB];
+#pragma unroll
+          for (int nb = 0; nb < HB; ++nb) {
+            const float x0 = acc[mt][nb][j], x1 = acc[mt][nb + HB][j];
+            kr[nb] = x0 * cs[nb] - x1 * sn[nb];
+            kr[nb + HB] = x1 * cs[nb] + x0 * sn[nb];
+          }
+          if (a.k_sparse_out && ok && g0 == 0) {
+            float* orow = a.k_sparse_out + ((size_t)unit * kc + (row0 + mt * 16 + rg * 4 + j)) * D;
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) orow[nb * 16 + sub] = kr[nb];
+          }
+          float dot[GH];
+#pragma unroll
+          for (int g = 0; g < GH; ++g) {
+            dot[g] = 0.f;
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) dot[g] = fmaf(kr[nb], qc[g][nb], dot[g]);
+          }
+          allsum16_vec<GH>(dot);
+#pragma unroll
+          for (int g = 0; g < GH; ++g) lg[mt][j][g] = ok ? dot[g] : -INFINITY;
+        }
+      }
+      // -- ... then one softmax rescale per head for the whole block
+#pragma unroll
+      for (int g = 0; g < GH; ++g) {
+        float mn = st.m[g];
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) mn = fmaxf(mn, lg[mt][j][g]);
+        if (mn == -INFINITY) continue;  // nothing valid yet in this row group
+        const float corr = __builtin_amdgcn_exp2f(st.m[g] - mn);
+        st.m[g] = mn;
+        st.l[g] *= corr;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) st.acc[g][e] *= corr;
+      }
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          float vx[EPL];
+          unpack_bf16<EPL>(vraw[mt][j], vx);
+#pragma unroll
+          for (int g = 0; g < GH; ++g) {
+            // masked rows carry -inf and contribute exp2(-inf) = 0; a still-empty state uses 0 as reference
+            const float p = __builtin_amdgcn_exp2f(lg[mt][j][g] - (st.m[g] == -INFINITY ? 0.f : st.m[g]));
+            st.l[g] += p;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) st.acc[g][e] = fmaf(p, vx[e], st.acc[g][e]);
+          }
+        }
     }
   }
 
-  // merge the four row groups of the wave
+  // ---------------- merge: row groups of the wave, waves of the workgroup ----------------
 #pragma unroll
   for (int g = 0; g < GH; ++g) {
-    float mt = fmaxf(m[g], __shfl_xor(m[g], 16, kWave));
+    float mt = fmaxf(st.m[g], __shfl_xor(st.m[g], 16, kWave));
     mt = fmaxf(mt, __shfl_xor(mt, 32, kWave));
-    const float sc = (m[g] == -INFINITY) ? 0.f : exp2f(m[g] - mt);
-    float lv = l[g] * sc;
+    const float sc = (st.m[g] == -INFINITY) ? 0.f : exp2f(st.m[g] - mt);
+    float lv = st.l[g] * sc;
     lv += __shfl_xor(lv, 16, kWave);
     lv += __shfl_xor(lv, 32, kWave);
 #pragma unroll
     for (int e = 0; e < EPL; ++e) {
-      float v = acc[g][e] * sc;
+      float v = st.acc[g][e] * sc;
       v += __shfl_xor(v, 16, kWave);
       v += __shfl_xor(v, 32, kWave);
       if (rg == 0) sm_acc[wave][g][sub * EPL + e] = v;
@@ -127,7 +371,6 @@ __global__ __launch_bounds__(256) void attn_split_kernel(AttnArgs a) {
     if (lane == 0) { sm_m[wave][g] = mt; sm_l[wave][g] = lv; }
   }
   __syncthreads();
-  // merge the four waves and write this split's partial state
   for (int idx = threadIdx.x; idx < GH * D; idx += 256) {
     const int g = idx / D, e = idx - g * D;
     float M = -INFINITY;
@@ -157,25 +400,45 @@ __global__ __launch_bounds__(D) void attn_combine_kernel(const float* __restrict
   for (int sp = 0; sp < n_splits; ++sp) M = fmaxf(M, ml[sp].x);
   float num = 0.f, den = 0.f;
   for (int sp = 0; sp < n_splits; ++sp) {
-    const float sc = exp2f(ml[sp].x - M);
+    const float sc = (ml[sp].x == -INFINITY) ? 0.f : exp2f(ml[sp].x - M);
     num = fmaf(part_acc[(head * n_splits + sp) * D + e], sc, num);
     den = fmaf(ml[sp].y, sc, den);
   }
   out[head * D + e] = f32_to_bf16(num / den);
 }
 
+template <int D, int GH, int KSMAX, bool FAST4>
+static hipError_t launch_sparse(const AttnArgs& a, dim3 grid, size_t lds, hipStream_t st) {
+  if (lds > 48 * 1024) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sparse_attn_kernel<D, GH, KSMAX, FAST4>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL((sparse_attn_kernel<D, GH, KSMAX, FAST4>), grid, dim3(256), lds, st, a);
+  return hipGetLastError();
+}
+
+template <int D, int GH>
+static hipError_t launch_sparse_ks(const AttnArgs& a, dim3 grid, size_t lds, hipStream_t st) {
+  const bool fast4 = a.c % 4 == 0;
+  if (a.r32 <= 160)
+    return fast4 ? launch_sparse<D, GH, 5, true>(a, grid, lds, st) : launch_sparse<D, GH, 5, false>(a, grid, lds, st);
+  return fast4 ? launch_sparse<D, GH, 8, true>(a, grid, lds, st) : launch_sparse<D, GH, 8, false>(a, grid, lds, st);
+}
+
 template <int D>
 static hipError_t launch_attention_d(const AttnArgs& a, hipStream_t st) {
   const int G = a.hq / a.hkv;
-  const int gh = (G % 8 == 0) ? 8 : (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1;
-  dim3 grid(a.n_splits, a.batch * a.hkv, G / gh), block(256);
+  const int gh = attention_heads_per_group(G);
+  const size_t lds = (size_t)D * a.rp * sizeof(bf16_t);
+  dim3 grid(a.n_splits, a.batch * a.hkv, G / gh);
+  hipError_t e;
   switch (gh) {
-    case 8: hipLaunchKernelGGL((attn_split_kernel<D, 8>), grid, block, 0, st, a); break;
-    case 4: hipLaunchKernelGGL((attn_split_kernel<D, 4>), grid, block, 0, st, a); break;
-    case 2: hipLaunchKernelGGL((attn_split_kernel<D, 2>), grid, block, 0, st, a); break;
-    default: hipLaunchKernelGGL((attn_split_kernel<D, 1>), grid, block, 0, st, a); break;
+    case 8: e = launch_sparse_ks<D, 8>(a, grid, lds, st); break;
+    case 4: e = launch_sparse_ks<D, 4>(a, grid, lds, st); break;
+    case 2: e = launch_sparse_ks<D, 2>(a, grid, lds, st); break;
+    default: e = launch_sparse_ks<D, 1>(a, grid, lds, st); break;
   }
-  hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((attn_combine_kernel<D>), dim3(a.batch * a.hq), dim3(D), 0, st, a.part_acc, a.part_ml, a.out,
                      a.n_splits);

@@ -6,6 +6,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <vector>
@@ -44,7 +45,7 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 struct Shape {
   int b, hq, hkv, G, d, s, c, r, o, k, w, n_ch, n_c, units;
-  bool stage;
+  bool stage, keep_keys;
 };
 
 // Shape rules shared by both entry points.  Returns SHADOWKV_OK or EINVAL with a reason.
@@ -71,6 +72,7 @@ int check_params(const shadowkv_params* p, bool decode, Shape* sh) {
   sh->n_ch = (int)n_ch; sh->n_c = (int)n_ch - sh->o; sh->units = (int)units;
   sh->r = p->rank; sh->k = p->topk_chunks; sh->w = p->local_len;
   sh->stage = p->value_location == SHADOWKV_VALUES_HOST || (p->flags & SHADOWKV_FLAG_STAGE_VALUES);
+  sh->keep_keys = (p->flags & SHADOWKV_FLAG_KEEP_REBUILT_KEYS) != 0;
   if (!decode) return SHADOWKV_OK;
   if (p->rank < 8 || p->rank > 256 || p->rank % 8) return fail_inval("rank must be a multiple of 8 in [8, 256]");
   if (p->local_len < 0) return fail_inval("local_len must be >= 0");
@@ -87,19 +89,33 @@ int check_params(const shadowkv_params* p, bool decode, Shape* sh) {
   return SHADOWKV_OK;
 }
 
+// Split plan of the attention kernel: resident rows (outliers + recent tokens) and selected rows
+// are cut separately; a sparse split is a multiple of 32 rows (one MFMA row block of one wave).
 struct AttnPlan {
-  int split_len, n_splits;
+  int res_split_len, n_res_splits, sparse_split_len, n_sparse_splits, n_splits;
 };
 AttnPlan plan_attention(const Shape& sh) {
-  const int gh = (sh.G % 8 == 0) ? 8 : (sh.G % 4 == 0) ? 4 : (sh.G % 2 == 0) ? 2 : 1;
-  const long T = (long)sh.o * sh.c + (long)sh.k * sh.c + sh.w;
-  long want = T * sh.units * (sh.G / gh) / 2048;
-  want = (want + 15) / 16 * 16;
-  if (want < 32) want = 32;
-  if (want > 256) want = 256;
+  const long z = sh.G / attention_heads_per_group(sh.G);
+  const long groups = (long)sh.units * z;
+  const long kc = (long)sh.k * sh.c, n_res = (long)sh.o * sh.c + sh.w;
   AttnPlan ap;
-  ap.split_len = (int)want;
-  ap.n_splits = (int)((T + want - 1) / want);
+  // selected rows: aim at >= 2048 workgroups with 128..512 rows each; shrink below 128 only to reach 512
+  long len = 128;
+  for (long cand : {512l, 256l}) if (kc * groups / cand >= 2048) { len = cand; break; }
+  if (kc * groups / 128 < 512) {
+    len = 32;
+    for (long cand : {64l}) if (kc * groups / cand >= 512) len = cand;
+  }
+  if (const char* ov = std::getenv("SHADOWKV_SPARSE_SPLIT")) {  // tuning override: rows per sparse split
+    const long v = std::atol(ov);
+    if (v >= 32 && v <= 4096 && v % 32 == 0) len = v;
+  }
+  ap.sparse_split_len = (int)len;
+  ap.n_sparse_splits = (int)((kc + len - 1) / len);
+  long rl = (n_res * groups / 128 >= 512) ? 128 : 32;
+  ap.res_split_len = (int)rl;
+  ap.n_res_splits = (int)((n_res + rl - 1) / rl);
+  ap.n_splits = ap.n_res_splits + ap.n_sparse_splits;
   return ap;
 }
 
@@ -121,7 +137,7 @@ DecodeLayout decode_layout(const Shape& sh) {
   L.cand_key = off; off += up((size_t)sh.units * L.sel.cand_stride * sizeof(uint64_t));
   L.cand_idx = off; off += up((size_t)sh.units * L.sel.cand_stride * sizeof(int32_t));
   L.sel_ids = off; off += up((size_t)sh.units * sh.k * sizeof(int32_t));
-  L.k_sparse = off; off += up(rows * sh.d * sizeof(float));
+  L.k_sparse = off; off += sh.keep_keys ? up(rows * sh.d * sizeof(float)) : 0;
   L.v_sparse = off; off += sh.stage ? up(rows * sh.d * sizeof(bf16_t)) : 0;
   L.part_acc = off; off += up(heads * L.attn.n_splits * sh.d * sizeof(float));
   L.part_ml = off; off += up(heads * L.attn.n_splits * sizeof(float2));
@@ -176,7 +192,7 @@ int get_events(hipEvent_t* fork, hipEvent_t* join) {
 
 // Optional per-stage timing: HIP events recorded on the caller's stream at the stage
 // boundaries of every decode step between profile_begin and profile_end.
-constexpr int kStages = 4;  // score | select | rebuild keys (+ forked gather) | attention (+ join)
+constexpr int kStages = 4;  // score | select | staged value gather (+ join) | attention with key rebuild
 struct Profile {
   bool on = false;
   int max_steps = 0, n_steps = 0;
@@ -281,7 +297,7 @@ void* shadowkv_decode_workspace_view(const shadowkv_params* params, void* worksp
   const DecodeLayout L = decode_layout(sh);
   char* ws = static_cast<char*>(workspace);
   switch (which) {
-    case 0: return ws + L.k_sparse;
+    case 0: return sh.keep_keys ? ws + L.k_sparse : nullptr;
     case 1: return sh.stage ? ws + L.v_sparse : nullptr;
     case 2: return ws + L.sel_ids;
     case 3: return ws + L.logits;
@@ -360,7 +376,6 @@ int shadowkv_decode_step(const shadowkv_params* params, const shadowkv_bf16* q, 
   double* logits = reinterpret_cast<double*>(ws + L.logits);
   double2* partials = reinterpret_cast<double2*>(ws + L.partials);
   int32_t* sel_ids = reinterpret_cast<int32_t*>(ws + L.sel_ids);
-  float* k_sparse = reinterpret_cast<float*>(ws + L.k_sparse);
   bf16_t* v_sparse = sh.stage ? reinterpret_cast<bf16_t*>(ws + L.v_sparse) : nullptr;
   const double scale = params->softmax_scale != 0.0 ? params->softmax_scale : 1.0 / std::sqrt((double)sh.d);
 
@@ -394,7 +409,7 @@ int shadowkv_decode_step(const shadowkv_params* params, const shadowkv_bf16* q, 
   e = launch_select(a, L.sel, kSrcLogits, sh.units, st);
   if (e != hipSuccess) return fail_hip("select chunks", e);
   prof_mark(st, pstep, 2);
-  // 3. values of the selected chunks (side stream) while 4. keys are rebuilt and rotated
+  // 3. values of the selected chunks: staged by the gather kernel (side stream when given) ...
   if (sh.stage) {
     hipStream_t gs = st;
     if (fork) {
@@ -404,23 +419,27 @@ int shadowkv_decode_step(const shadowkv_params* params, const shadowkv_bf16* q, 
     }
     e = launch_gather_values(value_store, sel_ids, v_sparse, sh.units, sh.d, sh.s, sh.c, sh.k, gs);
     if (e != hipSuccess) return fail_hip("gather values", e);
-    if (fork && (e = hipEventRecord(ev_join, side)) != hipSuccess) return fail_hip("hipEventRecord", e);
+    if (fork) {
+      if ((e = hipEventRecord(ev_join, side)) != hipSuccess) return fail_hip("hipEventRecord", e);
+      if ((e = hipStreamWaitEvent(st, ev_join, 0)) != hipSuccess) return fail_hip("hipStreamWaitEvent", e);
+    }
   }
-  e = launch_recon(A, B, sel_ids, pos_offset, k_sparse, freqs, params->inv_freq, sh.b, sh.hkv, sh.d, sh.s, sh.r, sh.c,
-                   sh.k, st);
-  if (e != hipSuccess) return fail_hip("reconstruct keys", e);
   prof_mark(st, pstep, 3);
-  if (fork && (e = hipStreamWaitEvent(st, ev_join, 0)) != hipSuccess) return fail_hip("hipStreamWaitEvent", e);
-  // 5. attention over [outliers ; selected ; recent]
+  // 4. ... then keys rebuilt and rotated inside the attention over [outliers ; selected ; recent]
   AttnArgs t{};
-  t.q = q; t.k_outlier = k_outlier; t.v_outlier = v_outlier; t.k_sparse = k_sparse; t.v_sparse = v_sparse;
-  t.v_store = value_store; t.sel_ids = sel_ids; t.k_local = k_local; t.v_local = v_local;
+  t.q = q; t.A = A; t.B = B; t.k_outlier = k_outlier; t.v_outlier = v_outlier;
+  t.k_local = k_local; t.v_local = v_local; t.v_sparse = v_sparse; t.v_store = value_store;
+  t.sel_ids = sel_ids; t.pos_offset = pos_offset; t.inv_freq_dev = params->inv_freq;
+  t.k_sparse_out = sh.keep_keys ? reinterpret_cast<float*>(ws + L.k_sparse) : nullptr;
   t.part_acc = reinterpret_cast<float*>(ws + L.part_acc);
   t.part_ml = reinterpret_cast<float2*>(ws + L.part_ml);
   t.out = out;
   t.batch = sh.b; t.hq = sh.hq; t.hkv = sh.hkv; t.d = sh.d; t.s = sh.s; t.c = sh.c; t.o = sh.o; t.k = sh.k; t.w = sh.w;
-  t.split_len = L.attn.split_len; t.n_splits = L.attn.n_splits;
+  t.r = sh.r; t.r32 = (sh.r + 31) / 32 * 32; t.rp = t.r32 + 8;  // +8: 16-byte multiple that spreads LDS banks
+  t.res_split_len = L.attn.res_split_len; t.n_res_splits = L.attn.n_res_splits;
+  t.sparse_split_len = L.attn.sparse_split_len; t.n_splits = L.attn.n_splits;
   t.scale_log2 = (float)(scale * 1.4426950408889634074);
+  t.freqs = freqs;
   e = launch_attention(t, st);
   if (e != hipSuccess) return fail_hip("attention", e);
   prof_mark(st, pstep, 4);

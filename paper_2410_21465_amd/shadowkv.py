@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libshadowkv.so")
 OK, EINVAL, EWORKSPACE, EHIP = 0, -1, -2, -3
 VALUES_DEVICE, VALUES_HOST = 0, 1
 FLAG_STAGE_VALUES = 1
+FLAG_KEEP_REBUILT_KEYS = 2
 
 EXPORTS = (
     "shadowkv_build_landmarks", "shadowkv_decode_step", "shadowkv_build_workspace_bytes",
@@ -26,7 +27,7 @@ EXPORTS = (
     "shadowkv_status_string", "shadowkv_last_error", "shadowkv_version", "shadowkv_shutdown",
     "shadowkv_profile_begin", "shadowkv_profile_end",
 )
-STAGES = ("score", "select", "rebuild_keys", "attention")
+STAGES = ("score", "select", "gather_values", "attention")
 
 
 class CParams(C.Structure):

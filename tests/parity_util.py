@@ -97,7 +97,8 @@ def run_build_parity(wl: Workload, t: dict, device="cuda"):
 
 
 def run_decode_parity(wl: Workload, t: dict, ref_build: dict, qi: int = 0, side_stream: bool = True, flags: int = 0,
-                      inv_freq=None, softmax_scale: float = 0.0, pos_offset=None, device="cuda"):
+                      inv_freq=None, softmax_scale: float = 0.0, pos_offset=None, device="cuda",
+                      check_keys: bool = True):
     """shadowkv_decode_step against the oracle, both fed the ORACLE's landmarks and outliers."""
     b, hq, h, d, c, k = wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.chunk_size, wl.topk_chunks
     units = b * h
@@ -111,7 +112,8 @@ def run_decode_parity(wl: Workload, t: dict, ref_build: dict, qi: int = 0, side_
     def dev_bf16(bits):
         return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(device)
 
-    gp = S.Params.from_workload(wl, flags=flags, softmax_scale=softmax_scale,
+    gp = S.Params.from_workload(wl, flags=flags | (S.FLAG_KEEP_REBUILT_KEYS if check_keys else 0),
+                                softmax_scale=softmax_scale,
                                 inv_freq=None if inv_freq is None else torch.from_numpy(inv_freq).to(device))
     lm = dev_bf16(ref_build["landmarks"])
     lm_ids = torch.from_numpy(ref_build["landmark_chunk_ids"]).to(device)
@@ -136,11 +138,13 @@ def run_decode_parity(wl: Workload, t: dict, ref_build: dict, qi: int = 0, side_
     ties = check_index_sets(g_ids, w_ids, score, "top-k chunks")
 
     # --- rebuilt keys (fp32 workspace) against the oracle's, matched through the chunk ids ---
-    ks = S.workspace_view(gp, ws, "k_sparse").cpu().numpy().reshape(units, k, c, d).astype(np.float64)
     ks_ref = ref["k_sparse"].reshape(units, k, c, d)
     kmax = np.abs(ks_ref).max()
     worst_k = 0.0
-    for u in range(units):
+    ks = None
+    if check_keys:
+        ks = S.workspace_view(gp, ws, "k_sparse").cpu().numpy().reshape(units, k, c, d).astype(np.float64)
+    for u in range(units if check_keys else 0):
         order = np.argsort(w_ids[u])
         common = np.isin(w_ids[u][order], g_ids[u])
         gsel = np.isin(g_ids[u], w_ids[u])

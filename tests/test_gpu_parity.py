@@ -43,7 +43,8 @@ def test_build_and_decode_small(wl):
     t = PU.draw(wl)
     ref_b, _ = PU.run_build_parity(wl, t)
     for qi in range(wl.n_queries):
-        stats, _, _ = PU.run_decode_parity(wl, t, ref_b, qi=qi)
+        # query 0 also checks the rebuilt keys (diagnostic copy); query 1 runs the production path
+        stats, _, _ = PU.run_decode_parity(wl, t, ref_b, qi=qi, check_keys=(qi == 0))
         print(f"[decode] {wl.name} q{qi}: {stats}", flush=True)
 
 
