@@ -158,6 +158,7 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
     const int last_chunk = a.s / a.c - 1;  // ids are clamped: a bad id can never address outside A or V
     const int32_t* ids = a.sel_ids + (size_t)unit * a.k;
     const int r = a.r, rp = a.rp, r32 = a.r32;
+#ifndef SKV_X_NOSTAGE
     {  // stage B^T, zero beyond rank r
       const bf16_t* Bu = a.B + (size_t)unit * r * D;
       for (int idx = threadIdx.x; idx < r32 * (D / 8); idx += 256) {
@@ -172,6 +173,7 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
         }
       }
     }
+#endif
     // q in accumulator-column layout (column nb*16 + sub), pre-scaled to log2 units
     float qc[GH][NB];
 #pragma unroll
@@ -216,7 +218,11 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
 #pragma unroll
         for (int ks = 0; ks < KSMAX; ++ks) {
           uint4 wv = make_uint4(0u, 0u, 0u, 0u);
+#ifdef SKV_X_NOA
+          wv = make_uint4(0x3f803f80u + (uint32_t)(uintptr_t)arow, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);
+#else
           if (ks < ksteps && (!ragged_rank || ks * 32 + rg * 8 < r)) wv = *reinterpret_cast<const uint4*>(arow + ks * 32);
+#endif
           af[ks][mt] = *reinterpret_cast<bf16x8*>(&wv);
         }
       }
@@ -236,7 +242,11 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
           const bf16_t* vp = (a.v_sparse ? a.v_sparse + ((size_t)unit * kc + ic) * D
                                          : a.v_store + ((size_t)unit * a.s + n0) * D) + sub * EPL;
 #pragma unroll
+#ifdef SKV_X_NOV
+          for (int j = 0; j < 4; ++j) for (int e = 0; e < EPL / 2; ++e) vraw[mt][j][e] = 0x3f803f80u + (uint32_t)(uintptr_t)vp;
+#else
           for (int j = 0; j < 4; ++j) load_raw<EPL>(vp + (size_t)j * D, vraw[mt][j]);
+#endif
         } else {
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
@@ -258,6 +268,9 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
       for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) acc[mt][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#ifdef SKV_X_NOMFMA
+      for (int ks = 0; ks < KSMAX; ++ks) for (int mt = 0; mt < 2; ++mt) { uint4 w = *reinterpret_cast<uint4*>(&af[ks][mt]); acc[mt][ks][0] += __uint_as_float(w.x ^ w.y ^ w.z ^ w.w); }
+#else
 #pragma unroll
       for (int ks = 0; ks < KSMAX; ++ks) {
         if (ks < ksteps) {
@@ -269,6 +282,16 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
           }
         }
       }
+#endif
+#ifdef SKV_X_NOEPI
+      {
+        float t = 0.f;
+        for (int mt = 0; mt < 2; ++mt) for (int nb = 0; nb < NB; ++nb) for (int j = 0; j < 4; ++j) t += acc[mt][nb][j];
+        for (int mt = 0; mt < 2; ++mt) for (int j = 0; j < 4; ++j) for (int e = 0; e < EPL / 2; ++e) t += __uint_as_float(vraw[mt][j][e]);
+        st.l[0] += t; st.m[0] = 0.f;
+        continue;
+      }
+#endif
       // -- RoPE and q.K row by row (logits of the 8 rows x GH heads stay in registers) ...
       float lg[2][4][GH];
 #pragma unroll

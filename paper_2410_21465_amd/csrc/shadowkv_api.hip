@@ -99,13 +99,9 @@ AttnPlan plan_attention(const Shape& sh) {
   const long groups = (long)sh.units * z;
   const long kc = (long)sh.k * sh.c, n_res = (long)sh.o * sh.c + sh.w;
   AttnPlan ap;
-  // selected rows: aim at >= 2048 workgroups with 128..512 rows each; shrink below 128 only to reach 512
-  long len = 128;
-  for (long cand : {512l, 256l}) if (kc * groups / cand >= 2048) { len = cand; break; }
-  if (kc * groups / 128 < 512) {
-    len = 32;
-    for (long cand : {64l}) if (kc * groups / cand >= 512) len = cand;
-  }
+  // selected rows: the largest split (fewest B^T stagings) that still gives >= 512 workgroups
+  long len = 32;
+  for (long cand : {512l, 256l, 128l, 64l}) if (kc * groups / cand >= 512) { len = cand; break; }
   if (const char* ov = std::getenv("SHADOWKV_SPARSE_SPLIT")) {  // tuning override: rows per sparse split
     const long v = std::atol(ov);
     if (v >= 32 && v <= 4096 && v % 32 == 0) len = v;
@@ -113,6 +109,10 @@ AttnPlan plan_attention(const Shape& sh) {
   ap.sparse_split_len = (int)len;
   ap.n_sparse_splits = (int)((kc + len - 1) / len);
   long rl = (n_res * groups / 128 >= 512) ? 128 : 32;
+  if (const char* ov = std::getenv("SHADOWKV_RES_SPLIT")) {  // tuning override: rows per resident split
+    const long v = std::atol(ov);
+    if (v >= 16 && v <= 4096 && v % 16 == 0) rl = v;
+  }
   ap.res_split_len = (int)rl;
   ap.n_res_splits = (int)((n_res + rl - 1) / rl);
   ap.n_splits = ap.n_res_splits + ap.n_sparse_splits;

@@ -14,7 +14,7 @@ from typing import Optional
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libshadowkv.so")
+LIB_PATH = os.environ.get("SHADOWKV_LIB", os.path.join(_HERE, "libshadowkv.so"))
 
 OK, EINVAL, EWORKSPACE, EHIP = 0, -1, -2, -3
 VALUES_DEVICE, VALUES_HOST = 0, 1
