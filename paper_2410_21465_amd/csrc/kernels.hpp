@@ -50,7 +50,8 @@ hipError_t launch_gather_values(const bf16_t* store, const int32_t* sel_ids, bf1
 
 // ---- attention over [outliers ; recent] and [selected chunks], keys rebuilt in-kernel ----
 // K_sparse = RoPE(Gather(A, I) B) is formed per 32-row block on the matrix cores and consumed
-// from registers.  Splits 0 .. n_res_splits-1 cover the resident rows, the rest the selected rows.
+// from registers.  Split i covers selected rows [i*sparse_split_len, ...) and resident rows
+// [i*res_split_len, ...); a combine kernel merges the splits into `out`.
 struct AttnArgs {
   const bf16_t* q;          // [b, h_q, d]
   const bf16_t* A;          // [b, s, r]
@@ -69,7 +70,7 @@ struct AttnArgs {
   float2* part_ml;          // [b*h_q, n_splits] (max in log2 units, sum)
   bf16_t* out;              // [b, h_q, d]
   int batch, hq, hkv, d, s, c, o, k, w, r, r32, rp;
-  int res_split_len, n_res_splits, sparse_split_len, n_splits;
+  int res_split_len, sparse_split_len, n_splits;
   float scale_log2;         // softmax scale * log2(e)
   RopeFreqs freqs;
 };

@@ -3,22 +3,24 @@
 //   out_g = softmax(q_g K^T * scale) V      (last lines of the decoding algorithm and the "standard
 //   attention computation for the top-k chunks and predefined outliers").
 //
-// Split-K flash-decode.  The attended tokens of a (batch, KV head) unit are cut into splits; one
-// workgroup streams one split for up to 8 query heads of the GQA group, so K and V are touched
-// once per group.  Two kinds of split:
-//   * resident splits (outlier and recent tokens): K rows are read as stored (bf16);
-//   * sparse splits (selected chunks): the keys never exist in memory.  Each wave gathers 32 rows
-//     of A straight into MFMA operand layout, multiplies by B^T staged in LDS
-//     (v_mfma_f32_16x16x32_bf16, fp32 accumulate), rotates the accumulators in registers (the
-//     RoPE partner i + d/2 of a column sits in the same lane, d/32 column blocks away), and forms
-//     q.K from the same registers; a 16-lane reduction gives every lane the logit of its rows.
-// In both kinds 16 lanes share a V row (d/16 columns each) and every lane keeps an online-softmax
-// state (running max in log2 units, sum, its output columns) per head; states are merged across
-// the four row groups of a wave by shuffles, across waves through LDS, and across splits by the
-// combine kernel.  Keeping the rebuilt keys in fp32 registers matters: rounding them to bf16
-// alone would use up most of the output tolerance.
-// RoPE angle: position * frequency in fp64 revolutions, reduced to [-0.5, 0.5), then fp32
-// sin/cos of 2*pi*x -- accurate at positions beyond 2^20.
+// Split-K flash-decode.  The selected tokens of a (batch, KV head) unit are cut into splits; one
+// workgroup owns one split plus an equal share of the unit's resident tokens (outliers, recent),
+// for up to 8 query heads of the GQA group, so K and V are touched once per group.
+//   * resident rows: K rows are read as stored (bf16);
+//   * selected rows: the keys never exist in memory.  Each wave gathers 32 rows of A straight
+//     into MFMA operand layout, multiplies by B^T staged in LDS (v_mfma_f32_16x16x32_bf16, fp32
+//     accumulate), rotates the accumulators in registers (the RoPE partner i + d/2 of a column
+//     sits in the same lane, d/32 column blocks away), and forms q.K from the same registers; a
+//     16-lane DPP reduction gives every lane the logits of its rows.
+// 16 lanes share a V row (d/16 columns each) and every lane keeps an online-softmax state
+// (running max in log2 units, sum, its output columns) per head; states are merged across the
+// four row groups of a wave by shuffles, across waves through LDS, across splits by the small
+// combine kernel.  Keeping the rebuilt keys in fp32
+// registers matters: rounding them to bf16 alone would use up most of the output tolerance.
+// RoPE angle: position * frequency in fp64 revolutions, reduced to [-0.5, 0.5], then the
+// hardware sin/cos of 2*pi*x -- accurate at positions beyond 2^20.  When the chunk size is a
+// multiple of 4 the four rows a lane holds per tile are consecutive tokens: one such angle per
+// tile and frequency is stepped by one position three times.
 #include "kernels.hpp"
 
 namespace skv {
@@ -32,16 +34,7 @@ template <int N>
 __device__ __forceinline__ float row_ror_f32(float x) {
   return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x120 + N, 0xf, 0xf, false));
 }
-__device__ __forceinline__ float allsum16_f32(float v) {
-  v += row_ror_f32<8>(v);
-  v += row_ror_f32<4>(v);
-  v += row_ror_f32<2>(v);
-  v += row_ror_f32<1>(v);
-  return v;
-}
-
-// The same for GH independent values, interleaved so that no DPP operand was written by the
-// instruction just before it.
+// GH independent sums, interleaved so that no DPP operand was written by the instruction just before it.
 template <int GH>
 __device__ __forceinline__ void allsum16_vec(float (&v)[GH]) {
 #pragma unroll
@@ -53,28 +46,6 @@ __device__ __forceinline__ void allsum16_vec(float (&v)[GH]) {
 #pragma unroll
   for (int g = 0; g < GH; ++g) v[g] += row_ror_f32<1>(v[g]);
 }
-
-template <int GH, int EPL>
-struct OnlineSoftmax {
-  float m[GH], l[GH], acc[GH][EPL];
-  __device__ __forceinline__ void init() {
-#pragma unroll
-    for (int g = 0; g < GH; ++g) {
-      m[g] = -INFINITY; l[g] = 0.f;
-#pragma unroll
-      for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
-    }
-  }
-  __device__ __forceinline__ void update(int g, float logit2, const float (&vx)[EPL]) {
-    const float mn = fmaxf(m[g], logit2);
-    const float corr = __builtin_amdgcn_exp2f(m[g] - mn);
-    const float p = __builtin_amdgcn_exp2f(logit2 - mn);
-    l[g] = l[g] * corr + p;
-#pragma unroll
-    for (int e = 0; e < EPL; ++e) acc[g][e] = fmaf(p, vx[e], acc[g][e] * corr);
-    m[g] = mn;
-  }
-};
 
 template <int EPL>
 __device__ __forceinline__ void unpack_bf16(const uint32_t (&w)[EPL / 2], float (&x)[EPL]) {
@@ -95,6 +66,50 @@ __device__ __forceinline__ void load_raw(const bf16_t* __restrict__ p, uint32_t 
   }
 }
 
+// Online-softmax state of one lane: NR rows at a time are folded in with one rescale per head.
+template <int GH, int EPL>
+struct OnlineSoftmax {
+  float m[GH], l[GH], acc[GH][EPL];
+  __device__ __forceinline__ void init() {
+#pragma unroll
+    for (int g = 0; g < GH; ++g) {
+      m[g] = -INFINITY; l[g] = 0.f;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
+    }
+  }
+  // lg[row][g]: logits in log2 units, -inf for masked rows; vraw[row]: the lane's V columns (bf16 pairs)
+  template <int NR>
+  __device__ __forceinline__ void fold(const float (&lg)[NR][GH], const uint32_t (&vraw)[NR][EPL / 2]) {
+#pragma unroll
+    for (int g = 0; g < GH; ++g) {
+      float mn = m[g];
+#pragma unroll
+      for (int i = 0; i < NR; ++i) mn = fmaxf(mn, lg[i][g]);
+      if (mn != -INFINITY) {
+        const float corr = __builtin_amdgcn_exp2f(m[g] - mn);
+        m[g] = mn;
+        l[g] *= corr;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[g][e] *= corr;
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < NR; ++i) {
+      float vx[EPL];
+      unpack_bf16<EPL>(vraw[i], vx);
+#pragma unroll
+      for (int g = 0; g < GH; ++g) {
+        // masked rows carry -inf and contribute exp2(-inf) = 0; a still-empty state uses 0 as reference
+        const float p = __builtin_amdgcn_exp2f(lg[i][g] - (m[g] == -INFINITY ? 0.f : m[g]));
+        l[g] += p;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[g][e] = fmaf(p, vx[e], acc[g][e]);
+      }
+    }
+  }
+};
+
 // KSMAX = number of 32-wide rank steps the A prefetch buffer is sized for (5: r <= 160, 8: r <= 256)
 template <int D, int GH, int KSMAX, bool FAST4>
 __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
@@ -108,12 +123,31 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int sub = lane & 15, rg = lane >> 4;
   const int oc = a.o * a.c, kc = a.k * a.c;
+  const int32_t* ids = a.sel_ids + (size_t)unit * a.k;
+  const int r = a.r, rp = a.rp, r32 = a.r32;
+
+  // ---- B^T of this KV head into LDS (zero beyond rank r).  A wave reads 16 rank rows x 64 bytes
+  //      per load and scatters them as 16-bit LDS writes.
+  {
+    const bf16_t* Bu = a.B + (size_t)unit * r * D;
+    for (int idx = threadIdx.x; idx < r32 * (D / 8); idx += 256) {
+      const int n8 = (idx & 3) + 4 * (idx / (4 * r32)), kk = (idx >> 2) % r32;
+      uint4 wv = make_uint4(0u, 0u, 0u, 0u);
+      if (kk < r) wv = *reinterpret_cast<const uint4*>(Bu + (size_t)kk * D + n8 * 8);
+      const uint32_t w4[4] = {wv.x, wv.y, wv.z, wv.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        Bt[(n8 * 8 + 2 * i) * rp + kk] = (bf16_t)(w4[i] & 0xffffu);
+        Bt[(n8 * 8 + 2 * i + 1) * rp + kk] = (bf16_t)(w4[i] >> 16);
+      }
+    }
+  }
 
   OnlineSoftmax<GH, EPL> st;
   st.init();
 
-  if (split < a.n_res_splits) {
-    // ---------------- resident tokens: [outliers ; recent] ----------------
+  // ---------------- this split's share of the resident tokens: [outliers ; recent] ----------------
+  {
     float qv[GH][EPL];
 #pragma unroll
     for (int g = 0; g < GH; ++g) {
@@ -123,57 +157,50 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
       for (int e = 0; e < EPL; ++e) qv[g][e] = x[e] * a.scale_log2;
     }
     const int n_res = oc + a.w;
-    const int i_begin = split * a.res_split_len;
+    const int i_begin = min(n_res, split * a.res_split_len);
     const int i_end = min(n_res, i_begin + a.res_split_len);
-    const int n_iter = (i_end - i_begin + 15) / 16;
-    for (int it = 0; it < n_iter; ++it) {
-      const int i = i_begin + it * 16 + wave * 4 + rg;
-      const bool ok = i < i_end;
-      float kx[EPL], vx[EPL];
+    for (int i0 = i_begin + wave * 8; i0 < i_end; i0 += 32) {
+      // two rows per lane group and step: rows i0 + rg and i0 + 4 + rg
+      uint32_t kraw[2][EPL / 2], vraw[2][EPL / 2];
+      bool ok[2];
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) { kx[e] = 0.f; vx[e] = 0.f; }
-      if (ok) {
+      for (int x = 0; x < 2; ++x) {
+        const int i = i0 + 4 * x + rg;
+        ok[x] = i < i_end;
+        const int ic = min(i, i_end - 1);
         const bf16_t *kp, *vp;
-        if (i < oc) {
-          kp = a.k_outlier + ((size_t)unit * oc + i) * D;
-          vp = a.v_outlier + ((size_t)unit * oc + i) * D;
+        if (ic < oc) {
+          kp = a.k_outlier + ((size_t)unit * oc + ic) * D;
+          vp = a.v_outlier + ((size_t)unit * oc + ic) * D;
         } else {
-          kp = a.k_local + ((size_t)unit * a.w + (i - oc)) * D;
-          vp = a.v_local + ((size_t)unit * a.w + (i - oc)) * D;
+          kp = a.k_local + ((size_t)unit * a.w + (ic - oc)) * D;
+          vp = a.v_local + ((size_t)unit * a.w + (ic - oc)) * D;
         }
-        load_bf16_row<EPL>(kp + sub * EPL, kx);
-        load_bf16_row<EPL>(vp + sub * EPL, vx);
+        load_raw<EPL>(kp + sub * EPL, kraw[x]);
+        load_raw<EPL>(vp + sub * EPL, vraw[x]);
       }
+      float lg[2][GH];
 #pragma unroll
-      for (int g = 0; g < GH; ++g) {
-        float dot = 0.f;
+      for (int x = 0; x < 2; ++x) {
+        float kx[EPL], dot[GH];
+        unpack_bf16<EPL>(kraw[x], kx);
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) dot = fmaf(kx[e], qv[g][e], dot);
-        dot = allsum16_f32(dot);
-        if (ok) st.update(g, dot, vx);
+        for (int g = 0; g < GH; ++g) {
+          dot[g] = 0.f;
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) dot[g] = fmaf(kx[e], qv[g][e], dot[g]);
+        }
+        allsum16_vec<GH>(dot);
+#pragma unroll
+        for (int g = 0; g < GH; ++g) lg[x][g] = ok[x] ? dot[g] : -INFINITY;
       }
+      st.template fold<2>(lg, vraw);
     }
-  } else {
-    // ---------------- selected chunks: rebuild keys on the matrix cores ----------------
+  }
+
+  // ---------------- selected chunks: rebuild keys on the matrix cores ----------------
+  {
     const int last_chunk = a.s / a.c - 1;  // ids are clamped: a bad id can never address outside A or V
-    const int32_t* ids = a.sel_ids + (size_t)unit * a.k;
-    const int r = a.r, rp = a.rp, r32 = a.r32;
-#ifndef SKV_X_NOSTAGE
-    {  // stage B^T, zero beyond rank r
-      const bf16_t* Bu = a.B + (size_t)unit * r * D;
-      for (int idx = threadIdx.x; idx < r32 * (D / 8); idx += 256) {
-        const int kk = idx % r32, n8 = idx / r32;
-        uint4 wv = make_uint4(0u, 0u, 0u, 0u);
-        if (kk < r) wv = *reinterpret_cast<const uint4*>(Bu + (size_t)kk * D + n8 * 8);
-        const uint32_t w4[4] = {wv.x, wv.y, wv.z, wv.w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          Bt[(n8 * 8 + 2 * i) * rp + kk] = (bf16_t)(w4[i] & 0xffffu);
-          Bt[(n8 * 8 + 2 * i + 1) * rp + kk] = (bf16_t)(w4[i] >> 16);
-        }
-      }
-    }
-#endif
     // q in accumulator-column layout (column nb*16 + sub), pre-scaled to log2 units
     float qc[GH][NB];
 #pragma unroll
@@ -187,15 +214,7 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
       frev[nb] = a.inv_freq_dev ? (double)a.inv_freq_dev[f] * 0.15915494309189533577 : a.freqs.rev[f];
     }
     const double pos0 = a.pos_offset ? (double)a.pos_offset[b] : 0.0;
-    __syncthreads();
-
-    const int s_begin = (split - a.n_res_splits) * a.sparse_split_len;
-    const int s_end = min(kc, s_begin + a.sparse_split_len);
-    const int ksteps = r32 / 32;
-    const bool ragged_rank = (r & 31) != 0;  // last rank step only partly backed by A
-    // FAST4 (chunk size a multiple of 4): the 4 rows a lane holds per tile are consecutive tokens,
-    // so one accurate angle per tile and frequency is stepped by one position three times.
-    float cd[HB], sd[HB];
+    float cd[HB], sd[HB];  // one-position rotation step per frequency (FAST4)
     if constexpr (FAST4) {
 #pragma unroll
       for (int nb = 0; nb < HB; ++nb) {
@@ -205,6 +224,12 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
         sd[nb] = __builtin_amdgcn_sinf((float)rv);
       }
     }
+    __syncthreads();  // B^T is in place
+
+    const int s_begin = split * a.sparse_split_len;
+    const int s_end = min(kc, s_begin + a.sparse_split_len);
+    const int ksteps = r32 / 32;
+    const bool ragged_rank = (r & 31) != 0;  // last rank step only partly backed by A
     for (int row0 = s_begin + wave * 32; row0 < s_end; row0 += 128) {
       // -- this lane's A rows (operand layout: row = lane % 16 of each 16-row tile), all loads up front.
       //    Rows past the end of the split are clamped onto its last row; their logits are masked below.
@@ -218,16 +243,12 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
 #pragma unroll
         for (int ks = 0; ks < KSMAX; ++ks) {
           uint4 wv = make_uint4(0u, 0u, 0u, 0u);
-#ifdef SKV_X_NOA
-          wv = make_uint4(0x3f803f80u + (uint32_t)(uintptr_t)arow, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);
-#else
           if (ks < ksteps && (!ragged_rank || ks * 32 + rg * 8 < r)) wv = *reinterpret_cast<const uint4*>(arow + ks * 32);
-#endif
           af[ks][mt] = *reinterpret_cast<bf16x8*>(&wv);
         }
       }
       // -- rows whose logits this lane will hold (accumulator layout: rows 4*(lane/16)+j), their V slices
-      uint32_t vraw[2][4][EPL / 2];
+      uint32_t vraw[8][EPL / 2];
       int tok[2][FAST4 ? 1 : 4];
       bool okr[2][FAST4 ? 1 : 4];
 #pragma unroll
@@ -242,11 +263,7 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
           const bf16_t* vp = (a.v_sparse ? a.v_sparse + ((size_t)unit * kc + ic) * D
                                          : a.v_store + ((size_t)unit * a.s + n0) * D) + sub * EPL;
 #pragma unroll
-#ifdef SKV_X_NOV
-          for (int j = 0; j < 4; ++j) for (int e = 0; e < EPL / 2; ++e) vraw[mt][j][e] = 0x3f803f80u + (uint32_t)(uintptr_t)vp;
-#else
-          for (int j = 0; j < 4; ++j) load_raw<EPL>(vp + (size_t)j * D, vraw[mt][j]);
-#endif
+          for (int j = 0; j < 4; ++j) load_raw<EPL>(vp + (size_t)j * D, vraw[mt * 4 + j]);
         } else {
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
@@ -258,7 +275,7 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
             tok[mt][j] = n;
             const bf16_t* vp = a.v_sparse ? a.v_sparse + ((size_t)unit * kc + ic) * D
                                           : a.v_store + ((size_t)unit * a.s + n) * D;
-            load_raw<EPL>(vp + sub * EPL, vraw[mt][j]);
+            load_raw<EPL>(vp + sub * EPL, vraw[mt * 4 + j]);
           }
         }
       }
@@ -268,9 +285,6 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
       for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) acc[mt][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
-#ifdef SKV_X_NOMFMA
-      for (int ks = 0; ks < KSMAX; ++ks) for (int mt = 0; mt < 2; ++mt) { uint4 w = *reinterpret_cast<uint4*>(&af[ks][mt]); acc[mt][ks][0] += __uint_as_float(w.x ^ w.y ^ w.z ^ w.w); }
-#else
 #pragma unroll
       for (int ks = 0; ks < KSMAX; ++ks) {
         if (ks < ksteps) {
@@ -282,18 +296,8 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
           }
         }
       }
-#endif
-#ifdef SKV_X_NOEPI
-      {
-        float t = 0.f;
-        for (int mt = 0; mt < 2; ++mt) for (int nb = 0; nb < NB; ++nb) for (int j = 0; j < 4; ++j) t += acc[mt][nb][j];
-        for (int mt = 0; mt < 2; ++mt) for (int j = 0; j < 4; ++j) for (int e = 0; e < EPL / 2; ++e) t += __uint_as_float(vraw[mt][j][e]);
-        st.l[0] += t; st.m[0] = 0.f;
-        continue;
-      }
-#endif
-      // -- RoPE and q.K row by row (logits of the 8 rows x GH heads stay in registers) ...
-      float lg[2][4][GH];
+      // -- RoPE and q.K row by row; the logits of the 8 rows x GH heads stay in registers
+      float lg[8][GH];
 #pragma unroll
       for (int mt = 0; mt < 2; ++mt) {
         float cs[HB], sn[HB];
@@ -339,39 +343,10 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
           }
           allsum16_vec<GH>(dot);
 #pragma unroll
-          for (int g = 0; g < GH; ++g) lg[mt][j][g] = ok ? dot[g] : -INFINITY;
+          for (int g = 0; g < GH; ++g) lg[mt * 4 + j][g] = ok ? dot[g] : -INFINITY;
         }
       }
-      // -- ... then one softmax rescale per head for the whole block
-#pragma unroll
-      for (int g = 0; g < GH; ++g) {
-        float mn = st.m[g];
-#pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-          for (int j = 0; j < 4; ++j) mn = fmaxf(mn, lg[mt][j][g]);
-        if (mn == -INFINITY) continue;  // nothing valid yet in this row group
-        const float corr = __builtin_amdgcn_exp2f(st.m[g] - mn);
-        st.m[g] = mn;
-        st.l[g] *= corr;
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) st.acc[g][e] *= corr;
-      }
-#pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          float vx[EPL];
-          unpack_bf16<EPL>(vraw[mt][j], vx);
-#pragma unroll
-          for (int g = 0; g < GH; ++g) {
-            // masked rows carry -inf and contribute exp2(-inf) = 0; a still-empty state uses 0 as reference
-            const float p = __builtin_amdgcn_exp2f(lg[mt][j][g] - (st.m[g] == -INFINITY ? 0.f : st.m[g]));
-            st.l[g] += p;
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) st.acc[g][e] = fmaf(p, vx[e], st.acc[g][e]);
-          }
-        }
+      st.template fold<8>(lg, vraw);
     }
   }
 
@@ -380,7 +355,7 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
   for (int g = 0; g < GH; ++g) {
     float mt = fmaxf(st.m[g], __shfl_xor(st.m[g], 16, kWave));
     mt = fmaxf(mt, __shfl_xor(mt, 32, kWave));
-    const float sc = (st.m[g] == -INFINITY) ? 0.f : exp2f(st.m[g] - mt);
+    const float sc = (st.m[g] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(st.m[g] - mt);
     float lv = st.l[g] * sc;
     lv += __shfl_xor(lv, 16, kWave);
     lv += __shfl_xor(lv, 32, kWave);
@@ -402,7 +377,7 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
     float num = 0.f, den = 0.f;
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
-      const float sc = (sm_m[w][g] == -INFINITY) ? 0.f : exp2f(sm_m[w][g] - M);
+      const float sc = (sm_m[w][g] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(sm_m[w][g] - M);
       num = fmaf(sm_acc[w][g][e], sc, num);
       den = fmaf(sm_l[w][g], sc, den);
     }
@@ -412,6 +387,9 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
   }
 }
 
+// Merge of the per-split states of one head: out = sum_s acc_s 2^(m_s - M) / sum_s l_s 2^(m_s - M).
+// A separate launch on purpose: a device-scope release inside the attention kernel would make every
+// workgroup write back its XCD's L2, which costs far more than this kernel.
 template <int D>
 __global__ __launch_bounds__(D) void attn_combine_kernel(const float* __restrict__ part_acc,
                                                          const float2* __restrict__ part_ml,
@@ -423,7 +401,7 @@ __global__ __launch_bounds__(D) void attn_combine_kernel(const float* __restrict
   for (int sp = 0; sp < n_splits; ++sp) M = fmaxf(M, ml[sp].x);
   float num = 0.f, den = 0.f;
   for (int sp = 0; sp < n_splits; ++sp) {
-    const float sc = (ml[sp].x == -INFINITY) ? 0.f : exp2f(ml[sp].x - M);
+    const float sc = (ml[sp].x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ml[sp].x - M);
     num = fmaf(part_acc[(head * n_splits + sp) * D + e], sc, num);
     den = fmaf(ml[sp].y, sc, den);
   }

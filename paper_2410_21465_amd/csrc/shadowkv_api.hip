@@ -89,33 +89,27 @@ int check_params(const shadowkv_params* p, bool decode, Shape* sh) {
   return SHADOWKV_OK;
 }
 
-// Split plan of the attention kernel: resident rows (outliers + recent tokens) and selected rows
-// are cut separately; a sparse split is a multiple of 32 rows (one MFMA row block of one wave).
+// Split plan of the attention kernel: the selected rows are cut into splits that are multiples of
+// 32 rows (one MFMA row block of one wave); every split also takes an equal share of the resident
+// rows (outliers + recent tokens).
 struct AttnPlan {
-  int res_split_len, n_res_splits, sparse_split_len, n_sparse_splits, n_splits;
+  int res_split_len, sparse_split_len, n_splits, z;
 };
 AttnPlan plan_attention(const Shape& sh) {
-  const long z = sh.G / attention_heads_per_group(sh.G);
-  const long groups = (long)sh.units * z;
-  const long kc = (long)sh.k * sh.c, n_res = (long)sh.o * sh.c + sh.w;
   AttnPlan ap;
-  // selected rows: the largest split (fewest B^T stagings) that still gives >= 512 workgroups
+  ap.z = sh.G / attention_heads_per_group(sh.G);
+  const long groups = (long)sh.units * ap.z;
+  const long kc = (long)sh.k * sh.c, n_res = (long)sh.o * sh.c + sh.w;
+  // the largest split (fewest B^T stagings) that still gives >= 512 workgroups
   long len = 32;
   for (long cand : {512l, 256l, 128l, 64l}) if (kc * groups / cand >= 512) { len = cand; break; }
-  if (const char* ov = std::getenv("SHADOWKV_SPARSE_SPLIT")) {  // tuning override: rows per sparse split
+  if (const char* ov = std::getenv("SHADOWKV_SPARSE_SPLIT")) {  // tuning override: rows per split
     const long v = std::atol(ov);
     if (v >= 32 && v <= 4096 && v % 32 == 0) len = v;
   }
   ap.sparse_split_len = (int)len;
-  ap.n_sparse_splits = (int)((kc + len - 1) / len);
-  long rl = (n_res * groups / 128 >= 512) ? 128 : 32;
-  if (const char* ov = std::getenv("SHADOWKV_RES_SPLIT")) {  // tuning override: rows per resident split
-    const long v = std::atol(ov);
-    if (v >= 16 && v <= 4096 && v % 16 == 0) rl = v;
-  }
-  ap.res_split_len = (int)rl;
-  ap.n_res_splits = (int)((n_res + rl - 1) / rl);
-  ap.n_splits = ap.n_res_splits + ap.n_sparse_splits;
+  ap.n_splits = (int)((kc + len - 1) / len);
+  ap.res_split_len = (int)((n_res + ap.n_splits - 1) / ap.n_splits);
   return ap;
 }
 
@@ -436,8 +430,7 @@ int shadowkv_decode_step(const shadowkv_params* params, const shadowkv_bf16* q, 
   t.out = out;
   t.batch = sh.b; t.hq = sh.hq; t.hkv = sh.hkv; t.d = sh.d; t.s = sh.s; t.c = sh.c; t.o = sh.o; t.k = sh.k; t.w = sh.w;
   t.r = sh.r; t.r32 = (sh.r + 31) / 32 * 32; t.rp = t.r32 + 8;  // +8: 16-byte multiple that spreads LDS banks
-  t.res_split_len = L.attn.res_split_len; t.n_res_splits = L.attn.n_res_splits;
-  t.sparse_split_len = L.attn.sparse_split_len; t.n_splits = L.attn.n_splits;
+  t.res_split_len = L.attn.res_split_len; t.sparse_split_len = L.attn.sparse_split_len; t.n_splits = L.attn.n_splits;
   t.scale_log2 = (float)(scale * 1.4426950408889634074);
   t.freqs = freqs;
   e = launch_attention(t, st);
