@@ -19,11 +19,18 @@
 
 namespace skv {
 
+// exp(x) for x <= 0 through the fp32 exp2 unit.  It only feeds the softmax normaliser (a sum of
+// such terms kept in fp64): its ~1e-7 relative error moves a head's log-sum-exp by ~1e-7, an
+// order below the 1e-6 at which two scores count as tied; the logits themselves stay fp64.
+__device__ __forceinline__ double exp_neg(double x) {
+  return (double)__builtin_amdgcn_exp2f((float)(x * 1.4426950408889634074));
+}
+
 // (m, s) <- (m, s) (+) (m2, s2) for s = sum exp(p - m)
 __device__ __forceinline__ void lse_merge(double& m, double& s, double m2, double s2) {
   if (m2 == -INFINITY) return;
   if (m == -INFINITY) { m = m2; s = s2; return; }
-  const double e = exp(-fabs(m - m2));
+  const double e = exp_neg(-fabs(m - m2));
   if (m2 > m) { s = s * e + s2; m = m2; } else { s += s2 * e; }
 }
 
