@@ -97,3 +97,47 @@ def test_repeated_calls_are_deterministic():
     _, _, (o1, i1, _) = PU.run_decode_parity(wl, t, ref_b)
     _, _, (o2, i2, _) = PU.run_decode_parity(wl, t, ref_b)
     assert torch.equal(o1, o2) and torch.equal(i1, i2)
+
+
+@pytest.mark.parametrize("host_values", [False, True])
+def test_hip_graph_replays_match_eager(host_values):
+    """A captured decode step (with the side-stream fork when values are staged) replays to the eager result,
+    several times, with eager work and synchronisations between the replays."""
+    wl = small("graph", ctx_len=8192, topk_chunks=48, value_location="host" if host_values else "hbm", n_queries=3)
+    t = PU.draw(wl)
+    p = S.Params.from_workload(wl)
+    bl = S.build_landmarks(p, t["k_rope"], t["v"])
+    ws = S.alloc_workspace(S.decode_workspace_bytes(p))
+    q = t["q_pool"][0].clone()
+    out = torch.empty(wl.batch, wl.n_q_heads, wl.head_dim, dtype=torch.bfloat16, device="cuda")
+    ids = torch.empty(wl.batch, wl.n_kv_heads, wl.topk_chunks, dtype=torch.int32, device="cuda")
+    side = torch.cuda.Stream()
+
+    def step(stream_side):
+        S.decode_step(p, q, t["A"], t["B"], bl["landmarks"], bl["landmark_chunk_ids"], bl["k_outlier"],
+                      bl["v_outlier"], t["k_local"], t["v_local"], t["v"], t["pos_offset"], out=out,
+                      out_chunk_ids=ids, workspace=ws, side_stream=stream_side)
+
+    eager = []
+    for qi in range(3):
+        q.copy_(t["q_pool"][qi])
+        step(side)
+        torch.cuda.synchronize()
+        eager.append((out.clone(), ids.clone()))
+    cap = torch.cuda.Stream()
+    cap.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(cap):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=cap):
+            step(side)
+    torch.cuda.current_stream().wait_stream(cap)
+    for rep in range(6):
+        qi = rep % 3
+        q.copy_(t["q_pool"][qi])
+        out.zero_(); ids.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager[qi][0]) and torch.equal(ids, eager[qi][1]), f"replay {rep}"
+        step(side)                      # eager work between replays
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager[qi][0])
