@@ -141,3 +141,48 @@ def test_hip_graph_replays_match_eager(host_values):
         step(side)                      # eager work between replays
         torch.cuda.synchronize()
         assert torch.equal(out, eager[qi][0])
+
+
+def _grouped_landmarks(ref_b, wl, vary_first_element):
+    """Landmark rows made identical in groups of four (optionally differing in element 0 only)."""
+    rb = dict(ref_b)
+    lm = ref_b["landmarks"].copy()
+    n_c = lm.shape[2]
+    src = (np.arange(n_c) // 4) * 4
+    lm = lm[:, :, src, :]
+    if vary_first_element:
+        import torch as _t
+        vals = _t.tensor([0.0, 1.0, 2.0, 3.0]).to(_t.bfloat16).view(_t.int16).numpy().view(np.uint16)
+        lm[:, :, :, 0] = vals[np.arange(n_c) % 4]
+    rb["landmarks"] = np.ascontiguousarray(lm)
+    return rb
+
+
+def test_exact_ties_at_the_boundary_go_to_the_lower_slot():
+    """Every score occurs four times; k is not a multiple of four, so the boundary cuts a tie group."""
+    wl = small("ties", topk_chunks=26, ctx_len=8192)
+    t = PU.draw(wl)
+    ref_b, _ = PU.run_build_parity(wl, t)
+    rb = _grouped_landmarks(ref_b, wl, vary_first_element=False)
+    for qi in range(2):
+        stats, ref_d, (out, ids, ws) = PU.run_decode_parity(wl, t, rb, qi=qi, check_keys=False)
+        assert stats["ties"] == 0
+        np.testing.assert_array_equal(np.sort(ref_d["chunk_ids"], axis=-1), ids.cpu().numpy())
+
+
+def test_scores_closer_than_fp32_resolution_are_ordered_exactly():
+    """Rows of a group differ only where q is 2^-20: their logits differ by ~1e-7, below the fp32 rounding
+    of the stored logits, and the exact order (higher element 0 first) must still be found."""
+    wl = small("near-ties", topk_chunks=26, ctx_len=8192)
+    t = PU.draw(wl)
+    ref_b, _ = PU.run_build_parity(wl, t)
+    rb = _grouped_landmarks(ref_b, wl, vary_first_element=True)
+    t["q_pool"][:, :, :, 0] = 2.0 ** -20
+    for qi in range(2):
+        stats, ref_d, (out, ids, ws) = PU.run_decode_parity(wl, t, rb, qi=qi, check_keys=False)
+        np.testing.assert_array_equal(np.sort(ref_d["chunk_ids"], axis=-1), ids.cpu().numpy())
+        z2 = ref_d["z2"].reshape(wl.units, -1)
+        srt = -np.sort(-z2, axis=-1)
+        gap = srt[:, wl.topk_chunks - 1] - srt[:, wl.topk_chunks]
+        print(f"[near-ties] q{qi}: boundary gaps {gap.tolist()}", flush=True)
+        assert np.all(gap > 0) and gap.min() < 1e-6      # the case is what it claims to be
