@@ -4,13 +4,65 @@
 // (ascending chunk order) and the gather of the outlier chunks' keys and values.
 //
 // chunk_stats: 16 lanes own one chunk (d/16 columns each, all c rows), so the mean needs
-// no cross-lane traffic; the per-token dot products and norms are reduced over the 16
-// lanes in fp64 (the minimum cosine decides an index set against an fp64 reference).
+// no cross-lane traffic.  For c <= 8 the rows stay in registers (one pass over HBM).  The
+// per-row dot products <mean, k_t> and squared norms are partial sums over a lane's columns;
+// a transposed butterfly over the 16 lanes (DPP pairings xor 8, 7, 2, 1) leaves row t's dot
+// in lane t and its squared norm in lane t+8, so each cosine -- an fp64 sqrt and divide -- is
+// evaluated once, not 16 times.  Everything is fp64: the minimum cosine decides an index set
+// against an fp64 reference.
 #include "kernels.hpp"
 
 namespace skv {
 
-template <int D>
+// 64-bit DPP move: value of the lane that the control word pairs this lane with (same 16-lane row)
+template <int CTRL>
+__device__ __forceinline__ double dpp_f64(double v) {
+  const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, 0xf, 0xf, false);
+  const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, 0xf, 0xf, false);
+  return __hiloint2double(hi, lo);
+}
+constexpr int kDppXor8 = 0x128;  // row_ror:8
+constexpr int kDppXor7 = 0x141;  // row_half_mirror: lane x <-> 7 - x inside each group of 8
+constexpr int kDppXor2 = 0x4E;   // quad_perm [2,3,0,1]
+constexpr int kDppXor1 = 0xB1;   // quad_perm [1,0,3,2]
+
+__device__ __forceinline__ double allsum16_f64(double v) {
+  v += dpp_f64<0x128>(v);
+  v += dpp_f64<0x124>(v);
+  v += dpp_f64<0x122>(v);
+  v += dpp_f64<0x121>(v);
+  return v;
+}
+__device__ __forceinline__ double allmin16_f64(double v) {
+  v = fmin(v, dpp_f64<kDppXor8>(v));
+  v = fmin(v, dpp_f64<kDppXor7>(v));
+  v = fmin(v, dpp_f64<kDppXor2>(v));
+  v = fmin(v, dpp_f64<kDppXor1>(v));
+  return v;
+}
+
+// One butterfly stage: N values in, N/2 out.  Lanes whose selector bit is set keep the upper half.
+template <int N, int CTRL>
+__device__ __forceinline__ void scatter_stage(const double (&in)[N], double (&out)[N / 2], bool upper) {
+#pragma unroll
+  for (int i = 0; i < N / 2; ++i) {
+    const double keep = upper ? in[N / 2 + i] : in[i];
+    const double send = upper ? in[i] : in[N / 2 + i];
+    out[i] = keep + dpp_f64<CTRL>(send);
+  }
+}
+// Sum of v[i] over the 16 lanes of a row, delivered to lane i (i = lane % 16).
+__device__ __forceinline__ double reduce_scatter16_f64(const double (&v)[16], int sub) {
+  double a[8], b[4], c[2], d[1];
+  scatter_stage<16, kDppXor8>(v, a, (sub & 8) != 0);
+  scatter_stage<8, kDppXor7>(a, b, (sub & 4) != 0);
+  scatter_stage<4, kDppXor2>(b, c, (sub & 2) != 0);
+  scatter_stage<2, kDppXor1>(c, d, (sub & 1) != 0);
+  return d[0];
+}
+
+// REG: the chunk's rows are kept in registers (c <= 8); otherwise they are read twice.
+template <int D, bool REG>
 __global__ __launch_bounds__(256) void chunk_stats_kernel(const bf16_t* __restrict__ k_rope,
                                                           bf16_t* __restrict__ chunk_mean,
                                                           double* __restrict__ chunk_min_cos, int s, int c,
@@ -23,37 +75,86 @@ __global__ __launch_bounds__(256) void chunk_stats_kernel(const bf16_t* __restri
   const bool ok = j < n_ch;
   const bf16_t* base = k_rope + ((size_t)unit * s + (size_t)(ok ? j : 0) * c) * D + sub * EPL;
 
+  uint32_t raw[REG ? 8 : 1][EPL / 2];
   double mean[EPL];
 #pragma unroll
   for (int e = 0; e < EPL; ++e) mean[e] = 0.0;
-  for (int t = 0; t < c; ++t) {
-    float x[EPL];
-    load_bf16_row<EPL>(base + (size_t)t * D, x);
+  if constexpr (REG) {
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) mean[e] += (double)x[e];
+    for (int t = 0; t < 8; ++t) {
+#pragma unroll
+      for (int e = 0; e < EPL / 2; ++e) raw[t][e] = 0u;
+      if (t < c) {
+        if constexpr (EPL == 8) {
+          const uint4 w = *reinterpret_cast<const uint4*>(base + (size_t)t * D);
+          raw[t][0] = w.x; raw[t][1] = w.y; raw[t][2] = w.z; raw[t][3] = w.w;
+        } else {
+          const uint32_t* q = reinterpret_cast<const uint32_t*>(base + (size_t)t * D);
+#pragma unroll
+          for (int e = 0; e < EPL / 2; ++e) raw[t][e] = q[e];
+        }
+      }
+    }
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+#pragma unroll
+      for (int e = 0; e < EPL / 2; ++e) {
+        mean[2 * e] += (double)bf16_lo(raw[t][e]);
+        mean[2 * e + 1] += (double)bf16_hi(raw[t][e]);
+      }
+  } else {
+    for (int t = 0; t < c; ++t) {
+      float x[EPL];
+      load_bf16_row<EPL>(base + (size_t)t * D, x);
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) mean[e] += (double)x[e];
+    }
   }
+  // sum / c: the multiplication by 1/c is exact (and identical to the division) when c is a power of two
+  const bool pow2 = (c & (c - 1)) == 0;
+  const double inv_c = 1.0 / (double)c;
   double cn2 = 0.0;
 #pragma unroll
   for (int e = 0; e < EPL; ++e) {
-    mean[e] = mean[e] / (double)c;
+    mean[e] = pow2 ? mean[e] * inv_c : mean[e] / (double)c;
     cn2 = fma(mean[e], mean[e], cn2);
   }
-  const double cn = fmax(sqrt(sum16_f64(cn2)), 1e-8);
+  const double cn = fmax(sqrt(allsum16_f64(cn2)), 1e-8);
+
   double mn = INFINITY;
-  for (int t = 0; t < c; ++t) {
-    float x[EPL];
-    load_bf16_row<EPL>(base + (size_t)t * D, x);
-    double dot = 0.0, kn2 = 0.0;
+  if constexpr (REG) {
+    double v[16];  // v[t] = partial <mean, k_t>, v[8 + t] = partial |k_t|^2
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) {
-      const double xd = (double)x[e];
-      dot = fma(mean[e], xd, dot);
-      kn2 = fma(xd, xd, kn2);
+    for (int t = 0; t < 8; ++t) {
+      double dot = 0.0, kn2 = 0.0;
+#pragma unroll
+      for (int e = 0; e < EPL / 2; ++e) {
+        const double x0 = (double)bf16_lo(raw[t][e]), x1 = (double)bf16_hi(raw[t][e]);
+        dot = fma(mean[2 * e], x0, dot); dot = fma(mean[2 * e + 1], x1, dot);
+        kn2 = fma(x0, x0, kn2); kn2 = fma(x1, x1, kn2);
+      }
+      v[t] = dot; v[8 + t] = kn2;
     }
-    dot = sum16_f64(dot);
-    kn2 = sum16_f64(kn2);
-    const double cs = dot / (cn * fmax(sqrt(kn2), 1e-8));
-    mn = fmin(mn, cs);
+    const double mine = reduce_scatter16_f64(v, sub);   // lane t: dot_t, lane 8+t: |k_t|^2
+    const double kn2 = dpp_f64<kDppXor8>(mine);
+    double cs = INFINITY;
+    if (sub < c) cs = mine / (cn * fmax(sqrt(kn2), 1e-8));
+    mn = allmin16_f64(cs);
+  } else {
+    for (int t = 0; t < c; ++t) {
+      float x[EPL];
+      load_bf16_row<EPL>(base + (size_t)t * D, x);
+      double dot = 0.0, kn2 = 0.0;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) {
+        const double xd = (double)x[e];
+        dot = fma(mean[e], xd, dot);
+        kn2 = fma(xd, xd, kn2);
+      }
+      dot = allsum16_f64(dot);
+      kn2 = allsum16_f64(kn2);
+      mn = fmin(mn, dot / (cn * fmax(sqrt(kn2), 1e-8)));
+    }
   }
   if (ok) {
     bf16_t hm[EPL];
@@ -64,7 +165,8 @@ __global__ __launch_bounds__(256) void chunk_stats_kernel(const bf16_t* __restri
   }
 }
 
-// L <- C \ Gather(C, I): landmark slot -> the slot-th chunk that is not an outlier.
+// L <- C \ Gather(C, I): landmark slot s -> chunk s + t, t = number of outliers i with id_i - i <= s
+// (ids ascending), found by bisection.  A workgroup copies 128 consecutive slots.
 template <int D>
 __global__ __launch_bounds__(256) void compact_landmarks_kernel(const bf16_t* __restrict__ chunk_mean,
                                                                 const int32_t* __restrict__ outlier_ids,
@@ -74,20 +176,29 @@ __global__ __launch_bounds__(256) void compact_landmarks_kernel(const bf16_t* __
   constexpr int EPL = D / 16;
   __shared__ int32_t oid[1024];
   const int unit = blockIdx.y, n_c = n_ch - o;
-  for (int i = threadIdx.x; i < o; i += 256) oid[i] = outlier_ids[(size_t)unit * o + i];
+  for (int i = threadIdx.x; i < o; i += 256) oid[i] = outlier_ids[(size_t)unit * o + i] - i;
   __syncthreads();
   const int sub = threadIdx.x & 15;
-  const int slot = blockIdx.x * 16 + (threadIdx.x >> 4);
-  if (slot >= n_c) return;
-  int j = slot;
-  for (int i = 0; i < o && oid[i] <= j; ++i) ++j;  // ids ascending: skip every outlier at or below j
-  const bf16_t* src = chunk_mean + ((size_t)unit * n_ch + j) * D + sub * EPL;
-  bf16_t* dst = landmarks + ((size_t)unit * n_c + slot) * D + sub * EPL;
-  const uint32_t* s32 = reinterpret_cast<const uint32_t*>(src);
-  uint32_t* d32 = reinterpret_cast<uint32_t*>(dst);
+#pragma unroll 2
+  for (int it = 0; it < 8; ++it) {
+    const int slot = blockIdx.x * 128 + it * 16 + (threadIdx.x >> 4);
+    if (slot >= n_c) break;
+    int lo = 0, hi = o;  // first index with oid[i] > slot
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (oid[mid] <= slot) lo = mid + 1; else hi = mid;
+    }
+    const int j = slot + lo;
+    const uint32_t* s32 = reinterpret_cast<const uint32_t*>(chunk_mean + ((size_t)unit * n_ch + j) * D + sub * EPL);
+    uint32_t* d32 = reinterpret_cast<uint32_t*>(landmarks + ((size_t)unit * n_c + slot) * D + sub * EPL);
+    if constexpr (EPL == 8) {
+      *reinterpret_cast<uint4*>(d32) = *reinterpret_cast<const uint4*>(s32);
+    } else {
 #pragma unroll
-  for (int e = 0; e < EPL / 2; ++e) d32[e] = s32[e];
-  if (sub == 0) landmark_chunk_ids[(size_t)unit * n_c + slot] = j;
+      for (int e = 0; e < EPL / 2; ++e) d32[e] = s32[e];
+    }
+    if (sub == 0) landmark_chunk_ids[(size_t)unit * n_c + slot] = j;
+  }
 }
 
 __global__ __launch_bounds__(256) void gather_outliers_kernel(const uint4* __restrict__ k_rope,
@@ -111,12 +222,18 @@ hipError_t launch_chunk_stats(const bf16_t* k_rope, bf16_t* chunk_mean, double* 
                               int s, int c, hipStream_t st) {
   const int n_ch = s / c;
   dim3 grid((n_ch + 15) / 16, units), block(256);
+#define SKV_STATS(D_)                                                                                              \
+  do {                                                                                                             \
+    if (c <= 8) hipLaunchKernelGGL((chunk_stats_kernel<D_, true>), grid, block, 0, st, k_rope, chunk_mean, chunk_min_cos, s, c, n_ch); \
+    else hipLaunchKernelGGL((chunk_stats_kernel<D_, false>), grid, block, 0, st, k_rope, chunk_mean, chunk_min_cos, s, c, n_ch);       \
+  } while (0)
   switch (d) {
-    case 64: hipLaunchKernelGGL((chunk_stats_kernel<64>), grid, block, 0, st, k_rope, chunk_mean, chunk_min_cos, s, c, n_ch); break;
-    case 96: hipLaunchKernelGGL((chunk_stats_kernel<96>), grid, block, 0, st, k_rope, chunk_mean, chunk_min_cos, s, c, n_ch); break;
-    case 128: hipLaunchKernelGGL((chunk_stats_kernel<128>), grid, block, 0, st, k_rope, chunk_mean, chunk_min_cos, s, c, n_ch); break;
+    case 64: SKV_STATS(64); break;
+    case 96: SKV_STATS(96); break;
+    case 128: SKV_STATS(128); break;
     default: return hipErrorInvalidValue;
   }
+#undef SKV_STATS
   return hipGetLastError();
 }
 
@@ -124,7 +241,7 @@ hipError_t launch_compact_landmarks(const bf16_t* chunk_mean, const int32_t* out
                                     int32_t* landmark_chunk_ids, int units, int d, int n_ch, int o, hipStream_t st) {
   const int n_c = n_ch - o;
   if (n_c <= 0) return hipSuccess;
-  dim3 grid((n_c + 15) / 16, units), block(256);
+  dim3 grid((n_c + 127) / 128, units), block(256);
   switch (d) {
     case 64: hipLaunchKernelGGL((compact_landmarks_kernel<64>), grid, block, 0, st, chunk_mean, outlier_ids, landmarks, landmark_chunk_ids, n_ch, o); break;
     case 96: hipLaunchKernelGGL((compact_landmarks_kernel<96>), grid, block, 0, st, chunk_mean, outlier_ids, landmarks, landmark_chunk_ids, n_ch, o); break;
