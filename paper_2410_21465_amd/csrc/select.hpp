@@ -5,10 +5,9 @@
 // (tid, e) has order index tid * E + e.  Key 0 means "absent".  The method is a
 // most-significant-digit radix select (8-bit digits, LDS histograms private to each
 // wave) that first skips the bit prefix all keys share, and stops as soon as the
-// digit bin that straddles the k-th position is needed in full.  Every wave scans the
-// histogram for itself, and two histogram buffers alternate, so a pass costs two
-// barriers.  After that a single ordered scan gives every thread the output slot of
-// its selected elements: the result is written in ascending order index, no atomics.
+// digit bin that straddles the k-th position is needed in full.  After that a
+// single ordered scan gives every thread the output slot of its selected elements,
+// so the result is written in ascending order index without atomics.
 #pragma once
 #include "common.hpp"
 
@@ -17,10 +16,11 @@ namespace skv {
 template <int NT>
 struct SelectSmem {
   static constexpr int NW = NT / kWave;
-  uint32_t hist[2][NW][256];
+  uint32_t hist[NW][256];
   uint64_t red_and[NW];
   uint64_t red_or[NW];
   uint32_t wave_tot[NW];
+  uint32_t bin, above, cnt;
 };
 
 // Exclusive prefix sum of `v` over the workgroup in thread order; needs sm.wave_tot.
@@ -40,21 +40,21 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, SelectSmem<
 #pragma unroll
   for (int w = 0; w < NW; ++w)
     if (w < wave) base += sm.wave_tot[w];
-  __syncthreads();  // wave_tot may be reused by the next scan
+  __syncthreads();
   return base + incl - v;
 }
 
-// Radix passes only.  On return the k-th largest key K* satisfies (K* & det_mask) == det_val;
-// keys whose masked value is greater are among the k largest, and of those whose masked value
-// is equal exactly `need` are (all of them when the passes stopped early, need == their count).
+// On return: bit e of sel_mask is set iff element (tid, e) is among the k largest
+// (k must not exceed the number of present keys); out_pos is the number of
+// selected elements that precede this thread's in order index.
 template <int NT, int E>
-__device__ void block_select_threshold(const uint64_t (&key)[E], int k, SelectSmem<NT>& sm,
-                                       uint64_t& det_mask_out, uint64_t& det_val_out, uint32_t& need_out) {
+__device__ void block_select_topk(const uint64_t (&key)[E], int k, SelectSmem<NT>& sm,
+                                  uint32_t& sel_mask, int& out_pos) {
+  static_assert(E <= 32, "selection mask is 32 bits wide");
   constexpr int NW = NT / kWave;
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
 
-  // 1. bits shared by every present key; both histogram buffers start at zero
-  for (int i = threadIdx.x; i < 2 * NW * 256; i += NT) (&sm.hist[0][0][0])[i] = 0u;
+  // 1. bits shared by every present key
   uint64_t a = ~0ull, o = 0ull;
 #pragma unroll
   for (int e = 0; e < E; ++e)
@@ -66,6 +66,7 @@ __device__ void block_select_threshold(const uint64_t (&key)[E], int k, SelectSm
   a = ~0ull; o = 0ull;
 #pragma unroll
   for (int w = 0; w < NW; ++w) { a &= sm.red_and[w]; o |= sm.red_or[w]; }
+  __syncthreads();
 
   const uint64_t diff = a ^ o;
   int nb = diff ? 64 - __clzll((long long)diff) : 0;           // undetermined low bits
@@ -74,75 +75,55 @@ __device__ void block_select_threshold(const uint64_t (&key)[E], int k, SelectSm
   uint32_t need = (uint32_t)k;
 
   // 2. radix passes, most significant undetermined digit first
-  int buf = 0;
   while (nb > 0 && need > 0) {
     const int w = nb < 8 ? nb : 8;
     const int shift = nb - w;
     const uint32_t dmask = (1u << w) - 1u;
+    for (int i = threadIdx.x; i < NW * 256; i += NT) (&sm.hist[0][0])[i] = 0u;
+    __syncthreads();
 #pragma unroll
     for (int e = 0; e < E; ++e)
       if (key[e] && (key[e] & det_mask) == det_val)
-        atomicAdd(&sm.hist[buf][wave][(uint32_t)(key[e] >> shift) & dmask], 1u);
+        atomicAdd(&sm.hist[wave][(uint32_t)(key[e] >> shift) & dmask], 1u);
     __syncthreads();
-    // every wave: lane l owns bins 255-4l .. 252-4l (descending), suffix-scan over the lanes
-    uint32_t c[4], tot = 0;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int b = 255 - 4 * lane - i;
-      uint32_t s = 0;
-#pragma unroll
-      for (int ww = 0; ww < NW; ++ww) s += sm.hist[buf][ww][b];
-      c[i] = s; tot += s;
-    }
-    uint32_t incl = tot;
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) {
-      uint32_t t = (uint32_t)__shfl_up((int)incl, off, kWave);
-      if (lane >= off) incl += t;
-    }
-    const uint32_t excl = incl - tot;
-    uint32_t found = 0;
-    int my_bin = -1;
-    uint32_t my_above = 0, my_cnt = 0;
-    if (excl < need && need <= incl) {
-      uint32_t run = excl;
+    if (wave == 0) {
+      uint32_t c[4], tot = 0;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        if (my_bin < 0 && need <= run + c[i]) { my_bin = 255 - 4 * lane - i; my_above = run; my_cnt = c[i]; }
-        run += c[i];
+        const int b = 255 - 4 * lane - i;
+        uint32_t s = 0;
+#pragma unroll
+        for (int ww = 0; ww < NW; ++ww) s += sm.hist[ww][b];
+        c[i] = s; tot += s;
       }
-      found = 1;
+      uint32_t incl = tot;
+#pragma unroll
+      for (int off = 1; off < kWave; off <<= 1) {
+        uint32_t t = (uint32_t)__shfl_up((int)incl, off, kWave);
+        if (lane >= off) incl += t;
+      }
+      const uint32_t excl = incl - tot;
+      if (excl < need && need <= incl) {
+        uint32_t run = excl;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          if (need <= run + c[i]) { sm.bin = 255 - 4 * lane - i; sm.above = run; sm.cnt = c[i]; break; }
+          run += c[i];
+        }
+      }
     }
-    const uint64_t who = __ballot(found);
-    const int src = who ? __ffsll((long long)who) - 1 : 0;   // exactly one lane crosses the k-th position
-    const uint32_t bin = (uint32_t)__shfl(my_bin, src, kWave);
-    const uint32_t above = (uint32_t)__shfl((int)my_above, src, kWave);
-    const uint32_t cnt = (uint32_t)__shfl((int)my_cnt, src, kWave);
-    // zero the other buffer's leftovers of the pass before last (this pass's buffer is still being read)
-    for (int i = threadIdx.x; i < NW * 256; i += NT) (&sm.hist[buf ^ 1][0][0])[i] = 0u;
-    need -= above;
+    __syncthreads();
+    const uint32_t bin = sm.bin, cnt = sm.cnt;
+    need -= sm.above;
     det_val |= (uint64_t)bin << shift;
     det_mask |= (uint64_t)dmask << shift;
     nb = shift;
-    buf ^= 1;
     __syncthreads();
     if (cnt == need) break;  // the whole bin is wanted: no need to look at lower digits
   }
-  det_mask_out = det_mask; det_val_out = det_val; need_out = need;
-}
 
-// On return: bit e of sel_mask is set iff element (tid, e) is among the k largest
-// (k must not exceed the number of present keys); out_pos is the number of
-// selected elements that precede this thread's in order index.
-template <int NT, int E>
-__device__ void block_select_topk(const uint64_t (&key)[E], int k, SelectSmem<NT>& sm,
-                                  uint32_t& sel_mask, int& out_pos) {
-  static_assert(E <= 32, "selection mask is 32 bits wide");
-  uint64_t det_mask, det_val;
-  uint32_t need;
-  block_select_threshold<NT, E>(key, k, sm, det_mask, det_val, need);
-  // classify and place: prefix-greater elements are in; of the prefix-equal ones
-  // the first `need` in order index are in.
+  // 3. classify and place: prefix-greater elements are in; of the prefix-equal ones
+  //    the first `need` in order index are in.
   uint32_t gt = 0, eq = 0, cg = 0, ce = 0;
 #pragma unroll
   for (int e = 0; e < E; ++e) {
