@@ -19,12 +19,15 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "shadowkv_oracle.c")
-_LIB = os.path.join(_HERE, "liboracle_shadowkv.so")
+# SHADOWKV_ORACLE_LIB points the wrapper at another build of the oracle (used by the mutation test only)
+_LIB = os.environ.get("SHADOWKV_ORACLE_LIB", os.path.join(_HERE, "liboracle_shadowkv.so"))
 _lib = None
 
 
 def build(force: bool = False) -> str:
     """Compile the oracle if the library is missing or older than its source."""
+    if "SHADOWKV_ORACLE_LIB" in os.environ:
+        return _LIB
     stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
     if force or stale:
         cmd = ["gcc", "-std=c99", "-O2", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",

@@ -1,0 +1,61 @@
+"""The pins must notice plausible mistakes: each mutant below plants ONE mistake in a copy of the
+oracle's C source (a dropped term, a wrong sign or index, a transposed operand, a wrong tie rule),
+builds it, and runs the pin tests against it in a subprocess.  Every mutant has to fail them.
+CPU only; nothing here touches the GPU path."""
+import os
+import subprocess
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+SRC = os.path.join(ROOT, "oracle", "shadowkv_oracle.c")
+
+MUTANTS = [
+    ("rope-sign", "x[i] = x0 * cs - x1 * sn;", "x[i] = x0 * cs + x1 * sn;"),
+    ("rope-frequency", "-2.0 * (double)i / (double)p->head_dim", "-1.0 * (double)i / (double)p->head_dim"),
+    ("rope-pairing", "double x0 = x[i], x1 = x[i + half];", "double x0 = x[i], x1 = x[(i + 1) % half + half];"),
+    ("score-scale-dropped", "P[g * n_c + j] = dot * scale;", "P[g * n_c + j] = dot;"),
+    ("group-max-is-min", "if (P[g * n_c + j] > best) best = P[g * n_c + j];",
+     "if (best == -INFINITY || P[g * n_c + j] < best) best = P[g * n_c + j];"),
+    ("normaliser-dropped", "double lse = mx + log(se);", "double lse = 0.0 * se;"),
+    ("head-mapping", "const uint16_t *qg = q + (bi * hq + h * G + g) * d;\n      double mx = -INFINITY;\n      for (int64_t j = 0; j < n_c; ++j) {",
+     "const uint16_t *qg = q + (bi * hq + g * hkv + h) * d;\n      double mx = -INFINITY;\n      for (int64_t j = 0; j < n_c; ++j) {"),
+    ("mean-not-divided", "C[j * d + x] = acc / (double)c;", "C[j * d + x] = acc;"),
+    ("cosine-max-not-min", "if (cs < mn) mn = cs;", "if (mn == INFINITY || cs > mn) mn = cs;"),
+    ("b-transposed", "bf16_to_f64(B[((u * r) + rho) * d + x])", "bf16_to_f64(B[((u * d) + x) * r + rho])"),
+    ("position-offset-dropped", "rope_inplace(p, Kt + row * d, pos0 + (double)n);", "rope_inplace(p, Kt + row * d, (double)n);"),
+    ("tie-rule-reversed", "return (x->idx > y->idx) - (x->idx < y->idx);", "return (x->idx < y->idx) - (x->idx > y->idx);"),
+    ("attention-not-normalised", "double ov = T ? acc / se : 0.0;", "double ov = T ? acc : 0.0 * se;"),
+    ("value-of-wrong-token", "Vt[row * d + x] = bf16_to_f64(value_store[(u * s + n) * d + x]);",
+     "Vt[row * d + x] = bf16_to_f64(value_store[(u * s + ch * c) * d + x]);"),
+    ("outlier-order-by-max", "m[j].key = -mn;", "m[j].key = mn;"),
+]
+
+
+@pytest.mark.parametrize("name,old,new", MUTANTS, ids=[m[0] for m in MUTANTS])
+def test_pins_catch_mutant(tmp_path, name, old, new):
+    text = open(SRC).read()
+    assert text.count(old) >= 1, f"mutant {name}: pattern not found in the oracle source"
+    mutated = text.replace(old, new, 1)
+    c_file = tmp_path / "mutant.c"
+    so_file = tmp_path / "libmutant.so"
+    c_file.write_text(mutated)
+    subprocess.run(["gcc", "-std=c99", "-O1", "-fopenmp", "-fPIC", "-shared", "-w", "-o", str(so_file), str(c_file),
+                    "-lm"], check=True)
+    env = dict(os.environ, SHADOWKV_ORACLE_LIB=str(so_file))
+    res = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", "test_oracle_pins.py"), "-x", "-q",
+                          "-p", "no:cacheprovider"], cwd=ROOT, env=env, stdout=subprocess.PIPE,
+                         stderr=subprocess.STDOUT, text=True)
+    assert res.returncode != 0, f"mutant '{name}' passed every pin:\n{res.stdout[-2000:]}"
+
+
+def test_unmutated_source_passes_through_the_same_route(tmp_path):
+    so_file = tmp_path / "liboracle.so"
+    subprocess.run(["gcc", "-std=c99", "-O1", "-fopenmp", "-fPIC", "-shared", "-w", "-o", str(so_file), SRC, "-lm"],
+                   check=True)
+    env = dict(os.environ, SHADOWKV_ORACLE_LIB=str(so_file))
+    res = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", "test_oracle_pins.py"), "-x", "-q",
+                          "-p", "no:cacheprovider"], cwd=ROOT, env=env, stdout=subprocess.PIPE,
+                         stderr=subprocess.STDOUT, text=True)
+    assert res.returncode == 0, res.stdout[-2000:]
