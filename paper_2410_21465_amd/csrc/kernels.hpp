@@ -49,7 +49,7 @@ hipError_t launch_gather_values(const bf16_t* store, const int32_t* sel_ids, bf1
                                 int s, int c, int k, hipStream_t st);
 
 // ---- attention over [outliers ; recent] and [selected chunks], keys rebuilt in-kernel ----
-// K_sparse = RoPE(Gather(A, I) B) is formed per 32-row block on the matrix cores and consumed
+// K_sparse = RoPE(Gather(A, I) B) is formed per 16-row block on the matrix cores and consumed
 // from registers.  Split i covers selected rows [i*sparse_split_len, ...) and resident rows
 // [i*res_split_len, ...); a combine kernel merges the splits into `out`.
 struct AttnArgs {
@@ -71,6 +71,7 @@ struct AttnArgs {
   bf16_t* out;              // [b, h_q, d]
   int batch, hq, hkv, d, s, c, o, k, w, r, r32, rp;
   int res_split_len, sparse_split_len, n_splits;
+  int c_shift;              // log2(c) when c is a power of two, else -1
   float scale_log2;         // softmax scale * log2(e)
   RopeFreqs freqs;
 };

@@ -7,7 +7,7 @@
 // workgroup owns one split plus an equal share of the unit's resident tokens (outliers, recent),
 // for up to 8 query heads of the GQA group, so K and V are touched once per group.
 //   * resident rows: K rows are read as stored (bf16);
-//   * selected rows: the keys never exist in memory.  Each wave gathers 32 rows of A straight
+//   * selected rows: the keys never exist in memory.  Each wave gathers 16 rows of A straight
 //     into MFMA operand layout, multiplies by B^T staged in LDS (v_mfma_f32_16x16x32_bf16, fp32
 //     accumulate), rotates the accumulators in registers (the RoPE partner i + d/2 of a column
 //     sits in the same lane, d/32 column blocks away), and forms q.K from the same registers; a
@@ -114,31 +114,113 @@ struct OnlineSoftmax {
 template <int D, int GH, int KSMAX, bool FAST4>
 __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
   constexpr int EPL = D / 16, NB = D / 16, HB = NB / 2;
-  extern __shared__ __align__(16) bf16_t Bt[];  // [D][rp], element (n, kk) = B[kk][n]
+  constexpr int NT = FAST4 ? 1 : 4;  // token positions a lane keeps per block (FAST4: the first of 4 consecutive)
+  extern __shared__ __align__(16) bf16_t Bt[];  // [D][rp], element (n, kk) = B[kk][n]; then int tokb[]
   __shared__ float sm_acc[4][GH][D];
   __shared__ float sm_m[4][GH], sm_l[4][GH];
   const int unit = blockIdx.y, split = blockIdx.x, g0 = blockIdx.z * GH;
   const int G = a.hq / a.hkv, b = unit / a.hkv, h = unit % a.hkv;
   const size_t head0 = (size_t)b * a.hq + (size_t)h * G + g0;
-  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform: keeps the row loops scalar
   const int sub = lane & 15, rg = lane >> 4;
   const int oc = a.o * a.c, kc = a.k * a.c;
-  const int32_t* ids = a.sel_ids + (size_t)unit * a.k;
   const int r = a.r, rp = a.rp, r32 = a.r32;
+  const int s_begin = split * a.sparse_split_len;
+  const int s_end = min(kc, s_begin + a.sparse_split_len);
+  const int cshift = a.c_shift;  // log2(c) when c is a power of two, else -1
+  auto chunk_of = [&](int i) { return cshift >= 0 ? i >> cshift : i / a.c; };
+  const int ch_begin = chunk_of(s_begin);
+
+  // ---- first token of every selected chunk this split touches, into LDS.  Ids are clamped: a bad id
+  //      can never address outside A or V.
+  int* tokb = reinterpret_cast<int*>(Bt + (size_t)D * rp);
+  if (s_begin < s_end) {
+    const int last_chunk = a.s / a.c - 1;
+    const int32_t* ids = a.sel_ids + (size_t)unit * a.k;
+    const int n_ch = chunk_of(s_end - 1) - ch_begin + 1;
+    for (int idx = threadIdx.x; idx < n_ch; idx += 256) tokb[idx] = min(max(ids[ch_begin + idx], 0), last_chunk) * a.c;
+  }
+  __syncthreads();
+
+  // ---- one 16-row block of selected tokens: the lane's A row in MFMA operand layout (row = lane % 16)
+  //      and the V slices of the four rows whose logits it will hold (accumulator layout: rows 4*(lane/16)+j).
+  //      Rows past the end of the split are clamped onto its last rows; their logits are masked later.
+  const int ksteps = r32 / 32;
+  auto load_block = [&](int row0, bf16x8 (&af)[KSMAX], uint32_t (&vraw)[4][EPL / 2], int (&tok)[NT], bool (&okr)[NT]) {
+    {
+      const int i = min(row0 + sub, s_end - 1);
+      const int ch = chunk_of(i);
+      const size_t n = (size_t)(tokb[ch - ch_begin] + (i - ch * a.c));
+      const bf16_t* arow = a.A + ((size_t)b * a.s + n) * r;
+      // every load is issued (a fixed number in flight per block); rank positions past r read the row's
+      // last 16 bytes instead and are zeroed when the block is taken up
+#pragma unroll
+      for (int ks = 0; ks < KSMAX; ++ks) {
+        const int kk = ks * 32 + rg * 8;
+        uint4 wv = *reinterpret_cast<const uint4*>(arow + min(kk, r - 8));
+        af[ks] = *reinterpret_cast<bf16x8*>(&wv);
+      }
+    }
+    if constexpr (FAST4) {
+      const int i0 = row0 + rg * 4;
+      okr[0] = i0 < s_end;
+      const int ic = min(i0, s_end - 4);
+      const int ch = chunk_of(ic);
+      const int n0 = tokb[ch - ch_begin] + (ic - ch * a.c);
+      tok[0] = n0;
+      const bf16_t* vp = (a.v_sparse ? a.v_sparse + ((size_t)unit * kc + ic) * D
+                                     : a.v_store + ((size_t)unit * a.s + n0) * D) + sub * EPL;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) load_raw<EPL>(vp + (size_t)j * D, vraw[j]);
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int i = row0 + rg * 4 + j;
+        okr[j] = i < s_end;
+        const int ic = min(i, s_end - 1);
+        const int ch = chunk_of(ic);
+        const int n = tokb[ch - ch_begin] + (ic - ch * a.c);
+        tok[j] = n;
+        const bf16_t* vp = a.v_sparse ? a.v_sparse + ((size_t)unit * kc + ic) * D
+                                      : a.v_store + ((size_t)unit * a.s + n) * D;
+        load_raw<EPL>(vp + sub * EPL, vraw[j]);
+      }
+    }
+  };
+
+  // first block of this wave: in flight while B^T is staged and the resident rows are processed
+  bf16x8 afN[KSMAX];
+  uint32_t vN[4][EPL / 2];
+  int tokN[NT];
+  bool okN[NT];
+  if (s_begin < s_end) load_block(s_begin + wave * 16, afN, vN, tokN, okN);
 
   // ---- B^T of this KV head into LDS (zero beyond rank r).  A wave reads 16 rank rows x 64 bytes
   //      per load and scatters them as 16-bit LDS writes.
   {
+    constexpr int NBI = (KSMAX * 32 * (D / 8) + 255) / 256;  // 16-byte pieces per thread
     const bf16_t* Bu = a.B + (size_t)unit * r * D;
-    for (int idx = threadIdx.x; idx < r32 * (D / 8); idx += 256) {
+    const int pieces = r32 * (D / 8);
+    uint4 bw[NBI];
+    int dst[NBI];
+#pragma unroll
+    for (int it = 0; it < NBI; ++it) {
+      const int idx = min((int)threadIdx.x + it * 256, pieces - 1);
       const int n8 = (idx & 3) + 4 * (idx / (4 * r32)), kk = (idx >> 2) % r32;
-      uint4 wv = make_uint4(0u, 0u, 0u, 0u);
-      if (kk < r) wv = *reinterpret_cast<const uint4*>(Bu + (size_t)kk * D + n8 * 8);
-      const uint32_t w4[4] = {wv.x, wv.y, wv.z, wv.w};
+      bw[it] = *reinterpret_cast<const uint4*>(Bu + (size_t)min(kk, r - 1) * D + n8 * 8);
+      dst[it] = kk < r ? n8 * 8 * rp + kk : -(n8 * 8 * rp + kk) - 1;  // negative: store zeros
+    }
+#pragma unroll
+    for (int it = 0; it < NBI; ++it) {
+      // (threads past the last piece repeat it: same values to the same place, no branch)
+      const bool real = dst[it] >= 0;
+      const int at = real ? dst[it] : -(dst[it] + 1);
+      const uint32_t w4[4] = {real ? bw[it].x : 0u, real ? bw[it].y : 0u, real ? bw[it].z : 0u, real ? bw[it].w : 0u};
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        Bt[(n8 * 8 + 2 * i) * rp + kk] = (bf16_t)(w4[i] & 0xffffu);
-        Bt[(n8 * 8 + 2 * i + 1) * rp + kk] = (bf16_t)(w4[i] >> 16);
+        Bt[at + (2 * i) * rp] = (bf16_t)(w4[i] & 0xffffu);
+        Bt[at + (2 * i + 1) * rp] = (bf16_t)(w4[i] >> 16);
       }
     }
   }
@@ -159,10 +241,9 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
     const int n_res = oc + a.w;
     const int i_begin = min(n_res, split * a.res_split_len);
     const int i_end = min(n_res, i_begin + a.res_split_len);
-    for (int i0 = i_begin + wave * 8; i0 < i_end; i0 += 32) {
-      // two rows per lane group and step: rows i0 + rg and i0 + 4 + rg
-      uint32_t kraw[2][EPL / 2], vraw[2][EPL / 2];
-      bool ok[2];
+    // two rows per lane group and step: rows i0 + rg and i0 + 4 + rg; the next step's rows are loaded
+    // before the current ones are used
+    auto load_res = [&](int i0, uint32_t (&kraw)[2][EPL / 2], uint32_t (&vraw)[2][EPL / 2], bool (&ok)[2]) {
 #pragma unroll
       for (int x = 0; x < 2; ++x) {
         const int i = i0 + 4 * x + rg;
@@ -179,6 +260,8 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
         load_raw<EPL>(kp + sub * EPL, kraw[x]);
         load_raw<EPL>(vp + sub * EPL, vraw[x]);
       }
+    };
+    auto fold_res = [&](const uint32_t (&kraw)[2][EPL / 2], const uint32_t (&vraw)[2][EPL / 2], const bool (&ok)[2]) {
       float lg[2][GH];
 #pragma unroll
       for (int x = 0; x < 2; ++x) {
@@ -195,12 +278,28 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
         for (int g = 0; g < GH; ++g) lg[x][g] = ok[x] ? dot[g] : -INFINITY;
       }
       st.template fold<2>(lg, vraw);
+    };
+    if (i_begin < i_end) {
+      uint32_t kN[2][EPL / 2], vN2[2][EPL / 2];
+      bool okN2[2];
+      load_res(i_begin + wave * 8, kN, vN2, okN2);
+      for (int i0 = i_begin + wave * 8; i0 < i_end; i0 += 32) {
+        uint32_t kC[2][EPL / 2], vC[2][EPL / 2];
+        bool okC[2];
+#pragma unroll
+        for (int x = 0; x < 2; ++x) {
+          okC[x] = okN2[x];
+#pragma unroll
+          for (int e = 0; e < EPL / 2; ++e) { kC[x][e] = kN[x][e]; vC[x][e] = vN2[x][e]; }
+        }
+        load_res(i0 + 32, kN, vN2, okN2);  // rows past the end are clamped and masked
+        fold_res(kC, vC, okC);
+      }
     }
   }
 
   // ---------------- selected chunks: rebuild keys on the matrix cores ----------------
   {
-    const int last_chunk = a.s / a.c - 1;  // ids are clamped: a bad id can never address outside A or V
     // q in accumulator-column layout (column nb*16 + sub), pre-scaled to log2 units
     float qc[GH][NB];
 #pragma unroll
@@ -226,127 +325,93 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
     }
     __syncthreads();  // B^T is in place
 
-    const int s_begin = split * a.sparse_split_len;
-    const int s_end = min(kc, s_begin + a.sparse_split_len);
-    const int ksteps = r32 / 32;
-    const bool ragged_rank = (r & 31) != 0;  // last rank step only partly backed by A
-    for (int row0 = s_begin + wave * 32; row0 < s_end; row0 += 128) {
-      // -- this lane's A rows (operand layout: row = lane % 16 of each 16-row tile), all loads up front.
-      //    Rows past the end of the split are clamped onto its last row; their logits are masked below.
-      bf16x8 af[KSMAX][2];
-#pragma unroll
-      for (int mt = 0; mt < 2; ++mt) {
-        const int i = min(row0 + mt * 16 + sub, s_end - 1);
-        const int ch = i / a.c, t = i - ch * a.c;
-        const size_t n = (size_t)min(max(ids[ch], 0), last_chunk) * a.c + t;
-        const bf16_t* arow = a.A + ((size_t)b * a.s + n) * r + rg * 8;
-#pragma unroll
-        for (int ks = 0; ks < KSMAX; ++ks) {
-          uint4 wv = make_uint4(0u, 0u, 0u, 0u);
-          if (ks < ksteps && (!ragged_rank || ks * 32 + rg * 8 < r)) wv = *reinterpret_cast<const uint4*>(arow + ks * 32);
-          af[ks][mt] = *reinterpret_cast<bf16x8*>(&wv);
-        }
-      }
-      // -- rows whose logits this lane will hold (accumulator layout: rows 4*(lane/16)+j), their V slices
-      uint32_t vraw[8][EPL / 2];
-      int tok[2][FAST4 ? 1 : 4];
-      bool okr[2][FAST4 ? 1 : 4];
-#pragma unroll
-      for (int mt = 0; mt < 2; ++mt) {
-        if constexpr (FAST4) {
-          const int i0 = row0 + mt * 16 + rg * 4;
-          okr[mt][0] = i0 < s_end;
-          const int ic = min(i0, s_end - 4);
-          const int ch = ic / a.c, t = ic - ch * a.c;
-          const int n0 = min(max(ids[ch], 0), last_chunk) * a.c + t;
-          tok[mt][0] = n0;
-          const bf16_t* vp = (a.v_sparse ? a.v_sparse + ((size_t)unit * kc + ic) * D
-                                         : a.v_store + ((size_t)unit * a.s + n0) * D) + sub * EPL;
-#pragma unroll
-          for (int j = 0; j < 4; ++j) load_raw<EPL>(vp + (size_t)j * D, vraw[mt * 4 + j]);
-        } else {
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const int i = row0 + mt * 16 + rg * 4 + j;
-            okr[mt][j] = i < s_end;
-            const int ic = min(i, s_end - 1);
-            const int ch = ic / a.c, t = ic - ch * a.c;
-            const int n = min(max(ids[ch], 0), last_chunk) * a.c + t;
-            tok[mt][j] = n;
-            const bf16_t* vp = a.v_sparse ? a.v_sparse + ((size_t)unit * kc + ic) * D
-                                          : a.v_store + ((size_t)unit * a.s + n) * D;
-            load_raw<EPL>(vp + sub * EPL, vraw[mt * 4 + j]);
-          }
-        }
-      }
+    auto compute_block = [&](int row0, const bf16x8 (&af)[KSMAX], const uint32_t (&vraw)[4][EPL / 2],
+                             const int (&tok)[NT], const bool (&okr)[NT]) {
       // -- K tile = A_sel * B on the matrix cores
-      f32x4 acc[2][NB];
+      f32x4 acc[NB];
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) acc[mt][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int nb = 0; nb < NB; ++nb) acc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int ks = 0; ks < KSMAX; ++ks) {
         if (ks < ksteps) {
 #pragma unroll
           for (int nb = 0; nb < NB; ++nb) {
             const bf16x8 bfrag = *reinterpret_cast<const bf16x8*>(&Bt[(nb * 16 + sub) * rp + ks * 32 + rg * 8]);
-            acc[0][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[ks][0], bfrag, acc[0][nb], 0, 0, 0);
-            acc[1][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[ks][1], bfrag, acc[1][nb], 0, 0, 0);
+            acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[ks], bfrag, acc[nb], 0, 0, 0);
           }
         }
       }
-      // -- RoPE and q.K row by row; the logits of the 8 rows x GH heads stay in registers
-      float lg[8][GH];
+      // -- RoPE and q.K row by row; the logits of the 4 rows x GH heads stay in registers
+      float lg[4][GH];
+      float cs[HB], sn[HB];
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt) {
-        float cs[HB], sn[HB];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const bool ok = okr[mt][FAST4 ? 0 : j];
-          if (!FAST4 || j == 0) {
-            const double pos = pos0 + (double)tok[mt][FAST4 ? 0 : j];
-#pragma unroll
-            for (int nb = 0; nb < HB; ++nb) {
-              double rev = pos * frev[nb];
-              rev -= rint(rev);
-              const float rv = (float)rev;  // revolutions in [-0.5, 0.5]
-              sn[nb] = __builtin_amdgcn_sinf(rv);
-              cs[nb] = __builtin_amdgcn_cosf(rv);
-            }
-          } else {
-#pragma unroll
-            for (int nb = 0; nb < HB; ++nb) {
-              const float c1 = cs[nb] * cd[nb] - sn[nb] * sd[nb];
-              sn[nb] = sn[nb] * cd[nb] + cs[nb] * sd[nb];
-              cs[nb] = c1;
-            }
-          }
-          float kr[NB];
+      for (int j = 0; j < 4; ++j) {
+        const bool ok = okr[FAST4 ? 0 : j];
+        if (!FAST4 || j == 0) {
+          const double pos = pos0 + (double)tok[FAST4 ? 0 : j];
 #pragma unroll
           for (int nb = 0; nb < HB; ++nb) {
-            const float x0 = acc[mt][nb][j], x1 = acc[mt][nb + HB][j];
-            kr[nb] = x0 * cs[nb] - x1 * sn[nb];
-            kr[nb + HB] = x1 * cs[nb] + x0 * sn[nb];
+            double rev = pos * frev[nb];
+            rev -= rint(rev);
+            const float rv = (float)rev;  // revolutions in [-0.5, 0.5]
+            sn[nb] = __builtin_amdgcn_sinf(rv);
+            cs[nb] = __builtin_amdgcn_cosf(rv);
           }
-          if (a.k_sparse_out && ok && g0 == 0) {
-            float* orow = a.k_sparse_out + ((size_t)unit * kc + (row0 + mt * 16 + rg * 4 + j)) * D;
+        } else {
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) orow[nb * 16 + sub] = kr[nb];
+          for (int nb = 0; nb < HB; ++nb) {
+            const float c1 = cs[nb] * cd[nb] - sn[nb] * sd[nb];
+            sn[nb] = sn[nb] * cd[nb] + cs[nb] * sd[nb];
+            cs[nb] = c1;
           }
-          float dot[GH];
-#pragma unroll
-          for (int g = 0; g < GH; ++g) {
-            dot[g] = 0.f;
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) dot[g] = fmaf(kr[nb], qc[g][nb], dot[g]);
-          }
-          allsum16_vec<GH>(dot);
-#pragma unroll
-          for (int g = 0; g < GH; ++g) lg[mt * 4 + j][g] = ok ? dot[g] : -INFINITY;
         }
+        float kr[NB];
+#pragma unroll
+        for (int nb = 0; nb < HB; ++nb) {
+          const float x0 = acc[nb][j], x1 = acc[nb + HB][j];
+          kr[nb] = x0 * cs[nb] - x1 * sn[nb];
+          kr[nb + HB] = x1 * cs[nb] + x0 * sn[nb];
+        }
+        if (a.k_sparse_out && ok && g0 == 0) {
+          float* orow = a.k_sparse_out + ((size_t)unit * kc + (row0 + rg * 4 + j)) * D;
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb) orow[nb * 16 + sub] = kr[nb];
+        }
+        float dot[GH];
+#pragma unroll
+        for (int g = 0; g < GH; ++g) {
+          dot[g] = 0.f;
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb) dot[g] = fmaf(kr[nb], qc[g][nb], dot[g]);
+        }
+        allsum16_vec<GH>(dot);
+#pragma unroll
+        for (int g = 0; g < GH; ++g) lg[j][g] = ok ? dot[g] : -INFINITY;
       }
-      st.template fold<8>(lg, vraw);
+      st.template fold<4>(lg, vraw);
+    };
+
+    // the four waves take 16-row blocks in turn; the next block of a wave is requested before the
+    // current one is used (past the end of the split the request re-reads the split's last rows)
+    for (int row0 = s_begin + wave * 16; row0 < s_end; row0 += 64) {
+      bf16x8 afC[KSMAX];
+      uint32_t vC[4][EPL / 2];
+      int tokC[NT];
+      bool okC[NT];
+#pragma unroll
+      for (int ks = 0; ks < KSMAX; ++ks) {
+        uint4 wv = *reinterpret_cast<uint4*>(&afN[ks]);
+        if (ks * 32 + rg * 8 >= r) wv = make_uint4(0u, 0u, 0u, 0u);
+        afC[ks] = *reinterpret_cast<bf16x8*>(&wv);
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int e = 0; e < EPL / 2; ++e) vC[j][e] = vN[j][e];
+#pragma unroll
+      for (int j = 0; j < NT; ++j) { tokC[j] = tokN[j]; okC[j] = okN[j]; }
+      load_block(row0 + 64, afN, vN, tokN, okN);
+      compute_block(row0, afC, vC, tokC, okC);
     }
   }
 
@@ -431,7 +496,8 @@ template <int D>
 static hipError_t launch_attention_d(const AttnArgs& a, hipStream_t st) {
   const int G = a.hq / a.hkv;
   const int gh = attention_heads_per_group(G);
-  const size_t lds = (size_t)D * a.rp * sizeof(bf16_t);
+  // B^T, then the first token of each chunk a split touches
+  const size_t lds = (size_t)D * a.rp * sizeof(bf16_t) + ((size_t)a.sparse_split_len / a.c + 2) * sizeof(int);
   dim3 grid(a.n_splits, a.batch * a.hkv, G / gh);
   hipError_t e;
   switch (gh) {

@@ -105,7 +105,7 @@ AttnPlan plan_attention(const Shape& sh) {
   for (long cand : {512l, 256l, 128l, 64l}) if (kc * groups / cand >= 512) { len = cand; break; }
   if (const char* ov = std::getenv("SHADOWKV_SPARSE_SPLIT")) {  // tuning override: rows per split
     const long v = std::atol(ov);
-    if (v >= 32 && v <= 4096 && v % 32 == 0) len = v;
+    if (v >= 32 && v <= 1024 && v % 32 == 0) len = v;
   }
   ap.sparse_split_len = (int)len;
   ap.n_splits = (int)((kc + len - 1) / len);
@@ -431,6 +431,8 @@ int shadowkv_decode_step(const shadowkv_params* params, const shadowkv_bf16* q, 
   t.batch = sh.b; t.hq = sh.hq; t.hkv = sh.hkv; t.d = sh.d; t.s = sh.s; t.c = sh.c; t.o = sh.o; t.k = sh.k; t.w = sh.w;
   t.r = sh.r; t.r32 = (sh.r + 31) / 32 * 32; t.rp = t.r32 + 8;  // +8: 16-byte multiple that spreads LDS banks
   t.res_split_len = L.attn.res_split_len; t.sparse_split_len = L.attn.sparse_split_len; t.n_splits = L.attn.n_splits;
+  t.c_shift = -1;
+  for (int sft = 0; sft < 7; ++sft) if ((1 << sft) == sh.c) t.c_shift = sft;
   t.scale_log2 = (float)(scale * 1.4426950408889634074);
   t.freqs = freqs;
   e = launch_attention(t, st);
