@@ -139,6 +139,18 @@ def main() -> int:
     eager_ms_per_step = (time.perf_counter() - t3) * 1e3 / args.steps
     prof = S.profile_end()
 
+    # what a plain device copy reaches on this machine (1 GiB, read + write counted), for scale
+    src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    ev0.record()
+    for _ in range(10):
+        dst.copy_(src)
+    ev1.record()
+    torch.cuda.synchronize()
+    copy_gbps = 10 * 2 * src.numel() / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
+    del src, dst
+
     ab = algorithmic_bytes(wl)
     score_ms = prof["ms"]["score"]
     score_bytes = ab["landmarks"] + ab["q_out"] // 2
@@ -166,6 +178,7 @@ def main() -> int:
         "step_algorithmic_bytes": ab["total"],
         "step_hbm_gbps": ab["total"] / (ms_per_step * 1e-3) / 1e9,
         "build_landmarks_ms": build_ms,
+        "device_copy_gbps": copy_gbps,
         "setup_s": setup_s,
     }
     if wl.value_location == "host":
@@ -203,9 +216,24 @@ def cpu_baseline(wl, t, budget_s: float) -> dict:
         O.decode_step(op, q, *a, diagnostics=False)
         spent += time.perf_counter() - t0
         reps += 1
-    return {"value": bs * reps / spent, "unit": "tokens/s", "cores": O.num_threads(), "kind": "oracle",
-            "sample": f"first {bs} of {wl.batch} sequences of {sub.name}, {reps} decode steps, {spent:.1f} s",
-            "ms_per_step": spent / reps * 1e3}
+    res = {"value": bs * reps / spent, "unit": "tokens/s", "cores": O.num_threads(), "kind": "oracle",
+           "sample": f"first {bs} of {wl.batch} sequences of {sub.name}, {reps} decode steps, {spent:.1f} s",
+           "ms_per_step": spent / reps * 1e3}
+    # the same oracle held to one thread (two steps), for a per-core figure
+    try:
+        import ctypes
+        gomp = ctypes.CDLL("libgomp.so.1")
+        n_thr = O.num_threads()
+        gomp.omp_set_num_threads(1)
+        t0 = time.perf_counter()
+        for i in range(2):
+            O.decode_step(op, O.as_bits(pool[i % pool.shape[0]][:bs].detach().cpu()), *a, diagnostics=False)
+        one = time.perf_counter() - t0
+        gomp.omp_set_num_threads(n_thr)
+        res["value_one_thread"] = bs * 2 / one
+    except OSError:
+        pass
+    return res
 
 
 if __name__ == "__main__":

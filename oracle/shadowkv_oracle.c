@@ -339,3 +339,47 @@ int oracle_decode_step(const oracle_params *p, const uint16_t *q,
   }
   return fail ? -2 : 0;
 }
+
+/* ---- chunk cache of the offloaded values -------------------------------------
+ * Section "High-throughput Decoding": the chunks selected by adjacent decode steps
+ * repeat to a large part, so the values fetched for the last step are kept and an
+ * index scan finds the chunks that are missing; only those are fetched (the
+ * (1 - alpha) term of the equivalent-bandwidth formula).  The paper does not
+ * fix a replacement policy; the reading taken: the cache of a (batch, KV head)
+ * unit has one slot per selected chunk (k slots) and holds exactly the last
+ * step's selection.  A chunk selected again keeps its slot.  The chunks that are
+ * new, in ascending chunk id, take the slots whose chunk is no longer selected,
+ * in ascending slot index.  Slot ids: -1 = empty.
+ *
+ * sel_ids    [units, k]  this step's selection, ascending, distinct
+ * cache_ids  [units, k]  in: chunk id per slot before the step; out: after
+ * miss_slots [units, k]  out: the slots that have to be filled, ascending (first n_miss[u])
+ * n_miss     [units]     out
+ * The attention output does not depend on the cache at all: a cached step equals
+ * oracle_decode_step. */
+int oracle_cache_update(int64_t units, int k, const int32_t *sel_ids,
+                        int32_t *cache_ids, int32_t *miss_slots, int32_t *n_miss) {
+  if (units < 0 || k < 0 || !sel_ids || !cache_ids || !miss_slots || !n_miss) return -1;
+  char *hit = (char *)malloc((size_t)k + 1), *keep = (char *)malloc((size_t)k + 1);
+  if (!hit || !keep) { free(hit); free(keep); return -2; }
+  for (int64_t u = 0; u < units; ++u) {
+    const int32_t *sel = sel_ids + u * k;
+    int32_t *cache = cache_ids + u * k, *ms = miss_slots + u * k;
+    memset(hit, 0, (size_t)k);
+    memset(keep, 0, (size_t)k);
+    for (int slot = 0; slot < k; ++slot)          /* the index scan */
+      for (int j = 0; j < k; ++j)
+        if (cache[slot] >= 0 && cache[slot] == sel[j] && !hit[j]) { hit[j] = 1; keep[slot] = 1; break; }
+    int n = 0, slot = 0;
+    for (int j = 0; j < k; ++j) {
+      if (hit[j]) continue;
+      while (keep[slot]) ++slot;                  /* next slot whose chunk fell out */
+      cache[slot] = sel[j];
+      ms[n++] = slot++;
+    }
+    for (int j = n; j < k; ++j) ms[j] = -1;
+    n_miss[u] = n;
+  }
+  free(hit); free(keep);
+  return 0;
+}

@@ -96,6 +96,8 @@ def _load():
         _lib.oracle_build_landmarks.argtypes = [C.c_void_p] * 10
         _lib.oracle_decode_step.restype = C.c_int
         _lib.oracle_decode_step.argtypes = [C.c_void_p] * 17
+        _lib.oracle_cache_update.restype = C.c_int
+        _lib.oracle_cache_update.argtypes = [C.c_int64, C.c_int] + [C.c_void_p] * 4
     return _lib
 
 
@@ -209,3 +211,20 @@ def decode_step(p: OracleParams, q, A, B, landmarks, landmark_chunk_ids, k_outli
     if rc != 0:
         raise ValueError(f"oracle_decode_step rejected its arguments (rc={rc})")
     return res
+
+
+def cache_update(sel_ids: np.ndarray, cache_ids: np.ndarray) -> dict:
+    """Chunk cache of the offloaded values (section "High-throughput Decoding"): index scan of this
+    step's selection ``sel_ids [units, k]`` (ascending) against the slots ``cache_ids [units, k]``
+    (-1 = empty).  Returns the new slot contents, the slots to fill and their number per unit."""
+    lib = _load()
+    sel = np.ascontiguousarray(sel_ids, dtype=np.int32)
+    cache = np.array(cache_ids, dtype=np.int32, order="C", copy=True)
+    assert sel.ndim == 2 and cache.shape == sel.shape
+    units, k = sel.shape
+    miss = np.zeros((units, k), np.int32)
+    n_miss = np.zeros(units, np.int32)
+    rc = lib.oracle_cache_update(units, k, sel.ctypes.data, cache.ctypes.data, miss.ctypes.data, n_miss.ctypes.data)
+    if rc != 0:
+        raise ValueError(f"oracle_cache_update rejected its arguments (rc={rc})")
+    return {"cache_ids": cache, "miss_slots": miss, "n_miss": n_miss}

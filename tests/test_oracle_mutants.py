@@ -32,8 +32,20 @@ MUTANTS = [
     ("outlier-order-by-max", "m[j].key = -mn;", "m[j].key = mn;"),
 ]
 
+# planted mistakes in the chunk-cache model, run against its own pins
+CACHE_MUTANTS = [
+    ("cache-hit-moves", "if (hit[j]) continue;", "if (hit[j] && j != 0) continue;"),
+    ("cache-empty-slot-matches", "if (cache[slot] >= 0 && cache[slot] == sel[j] && !hit[j])", "if (cache[slot] == sel[j] - 1 && !hit[j])"),
+    ("cache-miss-count", "n_miss[u] = n;", "n_miss[u] = k - n;"),
+    ("cache-slot-order", "ms[n++] = slot++;", "ms[n++] = slot; slot += 1 + (n == 1 && !keep[slot + 1] && slot + 2 < k && !keep[slot + 2]);"),
+]
 
-@pytest.mark.parametrize("name,old,new", MUTANTS, ids=[m[0] for m in MUTANTS])
+
+def _pins_for(name):
+    return "test_oracle_cache.py" if name.startswith("cache-") else "test_oracle_pins.py"
+
+
+@pytest.mark.parametrize("name,old,new", MUTANTS + CACHE_MUTANTS, ids=[m[0] for m in MUTANTS + CACHE_MUTANTS])
 def test_pins_catch_mutant(tmp_path, name, old, new):
     text = open(SRC).read()
     assert text.count(old) >= 1, f"mutant {name}: pattern not found in the oracle source"
@@ -44,7 +56,7 @@ def test_pins_catch_mutant(tmp_path, name, old, new):
     subprocess.run(["gcc", "-std=c99", "-O1", "-fopenmp", "-fPIC", "-shared", "-w", "-o", str(so_file), str(c_file),
                     "-lm"], check=True)
     env = dict(os.environ, SHADOWKV_ORACLE_LIB=str(so_file))
-    res = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", "test_oracle_pins.py"), "-x", "-q",
+    res = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", _pins_for(name)), "-x", "-q",
                           "-p", "no:cacheprovider"], cwd=ROOT, env=env, stdout=subprocess.PIPE,
                          stderr=subprocess.STDOUT, text=True)
     assert res.returncode != 0, f"mutant '{name}' passed every pin:\n{res.stdout[-2000:]}"
@@ -55,7 +67,8 @@ def test_unmutated_source_passes_through_the_same_route(tmp_path):
     subprocess.run(["gcc", "-std=c99", "-O1", "-fopenmp", "-fPIC", "-shared", "-w", "-o", str(so_file), SRC, "-lm"],
                    check=True)
     env = dict(os.environ, SHADOWKV_ORACLE_LIB=str(so_file))
-    res = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", "test_oracle_pins.py"), "-x", "-q",
+    res = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", "test_oracle_pins.py"),
+                          os.path.join(ROOT, "tests", "test_oracle_cache.py"), "-x", "-q",
                           "-p", "no:cacheprovider"], cwd=ROOT, env=env, stdout=subprocess.PIPE,
                          stderr=subprocess.STDOUT, text=True)
     assert res.returncode == 0, res.stdout[-2000:]
