@@ -48,6 +48,15 @@ hipError_t launch_select(const SelectArgs& a, const SelectPlan& plan, int src, i
 hipError_t launch_gather_values(const bf16_t* store, const int32_t* sel_ids, bf16_t* v_sparse, int units, int d,
                                 int s, int c, int k, hipStream_t st);
 
+// ---- chunk cache of the offloaded values: index scan, fetch of the missing chunks ------
+constexpr int kMaxCachedTopK = 8192;  // slots per unit the index-scan kernel handles (LDS, 16-bit ranks)
+hipError_t launch_cache_update(const int32_t* sel_ids, int32_t* cache_ids, int32_t* miss_slots, int32_t* n_miss,
+                               int32_t* n_miss_copy, int units, int k, hipStream_t st);
+hipError_t launch_gather_missing(const bf16_t* store, const int32_t* cache_ids, const int32_t* miss_slots,
+                                 const int32_t* n_miss, bf16_t* v_cache, int units, int d, int s, int c, int k,
+                                 hipStream_t st);
+hipError_t launch_fill_i32(int32_t* p, size_t n, int32_t value, hipStream_t st);
+
 // ---- attention over [outliers ; recent] and [selected chunks], keys rebuilt in-kernel ----
 // K_sparse = RoPE(Gather(A, I) B) is formed per 16-row block on the matrix cores and consumed
 // from registers.  Split i covers selected rows [i*sparse_split_len, ...) and resident rows

@@ -114,7 +114,7 @@ AttnPlan plan_attention(const Shape& sh) {
 }
 
 struct DecodeLayout {
-  size_t logits, partials, cand_key, cand_idx, sel_ids, k_sparse, v_sparse, part_acc, part_ml, total;
+  size_t logits, partials, cand_key, cand_idx, sel_ids, miss_slots, n_miss, k_sparse, v_sparse, part_acc, part_ml, total;
   SelectPlan sel;
   AttnPlan attn;
   int n_tiles;
@@ -131,6 +131,8 @@ DecodeLayout decode_layout(const Shape& sh) {
   L.cand_key = off; off += up((size_t)sh.units * L.sel.cand_stride * sizeof(uint64_t));
   L.cand_idx = off; off += up((size_t)sh.units * L.sel.cand_stride * sizeof(int32_t));
   L.sel_ids = off; off += up((size_t)sh.units * sh.k * sizeof(int32_t));
+  L.miss_slots = off; off += up((size_t)sh.units * sh.k * sizeof(int32_t));  // chunk cache: slots to fill
+  L.n_miss = off; off += up((size_t)sh.units * sizeof(int32_t));
   L.k_sparse = off; off += sh.keep_keys ? up(rows * sh.d * sizeof(float)) : 0;
   L.v_sparse = off; off += sh.stage ? up(rows * sh.d * sizeof(bf16_t)) : 0;
   L.part_acc = off; off += up(heads * L.attn.n_splits * sh.d * sizeof(float));
@@ -295,6 +297,7 @@ void* shadowkv_decode_workspace_view(const shadowkv_params* params, void* worksp
     case 1: return sh.stage ? ws + L.v_sparse : nullptr;
     case 2: return ws + L.sel_ids;
     case 3: return ws + L.logits;
+    case 4: return ws + L.miss_slots;
     default: return nullptr;
   }
 }
@@ -342,13 +345,20 @@ int shadowkv_build_landmarks(const shadowkv_params* params, const shadowkv_bf16*
   return SHADOWKV_OK;
 }
 
-int shadowkv_decode_step(const shadowkv_params* params, const shadowkv_bf16* q, const shadowkv_bf16* A,
-                         const shadowkv_bf16* B, const shadowkv_bf16* landmarks, const int32_t* landmark_chunk_ids,
-                         const shadowkv_bf16* k_outlier, const shadowkv_bf16* v_outlier,
-                         const shadowkv_bf16* k_local, const shadowkv_bf16* v_local,
-                         const shadowkv_bf16* value_store, const int32_t* pos_offset, shadowkv_bf16* out,
-                         int32_t* out_chunk_ids, void* workspace, size_t workspace_bytes, void* stream,
-                         void* side_stream) {
+// Value cache handed to a cached step (all device pointers).
+struct CacheIO {
+  bf16_t* values;        // [units, k*c, d]
+  int32_t* chunk_ids;    // [units, k], -1 = empty
+  int32_t* miss_count;   // optional [units]
+};
+
+static int decode_impl(const shadowkv_params* params, const shadowkv_bf16* q, const shadowkv_bf16* A,
+                       const shadowkv_bf16* B, const shadowkv_bf16* landmarks, const int32_t* landmark_chunk_ids,
+                       const shadowkv_bf16* k_outlier, const shadowkv_bf16* v_outlier,
+                       const shadowkv_bf16* k_local, const shadowkv_bf16* v_local,
+                       const shadowkv_bf16* value_store, const int32_t* pos_offset, const CacheIO* cache,
+                       shadowkv_bf16* out, int32_t* out_chunk_ids, void* workspace, size_t workspace_bytes,
+                       void* stream, void* side_stream) {
   Shape sh;
   int rc = check_params(params, true, &sh);
   if (rc != SHADOWKV_OK) return rc;
@@ -359,13 +369,18 @@ int shadowkv_decode_step(const shadowkv_params* params, const shadowkv_bf16* q, 
   if (!aligned16(q) || !aligned16(A) || !aligned16(B) || !aligned16(landmarks) || !aligned16(k_outlier) ||
       !aligned16(v_outlier) || !aligned16(k_local) || !aligned16(v_local) || !aligned16(value_store) || !aligned16(out))
     return fail_inval("tensor pointers must be 16-byte aligned");
+  if (cache) {
+    if (!cache->values || !cache->chunk_ids) return fail_inval("value_cache and cache_chunk_ids must not be NULL");
+    if (!aligned16(cache->values)) return fail_inval("value_cache must be 16-byte aligned");
+    if (sh.k > kMaxCachedTopK) return fail_inval("topk_chunks %d exceeds the chunk cache's limit of %d", sh.k, kMaxCachedTopK);
+  }
   const DecodeLayout L = decode_layout(sh);
   rc = check_workspace(workspace, workspace_bytes, L.total);
   if (rc != SHADOWKV_OK) return rc;
 
   hipStream_t st = static_cast<hipStream_t>(stream);
   hipStream_t side = static_cast<hipStream_t>(side_stream);
-  const bool fork = sh.stage && side && side != st;
+  const bool fork = (sh.stage || cache) && side && side != st;
   char* ws = static_cast<char*>(workspace);
   double* logits = reinterpret_cast<double*>(ws + L.logits);
   double2* partials = reinterpret_cast<double2*>(ws + L.partials);
@@ -404,7 +419,30 @@ int shadowkv_decode_step(const shadowkv_params* params, const shadowkv_bf16* q, 
   if (e != hipSuccess) return fail_hip("select chunks", e);
   prof_mark(st, pstep, 2);
   // 3. values of the selected chunks: staged by the gather kernel (side stream when given) ...
-  if (sh.stage) {
+  const int32_t* attn_ids = sel_ids;
+  if (cache) {
+    // index scan against last step's chunks, then only the missing chunks cross the link
+    int32_t* miss_slots = reinterpret_cast<int32_t*>(ws + L.miss_slots);
+    int32_t* n_miss = reinterpret_cast<int32_t*>(ws + L.n_miss);
+    e = launch_cache_update(sel_ids, cache->chunk_ids, miss_slots, n_miss, cache->miss_count, sh.units, sh.k, st);
+    if (e != hipSuccess) return fail_hip("cache update", e);
+    hipStream_t gs = st;
+    if (fork) {
+      if ((e = hipEventRecord(ev_fork, st)) != hipSuccess) return fail_hip("hipEventRecord", e);
+      if ((e = hipStreamWaitEvent(side, ev_fork, 0)) != hipSuccess) return fail_hip("hipStreamWaitEvent", e);
+      gs = side;
+    }
+    e = launch_gather_missing(value_store, cache->chunk_ids, miss_slots, n_miss, cache->values, sh.units, sh.d, sh.s,
+                              sh.c, sh.k, gs);
+    if (e != hipSuccess) return fail_hip("gather missing values", e);
+    if (fork) {
+      if ((e = hipEventRecord(ev_join, side)) != hipSuccess) return fail_hip("hipEventRecord", e);
+      if ((e = hipStreamWaitEvent(st, ev_join, 0)) != hipSuccess) return fail_hip("hipStreamWaitEvent", e);
+    }
+    // attention is invariant to the order of its key/value set: run it over the slots
+    attn_ids = cache->chunk_ids;
+    v_sparse = cache->values;
+  } else if (sh.stage) {
     hipStream_t gs = st;
     if (fork) {
       if ((e = hipEventRecord(ev_fork, st)) != hipSuccess) return fail_hip("hipEventRecord", e);
@@ -423,7 +461,7 @@ int shadowkv_decode_step(const shadowkv_params* params, const shadowkv_bf16* q, 
   AttnArgs t{};
   t.q = q; t.A = A; t.B = B; t.k_outlier = k_outlier; t.v_outlier = v_outlier;
   t.k_local = k_local; t.v_local = v_local; t.v_sparse = v_sparse; t.v_store = value_store;
-  t.sel_ids = sel_ids; t.pos_offset = pos_offset; t.inv_freq_dev = params->inv_freq;
+  t.sel_ids = attn_ids; t.pos_offset = pos_offset; t.inv_freq_dev = params->inv_freq;
   t.k_sparse_out = sh.keep_keys ? reinterpret_cast<float*>(ws + L.k_sparse) : nullptr;
   t.part_acc = reinterpret_cast<float*>(ws + L.part_acc);
   t.part_ml = reinterpret_cast<float2*>(ws + L.part_ml);
@@ -438,6 +476,47 @@ int shadowkv_decode_step(const shadowkv_params* params, const shadowkv_bf16* q, 
   e = launch_attention(t, st);
   if (e != hipSuccess) return fail_hip("attention", e);
   prof_mark(st, pstep, 4);
+  return SHADOWKV_OK;
+}
+
+int shadowkv_decode_step(const shadowkv_params* params, const shadowkv_bf16* q, const shadowkv_bf16* A,
+                         const shadowkv_bf16* B, const shadowkv_bf16* landmarks, const int32_t* landmark_chunk_ids,
+                         const shadowkv_bf16* k_outlier, const shadowkv_bf16* v_outlier,
+                         const shadowkv_bf16* k_local, const shadowkv_bf16* v_local,
+                         const shadowkv_bf16* value_store, const int32_t* pos_offset, shadowkv_bf16* out,
+                         int32_t* out_chunk_ids, void* workspace, size_t workspace_bytes, void* stream,
+                         void* side_stream) {
+  return decode_impl(params, q, A, B, landmarks, landmark_chunk_ids, k_outlier, v_outlier, k_local, v_local,
+                     value_store, pos_offset, nullptr, out, out_chunk_ids, workspace, workspace_bytes, stream,
+                     side_stream);
+}
+
+int shadowkv_decode_step_cached(const shadowkv_params* params, const shadowkv_bf16* q, const shadowkv_bf16* A,
+                                const shadowkv_bf16* B, const shadowkv_bf16* landmarks,
+                                const int32_t* landmark_chunk_ids, const shadowkv_bf16* k_outlier,
+                                const shadowkv_bf16* v_outlier, const shadowkv_bf16* k_local,
+                                const shadowkv_bf16* v_local, const shadowkv_bf16* value_store,
+                                const int32_t* pos_offset, shadowkv_bf16* value_cache, int32_t* cache_chunk_ids,
+                                int32_t* out_miss_count, shadowkv_bf16* out, int32_t* out_chunk_ids, void* workspace,
+                                size_t workspace_bytes, void* stream, void* side_stream) {
+  CacheIO c{value_cache, cache_chunk_ids, out_miss_count};
+  return decode_impl(params, q, A, B, landmarks, landmark_chunk_ids, k_outlier, v_outlier, k_local, v_local,
+                     value_store, pos_offset, &c, out, out_chunk_ids, workspace, workspace_bytes, stream, side_stream);
+}
+
+size_t shadowkv_value_cache_bytes(const shadowkv_params* params) {
+  Shape sh;
+  if (check_params(params, true, &sh) != SHADOWKV_OK) return 0;
+  return (size_t)sh.units * sh.k * sh.c * sh.d * sizeof(bf16_t);
+}
+
+int shadowkv_value_cache_reset(const shadowkv_params* params, int32_t* cache_chunk_ids, void* stream) {
+  Shape sh;
+  int rc = check_params(params, true, &sh);
+  if (rc != SHADOWKV_OK) return rc;
+  if (!cache_chunk_ids) return fail_inval("cache_chunk_ids is NULL");
+  hipError_t e = launch_fill_i32(cache_chunk_ids, (size_t)sh.units * sh.k, -1, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return fail_hip("cache reset", e);
   return SHADOWKV_OK;
 }
 

@@ -25,7 +25,8 @@ EXPORTS = (
     "shadowkv_build_landmarks", "shadowkv_decode_step", "shadowkv_build_workspace_bytes",
     "shadowkv_decode_workspace_bytes", "shadowkv_validate_params", "shadowkv_decode_workspace_view",
     "shadowkv_status_string", "shadowkv_last_error", "shadowkv_version", "shadowkv_shutdown",
-    "shadowkv_profile_begin", "shadowkv_profile_end",
+    "shadowkv_profile_begin", "shadowkv_profile_end", "shadowkv_decode_step_cached", "shadowkv_value_cache_bytes",
+    "shadowkv_value_cache_reset",
 )
 STAGES = ("score", "select", "gather_values", "attention")
 
@@ -64,6 +65,12 @@ def lib() -> C.CDLL:
         L.shadowkv_build_landmarks.argtypes = [vp] * 9 + [sz, vp]
         L.shadowkv_decode_step.restype = i32
         L.shadowkv_decode_step.argtypes = [vp] * 15 + [sz, vp, vp]
+        L.shadowkv_decode_step_cached.restype = i32
+        L.shadowkv_decode_step_cached.argtypes = [vp] * 18 + [sz, vp, vp]
+        L.shadowkv_value_cache_bytes.restype = sz
+        L.shadowkv_value_cache_bytes.argtypes = [vp]
+        L.shadowkv_value_cache_reset.restype = i32
+        L.shadowkv_value_cache_reset.argtypes = [vp, vp, vp]
         L.shadowkv_build_workspace_bytes.restype = sz
         L.shadowkv_build_workspace_bytes.argtypes = [vp]
         L.shadowkv_decode_workspace_bytes.restype = sz
@@ -245,12 +252,56 @@ def decode_step(p: Params, q, A, B, landmarks, landmark_chunk_ids, k_outlier, v_
     return out, out_chunk_ids, workspace
 
 
+class ValueCache:
+    """Device buffers of the chunk cache of the value store: ``values [b,h_kv,k*c,d]`` bf16 and the chunk id
+    per slot ``chunk_ids [b,h_kv,k]`` int32 (-1 = empty), plus ``miss_count [b,h_kv]`` of the last step."""
+
+    def __init__(self, p: Params, device="cuda", stream=None):
+        st = p.c_struct()
+        n = int(lib().shadowkv_value_cache_bytes(C.addressof(st)))
+        if n == 0:
+            _check(lib().shadowkv_validate_params(C.addressof(st), 1))
+        self.values = torch.empty(p.batch, p.n_kv_heads, p.topk_chunks * p.chunk_size, p.head_dim,
+                                  dtype=torch.bfloat16, device=device)
+        assert self.values.numel() * 2 == n
+        self.chunk_ids = torch.empty(p.batch, p.n_kv_heads, p.topk_chunks, dtype=torch.int32, device=device)
+        self.miss_count = torch.zeros(p.batch, p.n_kv_heads, dtype=torch.int32, device=device)
+        self.reset(p, stream)
+
+    def reset(self, p: Params, stream=None):
+        st = p.c_struct()
+        _check(lib().shadowkv_value_cache_reset(C.addressof(st), _ptr(self.chunk_ids), _stream_ptr(stream)))
+
+
+def decode_step_cached(p: Params, q, A, B, landmarks, landmark_chunk_ids, k_outlier, v_outlier, k_local, v_local,
+                       value_store, cache: ValueCache, pos_offset=None, out=None, out_chunk_ids=None, workspace=None,
+                       stream=None, side_stream=None):
+    """One decode step that fetches only the chunks missing from ``cache``.  Returns like ``decode_step``."""
+    dev = q.device
+    if out is None:
+        out = torch.empty(p.batch, p.n_q_heads, p.head_dim, dtype=torch.bfloat16, device=dev)
+    if out_chunk_ids is None:
+        out_chunk_ids = torch.empty(p.batch, p.n_kv_heads, p.topk_chunks, dtype=torch.int32, device=dev)
+    st = p.c_struct()
+    if workspace is None:
+        workspace = alloc_workspace(int(lib().shadowkv_decode_workspace_bytes(C.addressof(st))), dev)
+    rc = lib().shadowkv_decode_step_cached(C.addressof(st), _ptr(q), _ptr(A), _ptr(B), _ptr(landmarks),
+                                           _ptr(landmark_chunk_ids), _ptr(k_outlier), _ptr(v_outlier), _ptr(k_local),
+                                           _ptr(v_local), _ptr(value_store), _ptr(pos_offset), _ptr(cache.values),
+                                           _ptr(cache.chunk_ids), _ptr(cache.miss_count), _ptr(out),
+                                           _ptr(out_chunk_ids), _ptr(workspace), workspace.numel(),
+                                           _stream_ptr(stream),
+                                           None if side_stream is None else _stream_ptr(side_stream))
+    _check(rc)
+    return out, out_chunk_ids, workspace
+
+
 def workspace_view(p: Params, workspace: torch.Tensor, which: str) -> Optional[torch.Tensor]:
     """Intermediate of the last decode step as a tensor aliasing ``workspace``.
 
     ``"k_sparse"`` fp32 [b,h_kv,k*c,d]; ``"v_sparse"`` bf16 (staged runs only); ``"logits"`` fp64 [b,h_q,n_c].
     """
-    code = {"k_sparse": 0, "v_sparse": 1, "sel_ids": 2, "logits": 3}[which]
+    code = {"k_sparse": 0, "v_sparse": 1, "sel_ids": 2, "logits": 3, "miss_slots": 4}[which]
     st = p.c_struct()
     ptr = lib().shadowkv_decode_workspace_view(C.addressof(st), workspace.data_ptr(), code)
     if not ptr:
@@ -263,7 +314,7 @@ def workspace_view(p: Params, workspace: torch.Tensor, which: str) -> Optional[t
     if which == "v_sparse":
         n = rows[0] * rows[1] * rows[2] * rows[3]
         return workspace[off:off + 2 * n].view(torch.bfloat16).view(rows)
-    if which == "sel_ids":
+    if which in ("sel_ids", "miss_slots"):
         n = p.batch * p.n_kv_heads * p.topk_chunks
         return workspace[off:off + 4 * n].view(torch.int32).view(p.batch, p.n_kv_heads, p.topk_chunks)
     n = p.batch * p.n_q_heads * p.n_landmarks

@@ -231,3 +231,22 @@ def generate(wl: Workload, device: Optional[str] = None, want_prefill: bool = Tr
         qp = qp + wl.needle_gain * pull.repeat_interleave(wl.group, dim=1)[None]
     out["q_pool"] = qp.to(bf)
     return out
+
+
+def query_sequence(wl: Workload, n_steps: int, rho_q: float = 0.9, device: Optional[str] = None) -> torch.Tensor:
+    """Queries of ``n_steps`` consecutive decode steps, ``[n_steps, b, h_q, d]`` bf16, correlated from step to
+    step so that consecutive selections overlap (the temporal locality the chunk cache of the value store
+    lives on).  A stationary AR(1) process ``q_t = rho_q q_{t-1} + sqrt(1 - rho_q^2) eps_t`` on a ring of
+    ``n_steps`` steps (built by circular filtering of white noise, so replaying the sequence in a loop has no
+    jump at the wrap), unit variance per element.  Own generator (seed ``2000 + wl.seed``): the other tensors
+    of the workload are unchanged by drawing it."""
+    dev = device or ("cuda" if torch.cuda.is_available() else "cpu")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(2000 + wl.seed)
+    eps = torch.randn(n_steps, wl.batch, wl.n_q_heads, wl.head_dim, generator=gen, device=dev, dtype=torch.float32)
+    f = torch.arange(n_steps, device=dev, dtype=torch.float32)
+    z = torch.polar(torch.ones_like(f), -2.0 * math.pi * f / n_steps)
+    hf = math.sqrt(1.0 - rho_q * rho_q) / (1.0 - rho_q * z)          # AR(1) transfer function on the ring
+    q = torch.fft.ifft(torch.fft.fft(eps, dim=0) * hf[:, None, None, None], dim=0).real
+    q = q / q.std()
+    return q.to(torch.bfloat16).contiguous()

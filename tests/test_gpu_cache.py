@@ -1,0 +1,113 @@
+"""Chunk cache of the value store: shadowkv_decode_step_cached against the oracle over a run of correlated
+decode steps.  Per step: selected ids and output as for the plain step; the slot contents, the slots fetched
+and their count bit-exact against the oracle's cache model; the cached values bit-exact copies of the store."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import shadowkv_oracle as O
+from paper_2410_21465_amd import shadowkv as S
+from paper_2410_21465_amd.workloads import Workload, generate, query_sequence
+from tests.parity_util import OUT_MAX_ABS, OUT_MEAN_ABS, oracle_params, to_bits
+
+pytestmark = pytest.mark.gpu
+
+
+def _dev_bf16(bits):
+    return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).cuda()
+
+
+def _run_sequence(wl: Workload, n_steps: int, rho_q: float, side_stream: bool, random_jump_at=None):
+    t = generate(wl, device="cuda")
+    op = oracle_params(wl)
+    ref_build = O.build_landmarks(op, to_bits(t["k_rope"]), to_bits(t["v"]))
+    qs = query_sequence(wl, n_steps, rho_q)
+    if random_jump_at is not None:       # an unrelated query in the middle: (almost) every chunk is new
+        qs[random_jump_at] = t["q_pool"][0]
+    p = S.Params.from_workload(wl)
+    lm, lm_ids = _dev_bf16(ref_build["landmarks"]), torch.from_numpy(ref_build["landmark_chunk_ids"]).cuda()
+    ko, vo = _dev_bf16(ref_build["k_outlier"]), _dev_bf16(ref_build["v_outlier"])
+    cache = S.ValueCache(p)
+    side = torch.cuda.Stream() if side_stream else None
+    ws = None
+    b, h, k, c, d = wl.batch, wl.n_kv_heads, wl.topk_chunks, wl.chunk_size, wl.head_dim
+    units = b * h
+    ocache = -np.ones((units, k), np.int32)
+    vbits = to_bits(t["v"]).reshape(units, -1, c, d)
+    fixed = (to_bits(t["A"]), to_bits(t["B"]), ref_build["landmarks"], ref_build["landmark_chunk_ids"],
+             ref_build["k_outlier"], ref_build["v_outlier"], to_bits(t["k_local"]), to_bits(t["v_local"]),
+             to_bits(t["v"]), t["pos_offset"].cpu().numpy())
+    misses = []
+    for step in range(n_steps):
+        q = qs[step]
+        out, ids, ws = S.decode_step_cached(p, q, t["A"], t["B"], lm, lm_ids, ko, vo, t["k_local"], t["v_local"],
+                                            t["v"], cache, t["pos_offset"], workspace=ws, side_stream=side)
+        torch.cuda.synchronize()
+        ref = O.decode_step(op, to_bits(q), *fixed, diagnostics=False)
+        g_ids = ids.cpu().numpy().reshape(units, k)
+        w_sorted = np.sort(ref["chunk_ids"].reshape(units, k), axis=1)
+        np.testing.assert_array_equal(g_ids, w_sorted, err_msg=f"step {step}: selected ids")
+        model = O.cache_update(w_sorted, ocache)
+        np.testing.assert_array_equal(cache.chunk_ids.cpu().numpy().reshape(units, k), model["cache_ids"],
+                                      err_msg=f"step {step}: slot contents")
+        np.testing.assert_array_equal(cache.miss_count.cpu().numpy().reshape(units), model["n_miss"],
+                                      err_msg=f"step {step}: miss count")
+        ms = S.workspace_view(p, ws, "miss_slots").cpu().numpy().reshape(units, k)
+        for u in range(units):
+            n = model["n_miss"][u]
+            np.testing.assert_array_equal(ms[u, :n], model["miss_slots"][u, :n])
+        # every slot holds a bit-exact copy of its chunk of the store
+        cv = to_bits(cache.values).reshape(units, k, c, d)
+        for u in range(units):
+            np.testing.assert_array_equal(cv[u], vbits[u, model["cache_ids"][u]])
+        err = np.abs(out.float().cpu().numpy().astype(np.float64) - O.bits_to_f64(ref["out"]))
+        assert err.max() <= OUT_MAX_ABS and err.mean() <= OUT_MEAN_ABS, (step, err.max(), err.mean())
+        ocache = model["cache_ids"]
+        misses.append(model["n_miss"].astype(np.float64).mean() / k)
+    return misses
+
+
+SMALL = dict(n_q_heads=8, n_kv_heads=2, head_dim=128, chunk_size=8, rank=160, local_len=32, rope_theta=5e5)
+
+
+@pytest.mark.parametrize("loc,side", [("host", True), ("host", False), ("hbm", True)])
+def test_cached_steps_match_oracle(loc, side):
+    wl = Workload(name="cache-small", batch=2, ctx_len=4096, n_outlier_chunks=8, topk_chunks=64, seed=11,
+                  value_location=loc, **SMALL)
+    misses = _run_sequence(wl, n_steps=6, rho_q=0.95, side_stream=side)
+    assert misses[0] == 1.0                      # empty cache: everything is fetched
+    assert max(misses[1:]) < 1.0                 # correlated queries: some chunks are already there
+    print("miss fraction per step:", [round(m, 3) for m in misses])
+
+
+def test_unrelated_query_refills_and_recovers():
+    wl = Workload(name="cache-jump", batch=1, ctx_len=8192, n_outlier_chunks=4, topk_chunks=48, seed=12,
+                  value_location="host", **SMALL)
+    misses = _run_sequence(wl, n_steps=5, rho_q=0.97, side_stream=True, random_jump_at=2)
+    assert misses[2] > misses[1]
+
+
+def test_ragged_shapes_d96_c4():
+    wl = Workload(name="cache-d96", batch=1, n_q_heads=4, n_kv_heads=4, head_dim=96, ctx_len=2048, chunk_size=4,
+                  rank=96, n_outlier_chunks=3, topk_chunks=37, local_len=5, rope_theta=1e4, seed=13,
+                  value_location="host")
+    _run_sequence(wl, n_steps=4, rho_q=0.9, side_stream=True)
+
+
+def test_full_budget_is_all_hits_after_the_first_step():
+    # k covers every landmark: the selection never changes, so nothing is fetched after step 0
+    wl = Workload(name="cache-full", batch=1, ctx_len=1024, n_outlier_chunks=4, topk_chunks=124, seed=14,
+                  value_location="host", **SMALL)
+    misses = _run_sequence(wl, n_steps=3, rho_q=0.5, side_stream=True)
+    assert misses == [1.0, 0.0, 0.0]
+
+
+def test_reset_empties_the_cache():
+    wl = Workload(name="cache-reset", batch=1, ctx_len=2048, n_outlier_chunks=4, topk_chunks=32, seed=15,
+                  value_location="hbm", **SMALL)
+    p = S.Params.from_workload(wl)
+    cache = S.ValueCache(p)
+    cache.chunk_ids.fill_(7)
+    cache.reset(p)
+    torch.cuda.synchronize()
+    assert bool((cache.chunk_ids == -1).all())
