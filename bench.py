@@ -49,6 +49,10 @@ def main() -> int:
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU time budget of the oracle leg")
     ap.add_argument("--no-side-stream", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="enqueue the timed steps eagerly instead of replaying a HIP graph")
+    ap.add_argument("--chunk-cache", action="store_true",
+                    help="run shadowkv_decode_step_cached over a ring of correlated queries (values fetched only for "
+                         "chunks missing from last step's selection); meant for the host-store workloads")
+    ap.add_argument("--rho-q", type=float, default=0.93, help="step-to-step correlation of the queries with --chunk-cache")
     ap.add_argument("--stage-values", action="store_true",
                     help="stage the selected values with the gather kernel even for an HBM store "
                          "(gives profiles a plain copy kernel of known size: k*c*d*2 bytes per unit each way)")
@@ -59,7 +63,7 @@ def main() -> int:
 
     import torch
     from paper_2410_21465_amd import shadowkv as S
-    from paper_2410_21465_amd.workloads import CONFIGS, generate
+    from paper_2410_21465_amd.workloads import CONFIGS, generate, query_sequence
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -92,8 +96,17 @@ def main() -> int:
     ids = torch.empty(wl.batch, wl.n_kv_heads, wl.topk_chunks, dtype=torch.int32, device=dev)
     side = None if args.no_side_stream else torch.cuda.Stream()
     pool = t["q_pool"]
+    cache = None
+    if args.chunk_cache:
+        pool = query_sequence(wl, 64, args.rho_q, device=dev)   # a ring: replaying it has no jump at the wrap
+        cache = S.ValueCache(p, device=dev)
 
     def step(i: int):
+        if cache is not None:
+            S.decode_step_cached(p, pool[i % pool.shape[0]], t["A"], t["B"], bl["landmarks"], bl["landmark_chunk_ids"],
+                                 bl["k_outlier"], bl["v_outlier"], t["k_local"], t["v_local"], t["v"], cache,
+                                 t["pos_offset"], out=out, out_chunk_ids=ids, workspace=ws, side_stream=side)
+            return
         S.decode_step(p, pool[i % pool.shape[0]], t["A"], t["B"], bl["landmarks"], bl["landmark_chunk_ids"],
                       bl["k_outlier"], bl["v_outlier"], t["k_local"], t["v_local"], t["v"], t["pos_offset"],
                       out=out, out_chunk_ids=ids, workspace=ws, side_stream=side)
@@ -139,6 +152,14 @@ def main() -> int:
     eager_ms_per_step = (time.perf_counter() - t3) * 1e3 / args.steps
     prof = S.profile_end()
 
+    hit_rate = None
+    if cache is not None:   # one more pass over the ring, reading the miss counts back after every step
+        miss = []
+        for i in range(pool.shape[0]):
+            step(args.steps + i)
+            miss.append(float(cache.miss_count.float().mean().item()) / wl.topk_chunks)
+        hit_rate = 1.0 - sum(miss) / len(miss)
+
     # what a plain device copy reaches on this machine (1 GiB, read + write counted), for scale
     src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
     dst = torch.empty_like(src)
@@ -183,6 +204,12 @@ def main() -> int:
     }
     if wl.value_location == "host":
         res["value_gather_pcie_bytes"] = ab["values"]
+    if cache is not None:
+        res["config"]["chunk_cache"] = True
+        res["config"]["rho_q"] = args.rho_q
+        res["cache_hit_rate"] = hit_rate
+        if wl.value_location == "host":
+            res["value_gather_pcie_bytes"] = ab["values"] * (1.0 - hit_rate)
 
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(wl, t, args.cpu_seconds)

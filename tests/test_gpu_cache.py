@@ -8,7 +8,7 @@ import torch
 from oracle import shadowkv_oracle as O
 from paper_2410_21465_amd import shadowkv as S
 from paper_2410_21465_amd.workloads import Workload, generate, query_sequence
-from tests.parity_util import OUT_MAX_ABS, OUT_MEAN_ABS, oracle_params, to_bits
+from parity_util import OUT_MAX_ABS, OUT_MEAN_ABS, oracle_params, to_bits
 
 pytestmark = pytest.mark.gpu
 
@@ -111,3 +111,56 @@ def test_reset_empties_the_cache():
     cache.reset(p)
     torch.cuda.synchronize()
     assert bool((cache.chunk_ids == -1).all())
+
+
+def test_cached_step_in_a_hip_graph_replays_to_the_eager_sequence():
+    """The cached step is stateful (the slots carry over).  A graph of one cached step, replayed over a query
+    sequence with eager uncached work between the replays, must walk through exactly the states and outputs of
+    the same sequence run eagerly."""
+    wl = Workload(name="cache-graph", batch=2, ctx_len=8192, n_outlier_chunks=4, topk_chunks=48, seed=16,
+                  value_location="host", **SMALL)
+    t = generate(wl, device="cuda")
+    p = S.Params.from_workload(wl)
+    bl = S.build_landmarks(p, t["k_rope"], t["v"])
+    qs = query_sequence(wl, 6, 0.9)
+    q = qs[0].clone()
+    out = torch.empty(wl.batch, wl.n_q_heads, wl.head_dim, dtype=torch.bfloat16, device="cuda")
+    ids = torch.empty(wl.batch, wl.n_kv_heads, wl.topk_chunks, dtype=torch.int32, device="cuda")
+    ws = S.alloc_workspace(S.decode_workspace_bytes(p))
+    ws2 = S.alloc_workspace(S.decode_workspace_bytes(p))
+    cache = S.ValueCache(p)
+    side = torch.cuda.Stream()
+
+    def step():
+        S.decode_step_cached(p, q, t["A"], t["B"], bl["landmarks"], bl["landmark_chunk_ids"], bl["k_outlier"],
+                             bl["v_outlier"], t["k_local"], t["v_local"], t["v"], cache, t["pos_offset"], out=out,
+                             out_chunk_ids=ids, workspace=ws, side_stream=side)
+
+    eager = []
+    for i in range(6):
+        q.copy_(qs[i])
+        step()
+        torch.cuda.synchronize()
+        eager.append((out.clone(), ids.clone(), cache.chunk_ids.clone(), cache.miss_count.clone()))
+    assert int(eager[1][3].sum()) < int(eager[0][3].sum())
+    cache.reset(p)
+    torch.cuda.synchronize()
+    cap = torch.cuda.Stream()
+    cap.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(cap):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=cap):
+            step()
+    torch.cuda.current_stream().wait_stream(cap)
+    for i in range(6):
+        q.copy_(qs[i])
+        out.zero_(); ids.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager[i][0]) and torch.equal(ids, eager[i][1]), f"replay {i}"
+        assert torch.equal(cache.chunk_ids, eager[i][2]) and torch.equal(cache.miss_count, eager[i][3]), f"replay {i}"
+        # eager, uncached work between the replays (own workspace and outputs)
+        S.decode_step(p, qs[(i + 3) % 6], t["A"], t["B"], bl["landmarks"], bl["landmark_chunk_ids"], bl["k_outlier"],
+                      bl["v_outlier"], t["k_local"], t["v_local"], t["v"], t["pos_offset"], workspace=ws2,
+                      side_stream=side)
+        torch.cuda.synchronize()
