@@ -44,7 +44,17 @@ typedef struct oracle_params {
   double rope_theta;      /* base of the rotary frequencies */
   const float *inv_freq;  /* optional [d/2]; replaces theta^(-2i/d) */
   double softmax_scale;   /* 0 => 1/sqrt(d) */
+  int32_t ctx_capacity;   /* tokens the context arrays are laid out for (0 => ctx_len); see below */
 } oracle_params;
+
+/* Room to grow (generated tokens are appended chunk by chunk, oracle_append_chunk): the arrays that
+ * have a token or landmark axis are laid out for `cap` = ctx_capacity tokens --
+ * A [b, cap, r], value_store [b, h_kv, cap, d], landmarks [b, h_kv, cap/c - o, d],
+ * landmark_chunk_ids [b, h_kv, cap/c - o] -- and only the first ctx_len tokens (n_c landmarks)
+ * of each are valid. */
+static int64_t capacity_of(const oracle_params *p) {
+  return p->ctx_capacity > 0 ? p->ctx_capacity : p->ctx_len;
+}
 
 int oracle_num_threads(void) {
 #ifdef _OPENMP
@@ -125,7 +135,8 @@ static int cmp_desc(const void *a, const void *b) {
 }
 
 /* ---- Alg. 1 (after the SVD line): landmarks and outliers ----------------
- * k_rope, v: [b, h_kv, s, d] bf16.  Outputs per (b, h_kv):
+ * k_rope [b, h_kv, s, d] bf16 (the prefill keys, dense); v = the value store
+ * [b, h_kv, cap, d].  Outputs per (b, h_kv):
  *   landmarks [n_c, d] bf16, landmark_chunk_ids [n_c] ascending,
  *   outlier_chunk_ids [o] most-outlying first, k_outlier/v_outlier [o*c, d].
  * Optional fp64 diagnostics: chunk_min_cos [b,h_kv,n_ch], chunk_mean
@@ -141,6 +152,9 @@ int oracle_build_landmarks(const oracle_params *p, const uint16_t *k_rope,
   if (d <= 0 || c <= 0 || s % c) return -1;
   const int64_t n_ch = s / c, n_c = n_ch - o;
   if (o < 0 || n_c < 0) return -1;
+  const int64_t cap = capacity_of(p);
+  if (cap < s || cap % c) return -1;
+  const int64_t nc_cap = cap / c - o; /* landmark rows the arrays are laid out for */
   const int64_t units = (int64_t)p->batch * p->n_kv_heads;
   const double eps = 1e-8;
   int fail = 0;
@@ -191,16 +205,16 @@ int oracle_build_landmarks(const oracle_params *p, const uint16_t *k_rope,
       outlier_chunk_ids[u * o + i] = (int32_t)j;
       memcpy(k_outlier + (u * o + i) * c * d, K + j * c * d, sizeof(uint16_t) * c * d);
       if (v && v_outlier)
-        memcpy(v_outlier + (u * o + i) * c * d, v + (u * s + j * c) * d,
+        memcpy(v_outlier + (u * o + i) * c * d, v + (u * cap + j * c) * d,
                sizeof(uint16_t) * c * d);
     }
     /* L <- C without the outlier rows, in ascending chunk order */
     int64_t slot = 0;
     for (int64_t j = 0; j < n_ch; ++j) {
       if (is_out[j]) continue;
-      landmark_chunk_ids[u * n_c + slot] = (int32_t)j;
+      landmark_chunk_ids[u * nc_cap + slot] = (int32_t)j;
       for (int x = 0; x < d; ++x)
-        landmarks[(u * n_c + slot) * d + x] = oracle_f64_to_bf16(C[j * d + x]);
+        landmarks[(u * nc_cap + slot) * d + x] = oracle_f64_to_bf16(C[j * d + x]);
       ++slot;
     }
     free(C); free(m); free(is_out);
@@ -209,9 +223,9 @@ int oracle_build_landmarks(const oracle_params *p, const uint16_t *k_rope,
 }
 
 /* ---- Alg. 2 + sparse attention: one decode step -------------------------
- * q [b,h_q,d]; A [b,s,r]; B [b,h_kv,r,d]; landmarks [b,h_kv,n_c,d];
- * landmark_chunk_ids [b,h_kv,n_c]; k_outlier/v_outlier [b,h_kv,o*c,d];
- * k_local/v_local [b,h_kv,w,d]; value_store [b,h_kv,s,d]; pos_offset [b] or
+ * q [b,h_q,d]; A [b,cap,r]; B [b,h_kv,r,d]; landmarks [b,h_kv,cap/c-o,d];
+ * landmark_chunk_ids [b,h_kv,cap/c-o]; k_outlier/v_outlier [b,h_kv,o*c,d];
+ * k_local/v_local [b,h_kv,w,d]; value_store [b,h_kv,cap,d]; pos_offset [b] or
  * NULL.  All bf16 except ids.  Outputs: out_bf16 [b,h_q,d]; optional:
  * out_f64 [b,h_q,d], chunk_ids [b,h_kv,k] (true chunk ids, best first),
  * z2 [b,h_kv,n_c] (log-domain group score per landmark slot),
@@ -233,6 +247,9 @@ int oracle_decode_step(const oracle_params *p, const uint16_t *q,
   const int G = hq / hkv;
   const int64_t n_ch = s / c, n_c = n_ch - o;
   if (k < 0 || k > n_c) return -1;
+  const int64_t cap = capacity_of(p);
+  if (cap < s || cap % c) return -1;
+  const int64_t nc_cap = cap / c - o;
   const int64_t T = (int64_t)o * c + (int64_t)k * c + w;
   const double scale = p->softmax_scale != 0.0 ? p->softmax_scale : 1.0 / sqrt((double)d);
   const int64_t units = (int64_t)p->batch * hkv;
@@ -241,8 +258,8 @@ int oracle_decode_step(const oracle_params *p, const uint16_t *q,
 #pragma omp parallel for schedule(dynamic, 1)
   for (int64_t u = 0; u < units; ++u) {
     const int64_t bi = u / hkv, h = u % hkv;
-    const uint16_t *L = landmarks + u * n_c * d;
-    const int32_t *Lid = landmark_chunk_ids + u * n_c;
+    const uint16_t *L = landmarks + u * nc_cap * d;
+    const int32_t *Lid = landmark_chunk_ids + u * nc_cap;
     double *P = malloc(sizeof(double) * (size_t)G * (n_c ? n_c : 1));
     keyed *z2 = malloc(sizeof(keyed) * (n_c ? n_c : 1));
     double *Kt = malloc(sizeof(double) * (T ? T : 1) * d); /* attended keys   */
@@ -294,7 +311,7 @@ int oracle_decode_step(const oracle_params *p, const uint16_t *q,
       if (chunk_ids) chunk_ids[u * k + i] = (int32_t)ch;
       for (int t = 0; t < c; ++t, ++row) {
         const int64_t n = ch * c + t; /* token index inside the context */
-        const uint16_t *Arow = A + (bi * s + n) * r;
+        const uint16_t *Arow = A + (bi * cap + n) * r;
         for (int x = 0; x < d; ++x) {
           double acc = 0.0;
           for (int rho = 0; rho < r; ++rho)
@@ -305,7 +322,7 @@ int oracle_decode_step(const oracle_params *p, const uint16_t *q,
         if (k_sparse_out)
           memcpy(k_sparse_out + ((u * k + i) * c + t) * d, Kt + row * d, sizeof(double) * d);
         for (int x = 0; x < d; ++x)
-          Vt[row * d + x] = bf16_to_f64(value_store[(u * s + n) * d + x]);
+          Vt[row * d + x] = bf16_to_f64(value_store[(u * cap + n) * d + x]);
       }
     }
     for (int64_t i = 0; i < w; ++i, ++row)
@@ -381,5 +398,54 @@ int oracle_cache_update(int64_t units, int k, const int32_t *sel_ids,
     n_miss[u] = n;
   }
   free(hit); free(keep);
+  return 0;
+}
+
+/* ---- generated tokens: one more chunk of context --------------------------
+ * Section "High-throughput Decoding", last paragraph and its footnote: new
+ * pre-RoPE keys K' are stored as the low-rank states K' Psi, with Psi the right
+ * singular matrix of the context keys, and projected back with Psi^T when needed.
+ * Here Psi^T is B: Psi[(h, x), rho] = B[b, h, rho, x] over the full key width
+ * h_kv * d.  When c tokens have left the recent-token window they become chunk
+ * number n_ch = s / c of the context, exactly as if the pre-filling algorithm had
+ * seen them: rows of A, one landmark (mean of the chunk's post-RoPE keys), the
+ * chunk's values in the store.  The chunk is never an outlier (the outlier set
+ * is fixed at pre-filling).
+ *
+ * k_pre  [b, c, h_kv*d]   pre-RoPE keys of the c tokens, heads side by side
+ * k_rope [b, h_kv, c, d]  the same keys after RoPE at their positions
+ * v      [b, h_kv, c, d]
+ * in/out (laid out for cap tokens, valid up to s before / s + c after):
+ * A, landmarks, landmark_chunk_ids, value_store.  Needs s + c <= cap.
+ * The caller then continues with ctx_len = s + c.                          */
+int oracle_append_chunk(const oracle_params *p, const uint16_t *k_pre,
+                        const uint16_t *k_rope, const uint16_t *v,
+                        const uint16_t *B, uint16_t *A, uint16_t *landmarks,
+                        int32_t *landmark_chunk_ids, uint16_t *value_store) {
+  const int d = p->head_dim, c = p->chunk_size, r = p->rank, o = p->n_outlier_chunks;
+  const int hkv = p->n_kv_heads;
+  const int64_t s = p->ctx_len, cap = capacity_of(p);
+  if (d <= 0 || c <= 0 || s % c || cap % c || s + c > cap) return -1;
+  const int64_t n_ch = s / c, n_c = n_ch - o, nc_cap = cap / c - o;
+  if (n_c < 0) return -1;
+  for (int64_t bi = 0; bi < p->batch; ++bi)
+    for (int t = 0; t < c; ++t)
+      for (int rho = 0; rho < r; ++rho) {       /* A' = K' Psi */
+        double acc = 0.0;
+        for (int h = 0; h < hkv; ++h)
+          for (int x = 0; x < d; ++x)
+            acc += bf16_to_f64(k_pre[((bi * c + t) * hkv + h) * d + x]) *
+                   bf16_to_f64(B[(((bi * hkv + h) * r) + rho) * d + x]);
+        A[(bi * cap + s + t) * r + rho] = oracle_f64_to_bf16(acc);
+      }
+  for (int64_t u = 0; u < (int64_t)p->batch * hkv; ++u) {
+    for (int x = 0; x < d; ++x) {                /* landmark = mean of the chunk */
+      double acc = 0.0;
+      for (int t = 0; t < c; ++t) acc += bf16_to_f64(k_rope[(u * c + t) * d + x]);
+      landmarks[(u * nc_cap + n_c) * d + x] = oracle_f64_to_bf16(acc / (double)c);
+    }
+    landmark_chunk_ids[u * nc_cap + n_c] = (int32_t)n_ch;
+    memcpy(value_store + (u * cap + s) * d, v + u * c * d, sizeof(uint16_t) * c * d);
+  }
   return 0;
 }

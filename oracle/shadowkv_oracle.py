@@ -30,9 +30,11 @@ def build(force: bool = False) -> str:
         return _LIB
     stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
     if force or stale:
+        tmp = f"{_LIB}.{os.getpid()}.tmp"   # several test workers may build at once: replace atomically
         cmd = ["gcc", "-std=c99", "-O2", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
-               "-o", _LIB, _SRC, "-lm"]
+               "-o", tmp, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
+        os.replace(tmp, _LIB)
     return _LIB
 
 
@@ -42,7 +44,7 @@ class _Params(C.Structure):
         ("head_dim", C.c_int32), ("ctx_len", C.c_int32), ("chunk_size", C.c_int32),
         ("rank", C.c_int32), ("n_outlier_chunks", C.c_int32), ("topk_chunks", C.c_int32),
         ("local_len", C.c_int32), ("rope_theta", C.c_double), ("inv_freq", C.c_void_p),
-        ("softmax_scale", C.c_double),
+        ("softmax_scale", C.c_double), ("ctx_capacity", C.c_int32),
     ]
 
 
@@ -61,10 +63,19 @@ class OracleParams:
     rope_theta: float = 5e5
     inv_freq: Optional[np.ndarray] = None  # float32 [head_dim/2]
     softmax_scale: float = 0.0
+    ctx_capacity: int = 0  # tokens the context arrays are laid out for (0 => ctx_len)
 
     @property
     def n_chunks(self) -> int:
         return self.ctx_len // self.chunk_size
+
+    @property
+    def capacity(self) -> int:
+        return self.ctx_capacity or self.ctx_len
+
+    @property
+    def landmark_capacity(self) -> int:
+        return self.capacity // self.chunk_size - self.n_outlier_chunks
 
     @property
     def n_landmarks(self) -> int:
@@ -78,7 +89,8 @@ class OracleParams:
         st = _Params(self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim, self.ctx_len,
                      self.chunk_size, self.rank, self.n_outlier_chunks, self.topk_chunks,
                      self.local_len, float(self.rope_theta),
-                     inv.ctypes.data if inv is not None else None, float(self.softmax_scale))
+                     inv.ctypes.data if inv is not None else None, float(self.softmax_scale),
+                     int(self.ctx_capacity))
         return st, inv  # keep `inv` alive while the struct is in use
 
 
@@ -96,6 +108,8 @@ def _load():
         _lib.oracle_build_landmarks.argtypes = [C.c_void_p] * 10
         _lib.oracle_decode_step.restype = C.c_int
         _lib.oracle_decode_step.argtypes = [C.c_void_p] * 17
+        _lib.oracle_append_chunk.restype = C.c_int
+        _lib.oracle_append_chunk.argtypes = [C.c_void_p] * 9
         _lib.oracle_cache_update.restype = C.c_int
         _lib.oracle_cache_update.argtypes = [C.c_int64, C.c_int] + [C.c_void_p] * 4
     return _lib
@@ -146,15 +160,15 @@ def rope(p: OracleParams, x: np.ndarray, pos: np.ndarray) -> np.ndarray:
 
 
 def build_landmarks(p: OracleParams, k_rope, v=None, diagnostics: bool = False) -> dict:
-    """Alg. 1 after the SVD.  k_rope, v: [b, h_kv, s, d] bf16 bits."""
+    """Alg. 1 after the SVD.  k_rope [b, h_kv, s, d], v = value store [b, h_kv, cap, d], bf16 bits."""
     lib = _load()
     b, h, s, d, c, o = p.batch, p.n_kv_heads, p.ctx_len, p.head_dim, p.chunk_size, p.n_outlier_chunks
-    n_ch, n_c = p.n_chunks, p.n_landmarks
+    n_ch, n_c = p.n_chunks, p.landmark_capacity
     k_rope = as_bits(k_rope)
     assert k_rope.shape == (b, h, s, d), k_rope.shape
     if v is not None:
         v = as_bits(v)
-        assert v.shape == (b, h, s, d)
+        assert v.shape == (b, h, p.capacity, d)
     res = {
         "landmarks": np.zeros((b, h, n_c, d), np.uint16),
         "landmark_chunk_ids": np.zeros((b, h, n_c), np.int32),
@@ -181,16 +195,17 @@ def decode_step(p: OracleParams, q, A, B, landmarks, landmark_chunk_ids, k_outli
     lib = _load()
     b, hq, h, s, d = p.batch, p.n_q_heads, p.n_kv_heads, p.ctx_len, p.head_dim
     c, r, o, k, w, n_c = p.chunk_size, p.rank, p.n_outlier_chunks, p.topk_chunks, p.local_len, p.n_landmarks
+    cap, nc_cap = p.capacity, p.landmark_capacity
     q, A, B = as_bits(q), as_bits(A), as_bits(B)
     landmarks, value_store = as_bits(landmarks), as_bits(value_store)
     k_outlier, v_outlier = as_bits(k_outlier), as_bits(v_outlier)
     k_local, v_local = as_bits(k_local), as_bits(v_local)
     ids = np.ascontiguousarray(landmark_chunk_ids, dtype=np.int32)
-    assert q.shape == (b, hq, d) and A.shape == (b, s, r) and B.shape == (b, h, r, d)
-    assert landmarks.shape == (b, h, n_c, d) and ids.shape == (b, h, n_c)
+    assert q.shape == (b, hq, d) and A.shape == (b, cap, r) and B.shape == (b, h, r, d)
+    assert landmarks.shape == (b, h, nc_cap, d) and ids.shape == (b, h, nc_cap)
     assert k_outlier.shape == (b, h, o * c, d) and v_outlier.shape == (b, h, o * c, d)
     assert k_local.shape == (b, h, w, d) and v_local.shape == (b, h, w, d)
-    assert value_store.shape == (b, h, s, d)
+    assert value_store.shape == (b, h, cap, d)
     pos = None
     if pos_offset is not None:
         pos = np.ascontiguousarray(pos_offset, dtype=np.int32)
@@ -228,3 +243,24 @@ def cache_update(sel_ids: np.ndarray, cache_ids: np.ndarray) -> dict:
     if rc != 0:
         raise ValueError(f"oracle_cache_update rejected its arguments (rc={rc})")
     return {"cache_ids": cache, "miss_slots": miss, "n_miss": n_miss}
+
+
+def append_chunk(p: OracleParams, k_pre, k_rope, v, B, A, landmarks, landmark_chunk_ids, value_store) -> None:
+    """One more chunk of context from generated tokens (low-rank states K' Psi, landmark, values), written in
+    place into ``A``, ``landmarks``, ``landmark_chunk_ids`` (int32) and ``value_store`` (uint16 ndarrays laid
+    out for ``p.capacity`` tokens).  ``p.ctx_len`` is the length BEFORE the call."""
+    lib = _load()
+    b, h, d, c, r = p.batch, p.n_kv_heads, p.head_dim, p.chunk_size, p.rank
+    cap, nc_cap = p.capacity, p.landmark_capacity
+    k_pre, k_rope, v, B = as_bits(k_pre), as_bits(k_rope), as_bits(v), as_bits(B)
+    assert k_pre.shape == (b, c, h * d) and k_rope.shape == (b, h, c, d) and v.shape == (b, h, c, d)
+    assert B.shape == (b, h, r, d)
+    for arr, shape, dt in ((A, (b, cap, r), np.uint16), (landmarks, (b, h, nc_cap, d), np.uint16),
+                           (landmark_chunk_ids, (b, h, nc_cap), np.int32), (value_store, (b, h, cap, d), np.uint16)):
+        assert isinstance(arr, np.ndarray) and arr.dtype == dt and arr.shape == shape and arr.flags.c_contiguous
+    st, keep = p._c()
+    rc = lib.oracle_append_chunk(C.addressof(st), _ptr(k_pre), _ptr(k_rope), _ptr(v), _ptr(B), _ptr(A),
+                                 _ptr(landmarks), _ptr(landmark_chunk_ids), _ptr(value_store))
+    del keep
+    if rc != 0:
+        raise ValueError(f"oracle_append_chunk rejected its arguments (rc={rc})")

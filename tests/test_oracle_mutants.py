@@ -27,8 +27,8 @@ MUTANTS = [
     ("position-offset-dropped", "rope_inplace(p, Kt + row * d, pos0 + (double)n);", "rope_inplace(p, Kt + row * d, (double)n);"),
     ("tie-rule-reversed", "return (x->idx > y->idx) - (x->idx < y->idx);", "return (x->idx < y->idx) - (x->idx > y->idx);"),
     ("attention-not-normalised", "double ov = T ? acc / se : 0.0;", "double ov = T ? acc : 0.0 * se;"),
-    ("value-of-wrong-token", "Vt[row * d + x] = bf16_to_f64(value_store[(u * s + n) * d + x]);",
-     "Vt[row * d + x] = bf16_to_f64(value_store[(u * s + ch * c) * d + x]);"),
+    ("value-of-wrong-token", "Vt[row * d + x] = bf16_to_f64(value_store[(u * cap + n) * d + x]);",
+     "Vt[row * d + x] = bf16_to_f64(value_store[(u * cap + ch * c) * d + x]);"),
     ("outlier-order-by-max", "m[j].key = -mn;", "m[j].key = mn;"),
 ]
 
@@ -41,11 +41,26 @@ CACHE_MUTANTS = [
 ]
 
 
+# planted mistakes in the capacity layout and in the append of generated tokens
+APPEND_MUTANTS = [
+    ("append-head-order", "k_pre[((bi * c + t) * hkv + h) * d + x]", "k_pre[((bi * hkv + h) * c + t) * d + x]"),
+    ("append-b-transposed", "bf16_to_f64(B[(((bi * hkv + h) * r) + rho) * d + x]);", "bf16_to_f64(B[(((bi * hkv + h) * d) + x) * r + rho]);"),
+    ("append-chunk-id", "landmark_chunk_ids[u * nc_cap + n_c] = (int32_t)n_ch;", "landmark_chunk_ids[u * nc_cap + n_c] = (int32_t)n_c;"),
+    ("append-landmark-sum", "oracle_f64_to_bf16(acc / (double)c);\n    }\n    landmark_chunk_ids", "oracle_f64_to_bf16(acc);\n    }\n    landmark_chunk_ids"),
+    ("append-row-offset", "A[(bi * cap + s + t) * r + rho] = oracle_f64_to_bf16(acc);", "A[(bi * cap + s) * r + t + rho] = oracle_f64_to_bf16(acc);"),
+    ("append-stride-of-A", "const uint16_t *Arow = A + (bi * cap + n) * r;", "const uint16_t *Arow = A + (bi * s + n) * r;"),
+    ("append-stride-of-landmarks", "const uint16_t *L = landmarks + u * nc_cap * d;", "const uint16_t *L = landmarks + u * n_c * d;"),
+]
+
+
 def _pins_for(name):
+    if name.startswith("append-"):
+        return "test_oracle_append.py"
     return "test_oracle_cache.py" if name.startswith("cache-") else "test_oracle_pins.py"
 
 
-@pytest.mark.parametrize("name,old,new", MUTANTS + CACHE_MUTANTS, ids=[m[0] for m in MUTANTS + CACHE_MUTANTS])
+@pytest.mark.parametrize("name,old,new", MUTANTS + CACHE_MUTANTS + APPEND_MUTANTS,
+                         ids=[m[0] for m in MUTANTS + CACHE_MUTANTS + APPEND_MUTANTS])
 def test_pins_catch_mutant(tmp_path, name, old, new):
     text = open(SRC).read()
     assert text.count(old) >= 1, f"mutant {name}: pattern not found in the oracle source"
@@ -68,7 +83,8 @@ def test_unmutated_source_passes_through_the_same_route(tmp_path):
                    check=True)
     env = dict(os.environ, SHADOWKV_ORACLE_LIB=str(so_file))
     res = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", "test_oracle_pins.py"),
-                          os.path.join(ROOT, "tests", "test_oracle_cache.py"), "-x", "-q",
+                          os.path.join(ROOT, "tests", "test_oracle_cache.py"),
+                          os.path.join(ROOT, "tests", "test_oracle_append.py"), "-x", "-q",
                           "-p", "no:cacheprovider"], cwd=ROOT, env=env, stdout=subprocess.PIPE,
                          stderr=subprocess.STDOUT, text=True)
     assert res.returncode == 0, res.stdout[-2000:]
