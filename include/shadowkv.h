@@ -75,7 +75,19 @@ typedef struct shadowkv_params {
   double rope_theta;        /* RoPE base; frequency i is theta^(-2i/d), i < d/2, pairs (i, i + d/2) */
   double softmax_scale;     /* 0 => 1/sqrt(d); used for landmark scores and for attention */
   const float *inv_freq;    /* optional dev [d/2]: replaces theta^(-2i/d) (scaled-RoPE models) */
+  int32_t ctx_capacity;     /* cap: tokens the context arrays are laid out for; 0 => ctx_len.  Multiple of
+                               chunk_size, >= ctx_len.  Room for shadowkv_append_chunk to grow the context. */
 } shadowkv_params;
+
+/*
+ * Layout with room to grow.  The arrays that have a token or a landmark axis are laid out for
+ * cap = ctx_capacity tokens (nc_cap = cap/c - o landmark rows), and only the first s = ctx_len tokens
+ * (n_c landmark rows) of each unit are valid:
+ *   A [b, cap, r]   value_store [b, h_kv, cap, d]   landmarks [b, h_kv, nc_cap, d]
+ *   landmark_chunk_ids [b, h_kv, nc_cap]
+ * With ctx_capacity == 0 these are the dense shapes written next to each argument below (s for cap,
+ * n_c for nc_cap).  Everything else (k_rope of the prefill, outliers, recent tokens, outputs) is dense.
+ */
 
 /*
  * Alg. 1, every line after the SVD.  Per (batch, KV head):
@@ -85,7 +97,8 @@ typedef struct shadowkv_params {
  *   landmarks = bf16(C_j) of the other chunks in ascending chunk order.
  *
  *   k_rope              dev        [b, h_kv, s, d] bf16   post-RoPE keys
- *   v                   dev|pinned [b, h_kv, s, d] bf16   values; may be NULL (then v_outlier is untouched)
+ *   v                   dev|pinned [b, h_kv, s, d] bf16   the value store (laid out for cap tokens, see above);
+ *                                                          may be NULL (then v_outlier is untouched)
  *   landmarks           dev  out   [b, h_kv, n_c, d] bf16
  *   landmark_chunk_ids  dev  out   [b, h_kv, n_c] int32   true chunk id of each landmark slot, ascending
  *   outlier_chunk_ids   dev  out   [b, h_kv, o] int32     ascending chunk id
@@ -163,6 +176,30 @@ int shadowkv_decode_step_cached(const shadowkv_params *params, const shadowkv_bf
                                 int32_t *out_miss_count, shadowkv_bf16 *out, int32_t *out_chunk_ids,
                                 void *workspace, size_t workspace_bytes, void *stream,
                                 void *side_stream);
+
+/*
+ * One more chunk of context from generated tokens (last paragraph of section "High-throughput
+ * Decoding" and its footnote): the pre-RoPE keys K' of c tokens that have left the recent-token window
+ * are stored as the low-rank states K' Psi, Psi = right singular matrix of the context keys, which here
+ * is B transposed over the full key width: Psi[(h, x), rho] = B[b, h, rho, x].  The tokens become chunk
+ * number s/c exactly as if the pre-filling algorithm had seen them (never an outlier: the outlier set
+ * is fixed at pre-filling).
+ *
+ *   k_pre   dev [b, c, h_kv*d] bf16   pre-RoPE keys of the c tokens, heads side by side
+ *   k_rope  dev [b, h_kv, c, d] bf16  the same keys after RoPE at their positions
+ *   v       dev [b, h_kv, c, d] bf16  their values
+ *   B       dev [b, h_kv, r, d] bf16
+ *   in/out, laid out for ctx_capacity tokens: A (rows s .. s+c-1 written, fp64 accumulate, rounded once),
+ *   landmarks (row n_c: mean of the chunk's post-RoPE keys), landmark_chunk_ids (entry n_c = s/c),
+ *   value_store (dev|pinned; tokens s .. s+c-1).
+ * Needs ctx_len + chunk_size <= ctx_capacity (else SHADOWKV_EINVAL).  params->ctx_len is the length
+ * BEFORE the call; the caller continues with ctx_len + chunk_size.  The fields topk_chunks and local_len
+ * are ignored.  A value cache (shadowkv_decode_step_cached) stays valid: existing chunks do not change.
+ */
+int shadowkv_append_chunk(const shadowkv_params *params, const shadowkv_bf16 *k_pre,
+                          const shadowkv_bf16 *k_rope, const shadowkv_bf16 *v, const shadowkv_bf16 *B,
+                          shadowkv_bf16 *A, shadowkv_bf16 *landmarks, int32_t *landmark_chunk_ids,
+                          shadowkv_bf16 *value_store, void *stream);
 
 /* Bytes of `value_cache` for the given shape (0 if params are invalid). */
 size_t shadowkv_value_cache_bytes(const shadowkv_params *params);

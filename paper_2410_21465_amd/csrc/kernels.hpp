@@ -18,8 +18,9 @@ struct RopeFreqs {
 
 // ---- landmark scoring (decoding algorithm, P = Q L^T / sqrt(d)) ----------------
 // logits [b*h_q, n_c] fp64; partials [b*h_q, n_tiles] (max, sum exp(p - max)) per tile.
+// landmarks [units, nc_stride, d]: n_c valid rows per unit.
 hipError_t launch_score(const bf16_t* q, const bf16_t* landmarks, double* logits, double2* partials,
-                        int batch, int hq, int hkv, int d, int n_c, double scale, hipStream_t st);
+                        int batch, int hq, int hkv, int d, int n_c, int nc_stride, double scale, hipStream_t st);
 
 // ---- ArgTopK -------------------------------------------------------------------
 constexpr int kSrcLogits = 0;  // key = max over the group of (logit - lse)
@@ -34,7 +35,8 @@ struct SelectArgs {
   int n, k, slice_len, n_slices, cand_stride;
   uint64_t* cand_key;       // [units, cand_stride] survivors of the slices
   int32_t* cand_idx;
-  const int32_t* id_map;    // optional [units, n]: index -> reported id
+  const int32_t* id_map;    // optional [units, id_stride]: index -> reported id
+  int id_stride;
   int32_t* out_ids;         // [units, k], ascending index order
   int32_t* out_ids2;        // optional copy
 };
@@ -45,16 +47,17 @@ bool plan_select(int n, int k, SelectPlan* plan);
 hipError_t launch_select(const SelectArgs& a, const SelectPlan& plan, int src, int units, hipStream_t st);
 
 // ---- value chunk gather (V_sparse = Gather(V_store, I)) -----------------------------
+// store [units, s_cap, d] of which s tokens are valid
 hipError_t launch_gather_values(const bf16_t* store, const int32_t* sel_ids, bf16_t* v_sparse, int units, int d,
-                                int s, int c, int k, hipStream_t st);
+                                int s, int s_cap, int c, int k, hipStream_t st);
 
 // ---- chunk cache of the offloaded values: index scan, fetch of the missing chunks ------
 constexpr int kMaxCachedTopK = 8192;  // slots per unit the index-scan kernel handles (LDS, 16-bit ranks)
 hipError_t launch_cache_update(const int32_t* sel_ids, int32_t* cache_ids, int32_t* miss_slots, int32_t* n_miss,
                                int32_t* n_miss_copy, int units, int k, hipStream_t st);
 hipError_t launch_gather_missing(const bf16_t* store, const int32_t* cache_ids, const int32_t* miss_slots,
-                                 const int32_t* n_miss, bf16_t* v_cache, int units, int d, int s, int c, int k,
-                                 hipStream_t st);
+                                 const int32_t* n_miss, bf16_t* v_cache, int units, int d, int s, int s_cap, int c,
+                                 int k, hipStream_t st);
 hipError_t launch_fill_i32(int32_t* p, size_t n, int32_t value, hipStream_t st);
 
 // ---- attention over [outliers ; recent] and [selected chunks], keys rebuilt in-kernel ----
@@ -63,14 +66,14 @@ hipError_t launch_fill_i32(int32_t* p, size_t n, int32_t value, hipStream_t st);
 // [i*res_split_len, ...); a combine kernel merges the splits into `out`.
 struct AttnArgs {
   const bf16_t* q;          // [b, h_q, d]
-  const bf16_t* A;          // [b, s, r]
+  const bf16_t* A;          // [b, s_cap, r]
   const bf16_t* B;          // [units, r, d]
   const bf16_t* k_outlier;  // [units, o*c, d]
   const bf16_t* v_outlier;
   const bf16_t* k_local;    // [units, w, d]
   const bf16_t* v_local;
   const bf16_t* v_sparse;   // staged [units, k*c, d], or NULL: read v_store through sel_ids
-  const bf16_t* v_store;    // [units, s, d] (HBM, or device-readable pinned host memory)
+  const bf16_t* v_store;    // [units, s_cap, d] (HBM, or device-readable pinned host memory)
   const int32_t* sel_ids;   // [units, k] true chunk ids
   const int32_t* pos_offset;  // [b] or NULL
   const float* inv_freq_dev;  // optional [d/2]
@@ -79,6 +82,7 @@ struct AttnArgs {
   float2* part_ml;          // [b*h_q, n_splits] (max in log2 units, sum)
   bf16_t* out;              // [b, h_q, d]
   int batch, hq, hkv, d, s, c, o, k, w, r, r32, rp;
+  int s_cap;                // tokens A and v_store are laid out for (>= s)
   int res_split_len, sparse_split_len, n_splits;
   int c_shift;              // log2(c) when c is a power of two, else -1
   float scale_log2;         // softmax scale * log2(e)
@@ -91,9 +95,15 @@ hipError_t launch_attention(const AttnArgs& a, hipStream_t st);
 hipError_t launch_chunk_stats(const bf16_t* k_rope, bf16_t* chunk_mean, double* chunk_min_cos, int units, int d,
                               int s, int c, hipStream_t st);
 hipError_t launch_compact_landmarks(const bf16_t* chunk_mean, const int32_t* outlier_ids, bf16_t* landmarks,
-                                    int32_t* landmark_chunk_ids, int units, int d, int n_ch, int o, hipStream_t st);
+                                    int32_t* landmark_chunk_ids, int units, int d, int n_ch, int o, int nc_stride,
+                                    hipStream_t st);
 hipError_t launch_gather_outliers(const bf16_t* k_rope, const bf16_t* v, const int32_t* outlier_ids,
-                                  bf16_t* k_outlier, bf16_t* v_outlier, int units, int d, int s, int c, int o,
-                                  hipStream_t st);
+                                  bf16_t* k_outlier, bf16_t* v_outlier, int units, int d, int s, int s_cap, int c,
+                                  int o, hipStream_t st);
+
+// ---- generated tokens: one more chunk of context (low-rank states K' Psi, landmark, values) ----
+hipError_t launch_append_chunk(const bf16_t* k_pre, const bf16_t* k_rope, const bf16_t* v, const bf16_t* B, bf16_t* A,
+                               bf16_t* landmarks, int32_t* landmark_chunk_ids, bf16_t* value_store, int batch, int hkv,
+                               int d, int s, int s_cap, int c, int r, int o, hipStream_t st);
 
 }  // namespace skv

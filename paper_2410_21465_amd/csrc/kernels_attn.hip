@@ -152,7 +152,7 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
       const int i = min(row0 + sub, s_end - 1);
       const int ch = chunk_of(i);
       const size_t n = (size_t)(tokb[ch - ch_begin] + (i - ch * a.c));
-      const bf16_t* arow = a.A + ((size_t)b * a.s + n) * r;
+      const bf16_t* arow = a.A + ((size_t)b * a.s_cap + n) * r;
       // every load is issued (a fixed number in flight per block); rank positions past r read the row's
       // last 16 bytes instead and are zeroed when the block is taken up
 #pragma unroll
@@ -170,7 +170,7 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
       const int n0 = tokb[ch - ch_begin] + (ic - ch * a.c);
       tok[0] = n0;
       const bf16_t* vp = (a.v_sparse ? a.v_sparse + ((size_t)unit * kc + ic) * D
-                                     : a.v_store + ((size_t)unit * a.s + n0) * D) + sub * EPL;
+                                     : a.v_store + ((size_t)unit * a.s_cap + n0) * D) + sub * EPL;
 #pragma unroll
       for (int j = 0; j < 4; ++j) load_raw<EPL>(vp + (size_t)j * D, vraw[j]);
     } else {
@@ -183,7 +183,7 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
         const int n = tokb[ch - ch_begin] + (ic - ch * a.c);
         tok[j] = n;
         const bf16_t* vp = a.v_sparse ? a.v_sparse + ((size_t)unit * kc + ic) * D
-                                      : a.v_store + ((size_t)unit * a.s + n) * D;
+                                      : a.v_store + ((size_t)unit * a.s_cap + n) * D;
         load_raw<EPL>(vp + sub * EPL, vraw[j]);
       }
     }

@@ -93,8 +93,7 @@ __global__ __launch_bounds__(256) void gather_missing_kernel(const uint4* __rest
                                                              const int32_t* __restrict__ miss_slots,
                                                              const int32_t* __restrict__ n_miss,
                                                              uint4* __restrict__ v_cache, int k, int vec_per_chunk,
-                                                             size_t vec_per_unit_store) {
-  const int last_chunk = (int)(vec_per_unit_store / vec_per_chunk) - 1;
+                                                             size_t vec_per_unit_store, int last_chunk) {
   const int unit = blockIdx.y;
   const int total = min(max(n_miss[unit], 0), k) * vec_per_chunk;  // 16-byte vectors this unit fetches
   const int32_t* slots = cache_ids + (size_t)unit * k;
@@ -143,15 +142,15 @@ hipError_t launch_cache_update(const int32_t* sel_ids, int32_t* cache_ids, int32
 }
 
 hipError_t launch_gather_missing(const bf16_t* store, const int32_t* cache_ids, const int32_t* miss_slots,
-                                 const int32_t* n_miss, bf16_t* v_cache, int units, int d, int s, int c, int k,
-                                 hipStream_t st) {
+                                 const int32_t* n_miss, bf16_t* v_cache, int units, int d, int s, int s_cap, int c,
+                                 int k, hipStream_t st) {
   const int vec_per_chunk = c * d * 2 / 16;
   const int total = k * vec_per_chunk;
   int gx = (total + 256 * kMissUnroll - 1) / (256 * kMissUnroll);
   if (gx < 1) gx = 1;
   hipLaunchKernelGGL(gather_missing_kernel, dim3(gx, units), dim3(256), 0, st, reinterpret_cast<const uint4*>(store),
                      cache_ids, miss_slots, n_miss, reinterpret_cast<uint4*>(v_cache), k, vec_per_chunk,
-                     (size_t)s * d * 2 / 16);
+                     (size_t)s_cap * d * 2 / 16, s / c - 1);
   return hipGetLastError();
 }
 

@@ -13,8 +13,7 @@ constexpr int kGatherUnroll = 4;
 __global__ __launch_bounds__(256) void gather_values_kernel(const uint4* __restrict__ store,
                                                             const int32_t* __restrict__ sel_ids,
                                                             uint4* __restrict__ v_sparse, int k, int vec_per_chunk,
-                                                            size_t vec_per_unit_store) {
-  const int last_chunk = (int)(vec_per_unit_store / vec_per_chunk) - 1;
+                                                            size_t vec_per_unit_store, int last_chunk) {
   const int unit = blockIdx.y;
   const int32_t* ids = sel_ids + (size_t)unit * k;
   const uint4* src_u = store + (size_t)unit * vec_per_unit_store;
@@ -40,14 +39,14 @@ __global__ __launch_bounds__(256) void gather_values_kernel(const uint4* __restr
 }
 
 hipError_t launch_gather_values(const bf16_t* store, const int32_t* sel_ids, bf16_t* v_sparse, int units, int d,
-                                int s, int c, int k, hipStream_t st) {
+                                int s, int s_cap, int c, int k, hipStream_t st) {
   const int vec_per_chunk = c * d * 2 / 16;
   const int total = k * vec_per_chunk;
   int gx = (total + 256 * kGatherUnroll - 1) / (256 * kGatherUnroll);
   if (gx < 1) gx = 1;
   dim3 grid(gx, units), block(256);
   hipLaunchKernelGGL(gather_values_kernel, grid, block, 0, st, reinterpret_cast<const uint4*>(store), sel_ids,
-                     reinterpret_cast<uint4*>(v_sparse), k, vec_per_chunk, (size_t)s * d * 2 / 16);
+                     reinterpret_cast<uint4*>(v_sparse), k, vec_per_chunk, (size_t)s_cap * d * 2 / 16, s / c - 1);
   return hipGetLastError();
 }
 

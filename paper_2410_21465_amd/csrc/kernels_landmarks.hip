@@ -172,7 +172,7 @@ __global__ __launch_bounds__(256) void compact_landmarks_kernel(const bf16_t* __
                                                                 const int32_t* __restrict__ outlier_ids,
                                                                 bf16_t* __restrict__ landmarks,
                                                                 int32_t* __restrict__ landmark_chunk_ids, int n_ch,
-                                                                int o) {
+                                                                int o, int nc_stride) {
   constexpr int EPL = D / 16;
   __shared__ int32_t oid[1024];
   const int unit = blockIdx.y, n_c = n_ch - o;
@@ -190,14 +190,14 @@ __global__ __launch_bounds__(256) void compact_landmarks_kernel(const bf16_t* __
     }
     const int j = slot + lo;
     const uint32_t* s32 = reinterpret_cast<const uint32_t*>(chunk_mean + ((size_t)unit * n_ch + j) * D + sub * EPL);
-    uint32_t* d32 = reinterpret_cast<uint32_t*>(landmarks + ((size_t)unit * n_c + slot) * D + sub * EPL);
+    uint32_t* d32 = reinterpret_cast<uint32_t*>(landmarks + ((size_t)unit * nc_stride + slot) * D + sub * EPL);
     if constexpr (EPL == 8) {
       *reinterpret_cast<uint4*>(d32) = *reinterpret_cast<const uint4*>(s32);
     } else {
 #pragma unroll
       for (int e = 0; e < EPL / 2; ++e) d32[e] = s32[e];
     }
-    if (sub == 0) landmark_chunk_ids[(size_t)unit * n_c + slot] = j;
+    if (sub == 0) landmark_chunk_ids[(size_t)unit * nc_stride + slot] = j;
   }
 }
 
@@ -206,7 +206,8 @@ __global__ __launch_bounds__(256) void gather_outliers_kernel(const uint4* __res
                                                               const int32_t* __restrict__ outlier_ids,
                                                               uint4* __restrict__ k_outlier,
                                                               uint4* __restrict__ v_outlier, int o,
-                                                              int vec_per_chunk, size_t vec_per_unit) {
+                                                              int vec_per_chunk, size_t vec_per_unit,
+                                                              size_t vec_per_unit_v) {
   const int unit = blockIdx.y, i = blockIdx.x;
   const int last_chunk = (int)(vec_per_unit / vec_per_chunk) - 1;
   const int id = min(max(outlier_ids[(size_t)unit * o + i], 0), last_chunk);
@@ -214,7 +215,7 @@ __global__ __launch_bounds__(256) void gather_outliers_kernel(const uint4* __res
   const size_t dst = ((size_t)unit * o + i) * vec_per_chunk;
   for (int x = threadIdx.x; x < vec_per_chunk; x += 256) {
     k_outlier[dst + x] = k_rope[src + x];
-    if (v) v_outlier[dst + x] = v[src + x];
+    if (v) v_outlier[dst + x] = v[(size_t)unit * vec_per_unit_v + (size_t)id * vec_per_chunk + x];
   }
 }
 
@@ -238,27 +239,29 @@ hipError_t launch_chunk_stats(const bf16_t* k_rope, bf16_t* chunk_mean, double* 
 }
 
 hipError_t launch_compact_landmarks(const bf16_t* chunk_mean, const int32_t* outlier_ids, bf16_t* landmarks,
-                                    int32_t* landmark_chunk_ids, int units, int d, int n_ch, int o, hipStream_t st) {
+                                    int32_t* landmark_chunk_ids, int units, int d, int n_ch, int o, int nc_stride,
+                                    hipStream_t st) {
   const int n_c = n_ch - o;
   if (n_c <= 0) return hipSuccess;
   dim3 grid((n_c + 127) / 128, units), block(256);
   switch (d) {
-    case 64: hipLaunchKernelGGL((compact_landmarks_kernel<64>), grid, block, 0, st, chunk_mean, outlier_ids, landmarks, landmark_chunk_ids, n_ch, o); break;
-    case 96: hipLaunchKernelGGL((compact_landmarks_kernel<96>), grid, block, 0, st, chunk_mean, outlier_ids, landmarks, landmark_chunk_ids, n_ch, o); break;
-    case 128: hipLaunchKernelGGL((compact_landmarks_kernel<128>), grid, block, 0, st, chunk_mean, outlier_ids, landmarks, landmark_chunk_ids, n_ch, o); break;
+    case 64: hipLaunchKernelGGL((compact_landmarks_kernel<64>), grid, block, 0, st, chunk_mean, outlier_ids, landmarks, landmark_chunk_ids, n_ch, o, nc_stride); break;
+    case 96: hipLaunchKernelGGL((compact_landmarks_kernel<96>), grid, block, 0, st, chunk_mean, outlier_ids, landmarks, landmark_chunk_ids, n_ch, o, nc_stride); break;
+    case 128: hipLaunchKernelGGL((compact_landmarks_kernel<128>), grid, block, 0, st, chunk_mean, outlier_ids, landmarks, landmark_chunk_ids, n_ch, o, nc_stride); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
 }
 
 hipError_t launch_gather_outliers(const bf16_t* k_rope, const bf16_t* v, const int32_t* outlier_ids,
-                                  bf16_t* k_outlier, bf16_t* v_outlier, int units, int d, int s, int c, int o,
-                                  hipStream_t st) {
+                                  bf16_t* k_outlier, bf16_t* v_outlier, int units, int d, int s, int s_cap, int c,
+                                  int o, hipStream_t st) {
   if (o <= 0) return hipSuccess;
   dim3 grid(o, units), block(256);
   hipLaunchKernelGGL(gather_outliers_kernel, grid, block, 0, st, reinterpret_cast<const uint4*>(k_rope),
                      reinterpret_cast<const uint4*>(v), outlier_ids, reinterpret_cast<uint4*>(k_outlier),
-                     reinterpret_cast<uint4*>(v_outlier), o, c * d * 2 / 16, (size_t)s * d * 2 / 16);
+                     reinterpret_cast<uint4*>(v_outlier), o, c * d * 2 / 16, (size_t)s * d * 2 / 16,
+                     (size_t)s_cap * d * 2 / 16);
   return hipGetLastError();
 }
 

@@ -37,7 +37,7 @@ __device__ __forceinline__ void lse_merge(double& m, double& s, double m2, doubl
 template <int D>
 __global__ __launch_bounds__(256) void score_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ L,
                                                     double* __restrict__ logits, double2* __restrict__ partials,
-                                                    int hq, int hkv, int G, int n_c, int n_tiles, double scale) {
+                                                    int hq, int hkv, int G, int n_c, int nc_stride, int n_tiles, double scale) {
   constexpr int NI = D / 32;  // 16-byte pieces per lane per row
   __shared__ double2 wred[4][4];
   const int unit = blockIdx.y, tile = blockIdx.x, g0 = blockIdx.z * 4;
@@ -60,7 +60,7 @@ __global__ __launch_bounds__(256) void score_kernel(const bf16_t* __restrict__ q
     }
   }
 
-  const bf16_t* Lu = L + (size_t)unit * n_c * D;
+  const bf16_t* Lu = L + (size_t)unit * nc_stride * D;  // the landmark array may have room to grow
   const int row0 = tile * kScoreTile + wave * kWave;
   uint4 w[4][NI];
 #pragma unroll
@@ -110,14 +110,14 @@ __global__ __launch_bounds__(256) void score_kernel(const bf16_t* __restrict__ q
 }
 
 hipError_t launch_score(const bf16_t* q, const bf16_t* landmarks, double* logits, double2* partials, int batch,
-                        int hq, int hkv, int d, int n_c, double scale, hipStream_t st) {
+                        int hq, int hkv, int d, int n_c, int nc_stride, double scale, hipStream_t st) {
   const int G = hq / hkv;
   const int n_tiles = (n_c + kScoreTile - 1) / kScoreTile;
   dim3 grid(n_tiles, batch * hkv, (G + 3) / 4), block(256);
   switch (d) {
-    case 64: hipLaunchKernelGGL((score_kernel<64>), grid, block, 0, st, q, landmarks, logits, partials, hq, hkv, G, n_c, n_tiles, scale); break;
-    case 96: hipLaunchKernelGGL((score_kernel<96>), grid, block, 0, st, q, landmarks, logits, partials, hq, hkv, G, n_c, n_tiles, scale); break;
-    case 128: hipLaunchKernelGGL((score_kernel<128>), grid, block, 0, st, q, landmarks, logits, partials, hq, hkv, G, n_c, n_tiles, scale); break;
+    case 64: hipLaunchKernelGGL((score_kernel<64>), grid, block, 0, st, q, landmarks, logits, partials, hq, hkv, G, n_c, nc_stride, n_tiles, scale); break;
+    case 96: hipLaunchKernelGGL((score_kernel<96>), grid, block, 0, st, q, landmarks, logits, partials, hq, hkv, G, n_c, nc_stride, n_tiles, scale); break;
+    case 128: hipLaunchKernelGGL((score_kernel<128>), grid, block, 0, st, q, landmarks, logits, partials, hq, hkv, G, n_c, nc_stride, n_tiles, scale); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();

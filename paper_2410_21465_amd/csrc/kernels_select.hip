@@ -73,7 +73,7 @@ __global__ __launch_bounds__(kSelNT) void select_slices(SelectArgs a) {
     for (int e = 0; e < E; ++e)
       if ((sel & (1u << e)) && pos < k_here) {
         const int j = base + threadIdx.x * E + e;
-        const int id = a.id_map ? a.id_map[(size_t)unit * a.n + j] : j;
+        const int id = a.id_map ? a.id_map[(size_t)unit * a.id_stride + j] : j;
         a.out_ids[(size_t)unit * a.k + pos] = id;
         if (a.out_ids2) a.out_ids2[(size_t)unit * a.k + pos] = id;
         ++pos;
@@ -112,7 +112,7 @@ __global__ __launch_bounds__(kSelNT) void select_merge(SelectArgs a) {
 #pragma unroll
   for (int e = 0; e < E; ++e)
     if ((sel & (1u << e)) && pos < a.k) {
-      const int id = a.id_map ? a.id_map[(size_t)unit * a.n + idx[e]] : idx[e];
+      const int id = a.id_map ? a.id_map[(size_t)unit * a.id_stride + idx[e]] : idx[e];
       a.out_ids[(size_t)unit * a.k + pos] = id;
       if (a.out_ids2) a.out_ids2[(size_t)unit * a.k + pos] = id;
       ++pos;

@@ -45,6 +45,7 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 struct Shape {
   int b, hq, hkv, G, d, s, c, r, o, k, w, n_ch, n_c, units;
+  int cap, nc_cap;  // tokens / landmark rows the context arrays are laid out for
   bool stage, keep_keys;
 };
 
@@ -70,6 +71,10 @@ int check_params(const shadowkv_params* p, bool decode, Shape* sh) {
   sh->b = p->batch; sh->hq = p->n_q_heads; sh->hkv = p->n_kv_heads; sh->G = sh->hq / sh->hkv;
   sh->d = p->head_dim; sh->s = p->ctx_len; sh->c = p->chunk_size; sh->o = p->n_outlier_chunks;
   sh->n_ch = (int)n_ch; sh->n_c = (int)n_ch - sh->o; sh->units = (int)units;
+  if (p->ctx_capacity != 0 && (p->ctx_capacity < p->ctx_len || p->ctx_capacity % p->chunk_size))
+    return fail_inval("ctx_capacity must be 0 or a multiple of chunk_size that is >= ctx_len");
+  sh->cap = p->ctx_capacity ? p->ctx_capacity : p->ctx_len;
+  sh->nc_cap = sh->cap / sh->c - sh->o;
   sh->r = p->rank; sh->k = p->topk_chunks; sh->w = p->local_len;
   sh->stage = p->value_location == SHADOWKV_VALUES_HOST || (p->flags & SHADOWKV_FLAG_STAGE_VALUES);
   sh->keep_keys = (p->flags & SHADOWKV_FLAG_KEEP_REBUILT_KEYS) != 0;
@@ -336,11 +341,12 @@ int shadowkv_build_landmarks(const shadowkv_params* params, const shadowkv_bf16*
     a.out_ids = outlier_chunk_ids;
     e = launch_select(a, L.sel, kSrcArray, sh.units, st);
     if (e != hipSuccess) return fail_hip("select outliers", e);
-    e = launch_gather_outliers(k_rope, v, outlier_chunk_ids, k_outlier, v_outlier, sh.units, sh.d, sh.s, sh.c, sh.o, st);
+    e = launch_gather_outliers(k_rope, v, outlier_chunk_ids, k_outlier, v_outlier, sh.units, sh.d, sh.s, sh.cap, sh.c,
+                               sh.o, st);
     if (e != hipSuccess) return fail_hip("gather outliers", e);
   }
   e = launch_compact_landmarks(chunk_mean, outlier_chunk_ids, landmarks, landmark_chunk_ids, sh.units, sh.d, sh.n_ch,
-                               sh.o, st);
+                               sh.o, sh.nc_cap, st);
   if (e != hipSuccess) return fail_hip("compact landmarks", e);
   return SHADOWKV_OK;
 }
@@ -403,7 +409,7 @@ static int decode_impl(const shadowkv_params* params, const shadowkv_bf16* q, co
   const int pstep = (g_prof.on && g_prof.n_steps < g_prof.max_steps) ? g_prof.n_steps++ : -1;
   prof_mark(st, pstep, 0);
   // 1. P = Q L^T / sqrt(d), per-tile softmax statistics
-  hipError_t e = launch_score(q, landmarks, logits, partials, sh.b, sh.hq, sh.hkv, sh.d, sh.n_c, scale, st);
+  hipError_t e = launch_score(q, landmarks, logits, partials, sh.b, sh.hq, sh.hkv, sh.d, sh.n_c, sh.nc_cap, scale, st);
   if (e != hipSuccess) return fail_hip("score", e);
   prof_mark(st, pstep, 1);
   // 2. softmax normaliser per head, max over the group, ArgTopK -> true chunk ids
@@ -413,7 +419,7 @@ static int decode_impl(const shadowkv_params* params, const shadowkv_bf16* q, co
   a.slice_len = L.sel.slice_len; a.n_slices = L.sel.n_slices; a.cand_stride = L.sel.cand_stride;
   a.cand_key = reinterpret_cast<uint64_t*>(ws + L.cand_key);
   a.cand_idx = reinterpret_cast<int32_t*>(ws + L.cand_idx);
-  a.id_map = landmark_chunk_ids;
+  a.id_map = landmark_chunk_ids; a.id_stride = sh.nc_cap;
   a.out_ids = sel_ids; a.out_ids2 = out_chunk_ids;
   e = launch_select(a, L.sel, kSrcLogits, sh.units, st);
   if (e != hipSuccess) return fail_hip("select chunks", e);
@@ -433,7 +439,7 @@ static int decode_impl(const shadowkv_params* params, const shadowkv_bf16* q, co
       gs = side;
     }
     e = launch_gather_missing(value_store, cache->chunk_ids, miss_slots, n_miss, cache->values, sh.units, sh.d, sh.s,
-                              sh.c, sh.k, gs);
+                              sh.cap, sh.c, sh.k, gs);
     if (e != hipSuccess) return fail_hip("gather missing values", e);
     if (fork) {
       if ((e = hipEventRecord(ev_join, side)) != hipSuccess) return fail_hip("hipEventRecord", e);
@@ -449,7 +455,7 @@ static int decode_impl(const shadowkv_params* params, const shadowkv_bf16* q, co
       if ((e = hipStreamWaitEvent(side, ev_fork, 0)) != hipSuccess) return fail_hip("hipStreamWaitEvent", e);
       gs = side;
     }
-    e = launch_gather_values(value_store, sel_ids, v_sparse, sh.units, sh.d, sh.s, sh.c, sh.k, gs);
+    e = launch_gather_values(value_store, sel_ids, v_sparse, sh.units, sh.d, sh.s, sh.cap, sh.c, sh.k, gs);
     if (e != hipSuccess) return fail_hip("gather values", e);
     if (fork) {
       if ((e = hipEventRecord(ev_join, side)) != hipSuccess) return fail_hip("hipEventRecord", e);
@@ -466,6 +472,7 @@ static int decode_impl(const shadowkv_params* params, const shadowkv_bf16* q, co
   t.part_acc = reinterpret_cast<float*>(ws + L.part_acc);
   t.part_ml = reinterpret_cast<float2*>(ws + L.part_ml);
   t.out = out;
+  t.s_cap = sh.cap;
   t.batch = sh.b; t.hq = sh.hq; t.hkv = sh.hkv; t.d = sh.d; t.s = sh.s; t.c = sh.c; t.o = sh.o; t.k = sh.k; t.w = sh.w;
   t.r = sh.r; t.r32 = (sh.r + 31) / 32 * 32; t.rp = t.r32 + 8;  // +8: 16-byte multiple that spreads LDS banks
   t.res_split_len = L.attn.res_split_len; t.sparse_split_len = L.attn.sparse_split_len; t.n_splits = L.attn.n_splits;
@@ -502,6 +509,27 @@ int shadowkv_decode_step_cached(const shadowkv_params* params, const shadowkv_bf
   CacheIO c{value_cache, cache_chunk_ids, out_miss_count};
   return decode_impl(params, q, A, B, landmarks, landmark_chunk_ids, k_outlier, v_outlier, k_local, v_local,
                      value_store, pos_offset, &c, out, out_chunk_ids, workspace, workspace_bytes, stream, side_stream);
+}
+
+int shadowkv_append_chunk(const shadowkv_params* params, const shadowkv_bf16* k_pre, const shadowkv_bf16* k_rope,
+                          const shadowkv_bf16* v, const shadowkv_bf16* B, shadowkv_bf16* A, shadowkv_bf16* landmarks,
+                          int32_t* landmark_chunk_ids, shadowkv_bf16* value_store, void* stream) {
+  Shape sh;
+  int rc = check_params(params, false, &sh);
+  if (rc != SHADOWKV_OK) return rc;
+  if (params->rank < 8 || params->rank > 256 || params->rank % 8)
+    return fail_inval("rank must be a multiple of 8 in [8, 256]");
+  if (sh.s + sh.c > sh.cap)
+    return fail_inval("no room for another chunk: ctx_len %d + chunk_size %d exceeds ctx_capacity %d", sh.s, sh.c, sh.cap);
+  if (!k_pre || !k_rope || !v || !B || !A || !landmarks || !landmark_chunk_ids || !value_store)
+    return fail_inval("k_pre, k_rope, v, B, A, landmarks, landmark_chunk_ids and value_store must not be NULL");
+  if (!aligned16(k_pre) || !aligned16(k_rope) || !aligned16(v) || !aligned16(B) || !aligned16(A) ||
+      !aligned16(landmarks) || !aligned16(value_store))
+    return fail_inval("tensor pointers must be 16-byte aligned");
+  hipError_t e = launch_append_chunk(k_pre, k_rope, v, B, A, landmarks, landmark_chunk_ids, value_store, sh.b, sh.hkv,
+                                     sh.d, sh.s, sh.cap, sh.c, sh.r, sh.o, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return fail_hip("append chunk", e);
+  return SHADOWKV_OK;
 }
 
 size_t shadowkv_value_cache_bytes(const shadowkv_params* params) {

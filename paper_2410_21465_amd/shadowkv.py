@@ -26,7 +26,7 @@ EXPORTS = (
     "shadowkv_decode_workspace_bytes", "shadowkv_validate_params", "shadowkv_decode_workspace_view",
     "shadowkv_status_string", "shadowkv_last_error", "shadowkv_version", "shadowkv_shutdown",
     "shadowkv_profile_begin", "shadowkv_profile_end", "shadowkv_decode_step_cached", "shadowkv_value_cache_bytes",
-    "shadowkv_value_cache_reset",
+    "shadowkv_value_cache_reset", "shadowkv_append_chunk",
 )
 STAGES = ("score", "select", "gather_values", "attention")
 
@@ -38,6 +38,7 @@ class CParams(C.Structure):
         ("n_outlier_chunks", C.c_int32), ("topk_chunks", C.c_int32), ("local_len", C.c_int32),
         ("value_location", C.c_int32), ("flags", C.c_uint32),
         ("rope_theta", C.c_double), ("softmax_scale", C.c_double), ("inv_freq", C.c_void_p),
+        ("ctx_capacity", C.c_int32),
     ]
 
 
@@ -71,6 +72,8 @@ def lib() -> C.CDLL:
         L.shadowkv_value_cache_bytes.argtypes = [vp]
         L.shadowkv_value_cache_reset.restype = i32
         L.shadowkv_value_cache_reset.argtypes = [vp, vp, vp]
+        L.shadowkv_append_chunk.restype = i32
+        L.shadowkv_append_chunk.argtypes = [vp] * 10
         L.shadowkv_build_workspace_bytes.restype = sz
         L.shadowkv_build_workspace_bytes.argtypes = [vp]
         L.shadowkv_decode_workspace_bytes.restype = sz
@@ -139,10 +142,19 @@ class Params:
     rope_theta: float = 5e5
     softmax_scale: float = 0.0
     inv_freq: Optional[torch.Tensor] = None   # device float32 [head_dim/2]
+    ctx_capacity: int = 0                     # tokens the context arrays are laid out for (0 => ctx_len)
 
     @property
     def n_chunks(self) -> int:
         return self.ctx_len // self.chunk_size
+
+    @property
+    def capacity(self) -> int:
+        return self.ctx_capacity or self.ctx_len
+
+    @property
+    def landmark_capacity(self) -> int:
+        return self.capacity // self.chunk_size - self.n_outlier_chunks
 
     @property
     def n_landmarks(self) -> int:
@@ -155,7 +167,7 @@ class Params:
             inv = self.inv_freq.data_ptr()
         return CParams(self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim, self.ctx_len, self.chunk_size,
                        self.rank, self.n_outlier_chunks, self.topk_chunks, self.local_len, self.value_location,
-                       self.flags, float(self.rope_theta), float(self.softmax_scale), inv)
+                       self.flags, float(self.rope_theta), float(self.softmax_scale), inv, int(self.ctx_capacity))
 
     @classmethod
     def from_workload(cls, wl, **kw) -> "Params":
@@ -206,11 +218,11 @@ def build_landmarks(p: Params, k_rope: torch.Tensor, v: Optional[torch.Tensor] =
                     workspace: Optional[torch.Tensor] = None, stream=None) -> dict:
     """Pre-filling algorithm after its SVD line.  Returns the new device tensors."""
     b, h, s, d, c, o = p.batch, p.n_kv_heads, p.ctx_len, p.head_dim, p.chunk_size, p.n_outlier_chunks
-    n_c = p.n_landmarks
+    n_c = p.landmark_capacity      # rows allocated; the first p.n_landmarks are written
     dev = k_rope.device
     assert k_rope.dtype == torch.bfloat16 and tuple(k_rope.shape) == (b, h, s, d)
     if v is not None:
-        assert v.dtype == torch.bfloat16 and tuple(v.shape) == (b, h, s, d)
+        assert v.dtype == torch.bfloat16 and tuple(v.shape) == (b, h, p.capacity, d)
     bf, i32 = torch.bfloat16, torch.int32
     out = {
         "landmarks": torch.empty(b, h, max(n_c, 0), d, dtype=bf, device=dev),
@@ -250,6 +262,14 @@ def decode_step(p: Params, q, A, B, landmarks, landmark_chunk_ids, k_outlier, v_
                                     None if side_stream is None else _stream_ptr(side_stream))
     _check(rc)
     return out, out_chunk_ids, workspace
+
+
+def append_chunk(p: Params, k_pre, k_rope, v, B, A, landmarks, landmark_chunk_ids, value_store, stream=None) -> None:
+    """Append one chunk of generated tokens to the context in place (``p.ctx_len`` is the length before)."""
+    st = p.c_struct()
+    _check(lib().shadowkv_append_chunk(C.addressof(st), _ptr(k_pre), _ptr(k_rope), _ptr(v), _ptr(B), _ptr(A),
+                                       _ptr(landmarks), _ptr(landmark_chunk_ids), _ptr(value_store),
+                                       _stream_ptr(stream)))
 
 
 class ValueCache:

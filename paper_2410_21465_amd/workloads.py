@@ -250,3 +250,44 @@ def query_sequence(wl: Workload, n_steps: int, rho_q: float = 0.9, device: Optio
     q = torch.fft.ifft(torch.fft.fft(eps, dim=0) * hf[:, None, None, None], dim=0).real
     q = q / q.std()
     return q.to(torch.bfloat16).contiguous()
+
+
+def with_capacity(t: Dict[str, torch.Tensor], wl: Workload, capacity: int) -> Dict[str, torch.Tensor]:
+    """The tensors of ``generate`` whose token axis can grow (``A [b, cap, r]``, ``v [b, h_kv, cap, d]``) moved
+    into arrays laid out for ``capacity`` tokens; the unused tail is filled with NaN so that any read of it shows.
+    Pinned host memory is kept pinned."""
+    s = wl.ctx_len
+    assert capacity >= s and capacity % wl.chunk_size == 0
+    out = dict(t)
+    A = torch.full((wl.batch, capacity, wl.rank), float("nan"), dtype=torch.bfloat16, device=t["A"].device)
+    A[:, :s] = t["A"]
+    v_old = t["v"]
+    v = _alloc((wl.batch, wl.n_kv_heads, capacity, wl.head_dim), torch.bfloat16, v_old.device,
+               pinned=v_old.device.type == "cpu" and v_old.is_pinned())
+    v.fill_(float("nan"))
+    v[:, :, :s] = v_old
+    out["A"], out["v"] = A, v
+    return out
+
+
+def generated_chunk(wl: Workload, t: Dict[str, torch.Tensor], index: int, device: Optional[str] = None):
+    """Keys and values of the ``index``-th chunk of generated tokens (tokens ``s + index*c ...``), as a model
+    would produce them: pre-RoPE keys in the low-rank subspace of the context keys (coefficients with the
+    per-column scale of ``A``, times ``B``) plus N(0, 0.02^2) noise, the same keys rotated at their positions,
+    and N(0,1) values.  Returns bf16 ``(k_pre [b, c, h_kv*d], k_rope [b, h_kv, c, d], v [b, h_kv, c, d])``.
+    Own generator (seed ``3000 + wl.seed + 17*index``)."""
+    dev = torch.device(device or ("cuda" if torch.cuda.is_available() else "cpu"))
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(3000 + wl.seed + 17 * index)
+    b, hkv, d, c, r, s = wl.batch, wl.n_kv_heads, wl.head_dim, wl.chunk_size, wl.rank, wl.ctx_len
+    A = t["A"][:, :s].to(dev).float()
+    Bm = t["B"].to(dev).float()                                        # [b, h, r, d]
+    col_std = A.std(dim=1)                                             # [b, r]
+    coef = torch.randn(b, c, r, generator=gen, device=dev) * col_std[:, None, :]
+    k_pre = torch.einsum("bcr,bhrx->bchx", coef, Bm)
+    k_pre = k_pre + 0.02 * torch.randn(b, c, hkv, d, generator=gen, device=dev)
+    k_pre = k_pre.to(torch.bfloat16)
+    pos = torch.arange(s + index * c, s + (index + 1) * c, device=dev)
+    k_rope = _rotate(k_pre.float().permute(0, 2, 1, 3), pos, wl.rope_theta).to(torch.bfloat16).contiguous()
+    v = torch.randn(b, hkv, c, d, generator=gen, device=dev).to(torch.bfloat16)
+    return k_pre.reshape(b, c, hkv * d).contiguous(), k_rope, v

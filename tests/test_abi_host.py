@@ -101,3 +101,24 @@ def test_calls_reject_null_and_bad_workspace_without_a_gpu():
     # missing outlier tensors with o > 0
     rc = lib.shadowkv_decode_step(C.addressof(st), *args[:5], None, None, *args[7:], fake, None, fake, 1 << 40, None, None)
     assert rc == S.EINVAL
+
+
+def test_append_chunk_rejects_a_full_context_and_bad_capacity():
+    lib = S.lib()
+    fake = C.c_void_p(0x1000)
+    p = S.Params(batch=1, n_q_heads=8, n_kv_heads=2, head_dim=128, ctx_len=1024, chunk_size=8, rank=32,
+                 n_outlier_chunks=2, topk_chunks=16, local_len=4)
+    st = p.c_struct()
+    rc = lib.shadowkv_append_chunk(C.addressof(st), *([fake] * 8), None)
+    assert rc == S.EINVAL and "no room" in S.last_error()
+    p.ctx_capacity = 1028                      # not a multiple of the chunk size
+    st = p.c_struct()
+    assert lib.shadowkv_append_chunk(C.addressof(st), *([fake] * 8), None) == S.EINVAL
+    assert lib.shadowkv_validate_params(C.addressof(st), 1) == S.EINVAL
+    p.ctx_capacity = 1016                      # below ctx_len
+    st = p.c_struct()
+    assert lib.shadowkv_validate_params(C.addressof(st), 1) == S.EINVAL
+    p.ctx_capacity = 1032
+    st = p.c_struct()
+    assert lib.shadowkv_validate_params(C.addressof(st), 1) == S.OK
+    assert lib.shadowkv_append_chunk(C.addressof(st), None, *([fake] * 7), None) == S.EINVAL   # NULL k_pre
