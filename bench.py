@@ -53,6 +53,9 @@ def main() -> int:
                     help="run shadowkv_decode_step_cached over a ring of correlated queries (values fetched only for "
                          "chunks missing from last step's selection); meant for the host-store workloads")
     ap.add_argument("--rho-q", type=float, default=0.93, help="step-to-step correlation of the queries with --chunk-cache")
+    ap.add_argument("--append", type=int, default=0, metavar="N",
+                    help="lay the context arrays out with room for N more chunks and time N shadowkv_append_chunk calls "
+                         "after the decode measurement (reported as append_chunk_ms)")
     ap.add_argument("--stage-values", action="store_true",
                     help="stage the selected values with the gather kernel even for an HBM store "
                          "(gives profiles a plain copy kernel of known size: k*c*d*2 bytes per unit each way)")
@@ -63,7 +66,7 @@ def main() -> int:
 
     import torch
     from paper_2410_21465_amd import shadowkv as S
-    from paper_2410_21465_amd.workloads import CONFIGS, generate, query_sequence
+    from paper_2410_21465_amd.workloads import CONFIGS, generate, generated_chunk, query_sequence, with_capacity
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -73,8 +76,12 @@ def main() -> int:
     t0 = time.time()
     print(f"[bench] drawing {wl.name}", file=sys.stderr, flush=True)
     t = generate(wl, device=dev)
+    ctx_cap = wl.ctx_len + args.append * wl.chunk_size
+    if args.append:
+        t = with_capacity(t, wl, ctx_cap)
     print("[bench] inputs drawn", file=sys.stderr, flush=True)
-    p = S.Params.from_workload(wl, flags=S.FLAG_STAGE_VALUES if args.stage_values else 0)
+    p = S.Params.from_workload(wl, flags=S.FLAG_STAGE_VALUES if args.stage_values else 0,
+                               ctx_capacity=ctx_cap if args.append else 0)
     # pre-filling algorithm (after the SVD) through the library itself
     torch.cuda.synchronize()
     tb = time.time()
@@ -160,6 +167,19 @@ def main() -> int:
             miss.append(float(cache.miss_count.float().mean().item()) / wl.topk_chunks)
         hit_rate = 1.0 - sum(miss) / len(miss)
 
+    append_ms = None
+    if args.append:   # grow the context chunk by chunk (the step after decode once c tokens left the window)
+        chunks = [generated_chunk(wl, t, i, device=dev) for i in range(min(args.append, 4))]
+        torch.cuda.synchronize()
+        ev0.record()
+        for i in range(args.append):
+            kp, kr, vv = chunks[i % len(chunks)]
+            pa = S.Params.from_workload(wl, ctx_len=wl.ctx_len + i * wl.chunk_size, ctx_capacity=ctx_cap)
+            S.append_chunk(pa, kp, kr, vv, t["B"], t["A"], bl["landmarks"], bl["landmark_chunk_ids"], t["v"])
+        ev1.record()
+        torch.cuda.synchronize()
+        append_ms = ev0.elapsed_time(ev1) / args.append
+
     # what a plain device copy reaches on this machine (1 GiB, read + write counted), for scale
     src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
     dst = torch.empty_like(src)
@@ -200,6 +220,7 @@ def main() -> int:
         "step_hbm_gbps": ab["total"] / (ms_per_step * 1e-3) / 1e9,
         "build_landmarks_ms": build_ms,
         "device_copy_gbps": copy_gbps,
+        "append_chunk_ms": append_ms,
         "setup_s": setup_s,
     }
     if wl.value_location == "host":
@@ -230,6 +251,8 @@ def cpu_baseline(wl, t, budget_s: float) -> dict:
     def bits(x):
         return O.as_bits(x[:bs].detach().cpu())
 
+    s_len = wl.ctx_len      # the oracle gets the dense layout (the arrays may have room to grow)
+    t = dict(t, A=t["A"][:bs, :s_len].contiguous(), v=t["v"][:bs, :, :s_len].contiguous())
     k_rope, v = bits(t["k_rope"]), bits(t["v"])
     bl = O.build_landmarks(op, k_rope, v)
     del k_rope
