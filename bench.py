@@ -191,6 +191,18 @@ def main() -> int:
     torch.cuda.synchronize()
     copy_gbps = 10 * 2 * src.numel() / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
     del src, dst
+    h2d_gbps = None
+    if wl.value_location == "host":   # what a plain pinned-host -> device copy reaches (the link the gather reads over)
+        hsrc = torch.empty(1 << 28, dtype=torch.uint8, pin_memory=True)
+        ddst = torch.empty(1 << 28, dtype=torch.uint8, device=dev)
+        ddst.copy_(hsrc, non_blocking=True)
+        ev0.record()
+        for _ in range(4):
+            ddst.copy_(hsrc, non_blocking=True)
+        ev1.record()
+        torch.cuda.synchronize()
+        h2d_gbps = 4 * hsrc.numel() / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
+        del hsrc, ddst
 
     ab = algorithmic_bytes(wl)
     score_ms = prof["ms"]["score"]
@@ -225,12 +237,15 @@ def main() -> int:
     }
     if wl.value_location == "host":
         res["value_gather_pcie_bytes"] = ab["values"]
+        res["pinned_h2d_copy_gbps"] = h2d_gbps
+        res["value_gather_pcie_gbps"] = ab["values"] / (prof["ms"]["gather_values"] * 1e-3) / 1e9
     if cache is not None:
         res["config"]["chunk_cache"] = True
         res["config"]["rho_q"] = args.rho_q
         res["cache_hit_rate"] = hit_rate
         if wl.value_location == "host":
             res["value_gather_pcie_bytes"] = ab["values"] * (1.0 - hit_rate)
+            res["value_gather_pcie_gbps"] = res["value_gather_pcie_bytes"] / (prof["ms"]["gather_values"] * 1e-3) / 1e9
 
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(wl, t, args.cpu_seconds)
