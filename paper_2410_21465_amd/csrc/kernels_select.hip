@@ -39,12 +39,34 @@ __global__ __launch_bounds__(kSelNT) void select_slices(SelectArgs a) {
 
   uint64_t key[E];
   if constexpr (SRC == kSrcLogits) {
-    unit_lse(a.partials + (size_t)unit * a.G * a.n_tiles, a.n_tiles, a.G, lse_sm);
+    // the logits of the first heads are requested before the normalisers are formed (the two do not
+    // depend on each other), the remaining heads of a large group afterwards
+    constexpr int GP = 4;
     const double* lg = a.logits + (size_t)unit * a.G * a.n;
+    const int j0 = base + threadIdx.x * E;
+    double pre[GP][E];
+#pragma unroll
+    for (int g = 0; g < GP; ++g) {
+      const double* row = lg + (size_t)min(g, a.G - 1) * a.n;
+#pragma unroll
+      for (int e = 0; e < E; ++e) pre[g][e] = row[min(j0 + e, a.n - 1)];
+    }
+    unit_lse(a.partials + (size_t)unit * a.G * a.n_tiles, a.n_tiles, a.G, lse_sm);
 #pragma unroll
     for (int e = 0; e < E; ++e) key[e] = 0ull;
-    const int j0 = base + threadIdx.x * E;
-    for (int g = 0; g < a.G; ++g) {
+#pragma unroll
+    for (int g = 0; g < GP; ++g) {
+      if (g < a.G) {
+        const double l = lse_sm[g];
+#pragma unroll
+        for (int e = 0; e < E; ++e)
+          if (j0 + e < a.n) {
+            const uint64_t kk = f64_key(pre[g][e] - l);
+            key[e] = kk > key[e] ? kk : key[e];   // max over the heads of the group
+          }
+      }
+    }
+    for (int g = GP; g < a.G; ++g) {
       const double l = lse_sm[g];
       const double* row = lg + (size_t)g * a.n;
 #pragma unroll
@@ -52,7 +74,7 @@ __global__ __launch_bounds__(kSelNT) void select_slices(SelectArgs a) {
         const int j = j0 + e;
         if (j < a.n) {
           const uint64_t kk = f64_key(row[j] - l);
-          key[e] = kk > key[e] ? kk : key[e];   // max over the heads of the group
+          key[e] = kk > key[e] ? kk : key[e];
         }
       }
     }
