@@ -33,6 +33,7 @@ struct SelectArgs {
   const double* scores;     // kSrcArray: [units, n]
   double sign;
   int n, k, slice_len, n_slices, cand_stride;
+  int group_cands, n_groups, cand2_off;  // middle level (0 groups = none): see SelectPlan
   uint64_t* cand_key;       // [units, cand_stride] survivors of the slices
   int32_t* cand_idx;
   const int32_t* id_map;    // optional [units, id_stride]: index -> reported id
@@ -40,8 +41,12 @@ struct SelectArgs {
   int32_t* out_ids;         // [units, k], ascending index order
   int32_t* out_ids2;        // optional copy
 };
+// Survivors of the slices are ranked by one workgroup per unit when there are at most 4096 of them;
+// otherwise groups of them (group_cands each) are first cut down to k per group by a middle level whose
+// output lives behind the slices' survivors in the same arrays (offset cand2_off inside a unit's stride).
 struct SelectPlan {
   int e, slice_len, n_slices, cand_stride, merge_e;
+  int group_cands, n_groups, cand2_off, mid_e;
 };
 bool plan_select(int n, int k, SelectPlan* plan);
 hipError_t launch_select(const SelectArgs& a, const SelectPlan& plan, int src, int units, hipStream_t st);

@@ -46,6 +46,19 @@ __global__ __launch_bounds__(256) void score_kernel(const bf16_t* __restrict__ q
   const int kq = lane >> 4, blk = (lane >> 2) & 3, ij = lane & 3;
   const size_t head0 = (size_t)b * hq + (size_t)h * G + g0;
 
+  const bf16_t* Lu = L + (size_t)unit * nc_stride * D;  // the landmark array may have room to grow
+  const int row0 = tile * kScoreTile + wave * kWave;
+  uint4 w[4][NI];  // requested before q: the landmark rows are the long-latency loads
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    const int r = row0 + t * 16 + blk * 4 + ij;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      w[t][i] = make_uint4(0u, 0u, 0u, 0u);
+      if (r < n_c) w[t][i] = *reinterpret_cast<const uint4*>(Lu + (size_t)r * D + 32 * i + 8 * kq);
+    }
+  }
+
   // A operand: q of head g0 + ij, the elements this lane's k-slot meets, as fp64
   double qa[NI][8];
   {
@@ -57,19 +70,6 @@ __global__ __launch_bounds__(256) void score_kernel(const bf16_t* __restrict__ q
       load_bf16_row<8>(qp + 32 * i, x);
 #pragma unroll
       for (int e = 0; e < 8; ++e) qa[i][e] = hv ? (double)x[e] : 0.0;
-    }
-  }
-
-  const bf16_t* Lu = L + (size_t)unit * nc_stride * D;  // the landmark array may have room to grow
-  const int row0 = tile * kScoreTile + wave * kWave;
-  uint4 w[4][NI];
-#pragma unroll
-  for (int t = 0; t < 4; ++t) {
-    const int r = row0 + t * 16 + blk * 4 + ij;
-#pragma unroll
-    for (int i = 0; i < NI; ++i) {
-      w[t][i] = make_uint4(0u, 0u, 0u, 0u);
-      if (r < n_c) w[t][i] = *reinterpret_cast<const uint4*>(Lu + (size_t)r * D + 32 * i + 8 * kq);
     }
   }
 

@@ -6,6 +6,7 @@
 // unit.  With a single slice the first kernel writes the final ids itself.
 #include "kernels.hpp"
 #include "select.hpp"
+#include <cstdlib>
 
 namespace skv {
 
@@ -112,15 +113,29 @@ __global__ __launch_bounds__(kSelNT) void select_slices(SelectArgs a) {
   }
 }
 
-template <int E>
+// MID: one workgroup per (group of survivors, unit) keeps the k best of its group as new survivors;
+// otherwise one workgroup per unit ranks the survivors (of the slices, or of the middle level) and
+// writes the final ids.
+template <int E, bool MID>
 __global__ __launch_bounds__(kSelNT) void select_merge(SelectArgs a) {
   __shared__ SelectSmem<kSelNT> sm;
-  const int unit = blockIdx.x;
+  const int unit = MID ? blockIdx.y : blockIdx.x;
   const int per = min(a.k, a.slice_len);
   const int n_last = a.n - (a.n_slices - 1) * a.slice_len;
-  const int n_cand = (a.n_slices - 1) * per + min(a.k, n_last);
+  const int n_first = (a.n_slices - 1) * per + min(a.k, n_last);  // survivors of the slices
   const uint64_t* ck = a.cand_key + (size_t)unit * a.cand_stride;
   const int32_t* ci = a.cand_idx + (size_t)unit * a.cand_stride;
+  int n_cand = n_first, k_here = a.k;
+  if constexpr (MID) {
+    const int g0 = blockIdx.x * a.group_cands;
+    ck += g0; ci += g0;
+    n_cand = min(a.group_cands, n_first - g0);
+    k_here = min(a.k, n_cand);
+  } else if (a.n_groups > 0) {  // the middle level ran: its survivors are packed k per group
+    ck += a.cand2_off; ci += a.cand2_off;
+    const int n_last_group = n_first - (a.n_groups - 1) * a.group_cands;
+    n_cand = (a.n_groups - 1) * a.k + min(a.k, n_last_group);
+  }
   uint64_t key[E];
   int idx[E];
 #pragma unroll
@@ -130,31 +145,63 @@ __global__ __launch_bounds__(kSelNT) void select_merge(SelectArgs a) {
     idx[e] = c < n_cand ? ci[c] : 0;
   }
   uint32_t sel; int pos;
-  block_select_topk<kSelNT, E>(key, a.k, sm, sel, pos);
+  block_select_topk<kSelNT, E>(key, k_here, sm, sel, pos);
+  if constexpr (MID) {
+    const size_t off = (size_t)unit * a.cand_stride + a.cand2_off + (size_t)blockIdx.x * a.k;
 #pragma unroll
-  for (int e = 0; e < E; ++e)
-    if ((sel & (1u << e)) && pos < a.k) {
-      const int id = a.id_map ? a.id_map[(size_t)unit * a.id_stride + idx[e]] : idx[e];
-      a.out_ids[(size_t)unit * a.k + pos] = id;
-      if (a.out_ids2) a.out_ids2[(size_t)unit * a.k + pos] = id;
-      ++pos;
-    }
+    for (int e = 0; e < E; ++e)
+      if ((sel & (1u << e)) && pos < k_here) {
+        a.cand_key[off + pos] = key[e];
+        a.cand_idx[off + pos] = idx[e];
+        ++pos;
+      }
+  } else {
+    // survivors are in ascending index within a slice / group and slices / groups are in order, so the
+    // output is in ascending index here as well
+#pragma unroll
+    for (int e = 0; e < E; ++e)
+      if ((sel & (1u << e)) && pos < a.k) {
+        const int id = a.id_map ? a.id_map[(size_t)unit * a.id_stride + idx[e]] : idx[e];
+        a.out_ids[(size_t)unit * a.k + pos] = id;
+        if (a.out_ids2) a.out_ids2[(size_t)unit * a.k + pos] = id;
+        ++pos;
+      }
+  }
 }
 
 // ---- host side ----------------------------------------------------------------
-// Smallest per-thread element count whose slice plan fits the merge kernel.
+// Smallest per-thread element count whose slice plan fits the merge kernels.  More than 4096
+// survivors go through the middle level in groups of 2048 (k <= 2048) or 16384.
 bool plan_select(int n, int k, SelectPlan* plan) {
   static const int es[] = {4, 8, 16, 32};
+  int forced = 0;
+  if (const char* ov = std::getenv("SHADOWKV_SELECT_E")) forced = std::atoi(ov);  // tuning override: keys per thread
+  const long cap = (long)kSelNT * 32;  // what one workgroup can rank
   for (int e : es) {
+    if (forced && e != forced && e != 32) continue;
     const int slice_len = kSelNT * e;
     const int n_slices = (n + slice_len - 1) / slice_len;
-    const long cand = (long)n_slices * (k < slice_len ? k : slice_len);
-    if (n_slices == 1 || cand <= (long)kSelNT * 32) {
-      plan->e = e; plan->slice_len = slice_len; plan->n_slices = n_slices;
-      plan->cand_stride = n_slices == 1 ? 0 : (int)cand;
-      int me = 1;
-      while ((long)kSelNT * me < cand) me *= 2;
-      plan->merge_e = n_slices == 1 ? 0 : me;
+    const long per = k < slice_len ? k : slice_len;
+    const long cand = (long)n_slices * per;
+    *plan = SelectPlan{};
+    plan->e = e; plan->slice_len = slice_len; plan->n_slices = n_slices;
+    if (n_slices == 1) return true;
+    auto fit = [](long c) { int me = 1; while ((long)kSelNT * me < c) me *= 2; return me; };
+    // middle level (more than 4096 survivors): groups of whole slices, at most `cap` survivors in, k out
+    if (cand > 4096 && !forced) {
+      long group = k <= 2048 ? 2048 : cap;
+      group = group / per * per;
+      const long n_groups = group > 0 ? (cand + group - 1) / group : 0;
+      const long cand2 = n_groups * k;
+      if (group >= 2 * per && n_groups >= 2 && cand2 <= 4096) {
+        plan->group_cands = (int)group; plan->n_groups = (int)n_groups; plan->cand2_off = (int)cand;
+        plan->cand_stride = (int)(cand + cand2);
+        plan->mid_e = fit(group); plan->merge_e = fit(cand2);
+        return true;
+      }
+    }
+    if (cand <= cap) {
+      plan->cand_stride = (int)cand; plan->merge_e = fit(cand);
       return true;
     }
   }
@@ -174,21 +221,32 @@ static hipError_t launch_slices(const SelectArgs& a, int e, int units, hipStream
   return hipGetLastError();
 }
 
-hipError_t launch_select(const SelectArgs& a, const SelectPlan& plan, int src, int units, hipStream_t st) {
-  hipError_t err = src == kSrcLogits ? launch_slices<kSrcLogits>(a, plan.e, units, st)
-                                     : launch_slices<kSrcArray>(a, plan.e, units, st);
-  if (err != hipSuccess || a.n_slices == 1) return err;
-  dim3 grid(units), block(kSelNT);
-  switch (plan.merge_e) {
-    case 1: hipLaunchKernelGGL((select_merge<1>), grid, block, 0, st, a); break;
-    case 2: hipLaunchKernelGGL((select_merge<2>), grid, block, 0, st, a); break;
-    case 4: hipLaunchKernelGGL((select_merge<4>), grid, block, 0, st, a); break;
-    case 8: hipLaunchKernelGGL((select_merge<8>), grid, block, 0, st, a); break;
-    case 16: hipLaunchKernelGGL((select_merge<16>), grid, block, 0, st, a); break;
-    case 32: hipLaunchKernelGGL((select_merge<32>), grid, block, 0, st, a); break;
+template <bool MID>
+static hipError_t launch_merge(const SelectArgs& a, int e, dim3 grid, hipStream_t st) {
+  dim3 block(kSelNT);
+  switch (e) {
+    case 1: hipLaunchKernelGGL((select_merge<1, MID>), grid, block, 0, st, a); break;
+    case 2: hipLaunchKernelGGL((select_merge<2, MID>), grid, block, 0, st, a); break;
+    case 4: hipLaunchKernelGGL((select_merge<4, MID>), grid, block, 0, st, a); break;
+    case 8: hipLaunchKernelGGL((select_merge<8, MID>), grid, block, 0, st, a); break;
+    case 16: hipLaunchKernelGGL((select_merge<16, MID>), grid, block, 0, st, a); break;
+    case 32: hipLaunchKernelGGL((select_merge<32, MID>), grid, block, 0, st, a); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
+}
+
+hipError_t launch_select(const SelectArgs& a0, const SelectPlan& plan, int src, int units, hipStream_t st) {
+  SelectArgs a = a0;
+  a.group_cands = plan.group_cands; a.n_groups = plan.n_groups; a.cand2_off = plan.cand2_off;
+  hipError_t err = src == kSrcLogits ? launch_slices<kSrcLogits>(a, plan.e, units, st)
+                                     : launch_slices<kSrcArray>(a, plan.e, units, st);
+  if (err != hipSuccess || a.n_slices == 1) return err;
+  if (plan.n_groups > 0) {
+    err = launch_merge<true>(a, plan.mid_e, dim3(plan.n_groups, units), st);
+    if (err != hipSuccess) return err;
+  }
+  return launch_merge<false>(a, plan.merge_e, dim3(units), st);
 }
 
 }  // namespace skv

@@ -33,6 +33,8 @@ CASES = [
     wl("budget-1", topk_chunks=1),
     wl("budget-4096", chunk_size=1, ctx_len=6000, n_outlier_chunks=3, topk_chunks=4096, head_dim=64, rank=16,
        n_q_heads=2, n_kv_heads=1),
+    wl("three-level-select", chunk_size=1, ctx_len=40000, n_outlier_chunks=3, topk_chunks=256, head_dim=64, rank=16,
+       n_q_heads=2, n_kv_heads=1),                                            # 20 slices -> 5120 survivors -> groups
     wl("batch-40-units-320", batch=40, n_q_heads=8, n_kv_heads=8, head_dim=64, rank=64, ctx_len=512, topk_chunks=10,
        n_outlier_chunks=2),
 ]
