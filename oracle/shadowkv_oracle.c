@@ -359,45 +359,72 @@ int oracle_decode_step(const oracle_params *p, const uint16_t *q,
 
 /* ---- chunk cache of the offloaded values -------------------------------------
  * Section "High-throughput Decoding": the chunks selected by adjacent decode steps
- * repeat to a large part, so the values fetched for the last step are kept and an
- * index scan finds the chunks that are missing; only those are fetched (the
- * (1 - alpha) term of the equivalent-bandwidth formula).  The paper does not
- * fix a replacement policy; the reading taken: the cache of a (batch, KV head)
- * unit has one slot per selected chunk (k slots) and holds exactly the last
- * step's selection.  A chunk selected again keeps its slot.  The chunks that are
- * new, in ascending chunk id, take the slots whose chunk is no longer selected,
- * in ascending slot index.  Slot ids: -1 = empty.
+ * repeat to a large part, so fetched values are kept, an index scan finds the
+ * chunks that are missing, and only those are fetched (the (1 - alpha) term of the
+ * equivalent-bandwidth formula).  The paper names "a cache policy" without fixing
+ * one; the reading taken is least-recently-used over S >= k slots of one chunk
+ * each per (batch, KV head) unit:
+ *   - every step advances the unit's clock by one;
+ *   - a selected chunk found in a slot is a hit: it stays there, stamped with the
+ *     clock;
+ *   - the n_miss selected chunks that are in no slot take the n_miss slots that
+ *     were not hit and have the oldest stamps (empty slots are older than anything;
+ *     equal stamps: lower slot first).  Among those slots the assignment is by
+ *     order: missing chunks in ascending chunk id to slots in ascending index.
+ * With S == k this keeps exactly the last step's selection.
  *
  * sel_ids    [units, k]  this step's selection, ascending, distinct
- * cache_ids  [units, k]  in: chunk id per slot before the step; out: after
- * miss_slots [units, k]  out: the slots that have to be filled, ascending (first n_miss[u])
+ * cache_ids  [units, S]  in/out: chunk id per slot, -1 = empty
+ * stamps     [units, S+1] in/out: clock value of each slot's last use (0 = never),
+ *                         entry S is the unit's clock
+ * sel_slots  [units, k]  out: slot of every selected chunk after the step
+ * miss_slots [units, k]  out: the slots that have to be filled, ascending (first n_miss[u]), rest -1
  * n_miss     [units]     out
  * The attention output does not depend on the cache at all: a cached step equals
  * oracle_decode_step. */
-int oracle_cache_update(int64_t units, int k, const int32_t *sel_ids,
-                        int32_t *cache_ids, int32_t *miss_slots, int32_t *n_miss) {
-  if (units < 0 || k < 0 || !sel_ids || !cache_ids || !miss_slots || !n_miss) return -1;
-  char *hit = (char *)malloc((size_t)k + 1), *keep = (char *)malloc((size_t)k + 1);
-  if (!hit || !keep) { free(hit); free(keep); return -2; }
+int oracle_cache_update(int64_t units, int k, int S, const int32_t *sel_ids,
+                        int32_t *cache_ids, int32_t *stamps, int32_t *sel_slots,
+                        int32_t *miss_slots, int32_t *n_miss) {
+  if (units < 0 || k < 0 || S < k || !sel_ids || !cache_ids || !stamps || !sel_slots || !miss_slots || !n_miss)
+    return -1;
+  char *hit = (char *)malloc((size_t)k + 1), *keep = (char *)malloc((size_t)S + 1);
+  char *victim = (char *)malloc((size_t)S + 1);
+  if (!hit || !keep || !victim) { free(hit); free(keep); free(victim); return -2; }
   for (int64_t u = 0; u < units; ++u) {
     const int32_t *sel = sel_ids + u * k;
-    int32_t *cache = cache_ids + u * k, *ms = miss_slots + u * k;
+    int32_t *cache = cache_ids + u * S, *stamp = stamps + u * (S + 1);
+    int32_t *ss = sel_slots + u * k, *ms = miss_slots + u * k;
+    const int32_t clock = ++stamp[S];
     memset(hit, 0, (size_t)k);
-    memset(keep, 0, (size_t)k);
-    for (int slot = 0; slot < k; ++slot)          /* the index scan */
+    memset(keep, 0, (size_t)S);
+    memset(victim, 0, (size_t)S);
+    int n = k;
+    for (int slot = 0; slot < S; ++slot)          /* the index scan */
       for (int j = 0; j < k; ++j)
-        if (cache[slot] >= 0 && cache[slot] == sel[j] && !hit[j]) { hit[j] = 1; keep[slot] = 1; break; }
-    int n = 0, slot = 0;
+        if (cache[slot] >= 0 && cache[slot] == sel[j] && !hit[j]) {
+          hit[j] = 1; keep[slot] = 1; ss[j] = slot; stamp[slot] = clock; --n; break;
+        }
+    for (int i = 0; i < n; ++i) {                 /* the n least recently used of the other slots */
+      int best = -1;
+      for (int slot = 0; slot < S; ++slot) {
+        if (keep[slot] || victim[slot]) continue;
+        const int32_t a = cache[slot] < 0 ? -1 : stamp[slot];   /* empty: older than anything */
+        const int32_t b = best < 0 ? 0 : (cache[best] < 0 ? -1 : stamp[best]);
+        if (best < 0 || a < b) best = slot;
+      }
+      victim[best] = 1;
+    }
+    int slot = 0, m = 0;
     for (int j = 0; j < k; ++j) {
       if (hit[j]) continue;
-      while (keep[slot]) ++slot;                  /* next slot whose chunk fell out */
-      cache[slot] = sel[j];
-      ms[n++] = slot++;
+      while (!victim[slot]) ++slot;
+      cache[slot] = sel[j]; stamp[slot] = clock; ss[j] = slot;
+      ms[m++] = slot++;
     }
-    for (int j = n; j < k; ++j) ms[j] = -1;
-    n_miss[u] = n;
+    for (int j = m; j < k; ++j) ms[j] = -1;
+    n_miss[u] = m;
   }
-  free(hit); free(keep);
+  free(hit); free(keep); free(victim);
   return 0;
 }
 

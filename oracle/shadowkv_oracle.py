@@ -111,7 +111,7 @@ def _load():
         _lib.oracle_append_chunk.restype = C.c_int
         _lib.oracle_append_chunk.argtypes = [C.c_void_p] * 9
         _lib.oracle_cache_update.restype = C.c_int
-        _lib.oracle_cache_update.argtypes = [C.c_int64, C.c_int] + [C.c_void_p] * 4
+        _lib.oracle_cache_update.argtypes = [C.c_int64, C.c_int, C.c_int] + [C.c_void_p] * 6
     return _lib
 
 
@@ -228,21 +228,28 @@ def decode_step(p: OracleParams, q, A, B, landmarks, landmark_chunk_ids, k_outli
     return res
 
 
-def cache_update(sel_ids: np.ndarray, cache_ids: np.ndarray) -> dict:
+def cache_update(sel_ids: np.ndarray, cache_ids: np.ndarray, stamps: Optional[np.ndarray] = None) -> dict:
     """Chunk cache of the offloaded values (section "High-throughput Decoding"): index scan of this
-    step's selection ``sel_ids [units, k]`` (ascending) against the slots ``cache_ids [units, k]``
-    (-1 = empty).  Returns the new slot contents, the slots to fill and their number per unit."""
+    step's selection ``sel_ids [units, k]`` (ascending) against the slots ``cache_ids [units, S]``
+    (-1 = empty, S >= k), least-recently-used replacement with ``stamps [units, S+1]`` (last entry = the
+    unit's clock; None = a fresh all-zero state).  Returns the new slot contents and stamps, the slot of
+    every selected chunk, the slots to fill and their number per unit."""
     lib = _load()
     sel = np.ascontiguousarray(sel_ids, dtype=np.int32)
     cache = np.array(cache_ids, dtype=np.int32, order="C", copy=True)
-    assert sel.ndim == 2 and cache.shape == sel.shape
+    assert sel.ndim == 2 and cache.ndim == 2 and cache.shape[0] == sel.shape[0]
     units, k = sel.shape
+    S = cache.shape[1]
+    st = np.zeros((units, S + 1), np.int32) if stamps is None else np.array(stamps, dtype=np.int32, order="C", copy=True)
+    assert st.shape == (units, S + 1)
+    slots = np.zeros((units, k), np.int32)
     miss = np.zeros((units, k), np.int32)
     n_miss = np.zeros(units, np.int32)
-    rc = lib.oracle_cache_update(units, k, sel.ctypes.data, cache.ctypes.data, miss.ctypes.data, n_miss.ctypes.data)
+    rc = lib.oracle_cache_update(units, k, S, sel.ctypes.data, cache.ctypes.data, st.ctypes.data, slots.ctypes.data,
+                                 miss.ctypes.data, n_miss.ctypes.data)
     if rc != 0:
         raise ValueError(f"oracle_cache_update rejected its arguments (rc={rc})")
-    return {"cache_ids": cache, "miss_slots": miss, "n_miss": n_miss}
+    return {"cache_ids": cache, "stamps": st, "sel_slots": slots, "miss_slots": miss, "n_miss": n_miss}
 
 
 def append_chunk(p: OracleParams, k_pre, k_rope, v, B, A, landmarks, landmark_chunk_ids, value_store) -> None:

@@ -72,3 +72,72 @@ def test_hit_rate_formula_on_a_shifting_window():
         r = O.cache_update(sel, cache)
         assert r["n_miss"][0] == (k if step == 0 else 2)
         cache = r["cache_ids"]
+
+
+# ---- more slots than selected chunks: least-recently-used replacement ----
+
+def test_lru_hand_worked_case():
+    # 5 slots, 2 selected per step
+    r = O.cache_update(np.array([[3, 7]]), -np.ones((1, 5), np.int32))              # clock 1: slots 0,1 <- 3,7
+    assert r["cache_ids"].tolist() == [[3, 7, -1, -1, -1]] and r["sel_slots"].tolist() == [[0, 1]]
+    r = O.cache_update(np.array([[4, 7]]), r["cache_ids"], r["stamps"])             # clock 2: 7 hits, 4 -> first empty
+    assert r["cache_ids"].tolist() == [[3, 7, 4, -1, -1]] and r["n_miss"].tolist() == [1]
+    assert r["sel_slots"].tolist() == [[2, 1]] and r["miss_slots"][0, 0] == 2
+    r = O.cache_update(np.array([[8, 9]]), r["cache_ids"], r["stamps"])             # clock 3: the two empties
+    assert r["cache_ids"].tolist() == [[3, 7, 4, 8, 9]]
+    r = O.cache_update(np.array([[1, 2]]), r["cache_ids"], r["stamps"])             # clock 4: oldest are 3 (1) and 7/4 (2): 3, then 7 (lower slot)
+    assert r["cache_ids"].tolist() == [[1, 2, 4, 8, 9]] and r["miss_slots"][0].tolist() == [0, 1]
+    r = O.cache_update(np.array([[4, 5]]), r["cache_ids"], r["stamps"])             # clock 5: 4 hits; 5 evicts the oldest other slot: 8 (stamp 3, slot 3)
+    assert r["cache_ids"].tolist() == [[1, 2, 4, 5, 9]] and r["sel_slots"].tolist() == [[2, 3]]
+    assert r["stamps"][0].tolist() == [4, 4, 5, 5, 3, 5]
+
+
+@pytest.mark.parametrize("seed,S", [(0, 16), (1, 24), (2, 40), (3, 64)])
+def test_lru_against_an_independent_simulation(seed, S):
+    rng = np.random.default_rng(seed)
+    k, n_chunks = 16, 60
+    cache = -np.ones((1, S), np.int32)
+    stamps = None
+    model = {}          # chunk -> [slot, last use]; written independently of the C code
+    free = list(range(S))
+    for step in range(1, 40):
+        pool = rng.choice(n_chunks, 24, replace=False) if step % 7 else np.arange(n_chunks)
+        sel = np.sort(rng.choice(pool, k, replace=False)).astype(np.int32)
+        r = O.cache_update(sel[None], cache, stamps)
+        hits = [c for c in sel if c in model]
+        for c in hits:
+            model[c][1] = step
+        new = [c for c in sel if c not in model]
+        occupied_not_hit = sorted((v[1], v[0], c) for c, v in model.items() if c not in hits)
+        victims = sorted(free)[:len(new)]
+        for _, slot, c in occupied_not_hit[:len(new) - len(victims)]:
+            victims.append(slot); del model[c]
+        free = [f for f in free if f not in victims]
+        for c, slot in zip(new, sorted(victims)):
+            model[int(c)] = [slot, step]
+        want = -np.ones(S, np.int32)
+        for c, (slot, _) in model.items():
+            want[slot] = c
+        assert r["cache_ids"][0].tolist() == want.tolist(), step
+        assert r["n_miss"][0] == len(new)
+        assert r["miss_slots"][0, :len(new)].tolist() == sorted(victims)
+        assert np.array_equal(r["cache_ids"][0][r["sel_slots"][0]], sel)          # every selected chunk is where it says
+        cache, stamps = r["cache_ids"], r["stamps"]
+        assert stamps[0, S] == step
+
+
+def test_a_cache_as_large_as_the_context_never_refetches():
+    rng = np.random.default_rng(5)
+    k, n_chunks = 8, 32
+    cache, stamps, seen = -np.ones((1, n_chunks), np.int32), None, set()
+    for _ in range(30):
+        sel = np.sort(rng.choice(n_chunks, k, replace=False)).astype(np.int32)
+        r = O.cache_update(sel[None], cache, stamps)
+        assert r["n_miss"][0] == len(set(sel.tolist()) - seen)
+        seen |= set(sel.tolist())
+        cache, stamps = r["cache_ids"], r["stamps"]
+
+
+def test_fewer_slots_than_selected_chunks_is_rejected():
+    with pytest.raises(ValueError):
+        O.cache_update(np.array([[1, 2, 3]]), -np.ones((1, 2), np.int32))

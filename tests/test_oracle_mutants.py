@@ -34,10 +34,13 @@ MUTANTS = [
 
 # planted mistakes in the chunk-cache model, run against its own pins
 CACHE_MUTANTS = [
-    ("cache-hit-moves", "if (hit[j]) continue;", "if (hit[j] && j != 0) continue;"),
-    ("cache-empty-slot-matches", "if (cache[slot] >= 0 && cache[slot] == sel[j] && !hit[j])", "if (cache[slot] == sel[j] - 1 && !hit[j])"),
-    ("cache-miss-count", "n_miss[u] = n;", "n_miss[u] = k - n;"),
-    ("cache-slot-order", "ms[n++] = slot++;", "ms[n++] = slot; slot += 1 + (n == 1 && !keep[slot + 1] && slot + 2 < k && !keep[slot + 2]);"),
+    ("cache-hit-moves", "if (hit[j]) continue;\n      while (!victim[slot]) ++slot;", "if (hit[j] && j != 0) continue;\n      while (!victim[slot]) ++slot;"),
+    ("cache-empty-slot-matches", "if (cache[slot] >= 0 && cache[slot] == sel[j] && !hit[j]) {", "if (cache[slot] == sel[j] - 1 && !hit[j]) {"),
+    ("cache-miss-count", "n_miss[u] = m;", "n_miss[u] = k - m;"),
+    ("cache-most-recently-used-evicted", "if (best < 0 || a < b) best = slot;", "if (best < 0 || a > b) best = slot;"),
+    ("cache-hit-not-stamped", "hit[j] = 1; keep[slot] = 1; ss[j] = slot; stamp[slot] = clock; --n; break;", "hit[j] = 1; keep[slot] = 1; ss[j] = slot; --n; break;"),
+    ("cache-empty-not-preferred", "const int32_t a = cache[slot] < 0 ? -1 : stamp[slot];", "const int32_t a = stamp[slot] + (cache[slot] < 0 ? 1000 : 0);"),
+    ("cache-wrong-slot-reported", "cache[slot] = sel[j]; stamp[slot] = clock; ss[j] = slot;", "cache[slot] = sel[j]; stamp[slot] = clock; ss[j] = m;"),
 ]
 
 
