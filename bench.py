@@ -52,6 +52,8 @@ def main() -> int:
     ap.add_argument("--chunk-cache", action="store_true",
                     help="run shadowkv_decode_step_cached over a ring of correlated queries (values fetched only for "
                          "chunks missing from last step's selection); meant for the host-store workloads")
+    ap.add_argument("--cache-slots", type=int, default=0,
+                    help="slots per (sequence, KV head) of the chunk cache (default: topk_chunks = last selection only)")
     ap.add_argument("--rho-q", type=float, default=0.93, help="step-to-step correlation of the queries with --chunk-cache")
     ap.add_argument("--append", type=int, default=0, metavar="N",
                     help="lay the context arrays out with room for N more chunks and time N shadowkv_append_chunk calls "
@@ -106,7 +108,7 @@ def main() -> int:
     cache = None
     if args.chunk_cache:
         pool = query_sequence(wl, 64, args.rho_q, device=dev)   # a ring: replaying it has no jump at the wrap
-        cache = S.ValueCache(p, device=dev)
+        cache = S.ValueCache(p, slots=args.cache_slots or None, device=dev)
 
     def step(i: int):
         if cache is not None:
@@ -241,6 +243,7 @@ def main() -> int:
         res["value_gather_pcie_gbps"] = ab["values"] / (prof["ms"]["gather_values"] * 1e-3) / 1e9
     if cache is not None:
         res["config"]["chunk_cache"] = True
+        res["config"]["cache_slots"] = cache.slots
         res["config"]["rho_q"] = args.rho_q
         res["cache_hit_rate"] = hit_rate
         if wl.value_location == "host":

@@ -150,21 +150,23 @@ int shadowkv_decode_step(const shadowkv_params *params, const shadowkv_bf16 *q,
  * "Theoretical Equivalent Bandwidth").  Meant for a store in pinned host memory; legal for HBM too.
  *
  * Arguments as shadowkv_decode_step, plus
- *   value_cache      dev in/out [b, h_kv, k*c, d] bf16  k slots of one chunk per (batch, KV head);
- *                                                       shadowkv_value_cache_bytes() bytes, 16-byte aligned
- *   cache_chunk_ids  dev in/out [b, h_kv, k] int32      true chunk id held by each slot, -1 = empty.  Must
- *                                                       be what the previous cached step (same params, same
- *                                                       store) left there, or freshly reset
+ *   cache_slots      S: slots of one chunk each per (batch, KV head); topk_chunks <= S <= 8192
+ *   value_cache      dev in/out [b, h_kv, S*c, d] bf16  shadowkv_value_cache_bytes() bytes, 16-byte aligned
+ *   cache_chunk_ids  dev in/out [b, h_kv, S] int32      true chunk id held by each slot, -1 = empty
+ *   cache_stamps     dev in/out [b, h_kv, S+1] int32    clock value of each slot's last use, then the
+ *                                                       unit's clock (one tick per step)
  *   out_miss_count   dev out    [b, h_kv] int32 or NULL number of chunks fetched for this step
+ * The three cache arrays must be what the previous cached step (same params, same store) left there,
+ * or freshly reset.
  *
- * Policy: after the step the slots hold exactly this step's selection.  A chunk selected again keeps
- * its slot; the new chunks, in ascending chunk id, take the slots whose chunk is no longer selected,
- * in ascending slot index.  Attention then runs over the slots in slot order (its result does not
- * depend on the order of the key/value set beyond rounding), so `out` equals the uncached step's
- * within rounding and out_chunk_ids is identical.  With SHADOWKV_FLAG_KEEP_REBUILT_KEYS the
- * diagnostic key rows are in slot order.  SHADOWKV_FLAG_STAGE_VALUES is ignored.  topk_chunks must
- * not exceed 8192.  Ownership: the caller owns both buffers and keeps them between steps; the library
- * keeps no pointer to them.
+ * Policy (the paper names "a cache policy" without fixing one): least recently used.  A selected
+ * chunk found in a slot stays there.  The selected chunks found nowhere take the slots that were not
+ * hit in this step and have the oldest stamps (empty slots first; equal stamps: lower slot first);
+ * among those slots, missing chunks in ascending chunk id go to slots in ascending index.  With
+ * S == topk_chunks the slots hold exactly the last step's selection.  Attention reads each selected
+ * chunk's values from its slot in the usual (ascending chunk id) order, so `out` and out_chunk_ids
+ * are bit-identical to shadowkv_decode_step with SHADOWKV_FLAG_STAGE_VALUES.  Ownership: the caller
+ * owns the buffers and keeps them between steps; the library keeps no pointer to them.
  */
 int shadowkv_decode_step_cached(const shadowkv_params *params, const shadowkv_bf16 *q,
                                 const shadowkv_bf16 *A, const shadowkv_bf16 *B,
@@ -172,7 +174,8 @@ int shadowkv_decode_step_cached(const shadowkv_params *params, const shadowkv_bf
                                 const shadowkv_bf16 *k_outlier, const shadowkv_bf16 *v_outlier,
                                 const shadowkv_bf16 *k_local, const shadowkv_bf16 *v_local,
                                 const shadowkv_bf16 *value_store, const int32_t *pos_offset,
-                                shadowkv_bf16 *value_cache, int32_t *cache_chunk_ids,
+                                int32_t cache_slots, shadowkv_bf16 *value_cache,
+                                int32_t *cache_chunk_ids, int32_t *cache_stamps,
                                 int32_t *out_miss_count, shadowkv_bf16 *out, int32_t *out_chunk_ids,
                                 void *workspace, size_t workspace_bytes, void *stream,
                                 void *side_stream);
@@ -201,11 +204,12 @@ int shadowkv_append_chunk(const shadowkv_params *params, const shadowkv_bf16 *k_
                           shadowkv_bf16 *A, shadowkv_bf16 *landmarks, int32_t *landmark_chunk_ids,
                           shadowkv_bf16 *value_store, void *stream);
 
-/* Bytes of `value_cache` for the given shape (0 if params are invalid). */
-size_t shadowkv_value_cache_bytes(const shadowkv_params *params);
+/* Bytes of `value_cache` for the given shape and slot count (0 if either is invalid). */
+size_t shadowkv_value_cache_bytes(const shadowkv_params *params, int32_t cache_slots);
 
-/* Marks every slot of `cache_chunk_ids` (dev, [b, h_kv, k] int32) empty; enqueued on `stream`. */
-int shadowkv_value_cache_reset(const shadowkv_params *params, int32_t *cache_chunk_ids, void *stream);
+/* Empties the cache: every slot of cache_chunk_ids -1, every stamp and the clocks 0; enqueued on `stream`. */
+int shadowkv_value_cache_reset(const shadowkv_params *params, int32_t cache_slots,
+                               int32_t *cache_chunk_ids, int32_t *cache_stamps, void *stream);
 
 /* Workspace sizes in bytes for the given shape (0 if params are invalid). */
 size_t shadowkv_build_workspace_bytes(const shadowkv_params *params);
@@ -221,7 +225,8 @@ int shadowkv_validate_params(const shadowkv_params *params, int for_decode);
  *        1 = staged values Gather(V_store, I), bf16 [b, h_kv, k*c, d] (NULL when the gather did not run);
  *        2 = selected true chunk ids, int32 [b, h_kv, k];
  *        3 = scaled landmark logits P / sqrt(d), fp64 [b, h_q, n_c];
- *        4 = slots filled by the last cached step, int32 [b, h_kv, k] (first out_miss_count entries per unit).
+ *        4 = slots filled by the last cached step, int32 [b, h_kv, k] (first out_miss_count entries per unit);
+ *        5 = slot of every selected chunk after the last cached step, int32 [b, h_kv, k].
  * Returns a pointer into `workspace`, or NULL.
  */
 void *shadowkv_decode_workspace_view(const shadowkv_params *params, void *workspace, int which);

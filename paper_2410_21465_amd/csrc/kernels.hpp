@@ -57,12 +57,14 @@ hipError_t launch_gather_values(const bf16_t* store, const int32_t* sel_ids, bf1
                                 int s, int s_cap, int c, int k, hipStream_t st);
 
 // ---- chunk cache of the offloaded values: index scan, fetch of the missing chunks ------
-constexpr int kMaxCachedTopK = 8192;  // slots per unit the index-scan kernel handles (LDS, 16-bit ranks)
-hipError_t launch_cache_update(const int32_t* sel_ids, int32_t* cache_ids, int32_t* miss_slots, int32_t* n_miss,
-                               int32_t* n_miss_copy, int units, int k, hipStream_t st);
+constexpr int kMaxCacheSlots = 8192;  // slots per unit the index-scan kernel handles (256 threads x 32, LDS)
+// cache_ids [units, S], stamps [units, S + 1] (entry S = the unit's clock), sel_slots / miss_slots [units, k]
+hipError_t launch_cache_update(const int32_t* sel_ids, int32_t* cache_ids, int32_t* stamps, int32_t* sel_slots,
+                               int32_t* miss_slots, int32_t* n_miss, int32_t* n_miss_copy, int units, int k, int S,
+                               hipStream_t st);
 hipError_t launch_gather_missing(const bf16_t* store, const int32_t* cache_ids, const int32_t* miss_slots,
                                  const int32_t* n_miss, bf16_t* v_cache, int units, int d, int s, int s_cap, int c,
-                                 int k, hipStream_t st);
+                                 int k, int S, hipStream_t st);
 hipError_t launch_fill_i32(int32_t* p, size_t n, int32_t value, hipStream_t st);
 
 // ---- attention over [outliers ; recent] and [selected chunks], keys rebuilt in-kernel ----
@@ -77,7 +79,9 @@ struct AttnArgs {
   const bf16_t* v_outlier;
   const bf16_t* k_local;    // [units, w, d]
   const bf16_t* v_local;
-  const bf16_t* v_sparse;   // staged [units, k*c, d], or NULL: read v_store through sel_ids
+  const bf16_t* v_sparse;   // staged [units, v_unit_rows, d], or NULL: read v_store through sel_ids
+  const int32_t* v_slots;   // optional [units, k]: chunk slot of selected chunk i inside v_sparse (NULL: slot i)
+  int v_unit_rows;          // rows per unit of v_sparse (k*c, or slots*c of a value cache)
   const bf16_t* v_store;    // [units, s_cap, d] (HBM, or device-readable pinned host memory)
   const int32_t* sel_ids;   // [units, k] true chunk ids
   const int32_t* pos_offset;  // [b] or NULL

@@ -134,12 +134,27 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
 
   // ---- first token of every selected chunk this split touches, into LDS.  Ids are clamped: a bad id
   //      can never address outside A or V.
+  //      Next to it the first row of the chunk's values inside the buffer they are read from: the store
+  //      itself, the staged copy (chunk i at slot i), or a value cache (chunk i at slot v_slots[i]).
   int* tokb = reinterpret_cast<int*>(Bt + (size_t)D * rp);
+  int* vrowb = tokb + (a.sparse_split_len / a.c + 2);
+  const bf16_t* vbase = a.v_sparse ? a.v_sparse + (size_t)unit * a.v_unit_rows * D
+                                   : a.v_store + (size_t)unit * a.s_cap * D;
   if (s_begin < s_end) {
     const int last_chunk = a.s / a.c - 1;
     const int32_t* ids = a.sel_ids + (size_t)unit * a.k;
     const int n_ch = chunk_of(s_end - 1) - ch_begin + 1;
-    for (int idx = threadIdx.x; idx < n_ch; idx += 256) tokb[idx] = min(max(ids[ch_begin + idx], 0), last_chunk) * a.c;
+    const int last_slot = a.v_unit_rows / a.c - 1;
+    for (int idx = threadIdx.x; idx < n_ch; idx += 256) {
+      const int tb = min(max(ids[ch_begin + idx], 0), last_chunk) * a.c;
+      tokb[idx] = tb;
+      int vb = tb;
+      if (a.v_sparse) {
+        const int slot = a.v_slots ? a.v_slots[(size_t)unit * a.k + ch_begin + idx] : ch_begin + idx;
+        vb = min(max(slot, 0), last_slot) * a.c;
+      }
+      vrowb[idx] = vb;
+    }
   }
   __syncthreads();
 
@@ -169,8 +184,7 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
       const int ch = chunk_of(ic);
       const int n0 = tokb[ch - ch_begin] + (ic - ch * a.c);
       tok[0] = n0;
-      const bf16_t* vp = (a.v_sparse ? a.v_sparse + ((size_t)unit * kc + ic) * D
-                                     : a.v_store + ((size_t)unit * a.s_cap + n0) * D) + sub * EPL;
+      const bf16_t* vp = vbase + (size_t)(vrowb[ch - ch_begin] + (ic - ch * a.c)) * D + sub * EPL;
 #pragma unroll
       for (int j = 0; j < 4; ++j) load_raw<EPL>(vp + (size_t)j * D, vraw[j]);
     } else {
@@ -182,8 +196,7 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
         const int ch = chunk_of(ic);
         const int n = tokb[ch - ch_begin] + (ic - ch * a.c);
         tok[j] = n;
-        const bf16_t* vp = a.v_sparse ? a.v_sparse + ((size_t)unit * kc + ic) * D
-                                      : a.v_store + ((size_t)unit * a.s_cap + n) * D;
+        const bf16_t* vp = vbase + (size_t)(vrowb[ch - ch_begin] + (ic - ch * a.c)) * D;
         load_raw<EPL>(vp + sub * EPL, vraw[j]);
       }
     }
@@ -496,8 +509,8 @@ template <int D>
 static hipError_t launch_attention_d(const AttnArgs& a, hipStream_t st) {
   const int G = a.hq / a.hkv;
   const int gh = attention_heads_per_group(G);
-  // B^T, then the first token of each chunk a split touches
-  const size_t lds = (size_t)D * a.rp * sizeof(bf16_t) + ((size_t)a.sparse_split_len / a.c + 2) * sizeof(int);
+  // B^T, then the first token and the first value row of each chunk a split touches
+  const size_t lds = (size_t)D * a.rp * sizeof(bf16_t) + 2 * ((size_t)a.sparse_split_len / a.c + 2) * sizeof(int);
   dim3 grid(a.n_splits, a.batch * a.hkv, G / gh);
   hipError_t e;
   switch (gh) {

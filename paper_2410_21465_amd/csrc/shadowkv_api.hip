@@ -119,7 +119,7 @@ AttnPlan plan_attention(const Shape& sh) {
 }
 
 struct DecodeLayout {
-  size_t logits, partials, cand_key, cand_idx, sel_ids, miss_slots, n_miss, k_sparse, v_sparse, part_acc, part_ml, total;
+  size_t logits, partials, cand_key, cand_idx, sel_ids, miss_slots, sel_slots, n_miss, k_sparse, v_sparse, part_acc, part_ml, total;
   SelectPlan sel;
   AttnPlan attn;
   int n_tiles;
@@ -137,6 +137,7 @@ DecodeLayout decode_layout(const Shape& sh) {
   L.cand_idx = off; off += up((size_t)sh.units * L.sel.cand_stride * sizeof(int32_t));
   L.sel_ids = off; off += up((size_t)sh.units * sh.k * sizeof(int32_t));
   L.miss_slots = off; off += up((size_t)sh.units * sh.k * sizeof(int32_t));  // chunk cache: slots to fill
+  L.sel_slots = off; off += up((size_t)sh.units * sh.k * sizeof(int32_t));   // chunk cache: slot of each selected chunk
   L.n_miss = off; off += up((size_t)sh.units * sizeof(int32_t));
   L.k_sparse = off; off += sh.keep_keys ? up(rows * sh.d * sizeof(float)) : 0;
   L.v_sparse = off; off += sh.stage ? up(rows * sh.d * sizeof(bf16_t)) : 0;
@@ -303,6 +304,7 @@ void* shadowkv_decode_workspace_view(const shadowkv_params* params, void* worksp
     case 2: return ws + L.sel_ids;
     case 3: return ws + L.logits;
     case 4: return ws + L.miss_slots;
+    case 5: return ws + L.sel_slots;
     default: return nullptr;
   }
 }
@@ -353,8 +355,10 @@ int shadowkv_build_landmarks(const shadowkv_params* params, const shadowkv_bf16*
 
 // Value cache handed to a cached step (all device pointers).
 struct CacheIO {
-  bf16_t* values;        // [units, k*c, d]
-  int32_t* chunk_ids;    // [units, k], -1 = empty
+  int slots;             // S >= k slots per unit
+  bf16_t* values;        // [units, S*c, d]
+  int32_t* chunk_ids;    // [units, S], -1 = empty
+  int32_t* stamps;       // [units, S + 1]: last use of each slot, then the unit's clock
   int32_t* miss_count;   // optional [units]
 };
 
@@ -376,9 +380,11 @@ static int decode_impl(const shadowkv_params* params, const shadowkv_bf16* q, co
       !aligned16(v_outlier) || !aligned16(k_local) || !aligned16(v_local) || !aligned16(value_store) || !aligned16(out))
     return fail_inval("tensor pointers must be 16-byte aligned");
   if (cache) {
-    if (!cache->values || !cache->chunk_ids) return fail_inval("value_cache and cache_chunk_ids must not be NULL");
+    if (!cache->values || !cache->chunk_ids || !cache->stamps)
+      return fail_inval("value_cache, cache_chunk_ids and cache_stamps must not be NULL");
     if (!aligned16(cache->values)) return fail_inval("value_cache must be 16-byte aligned");
-    if (sh.k > kMaxCachedTopK) return fail_inval("topk_chunks %d exceeds the chunk cache's limit of %d", sh.k, kMaxCachedTopK);
+    if (cache->slots < sh.k || cache->slots > kMaxCacheSlots)
+      return fail_inval("cache_slots %d must be in [topk_chunks = %d, %d]", cache->slots, sh.k, kMaxCacheSlots);
   }
   const DecodeLayout L = decode_layout(sh);
   rc = check_workspace(workspace, workspace_bytes, L.total);
@@ -425,12 +431,15 @@ static int decode_impl(const shadowkv_params* params, const shadowkv_bf16* q, co
   if (e != hipSuccess) return fail_hip("select chunks", e);
   prof_mark(st, pstep, 2);
   // 3. values of the selected chunks: staged by the gather kernel (side stream when given) ...
-  const int32_t* attn_ids = sel_ids;
+  const int32_t* v_slots = nullptr;
+  int v_unit_rows = sh.k * sh.c;
   if (cache) {
     // index scan against last step's chunks, then only the missing chunks cross the link
     int32_t* miss_slots = reinterpret_cast<int32_t*>(ws + L.miss_slots);
     int32_t* n_miss = reinterpret_cast<int32_t*>(ws + L.n_miss);
-    e = launch_cache_update(sel_ids, cache->chunk_ids, miss_slots, n_miss, cache->miss_count, sh.units, sh.k, st);
+    int32_t* sel_slots = reinterpret_cast<int32_t*>(ws + L.sel_slots);
+    e = launch_cache_update(sel_ids, cache->chunk_ids, cache->stamps, sel_slots, miss_slots, n_miss, cache->miss_count,
+                            sh.units, sh.k, cache->slots, st);
     if (e != hipSuccess) return fail_hip("cache update", e);
     hipStream_t gs = st;
     if (fork) {
@@ -439,15 +448,16 @@ static int decode_impl(const shadowkv_params* params, const shadowkv_bf16* q, co
       gs = side;
     }
     e = launch_gather_missing(value_store, cache->chunk_ids, miss_slots, n_miss, cache->values, sh.units, sh.d, sh.s,
-                              sh.cap, sh.c, sh.k, gs);
+                              sh.cap, sh.c, sh.k, cache->slots, gs);
     if (e != hipSuccess) return fail_hip("gather missing values", e);
     if (fork) {
       if ((e = hipEventRecord(ev_join, side)) != hipSuccess) return fail_hip("hipEventRecord", e);
       if ((e = hipStreamWaitEvent(st, ev_join, 0)) != hipSuccess) return fail_hip("hipStreamWaitEvent", e);
     }
-    // attention is invariant to the order of its key/value set: run it over the slots
-    attn_ids = cache->chunk_ids;
+    // attention reads every selected chunk's values from its slot
     v_sparse = cache->values;
+    v_slots = sel_slots;
+    v_unit_rows = cache->slots * sh.c;
   } else if (sh.stage) {
     hipStream_t gs = st;
     if (fork) {
@@ -467,7 +477,7 @@ static int decode_impl(const shadowkv_params* params, const shadowkv_bf16* q, co
   AttnArgs t{};
   t.q = q; t.A = A; t.B = B; t.k_outlier = k_outlier; t.v_outlier = v_outlier;
   t.k_local = k_local; t.v_local = v_local; t.v_sparse = v_sparse; t.v_store = value_store;
-  t.sel_ids = attn_ids; t.pos_offset = pos_offset; t.inv_freq_dev = params->inv_freq;
+  t.sel_ids = sel_ids; t.v_slots = v_slots; t.v_unit_rows = v_unit_rows; t.pos_offset = pos_offset; t.inv_freq_dev = params->inv_freq;
   t.k_sparse_out = sh.keep_keys ? reinterpret_cast<float*>(ws + L.k_sparse) : nullptr;
   t.part_acc = reinterpret_cast<float*>(ws + L.part_acc);
   t.part_ml = reinterpret_cast<float2*>(ws + L.part_ml);
@@ -503,10 +513,11 @@ int shadowkv_decode_step_cached(const shadowkv_params* params, const shadowkv_bf
                                 const int32_t* landmark_chunk_ids, const shadowkv_bf16* k_outlier,
                                 const shadowkv_bf16* v_outlier, const shadowkv_bf16* k_local,
                                 const shadowkv_bf16* v_local, const shadowkv_bf16* value_store,
-                                const int32_t* pos_offset, shadowkv_bf16* value_cache, int32_t* cache_chunk_ids,
-                                int32_t* out_miss_count, shadowkv_bf16* out, int32_t* out_chunk_ids, void* workspace,
-                                size_t workspace_bytes, void* stream, void* side_stream) {
-  CacheIO c{value_cache, cache_chunk_ids, out_miss_count};
+                                const int32_t* pos_offset, int32_t cache_slots, shadowkv_bf16* value_cache,
+                                int32_t* cache_chunk_ids, int32_t* cache_stamps, int32_t* out_miss_count,
+                                shadowkv_bf16* out, int32_t* out_chunk_ids, void* workspace, size_t workspace_bytes,
+                                void* stream, void* side_stream) {
+  CacheIO c{cache_slots, value_cache, cache_chunk_ids, cache_stamps, out_miss_count};
   return decode_impl(params, q, A, B, landmarks, landmark_chunk_ids, k_outlier, v_outlier, k_local, v_local,
                      value_store, pos_offset, &c, out, out_chunk_ids, workspace, workspace_bytes, stream, side_stream);
 }
@@ -532,18 +543,24 @@ int shadowkv_append_chunk(const shadowkv_params* params, const shadowkv_bf16* k_
   return SHADOWKV_OK;
 }
 
-size_t shadowkv_value_cache_bytes(const shadowkv_params* params) {
+size_t shadowkv_value_cache_bytes(const shadowkv_params* params, int32_t cache_slots) {
   Shape sh;
   if (check_params(params, true, &sh) != SHADOWKV_OK) return 0;
-  return (size_t)sh.units * sh.k * sh.c * sh.d * sizeof(bf16_t);
+  if (cache_slots < sh.k || cache_slots > kMaxCacheSlots) return 0;
+  return (size_t)sh.units * cache_slots * sh.c * sh.d * sizeof(bf16_t);
 }
 
-int shadowkv_value_cache_reset(const shadowkv_params* params, int32_t* cache_chunk_ids, void* stream) {
+int shadowkv_value_cache_reset(const shadowkv_params* params, int32_t cache_slots, int32_t* cache_chunk_ids,
+                               int32_t* cache_stamps, void* stream) {
   Shape sh;
   int rc = check_params(params, true, &sh);
   if (rc != SHADOWKV_OK) return rc;
-  if (!cache_chunk_ids) return fail_inval("cache_chunk_ids is NULL");
-  hipError_t e = launch_fill_i32(cache_chunk_ids, (size_t)sh.units * sh.k, -1, static_cast<hipStream_t>(stream));
+  if (cache_slots < sh.k || cache_slots > kMaxCacheSlots)
+    return fail_inval("cache_slots %d must be in [topk_chunks = %d, %d]", cache_slots, sh.k, kMaxCacheSlots);
+  if (!cache_chunk_ids || !cache_stamps) return fail_inval("cache_chunk_ids / cache_stamps is NULL");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  hipError_t e = launch_fill_i32(cache_chunk_ids, (size_t)sh.units * cache_slots, -1, st);
+  if (e == hipSuccess) e = launch_fill_i32(cache_stamps, (size_t)sh.units * (cache_slots + 1), 0, st);
   if (e != hipSuccess) return fail_hip("cache reset", e);
   return SHADOWKV_OK;
 }

@@ -67,11 +67,11 @@ def lib() -> C.CDLL:
         L.shadowkv_decode_step.restype = i32
         L.shadowkv_decode_step.argtypes = [vp] * 15 + [sz, vp, vp]
         L.shadowkv_decode_step_cached.restype = i32
-        L.shadowkv_decode_step_cached.argtypes = [vp] * 18 + [sz, vp, vp]
+        L.shadowkv_decode_step_cached.argtypes = [vp] * 12 + [i32] + [vp] * 7 + [sz, vp, vp]
         L.shadowkv_value_cache_bytes.restype = sz
-        L.shadowkv_value_cache_bytes.argtypes = [vp]
+        L.shadowkv_value_cache_bytes.argtypes = [vp, i32]
         L.shadowkv_value_cache_reset.restype = i32
-        L.shadowkv_value_cache_reset.argtypes = [vp, vp, vp]
+        L.shadowkv_value_cache_reset.argtypes = [vp, i32, vp, vp, vp]
         L.shadowkv_append_chunk.restype = i32
         L.shadowkv_append_chunk.argtypes = [vp] * 10
         L.shadowkv_build_workspace_bytes.restype = sz
@@ -273,24 +273,29 @@ def append_chunk(p: Params, k_pre, k_rope, v, B, A, landmarks, landmark_chunk_id
 
 
 class ValueCache:
-    """Device buffers of the chunk cache of the value store: ``values [b,h_kv,k*c,d]`` bf16 and the chunk id
-    per slot ``chunk_ids [b,h_kv,k]`` int32 (-1 = empty), plus ``miss_count [b,h_kv]`` of the last step."""
+    """Device buffers of the chunk cache of the value store with ``slots`` >= k slots per (batch, KV head):
+    ``values [b,h_kv,slots*c,d]`` bf16, ``chunk_ids [b,h_kv,slots]`` int32 (-1 = empty), ``stamps
+    [b,h_kv,slots+1]`` int32 (last use per slot, then the unit's clock), ``miss_count [b,h_kv]`` of the last step."""
 
-    def __init__(self, p: Params, device="cuda", stream=None):
+    def __init__(self, p: Params, slots: Optional[int] = None, device="cuda", stream=None):
+        self.slots = int(slots) if slots is not None else p.topk_chunks
         st = p.c_struct()
-        n = int(lib().shadowkv_value_cache_bytes(C.addressof(st)))
+        n = int(lib().shadowkv_value_cache_bytes(C.addressof(st), self.slots))
         if n == 0:
             _check(lib().shadowkv_validate_params(C.addressof(st), 1))
-        self.values = torch.empty(p.batch, p.n_kv_heads, p.topk_chunks * p.chunk_size, p.head_dim,
+            raise ValueError(f"cache slots {self.slots} outside [topk_chunks, 8192]")
+        self.values = torch.empty(p.batch, p.n_kv_heads, self.slots * p.chunk_size, p.head_dim,
                                   dtype=torch.bfloat16, device=device)
         assert self.values.numel() * 2 == n
-        self.chunk_ids = torch.empty(p.batch, p.n_kv_heads, p.topk_chunks, dtype=torch.int32, device=device)
+        self.chunk_ids = torch.empty(p.batch, p.n_kv_heads, self.slots, dtype=torch.int32, device=device)
+        self.stamps = torch.empty(p.batch, p.n_kv_heads, self.slots + 1, dtype=torch.int32, device=device)
         self.miss_count = torch.zeros(p.batch, p.n_kv_heads, dtype=torch.int32, device=device)
         self.reset(p, stream)
 
     def reset(self, p: Params, stream=None):
         st = p.c_struct()
-        _check(lib().shadowkv_value_cache_reset(C.addressof(st), _ptr(self.chunk_ids), _stream_ptr(stream)))
+        _check(lib().shadowkv_value_cache_reset(C.addressof(st), self.slots, _ptr(self.chunk_ids), _ptr(self.stamps),
+                                                _stream_ptr(stream)))
 
 
 def decode_step_cached(p: Params, q, A, B, landmarks, landmark_chunk_ids, k_outlier, v_outlier, k_local, v_local,
@@ -307,8 +312,9 @@ def decode_step_cached(p: Params, q, A, B, landmarks, landmark_chunk_ids, k_outl
         workspace = alloc_workspace(int(lib().shadowkv_decode_workspace_bytes(C.addressof(st))), dev)
     rc = lib().shadowkv_decode_step_cached(C.addressof(st), _ptr(q), _ptr(A), _ptr(B), _ptr(landmarks),
                                            _ptr(landmark_chunk_ids), _ptr(k_outlier), _ptr(v_outlier), _ptr(k_local),
-                                           _ptr(v_local), _ptr(value_store), _ptr(pos_offset), _ptr(cache.values),
-                                           _ptr(cache.chunk_ids), _ptr(cache.miss_count), _ptr(out),
+                                           _ptr(v_local), _ptr(value_store), _ptr(pos_offset), cache.slots,
+                                           _ptr(cache.values), _ptr(cache.chunk_ids), _ptr(cache.stamps),
+                                           _ptr(cache.miss_count), _ptr(out),
                                            _ptr(out_chunk_ids), _ptr(workspace), workspace.numel(),
                                            _stream_ptr(stream),
                                            None if side_stream is None else _stream_ptr(side_stream))
@@ -321,7 +327,7 @@ def workspace_view(p: Params, workspace: torch.Tensor, which: str) -> Optional[t
 
     ``"k_sparse"`` fp32 [b,h_kv,k*c,d]; ``"v_sparse"`` bf16 (staged runs only); ``"logits"`` fp64 [b,h_q,n_c].
     """
-    code = {"k_sparse": 0, "v_sparse": 1, "sel_ids": 2, "logits": 3, "miss_slots": 4}[which]
+    code = {"k_sparse": 0, "v_sparse": 1, "sel_ids": 2, "logits": 3, "miss_slots": 4, "sel_slots": 5}[which]
     st = p.c_struct()
     ptr = lib().shadowkv_decode_workspace_view(C.addressof(st), workspace.data_ptr(), code)
     if not ptr:
@@ -334,7 +340,7 @@ def workspace_view(p: Params, workspace: torch.Tensor, which: str) -> Optional[t
     if which == "v_sparse":
         n = rows[0] * rows[1] * rows[2] * rows[3]
         return workspace[off:off + 2 * n].view(torch.bfloat16).view(rows)
-    if which in ("sel_ids", "miss_slots"):
+    if which in ("sel_ids", "miss_slots", "sel_slots"):
         n = p.batch * p.n_kv_heads * p.topk_chunks
         return workspace[off:off + 4 * n].view(torch.int32).view(p.batch, p.n_kv_heads, p.topk_chunks)
     n = p.batch * p.n_q_heads * p.n_landmarks

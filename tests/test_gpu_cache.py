@@ -17,7 +17,7 @@ def _dev_bf16(bits):
     return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).cuda()
 
 
-def _run_sequence(wl: Workload, n_steps: int, rho_q: float, side_stream: bool, random_jump_at=None):
+def _run_sequence(wl: Workload, n_steps: int, rho_q: float, side_stream: bool, random_jump_at=None, slots=None):
     t = generate(wl, device="cuda")
     op = oracle_params(wl)
     ref_build = O.build_landmarks(op, to_bits(t["k_rope"]), to_bits(t["v"]))
@@ -27,12 +27,14 @@ def _run_sequence(wl: Workload, n_steps: int, rho_q: float, side_stream: bool, r
     p = S.Params.from_workload(wl)
     lm, lm_ids = _dev_bf16(ref_build["landmarks"]), torch.from_numpy(ref_build["landmark_chunk_ids"]).cuda()
     ko, vo = _dev_bf16(ref_build["k_outlier"]), _dev_bf16(ref_build["v_outlier"])
-    cache = S.ValueCache(p)
+    cache = S.ValueCache(p, slots=slots)
+    n_slots = cache.slots
     side = torch.cuda.Stream() if side_stream else None
     ws = None
+    p_staged = S.Params.from_workload(wl, flags=S.FLAG_STAGE_VALUES)
     b, h, k, c, d = wl.batch, wl.n_kv_heads, wl.topk_chunks, wl.chunk_size, wl.head_dim
     units = b * h
-    ocache = -np.ones((units, k), np.int32)
+    ocache, ostamps = -np.ones((units, n_slots), np.int32), None
     vbits = to_bits(t["v"]).reshape(units, -1, c, d)
     fixed = (to_bits(t["A"]), to_bits(t["B"]), ref_build["landmarks"], ref_build["landmark_chunk_ids"],
              ref_build["k_outlier"], ref_build["v_outlier"], to_bits(t["k_local"]), to_bits(t["v_local"]),
@@ -47,9 +49,13 @@ def _run_sequence(wl: Workload, n_steps: int, rho_q: float, side_stream: bool, r
         g_ids = ids.cpu().numpy().reshape(units, k)
         w_sorted = np.sort(ref["chunk_ids"].reshape(units, k), axis=1)
         np.testing.assert_array_equal(g_ids, w_sorted, err_msg=f"step {step}: selected ids")
-        model = O.cache_update(w_sorted, ocache)
-        np.testing.assert_array_equal(cache.chunk_ids.cpu().numpy().reshape(units, k), model["cache_ids"],
+        model = O.cache_update(w_sorted, ocache, ostamps)
+        np.testing.assert_array_equal(cache.chunk_ids.cpu().numpy().reshape(units, n_slots), model["cache_ids"],
                                       err_msg=f"step {step}: slot contents")
+        np.testing.assert_array_equal(cache.stamps.cpu().numpy().reshape(units, n_slots + 1), model["stamps"],
+                                      err_msg=f"step {step}: stamps")
+        np.testing.assert_array_equal(S.workspace_view(p, ws, "sel_slots").cpu().numpy().reshape(units, k),
+                                      model["sel_slots"], err_msg=f"step {step}: slot of each selected chunk")
         np.testing.assert_array_equal(cache.miss_count.cpu().numpy().reshape(units), model["n_miss"],
                                       err_msg=f"step {step}: miss count")
         ms = S.workspace_view(p, ws, "miss_slots").cpu().numpy().reshape(units, k)
@@ -57,12 +63,18 @@ def _run_sequence(wl: Workload, n_steps: int, rho_q: float, side_stream: bool, r
             n = model["n_miss"][u]
             np.testing.assert_array_equal(ms[u, :n], model["miss_slots"][u, :n])
         # every slot holds a bit-exact copy of its chunk of the store
-        cv = to_bits(cache.values).reshape(units, k, c, d)
+        cv = to_bits(cache.values).reshape(units, n_slots, c, d)
         for u in range(units):
-            np.testing.assert_array_equal(cv[u], vbits[u, model["cache_ids"][u]])
+            full = model["cache_ids"][u] >= 0
+            np.testing.assert_array_equal(cv[u][full], vbits[u, model["cache_ids"][u][full]])
+        # same bits as the uncached step that stages all selected values
+        out2, ids2, _ = S.decode_step(p_staged, q, t["A"], t["B"], lm, lm_ids, ko, vo, t["k_local"], t["v_local"], t["v"],
+                                      t["pos_offset"], side_stream=side)
+        torch.cuda.synchronize()
+        assert torch.equal(out, out2) and torch.equal(ids, ids2), f"step {step}: cached and staged steps differ"
         err = np.abs(out.float().cpu().numpy().astype(np.float64) - O.bits_to_f64(ref["out"]))
         assert err.max() <= OUT_MAX_ABS and err.mean() <= OUT_MEAN_ABS, (step, err.max(), err.mean())
-        ocache = model["cache_ids"]
+        ocache, ostamps = model["cache_ids"], model["stamps"]
         misses.append(model["n_miss"].astype(np.float64).mean() / k)
     return misses
 
@@ -78,6 +90,18 @@ def test_cached_steps_match_oracle(loc, side):
     assert misses[0] == 1.0                      # empty cache: everything is fetched
     assert max(misses[1:]) < 1.0                 # correlated queries: some chunks are already there
     print("miss fraction per step:", [round(m, 3) for m in misses])
+
+
+@pytest.mark.parametrize("slots", [128, 197, 512])
+def test_more_slots_than_selected_chunks_lru(slots):
+    """S > k: least-recently-used replacement; more slots can only lower the miss count."""
+    wl = Workload(name="cache-lru", batch=2, ctx_len=8192, n_outlier_chunks=8, topk_chunks=64, seed=17,
+                  value_location="host", **SMALL)
+    base = _run_sequence(wl, n_steps=8, rho_q=0.9, side_stream=True)
+    more = _run_sequence(wl, n_steps=8, rho_q=0.9, side_stream=True, slots=slots)
+    assert base[0] == more[0] == 1.0
+    assert all(m <= b + 1e-12 for m, b in zip(more, base)) and sum(more) < sum(base)
+    print("miss fraction, k slots:", [round(m, 3) for m in base], f"{slots} slots:", [round(m, 3) for m in more])
 
 
 def test_unrelated_query_refills_and_recovers():
@@ -108,9 +132,10 @@ def test_reset_empties_the_cache():
     p = S.Params.from_workload(wl)
     cache = S.ValueCache(p)
     cache.chunk_ids.fill_(7)
+    cache.stamps.fill_(9)
     cache.reset(p)
     torch.cuda.synchronize()
-    assert bool((cache.chunk_ids == -1).all())
+    assert bool((cache.chunk_ids == -1).all()) and bool((cache.stamps == 0).all())
 
 
 def test_cached_step_in_a_hip_graph_replays_to_the_eager_sequence():
@@ -128,7 +153,7 @@ def test_cached_step_in_a_hip_graph_replays_to_the_eager_sequence():
     ids = torch.empty(wl.batch, wl.n_kv_heads, wl.topk_chunks, dtype=torch.int32, device="cuda")
     ws = S.alloc_workspace(S.decode_workspace_bytes(p))
     ws2 = S.alloc_workspace(S.decode_workspace_bytes(p))
-    cache = S.ValueCache(p)
+    cache = S.ValueCache(p, slots=100)
     side = torch.cuda.Stream()
 
     def step():
@@ -141,7 +166,7 @@ def test_cached_step_in_a_hip_graph_replays_to_the_eager_sequence():
         q.copy_(qs[i])
         step()
         torch.cuda.synchronize()
-        eager.append((out.clone(), ids.clone(), cache.chunk_ids.clone(), cache.miss_count.clone()))
+        eager.append((out.clone(), ids.clone(), cache.chunk_ids.clone(), cache.miss_count.clone(), cache.stamps.clone()))
     assert int(eager[1][3].sum()) < int(eager[0][3].sum())
     cache.reset(p)
     torch.cuda.synchronize()
@@ -159,6 +184,7 @@ def test_cached_step_in_a_hip_graph_replays_to_the_eager_sequence():
         torch.cuda.synchronize()
         assert torch.equal(out, eager[i][0]) and torch.equal(ids, eager[i][1]), f"replay {i}"
         assert torch.equal(cache.chunk_ids, eager[i][2]) and torch.equal(cache.miss_count, eager[i][3]), f"replay {i}"
+        assert torch.equal(cache.stamps, eager[i][4]), f"replay {i}"
         # eager, uncached work between the replays (own workspace and outputs)
         S.decode_step(p, qs[(i + 3) % 6], t["A"], t["B"], bl["landmarks"], bl["landmark_chunk_ids"], bl["k_outlier"],
                       bl["v_outlier"], t["k_local"], t["v_local"], t["v"], t["pos_offset"], workspace=ws2,
