@@ -49,6 +49,8 @@ def main() -> int:
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU time budget of the oracle leg")
     ap.add_argument("--no-side-stream", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="enqueue the timed steps eagerly instead of replaying a HIP graph")
+    ap.add_argument("--force-graph", action="store_true",
+                    help="replay a HIP graph also where the default is eager (steps with a value gather on the side stream)")
     ap.add_argument("--chunk-cache", action="store_true",
                     help="run shadowkv_decode_step_cached over a ring of correlated queries (values fetched only for "
                          "chunks missing from last step's selection); meant for the host-store workloads")
@@ -129,7 +131,12 @@ def main() -> int:
     # host launch gaps between the five kernels of a step; --no-graph enqueues every step eagerly instead.
     n_pool = pool.shape[0]
     graph = None
-    if not args.no_graph and args.steps >= n_pool:
+    # Steps whose values come through a gather run it on the side stream next to the key phase of the attention;
+    # a replayed HIP graph does not overlap the two branches on this runtime (measured: replay = serial time), so
+    # those workloads are timed with eager enqueues unless --force-graph is given.
+    two_phase = wl.value_location == "host" or args.chunk_cache or args.stage_values
+    use_graph = not args.no_graph and (args.force_graph or not two_phase)
+    if use_graph and args.steps >= n_pool:
         cap = torch.cuda.Stream()
         cap.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(cap):

@@ -93,12 +93,17 @@ struct AttnArgs {
   int batch, hq, hkv, d, s, c, o, k, w, r, r32, rp;
   int s_cap;                // tokens A and v_store are laid out for (>= s)
   int res_split_len, sparse_split_len, n_splits;
+  float* logit_buf;         // two-phase path: [b*h_q, k*c] logits of the selected rows (log2 units)
+  int pv_split_len, n_pv_splits;  // two-phase path: selected rows per workgroup of the second phase
+  int n_part;               // partial states per head: n_splits (+ n_pv_splits on the two-phase path)
   int c_shift;              // log2(c) when c is a power of two, else -1
   float scale_log2;         // softmax scale * log2(e)
   RopeFreqs freqs;
 };
 inline int attention_heads_per_group(int G) { return (G % 8 == 0) ? 8 : (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1; }
-hipError_t launch_attention(const AttnArgs& a, hipStream_t st);
+hipError_t launch_attention(const AttnArgs& a, hipStream_t st);         // values readable now: one fused kernel
+hipError_t launch_attention_keys(const AttnArgs& a, hipStream_t st);    // two-phase path, before the values arrive
+hipError_t launch_attention_values(const AttnArgs& a, hipStream_t st);  // two-phase path, after
 
 // ---- pre-filling algorithm: chunk means, min cosine, compaction, outlier gather -------
 hipError_t launch_chunk_stats(const bf16_t* k_rope, bf16_t* chunk_mean, double* chunk_min_cos, int units, int d,

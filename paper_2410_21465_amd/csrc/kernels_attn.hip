@@ -110,8 +110,12 @@ struct OnlineSoftmax {
   }
 };
 
-// KSMAX = number of 32-wide rank steps the A prefetch buffer is sized for (5: r <= 160, 8: r <= 256)
-template <int D, int GH, int KSMAX, bool FAST4>
+// KSMAX = number of 32-wide rank steps the A prefetch buffer is sized for (5: r <= 160, 8: r <= 256).
+// KEYS_ONLY: the selected values are still on their way (a gather on another stream).  The kernel
+// then does everything that needs no selected value -- the resident rows in full, and for the
+// selected rows the key rebuild, RoPE and q.K -- and leaves the logits of the selected rows in
+// `logit_buf` for sparse_values_kernel, which runs once the values have arrived.
+template <int D, int GH, int KSMAX, bool FAST4, bool KEYS_ONLY>
 __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
   constexpr int EPL = D / 16, NB = D / 16, HB = NB / 2;
   constexpr int NT = FAST4 ? 1 : 4;  // token positions a lane keeps per block (FAST4: the first of 4 consecutive)
@@ -184,9 +188,11 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
       const int ch = chunk_of(ic);
       const int n0 = tokb[ch - ch_begin] + (ic - ch * a.c);
       tok[0] = n0;
-      const bf16_t* vp = vbase + (size_t)(vrowb[ch - ch_begin] + (ic - ch * a.c)) * D + sub * EPL;
+      if constexpr (!KEYS_ONLY) {
+        const bf16_t* vp = vbase + (size_t)(vrowb[ch - ch_begin] + (ic - ch * a.c)) * D + sub * EPL;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) load_raw<EPL>(vp + (size_t)j * D, vraw[j]);
+        for (int j = 0; j < 4; ++j) load_raw<EPL>(vp + (size_t)j * D, vraw[j]);
+      }
     } else {
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
@@ -196,8 +202,10 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
         const int ch = chunk_of(ic);
         const int n = tokb[ch - ch_begin] + (ic - ch * a.c);
         tok[j] = n;
-        const bf16_t* vp = vbase + (size_t)(vrowb[ch - ch_begin] + (ic - ch * a.c)) * D;
-        load_raw<EPL>(vp + sub * EPL, vraw[j]);
+        if constexpr (!KEYS_ONLY) {
+          const bf16_t* vp = vbase + (size_t)(vrowb[ch - ch_begin] + (ic - ch * a.c)) * D;
+          load_raw<EPL>(vp + sub * EPL, vraw[j]);
+        }
       }
     }
   };
@@ -401,7 +409,23 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
 #pragma unroll
         for (int g = 0; g < GH; ++g) lg[j][g] = ok ? dot[g] : -INFINITY;
       }
-      st.template fold<4>(lg, vraw);
+      if constexpr (KEYS_ONLY) {
+        // rows 4*rg + j of the block: lane sub = j stores that row's logit for every head
+        if (sub < 4) {
+          const int i = row0 + rg * 4 + sub;
+          if (i < s_end) {
+#pragma unroll
+            for (int g = 0; g < GH; ++g) {
+              float v = lg[0][g];
+#pragma unroll
+              for (int j = 1; j < 4; ++j) v = sub == j ? lg[j][g] : v;
+              a.logit_buf[(head0 + g) * (size_t)kc + i] = v;
+            }
+          }
+        }
+      } else {
+        st.template fold<4>(lg, vraw);
+      }
     };
 
     // the four waves take 16-row blocks in turn; the next block of a wave is requested before the
@@ -459,9 +483,108 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
       num = fmaf(sm_acc[w][g][e], sc, num);
       den = fmaf(sm_l[w][g], sc, den);
     }
-    const size_t pidx = (head0 + g) * a.n_splits + split;
+    const size_t pidx = (head0 + g) * a.n_part + split;
     a.part_acc[pidx * D + e] = num;
     if (e == 0) a.part_ml[pidx] = make_float2(M, den);
+  }
+}
+
+// Second phase of the two-phase path: out-contribution of the selected rows from their stored logits
+// (log2 units) and their values.  A workgroup takes pv_split_len consecutive selected rows of a unit for
+// GH heads: 16 lanes share a row (d/16 columns each), 16 rows at a time; the maximum of each head over
+// the workgroup's rows is formed first, so a single pass accumulates sum 2^(l - m) v.  Writes one
+// partial state (m, l, acc[d]) per head behind those of the first phase.
+template <int D, int GH>
+__global__ __launch_bounds__(256) void sparse_values_kernel(AttnArgs a) {
+  constexpr int EPL = D / 16;
+  __shared__ float sm_max[16][GH];
+  __shared__ float sm_l[16][GH];
+  __shared__ float sm_acc[16][GH][D];
+  const int unit = blockIdx.y, split = blockIdx.x, g0 = blockIdx.z * GH;
+  const int G = a.hq / a.hkv, b = unit / a.hkv, h = unit % a.hkv;
+  const size_t head0 = (size_t)b * a.hq + (size_t)h * G + g0;
+  const int sub = threadIdx.x & 15, grp = threadIdx.x >> 4;
+  const int kc = a.k * a.c;
+  const int r_begin = split * a.pv_split_len, r_end = min(kc, r_begin + a.pv_split_len);
+  const float* lg = a.logit_buf + head0 * (size_t)kc;
+  const bf16_t* vbase = a.v_sparse + (size_t)unit * a.v_unit_rows * D;
+  const int last_slot = a.v_unit_rows / a.c - 1;
+
+  // per-head maximum over the workgroup's rows
+  float mx[GH];
+#pragma unroll
+  for (int g = 0; g < GH; ++g) mx[g] = -INFINITY;
+  for (int i = r_begin + threadIdx.x; i < r_end; i += 256)
+#pragma unroll
+    for (int g = 0; g < GH; ++g) mx[g] = fmaxf(mx[g], lg[(size_t)g * kc + i]);
+#pragma unroll
+  for (int g = 0; g < GH; ++g) {
+#pragma unroll
+    for (int m = 8; m >= 1; m >>= 1) mx[g] = fmaxf(mx[g], __shfl_xor(mx[g], m, kWave));
+    if (sub == 0) sm_max[grp][g] = mx[g];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int g = 0; g < GH; ++g) {
+    float m = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) m = fmaxf(m, sm_max[w][g]);
+    mx[g] = m;
+  }
+
+  float l[GH], acc[GH][EPL];
+#pragma unroll
+  for (int g = 0; g < GH; ++g) {
+    l[g] = 0.f;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
+  }
+  for (int i0 = r_begin + grp; i0 < r_end; i0 += 64) {   // four rows per lane group in flight
+    uint32_t vraw[4][EPL / 2];
+    float p[4][GH];
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+      const int i = i0 + 16 * x;
+      const int ic = min(i, r_end - 1);
+      const int ch = ic / a.c, t = ic - ch * a.c;
+      const int slot = a.v_slots ? a.v_slots[(size_t)unit * a.k + ch] : ch;
+      load_raw<EPL>(vbase + ((size_t)min(max(slot, 0), last_slot) * a.c + t) * D + sub * EPL, vraw[x]);
+#pragma unroll
+      for (int g = 0; g < GH; ++g) p[x][g] = i < r_end ? lg[(size_t)g * kc + ic] : -INFINITY;
+    }
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+      float vx[EPL];
+      unpack_bf16<EPL>(vraw[x], vx);
+#pragma unroll
+      for (int g = 0; g < GH; ++g) {
+        const float w = __builtin_amdgcn_exp2f(p[x][g] - mx[g]);   // -inf for rows past the end: 0
+        l[g] += w;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[g][e] = fmaf(w, vx[e], acc[g][e]);
+      }
+    }
+  }
+#pragma unroll
+  for (int g = 0; g < GH; ++g) {
+    if (sub == 0) sm_l[grp][g] = l[g];
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) sm_acc[grp][g][sub * EPL + e] = acc[g][e];
+  }
+  __syncthreads();
+  for (int idx = threadIdx.x; idx < GH * D; idx += 256) {
+    const int g = idx / D, e = idx - g * D;
+    float num = 0.f, den = 0.f;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) { num += sm_acc[w][g][e]; den += sm_l[w][g]; }
+    const size_t pidx = (head0 + g) * a.n_part + a.n_splits + split;
+    a.part_acc[pidx * D + e] = num;
+    if (e == 0) {
+      float m = -INFINITY;
+#pragma unroll
+      for (int w = 0; w < 16; ++w) m = fmaxf(m, sm_max[w][g]);
+      a.part_ml[pidx] = make_float2(m, den);
+    }
   }
 }
 
@@ -486,50 +609,91 @@ __global__ __launch_bounds__(D) void attn_combine_kernel(const float* __restrict
   out[head * D + e] = f32_to_bf16(num / den);
 }
 
-template <int D, int GH, int KSMAX, bool FAST4>
+template <int D, int GH, int KSMAX, bool FAST4, bool KEYS_ONLY>
 static hipError_t launch_sparse(const AttnArgs& a, dim3 grid, size_t lds, hipStream_t st) {
   if (lds > 48 * 1024) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sparse_attn_kernel<D, GH, KSMAX, FAST4>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sparse_attn_kernel<D, GH, KSMAX, FAST4, KEYS_ONLY>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL((sparse_attn_kernel<D, GH, KSMAX, FAST4>), grid, dim3(256), lds, st, a);
+  hipLaunchKernelGGL((sparse_attn_kernel<D, GH, KSMAX, FAST4, KEYS_ONLY>), grid, dim3(256), lds, st, a);
   return hipGetLastError();
 }
 
-template <int D, int GH>
+template <int D, int GH, bool KEYS_ONLY>
 static hipError_t launch_sparse_ks(const AttnArgs& a, dim3 grid, size_t lds, hipStream_t st) {
   const bool fast4 = a.c % 4 == 0;
   if (a.r32 <= 160)
-    return fast4 ? launch_sparse<D, GH, 5, true>(a, grid, lds, st) : launch_sparse<D, GH, 5, false>(a, grid, lds, st);
-  return fast4 ? launch_sparse<D, GH, 8, true>(a, grid, lds, st) : launch_sparse<D, GH, 8, false>(a, grid, lds, st);
+    return fast4 ? launch_sparse<D, GH, 5, true, KEYS_ONLY>(a, grid, lds, st)
+                 : launch_sparse<D, GH, 5, false, KEYS_ONLY>(a, grid, lds, st);
+  return fast4 ? launch_sparse<D, GH, 8, true, KEYS_ONLY>(a, grid, lds, st)
+               : launch_sparse<D, GH, 8, false, KEYS_ONLY>(a, grid, lds, st);
 }
 
-template <int D>
-static hipError_t launch_attention_d(const AttnArgs& a, hipStream_t st) {
+template <int D, bool KEYS_ONLY>
+static hipError_t launch_keys_d(const AttnArgs& a, hipStream_t st) {
   const int G = a.hq / a.hkv;
   const int gh = attention_heads_per_group(G);
   // B^T, then the first token and the first value row of each chunk a split touches
   const size_t lds = (size_t)D * a.rp * sizeof(bf16_t) + 2 * ((size_t)a.sparse_split_len / a.c + 2) * sizeof(int);
   dim3 grid(a.n_splits, a.batch * a.hkv, G / gh);
-  hipError_t e;
   switch (gh) {
-    case 8: e = launch_sparse_ks<D, 8>(a, grid, lds, st); break;
-    case 4: e = launch_sparse_ks<D, 4>(a, grid, lds, st); break;
-    case 2: e = launch_sparse_ks<D, 2>(a, grid, lds, st); break;
-    default: e = launch_sparse_ks<D, 1>(a, grid, lds, st); break;
+    case 8: return launch_sparse_ks<D, 8, KEYS_ONLY>(a, grid, lds, st);
+    case 4: return launch_sparse_ks<D, 4, KEYS_ONLY>(a, grid, lds, st);
+    case 2: return launch_sparse_ks<D, 2, KEYS_ONLY>(a, grid, lds, st);
+    default: return launch_sparse_ks<D, 1, KEYS_ONLY>(a, grid, lds, st);
   }
-  if (e != hipSuccess) return e;
+}
+
+template <int D>
+static hipError_t launch_combine_d(const AttnArgs& a, hipStream_t st) {
   hipLaunchKernelGGL((attn_combine_kernel<D>), dim3(a.batch * a.hq), dim3(D), 0, st, a.part_acc, a.part_ml, a.out,
-                     a.n_splits);
+                     a.n_part);
   return hipGetLastError();
 }
 
+template <int D>
+static hipError_t launch_values_d(const AttnArgs& a, hipStream_t st) {
+  const int G = a.hq / a.hkv;
+  const int gh = G % 4 == 0 ? 4 : attention_heads_per_group(G);
+  dim3 grid(a.n_pv_splits, a.batch * a.hkv, G / gh);
+  switch (gh) {
+    case 4: hipLaunchKernelGGL((sparse_values_kernel<D, 4>), grid, dim3(256), 0, st, a); break;
+    case 2: hipLaunchKernelGGL((sparse_values_kernel<D, 2>), grid, dim3(256), 0, st, a); break;
+    default: hipLaunchKernelGGL((sparse_values_kernel<D, 1>), grid, dim3(256), 0, st, a); break;
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  return launch_combine_d<D>(a, st);
+}
+
+// Fused path: everything in one kernel (values already readable), then the merge of the splits.
 hipError_t launch_attention(const AttnArgs& a, hipStream_t st) {
+  hipError_t e;
   switch (a.d) {
-    case 64: return launch_attention_d<64>(a, st);
-    case 96: return launch_attention_d<96>(a, st);
-    case 128: return launch_attention_d<128>(a, st);
+    case 64: e = launch_keys_d<64, false>(a, st); return e != hipSuccess ? e : launch_combine_d<64>(a, st);
+    case 96: e = launch_keys_d<96, false>(a, st); return e != hipSuccess ? e : launch_combine_d<96>(a, st);
+    case 128: e = launch_keys_d<128, false>(a, st); return e != hipSuccess ? e : launch_combine_d<128>(a, st);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+// Two-phase path for values that arrive through a gather on another stream: this part needs none of them ...
+hipError_t launch_attention_keys(const AttnArgs& a, hipStream_t st) {
+  switch (a.d) {
+    case 64: return launch_keys_d<64, true>(a, st);
+    case 96: return launch_keys_d<96, true>(a, st);
+    case 128: return launch_keys_d<128, true>(a, st);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+// ... and this part runs once they are there (softmax of the stored logits times the values, merge of all parts).
+hipError_t launch_attention_values(const AttnArgs& a, hipStream_t st) {
+  switch (a.d) {
+    case 64: return launch_values_d<64>(a, st);
+    case 96: return launch_values_d<96>(a, st);
+    case 128: return launch_values_d<128>(a, st);
     default: return hipErrorInvalidValue;
   }
 }

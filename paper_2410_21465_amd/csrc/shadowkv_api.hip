@@ -99,6 +99,7 @@ int check_params(const shadowkv_params* p, bool decode, Shape* sh) {
 // rows (outliers + recent tokens).
 struct AttnPlan {
   int res_split_len, sparse_split_len, n_splits, z;
+  int pv_split_len, n_pv_splits;  // second phase of the two-phase path (values gathered meanwhile)
 };
 AttnPlan plan_attention(const Shape& sh) {
   AttnPlan ap;
@@ -115,11 +116,13 @@ AttnPlan plan_attention(const Shape& sh) {
   ap.sparse_split_len = (int)len;
   ap.n_splits = (int)((kc + len - 1) / len);
   ap.res_split_len = (int)((n_res + ap.n_splits - 1) / ap.n_splits);
+  ap.pv_split_len = 256;
+  ap.n_pv_splits = (int)((kc + ap.pv_split_len - 1) / ap.pv_split_len);
   return ap;
 }
 
 struct DecodeLayout {
-  size_t logits, partials, cand_key, cand_idx, sel_ids, miss_slots, sel_slots, n_miss, k_sparse, v_sparse, part_acc, part_ml, total;
+  size_t logits, partials, cand_key, cand_idx, sel_ids, miss_slots, sel_slots, n_miss, logit_buf, k_sparse, v_sparse, part_acc, part_ml, total;
   SelectPlan sel;
   AttnPlan attn;
   int n_tiles;
@@ -139,10 +142,12 @@ DecodeLayout decode_layout(const Shape& sh) {
   L.miss_slots = off; off += up((size_t)sh.units * sh.k * sizeof(int32_t));  // chunk cache: slots to fill
   L.sel_slots = off; off += up((size_t)sh.units * sh.k * sizeof(int32_t));   // chunk cache: slot of each selected chunk
   L.n_miss = off; off += up((size_t)sh.units * sizeof(int32_t));
+  L.logit_buf = off; off += up(heads * rows / sh.units * sizeof(float));  // two-phase path: [b*h_q, k*c]
   L.k_sparse = off; off += sh.keep_keys ? up(rows * sh.d * sizeof(float)) : 0;
   L.v_sparse = off; off += sh.stage ? up(rows * sh.d * sizeof(bf16_t)) : 0;
-  L.part_acc = off; off += up(heads * L.attn.n_splits * sh.d * sizeof(float));
-  L.part_ml = off; off += up(heads * L.attn.n_splits * sizeof(float2));
+  const size_t n_part = (size_t)L.attn.n_splits + L.attn.n_pv_splits;
+  L.part_acc = off; off += up(heads * n_part * sh.d * sizeof(float));
+  L.part_ml = off; off += up(heads * n_part * sizeof(float2));
   L.total = off;
   return L;
 }
@@ -430,68 +435,74 @@ static int decode_impl(const shadowkv_params* params, const shadowkv_bf16* q, co
   e = launch_select(a, L.sel, kSrcLogits, sh.units, st);
   if (e != hipSuccess) return fail_hip("select chunks", e);
   prof_mark(st, pstep, 2);
-  // 3. values of the selected chunks: staged by the gather kernel (side stream when given) ...
-  const int32_t* v_slots = nullptr;
-  int v_unit_rows = sh.k * sh.c;
-  if (cache) {
-    // index scan against last step's chunks, then only the missing chunks cross the link
-    int32_t* miss_slots = reinterpret_cast<int32_t*>(ws + L.miss_slots);
-    int32_t* n_miss = reinterpret_cast<int32_t*>(ws + L.n_miss);
-    int32_t* sel_slots = reinterpret_cast<int32_t*>(ws + L.sel_slots);
-    e = launch_cache_update(sel_ids, cache->chunk_ids, cache->stamps, sel_slots, miss_slots, n_miss, cache->miss_count,
-                            sh.units, sh.k, cache->slots, st);
-    if (e != hipSuccess) return fail_hip("cache update", e);
-    hipStream_t gs = st;
-    if (fork) {
-      if ((e = hipEventRecord(ev_fork, st)) != hipSuccess) return fail_hip("hipEventRecord", e);
-      if ((e = hipStreamWaitEvent(side, ev_fork, 0)) != hipSuccess) return fail_hip("hipStreamWaitEvent", e);
-      gs = side;
-    }
-    e = launch_gather_missing(value_store, cache->chunk_ids, miss_slots, n_miss, cache->values, sh.units, sh.d, sh.s,
-                              sh.cap, sh.c, sh.k, cache->slots, gs);
-    if (e != hipSuccess) return fail_hip("gather missing values", e);
-    if (fork) {
-      if ((e = hipEventRecord(ev_join, side)) != hipSuccess) return fail_hip("hipEventRecord", e);
-      if ((e = hipStreamWaitEvent(st, ev_join, 0)) != hipSuccess) return fail_hip("hipStreamWaitEvent", e);
-    }
-    // attention reads every selected chunk's values from its slot
-    v_sparse = cache->values;
-    v_slots = sel_slots;
-    v_unit_rows = cache->slots * sh.c;
-  } else if (sh.stage) {
-    hipStream_t gs = st;
-    if (fork) {
-      if ((e = hipEventRecord(ev_fork, st)) != hipSuccess) return fail_hip("hipEventRecord", e);
-      if ((e = hipStreamWaitEvent(side, ev_fork, 0)) != hipSuccess) return fail_hip("hipStreamWaitEvent", e);
-      gs = side;
-    }
-    e = launch_gather_values(value_store, sel_ids, v_sparse, sh.units, sh.d, sh.s, sh.cap, sh.c, sh.k, gs);
-    if (e != hipSuccess) return fail_hip("gather values", e);
-    if (fork) {
-      if ((e = hipEventRecord(ev_join, side)) != hipSuccess) return fail_hip("hipEventRecord", e);
-      if ((e = hipStreamWaitEvent(st, ev_join, 0)) != hipSuccess) return fail_hip("hipStreamWaitEvent", e);
-    }
-  }
-  prof_mark(st, pstep, 3);
-  // 4. ... then keys rebuilt and rotated inside the attention over [outliers ; selected ; recent]
   AttnArgs t{};
   t.q = q; t.A = A; t.B = B; t.k_outlier = k_outlier; t.v_outlier = v_outlier;
-  t.k_local = k_local; t.v_local = v_local; t.v_sparse = v_sparse; t.v_store = value_store;
-  t.sel_ids = sel_ids; t.v_slots = v_slots; t.v_unit_rows = v_unit_rows; t.pos_offset = pos_offset; t.inv_freq_dev = params->inv_freq;
+  t.k_local = k_local; t.v_local = v_local; t.v_store = value_store;
+  t.sel_ids = sel_ids; t.pos_offset = pos_offset; t.inv_freq_dev = params->inv_freq;
   t.k_sparse_out = sh.keep_keys ? reinterpret_cast<float*>(ws + L.k_sparse) : nullptr;
   t.part_acc = reinterpret_cast<float*>(ws + L.part_acc);
   t.part_ml = reinterpret_cast<float2*>(ws + L.part_ml);
+  t.logit_buf = reinterpret_cast<float*>(ws + L.logit_buf);
   t.out = out;
   t.s_cap = sh.cap;
   t.batch = sh.b; t.hq = sh.hq; t.hkv = sh.hkv; t.d = sh.d; t.s = sh.s; t.c = sh.c; t.o = sh.o; t.k = sh.k; t.w = sh.w;
   t.r = sh.r; t.r32 = (sh.r + 31) / 32 * 32; t.rp = t.r32 + 8;  // +8: 16-byte multiple that spreads LDS banks
   t.res_split_len = L.attn.res_split_len; t.sparse_split_len = L.attn.sparse_split_len; t.n_splits = L.attn.n_splits;
+  t.pv_split_len = L.attn.pv_split_len; t.n_pv_splits = L.attn.n_pv_splits;
+  t.v_unit_rows = sh.k * sh.c;
   t.c_shift = -1;
   for (int sft = 0; sft < 7; ++sft) if ((1 << sft) == sh.c) t.c_shift = sft;
   t.scale_log2 = (float)(scale * 1.4426950408889634074);
   t.freqs = freqs;
-  e = launch_attention(t, st);
-  if (e != hipSuccess) return fail_hip("attention", e);
+
+  if (!cache && !sh.stage) {
+    // 3./4. values readable in place: one fused kernel rebuilds and rotates the keys and attends over
+    //       [outliers ; selected ; recent]
+    prof_mark(st, pstep, 3);
+    t.n_part = t.n_splits;
+    e = launch_attention(t, st);
+    if (e != hipSuccess) return fail_hip("attention", e);
+    prof_mark(st, pstep, 4);
+    return SHADOWKV_OK;
+  }
+
+  // 3. the selected values have to be brought in by a gather (all of them, or with a cache only the
+  //    missing chunks).  It runs on the side stream while this stream does everything that needs none of
+  //    them: the resident rows, and key rebuild + RoPE + q.K of the selected rows.
+  int32_t* miss_slots = reinterpret_cast<int32_t*>(ws + L.miss_slots);
+  int32_t* n_miss = reinterpret_cast<int32_t*>(ws + L.n_miss);
+  int32_t* sel_slots = reinterpret_cast<int32_t*>(ws + L.sel_slots);
+  if (cache) {
+    e = launch_cache_update(sel_ids, cache->chunk_ids, cache->stamps, sel_slots, miss_slots, n_miss, cache->miss_count,
+                            sh.units, sh.k, cache->slots, st);
+    if (e != hipSuccess) return fail_hip("cache update", e);
+  }
+  hipStream_t gs = st;
+  if (fork) {
+    if ((e = hipEventRecord(ev_fork, st)) != hipSuccess) return fail_hip("hipEventRecord", e);
+    if ((e = hipStreamWaitEvent(side, ev_fork, 0)) != hipSuccess) return fail_hip("hipStreamWaitEvent", e);
+    gs = side;
+  }
+  if (cache) {
+    e = launch_gather_missing(value_store, cache->chunk_ids, miss_slots, n_miss, cache->values, sh.units, sh.d, sh.s,
+                              sh.cap, sh.c, sh.k, cache->slots, gs);
+    t.v_sparse = cache->values; t.v_slots = sel_slots; t.v_unit_rows = cache->slots * sh.c;
+  } else {
+    e = launch_gather_values(value_store, sel_ids, v_sparse, sh.units, sh.d, sh.s, sh.cap, sh.c, sh.k, gs);
+    t.v_sparse = v_sparse;
+  }
+  if (e != hipSuccess) return fail_hip("gather values", e);
+  t.n_part = t.n_splits + t.n_pv_splits;
+  e = launch_attention_keys(t, st);
+  if (e != hipSuccess) return fail_hip("attention (keys)", e);
+  if (fork) {
+    if ((e = hipEventRecord(ev_join, side)) != hipSuccess) return fail_hip("hipEventRecord", e);
+    if ((e = hipStreamWaitEvent(st, ev_join, 0)) != hipSuccess) return fail_hip("hipStreamWaitEvent", e);
+  }
+  prof_mark(st, pstep, 3);
+  // 4. softmax of the stored logits times the gathered values, merge with the resident part
+  e = launch_attention_values(t, st);
+  if (e != hipSuccess) return fail_hip("attention (values)", e);
   prof_mark(st, pstep, 4);
   return SHADOWKV_OK;
 }

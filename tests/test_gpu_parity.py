@@ -75,7 +75,10 @@ def test_staged_hbm_matches_in_place():
     ref_b, _ = PU.run_build_parity(wl, t)
     _, _, (o1, i1, _) = PU.run_decode_parity(wl, t, ref_b, flags=S.FLAG_STAGE_VALUES)
     _, _, (o2, i2, _) = PU.run_decode_parity(wl, t, ref_b, flags=0)
-    assert torch.equal(o1, o2) and torch.equal(i1, i2)
+    # the staged step runs the two-phase kernels (keys while the gather is under way, values after), the
+    # in-place step the fused kernel: same selection, outputs equal up to the rounding of the accumulation order
+    assert torch.equal(i1, i2)
+    assert float((o1.float() - o2.float()).abs().max()) <= 2.0 ** -6
 
 
 def test_positions_beyond_one_million_and_inv_freq_override():
