@@ -39,6 +39,14 @@ def algorithmic_bytes(wl) -> dict:
     return tot
 
 
+def equivalent_bandwidth(S: int, C: int, K: int, O: int, alpha: float, b_gpu: float, b_pcie: float) -> float:
+    """The paper's equivalent-bandwidth model (section "Theoretical Equivalent Bandwidth"): the bandwidth a dense
+    attention over S tokens would need to take the time ShadowKV takes -- landmarks S/C and attended K, V rows
+    2(K+O)C at GPU bandwidth, the missed share (1 - alpha) of the K*C selected value rows at PCIe bandwidth.
+    Same unit as ``b_gpu`` / ``b_pcie``.  Reported for context next to the measured numbers."""
+    return 2.0 * S * b_gpu / (S / C + 2.0 * (K + O) * C + (1.0 - alpha) * K * C * b_gpu / b_pcie)
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -248,6 +256,10 @@ def main() -> int:
         res["value_gather_pcie_bytes"] = ab["values"]
         res["pinned_h2d_copy_gbps"] = h2d_gbps
         res["value_gather_pcie_gbps"] = ab["values"] / (prof["ms"]["gather_values"] * 1e-3) / 1e9
+    if wl.value_location == "host":
+        # the paper's model with this machine's own rates: measured device copy and pinned-host copy, measured hit rate
+        res["paper_model_equivalent_bandwidth_gbps"] = equivalent_bandwidth(
+            wl.ctx_len, wl.chunk_size, wl.topk_chunks, wl.n_outlier_chunks, hit_rate or 0.0, copy_gbps, h2d_gbps)
     if cache is not None:
         res["config"]["chunk_cache"] = True
         res["config"]["cache_slots"] = cache.slots
