@@ -21,6 +21,13 @@
 // hardware sin/cos of 2*pi*x -- accurate at positions beyond 2^20.  When the chunk size is a
 // multiple of 4 the four rows a lane holds per tile are consecutive tokens: one such angle per
 // tile and frequency is stepped by one position three times.
+// Latency: the first token (and value row) of every chunk a split touches is staged in LDS once,
+// and a wave requests the A rows and value rows of its next 16-row block before it works on the
+// current one, with a fixed number of unconditional loads per block so that the wait before the
+// MFMAs covers only the current block's loads.
+// When the selected values are not readable yet (they are being gathered on another stream) the
+// work is done in two kernels: this one with KEYS_ONLY (no selected value touched, logits stored),
+// then sparse_values_kernel.
 #include "kernels.hpp"
 
 namespace skv {

@@ -95,7 +95,7 @@ int check_params(const shadowkv_params* p, bool decode, Shape* sh) {
 }
 
 // Split plan of the attention kernel: the selected rows are cut into splits that are multiples of
-// 32 rows (one MFMA row block of one wave); every split also takes an equal share of the resident
+// 32 rows (two MFMA row blocks); every split also takes an equal share of the resident
 // rows (outliers + recent tokens).
 struct AttnPlan {
   int res_split_len, sparse_split_len, n_splits, z;
