@@ -174,8 +174,8 @@ __global__ __launch_bounds__(kSelNT) void select_merge(SelectArgs a) {
 // survivors go through the middle level in groups of 2048 (k <= 2048) or 16384.
 bool plan_select(int n, int k, SelectPlan* plan) {
   static const int es[] = {4, 8, 16, 32};
-  int forced = 0;
-  if (const char* ov = std::getenv("SHADOWKV_SELECT_E")) forced = std::atoi(ov);  // tuning override: keys per thread
+  // tuning override: keys per thread of the slices (read once)
+  static const int forced = [] { const char* ov = std::getenv("SHADOWKV_SELECT_E"); return ov ? std::atoi(ov) : 0; }();
   const long cap = (long)kSelNT * 32;  // what one workgroup can rank
   for (int e : es) {
     if (forced && e != forced && e != 32) continue;

@@ -109,10 +109,9 @@ AttnPlan plan_attention(const Shape& sh) {
   // the largest split (fewest B^T stagings) that still gives >= 512 workgroups
   long len = 32;
   for (long cand : {512l, 256l, 128l, 64l}) if (kc * groups / cand >= 512) { len = cand; break; }
-  if (const char* ov = std::getenv("SHADOWKV_SPARSE_SPLIT")) {  // tuning override: rows per split
-    const long v = std::atol(ov);
-    if (v >= 32 && v <= 1024 && v % 32 == 0) len = v;
-  }
+  // tuning override: rows per split (read once)
+  static const long forced = [] { const char* ov = std::getenv("SHADOWKV_SPARSE_SPLIT"); return ov ? std::atol(ov) : 0l; }();
+  if (forced >= 32 && forced <= 1024 && forced % 32 == 0) len = forced;
   ap.sparse_split_len = (int)len;
   ap.n_splits = (int)((kc + len - 1) / len);
   ap.res_split_len = (int)((n_res + ap.n_splits - 1) / ap.n_splits);
