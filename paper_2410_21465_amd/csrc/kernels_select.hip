@@ -12,19 +12,28 @@ namespace skv {
 
 constexpr int kSelNT = 512;
 
-// Log-sum-exp of each query head of the unit from the per-tile (max, sum) pairs the
-// scoring kernel left behind; fp64 throughout.
+// Log-sum-exp of each query head of the unit from the per-tile (max, sum) pairs the scoring
+// kernel left behind.  Sums and the logarithm are fp64; the rescaling factors exp(m_t - m) go
+// through the fp32 exp2 unit exactly as they did when the scoring kernel formed the pairs (relative
+// error ~1e-7 on terms that are summed, an order below the 1e-6 at which two scores count as tied).
+// Every (max, sum) pair is read once.
+__device__ __forceinline__ double exp_neg_fast(double x) {
+  return (double)__builtin_amdgcn_exp2f((float)(x * 1.4426950408889634074));
+}
 __device__ void unit_lse(const double2* __restrict__ part, int n_tiles, int G, double* lse_sm) {
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   for (int g = wave; g < G; g += kSelNT / kWave) {
     const double2* p = part + (size_t)g * n_tiles;
-    double m = -INFINITY;
-    for (int t = lane; t < n_tiles; t += kWave) m = fmax(m, p[t].x);
-    m = wave_max_f64(m);
-    double s = 0.0;
-    for (int t = lane; t < n_tiles; t += kWave) s += p[t].y * exp(p[t].x - m);
+    double m = -INFINITY, s = 0.0;   // running (max, sum exp(. - max)) of this lane's tiles
+    for (int t = lane; t < n_tiles; t += kWave) {
+      const double2 v = p[t];
+      if (v.x > m) { s = s * exp_neg_fast(m - v.x) + v.y; m = v.x; }
+      else if (v.x != -INFINITY) s += v.y * exp_neg_fast(v.x - m);
+    }
+    const double mw = wave_max_f64(m);
+    s = (m == -INFINITY) ? 0.0 : s * exp_neg_fast(m - mw);
     s = wave_sum_f64(s);
-    if (lane == 0) lse_sm[g] = m + log(s);
+    if (lane == 0) lse_sm[g] = mw + log(s);
   }
   __syncthreads();
 }
