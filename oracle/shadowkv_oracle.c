@@ -1,11 +1,13 @@
 /*
  * ShadowKV CPU oracle -- TEST INFRASTRUCTURE, NOT PRODUCT CODE.
  *
- * A plain, slow, obviously-correct implementation of the two operations the
- * GPU library exports: landmark/outlier construction (pre-filling algorithm,
- * Alg. 1 of the paper, every step after the SVD) and one sparse decode step
+ * A plain, slow, obviously-correct implementation of the operations the GPU
+ * library exports: landmark/outlier construction (pre-filling algorithm,
+ * Alg. 1 of the paper, every step after the SVD), one sparse decode step
  * (decoding algorithm, Alg. 2, followed by the standard attention over the
- * selected set described in the "Theoretical Equivalent Bandwidth" section).
+ * selected set described in the "Theoretical Equivalent Bandwidth" section),
+ * the bookkeeping of the chunk cache of offloaded values and the append of a
+ * chunk of generated tokens (both from section "High-throughput Decoding").
  *
  * Rules this file keeps:
  *   - it shares nothing with the HIP path (no header, no helper, no table);
@@ -20,7 +22,10 @@
  * Pins (tests/test_oracle_*.py): brute-force re-implementation on tiny
  * shapes, dense softmax attention when the budget covers every chunk, exact
  * reconstruction at full rank, RoPE group identities, chunk-size-1 reduction
- * to token top-k, closed forms for the cosine criterion.  What is NOT pinned
+ * to token top-k, closed forms for the cosine criterion; for the cache model
+ * hand-worked cases, an independent simulation and its invariants; for the
+ * append exact projection inside the subspace and "append == longer
+ * prefill"; planted mistakes (mutants) must fail these pins.  What is NOT pinned
  * anywhere ("parity unpinned"): how well the method approximates dense
  * attention on a trained model -- that needs weights and evaluation suites.
  *
