@@ -1,11 +1,13 @@
 // Landmark scoring: P = Q L^T * scale for every landmark slot (first line of the
 // decoding algorithm), streamed once from HBM for up to four heads of a KV group.
 //
-// The scores decide an index set that has to match an fp64 reference to within
-// 1e-6, so the bf16 inputs are widened to fp64 and contracted on the fp64 matrix
-// pipe (v_mfma_f64_4x4x4f64: four independent 4x4x4 blocks per wave, 256 FMAs per
-// issue, no cross-lane reduction needed).  The vector ALU only unpacks and converts,
-// which leaves the kernel bound by the HBM read of L.
+// The scores decide an index set that has to match a reference bit for bit: the logit
+// is defined as the exact dot product of the bf16 inputs rounded once to fp32, so the
+// inputs are widened to fp64 and contracted on the fp64 matrix pipe
+// (v_mfma_f64_4x4x4f64: four independent 4x4x4 blocks per wave, 256 FMAs per issue, no
+// cross-lane reduction needed) and the sum is rounded at the end -- an fp32 accumulation
+// would make the stored value depend on the order of summation.  The vector ALU only
+// unpacks and converts, which leaves the kernel bound by the HBM read of L.
 //
 // Operand layout of the instruction, as measured on gfx950: input lane
 // = 16*k + 4*block + (i for A | j for B), result lane = 16*i + 4*block + j.
@@ -13,7 +15,7 @@
 // k = which 16-byte piece of each 64-byte row segment the lane loads.  A wave covers
 // 64 rows (four 16-row tiles, all loads issued before the first MFMA), a workgroup 256.
 // Result lane 16*i + r holds the logit of head i, row r of the tile: it stores it
-// (16 consecutive doubles per head) and folds it into its running (max, sum exp),
+// (16 consecutive floats per head) and folds it into its running (max, sum exp),
 // from which the selection kernel forms each head's log-sum-exp.
 #include "kernels.hpp"
 
@@ -36,7 +38,7 @@ __device__ __forceinline__ void lse_merge(double& m, double& s, double m2, doubl
 
 template <int D>
 __global__ __launch_bounds__(256) void score_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ L,
-                                                    double* __restrict__ logits, double2* __restrict__ partials,
+                                                    float* __restrict__ logits, double2* __restrict__ partials,
                                                     int hq, int hkv, int G, int n_c, int nc_stride, int n_tiles, double scale) {
   constexpr int NI = D / 32;  // 16-byte pieces per lane per row
   __shared__ double2 wred[4][4];
@@ -89,9 +91,9 @@ __global__ __launch_bounds__(256) void score_kernel(const bf16_t* __restrict__ q
     }
     const int r = row0 + t * 16 + (lane & 15);
     if (r < n_c && hd < G) {
-      const double p = acc * scale;
-      logits[(head0 + (lane >> 4)) * n_c + r] = p;
-      lse_merge(m, s, p, 1.0);
+      const float p32 = (float)(acc * scale);   // THE logit: exact dot product, rounded once to fp32
+      logits[(head0 + (lane >> 4)) * n_c + r] = p32;
+      lse_merge(m, s, (double)p32, 1.0);
     }
   }
 
@@ -109,7 +111,7 @@ __global__ __launch_bounds__(256) void score_kernel(const bf16_t* __restrict__ q
   }
 }
 
-hipError_t launch_score(const bf16_t* q, const bf16_t* landmarks, double* logits, double2* partials, int batch,
+hipError_t launch_score(const bf16_t* q, const bf16_t* landmarks, float* logits, double2* partials, int batch,
                         int hq, int hkv, int d, int n_c, int nc_stride, double scale, hipStream_t st) {
   const int G = hq / hkv;
   const int n_tiles = (n_c + kScoreTile - 1) / kScoreTile;

@@ -52,12 +52,12 @@ __global__ __launch_bounds__(kSelNT) void select_slices(SelectArgs a) {
     // the logits of the first heads are requested before the normalisers are formed (the two do not
     // depend on each other), the remaining heads of a large group afterwards
     constexpr int GP = 4;
-    const double* lg = a.logits + (size_t)unit * a.G * a.n;
+    const float* lg = a.logits + (size_t)unit * a.G * a.n;
     const int j0 = base + threadIdx.x * E;
-    double pre[GP][E];
+    float pre[GP][E];
 #pragma unroll
     for (int g = 0; g < GP; ++g) {
-      const double* row = lg + (size_t)min(g, a.G - 1) * a.n;
+      const float* row = lg + (size_t)min(g, a.G - 1) * a.n;
 #pragma unroll
       for (int e = 0; e < E; ++e) pre[g][e] = row[min(j0 + e, a.n - 1)];
     }
@@ -71,19 +71,19 @@ __global__ __launch_bounds__(kSelNT) void select_slices(SelectArgs a) {
 #pragma unroll
         for (int e = 0; e < E; ++e)
           if (j0 + e < a.n) {
-            const uint64_t kk = f64_key(pre[g][e] - l);
+            const uint64_t kk = f64_key((double)pre[g][e] - l);
             key[e] = kk > key[e] ? kk : key[e];   // max over the heads of the group
           }
       }
     }
     for (int g = GP; g < a.G; ++g) {
       const double l = lse_sm[g];
-      const double* row = lg + (size_t)g * a.n;
+      const float* row = lg + (size_t)g * a.n;
 #pragma unroll
       for (int e = 0; e < E; ++e) {
         const int j = j0 + e;
         if (j < a.n) {
-          const uint64_t kk = f64_key(row[j] - l);
+          const uint64_t kk = f64_key((double)row[j] - l);
           key[e] = kk > key[e] ? kk : key[e];
         }
       }
