@@ -98,7 +98,7 @@ __global__ __launch_bounds__(kSelNT) void select_slices(SelectArgs a) {
   }
 
   uint32_t sel; int pos;
-  block_select_topk<kSelNT, E>(key, k_here, sm, sel, pos);
+  block_select_topk<kSelNT, E, true>(key, k_here, sm, sel, pos);
 
   if (a.n_slices == 1) {
 #pragma unroll
@@ -154,7 +154,7 @@ __global__ __launch_bounds__(kSelNT) void select_merge(SelectArgs a) {
     idx[e] = c < n_cand ? ci[c] : 0;
   }
   uint32_t sel; int pos;
-  block_select_topk<kSelNT, E>(key, k_here, sm, sel, pos);
+  block_select_topk<kSelNT, E, true>(key, k_here, sm, sel, pos);
   if constexpr (MID) {
     const size_t off = (size_t)unit * a.cand_stride + a.cand2_off + (size_t)blockIdx.x * a.k;
 #pragma unroll
