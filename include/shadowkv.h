@@ -212,6 +212,20 @@ size_t shadowkv_value_cache_bytes(const shadowkv_params *params, int32_t cache_s
 int shadowkv_value_cache_reset(const shadowkv_params *params, int32_t cache_slots,
                                int32_t *cache_chunk_ids, int32_t *cache_stamps, void *stream);
 
+/*
+ * ArgTopK as both algorithms of the paper use it (outlier chunks in Alg. 1, selected chunks in Alg. 2),
+ * on its own: for each of `units` rows of `n` fp64 scores, the indices of the k largest values
+ * (largest = sign * score, sign = +1 or -1), ties to the lower index, written in ascending index order.
+ * NaN scores are not allowed.  Exact for any fp64 input (the internal search runs on a coarser monotone
+ * key first and settles coarse ties on the exact values).
+ *   scores    dev [units, n] fp64     out_ids  dev out [units, k] int32
+ *   workspace dev, >= shadowkv_argtopk_workspace_bytes(units, n, k), 256-byte aligned
+ * 1 <= k <= n, units <= 65535; SHADOWKV_EINVAL if the sizes exceed what the selection kernels hold.
+ */
+int shadowkv_argtopk(const double *scores, int32_t units, int32_t n, int32_t k, double sign,
+                     int32_t *out_ids, void *workspace, size_t workspace_bytes, void *stream);
+size_t shadowkv_argtopk_workspace_bytes(int32_t units, int32_t n, int32_t k);
+
 /* Workspace sizes in bytes for the given shape (0 if params are invalid). */
 size_t shadowkv_build_workspace_bytes(const shadowkv_params *params);
 size_t shadowkv_decode_workspace_bytes(const shadowkv_params *params);

@@ -553,6 +553,35 @@ int shadowkv_append_chunk(const shadowkv_params* params, const shadowkv_bf16* k_
   return SHADOWKV_OK;
 }
 
+size_t shadowkv_argtopk_workspace_bytes(int32_t units, int32_t n, int32_t k) {
+  SelectPlan plan;
+  if (units < 1 || units > 65535 || n < 1 || k < 1 || k > n || !plan_select(n, k, &plan)) return 0;
+  const size_t bytes = up((size_t)units * plan.cand_stride * sizeof(uint64_t)) +
+                       up((size_t)units * plan.cand_stride * sizeof(int32_t));
+  return bytes ? bytes : kAlign;
+}
+
+int shadowkv_argtopk(const double* scores, int32_t units, int32_t n, int32_t k, double sign, int32_t* out_ids,
+                     void* workspace, size_t workspace_bytes, void* stream) {
+  if (!scores || !out_ids) return fail_inval("scores and out_ids must not be NULL");
+  if (units < 1 || units > 65535 || n < 1 || k < 1 || k > n) return fail_inval("need 1 <= k <= n and 1 <= units <= 65535");
+  if (sign != 1.0 && sign != -1.0) return fail_inval("sign must be +1 or -1");
+  SelectPlan plan;
+  if (!plan_select(n, k, &plan)) return fail_inval("n / k combination exceeds the selection kernels' capacity");
+  int rc = check_workspace(workspace, workspace_bytes, shadowkv_argtopk_workspace_bytes(units, n, k));
+  if (rc != SHADOWKV_OK) return rc;
+  char* ws = static_cast<char*>(workspace);
+  SelectArgs a{};
+  a.scores = scores; a.sign = sign; a.n = n; a.k = k;
+  a.slice_len = plan.slice_len; a.n_slices = plan.n_slices; a.cand_stride = plan.cand_stride;
+  a.cand_key = reinterpret_cast<uint64_t*>(ws);
+  a.cand_idx = reinterpret_cast<int32_t*>(ws + up((size_t)units * plan.cand_stride * sizeof(uint64_t)));
+  a.out_ids = out_ids;
+  hipError_t e = launch_select(a, plan, kSrcArray, units, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return fail_hip("argtopk", e);
+  return SHADOWKV_OK;
+}
+
 size_t shadowkv_value_cache_bytes(const shadowkv_params* params, int32_t cache_slots) {
   Shape sh;
   if (check_params(params, true, &sh) != SHADOWKV_OK) return 0;

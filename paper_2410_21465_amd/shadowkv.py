@@ -26,7 +26,7 @@ EXPORTS = (
     "shadowkv_decode_workspace_bytes", "shadowkv_validate_params", "shadowkv_decode_workspace_view",
     "shadowkv_status_string", "shadowkv_last_error", "shadowkv_version", "shadowkv_shutdown",
     "shadowkv_profile_begin", "shadowkv_profile_end", "shadowkv_decode_step_cached", "shadowkv_value_cache_bytes",
-    "shadowkv_value_cache_reset", "shadowkv_append_chunk",
+    "shadowkv_value_cache_reset", "shadowkv_append_chunk", "shadowkv_argtopk", "shadowkv_argtopk_workspace_bytes",
 )
 STAGES = ("score", "select", "gather_values", "attention")
 
@@ -72,6 +72,10 @@ def lib() -> C.CDLL:
         L.shadowkv_value_cache_bytes.argtypes = [vp, i32]
         L.shadowkv_value_cache_reset.restype = i32
         L.shadowkv_value_cache_reset.argtypes = [vp, i32, vp, vp, vp]
+        L.shadowkv_argtopk.restype = i32
+        L.shadowkv_argtopk.argtypes = [vp, i32, i32, i32, C.c_double, vp, vp, sz, vp]
+        L.shadowkv_argtopk_workspace_bytes.restype = sz
+        L.shadowkv_argtopk_workspace_bytes.argtypes = [i32, i32, i32]
         L.shadowkv_append_chunk.restype = i32
         L.shadowkv_append_chunk.argtypes = [vp] * 10
         L.shadowkv_build_workspace_bytes.restype = sz
@@ -270,6 +274,19 @@ def append_chunk(p: Params, k_pre, k_rope, v, B, A, landmarks, landmark_chunk_id
     _check(lib().shadowkv_append_chunk(C.addressof(st), _ptr(k_pre), _ptr(k_rope), _ptr(v), _ptr(B), _ptr(A),
                                        _ptr(landmarks), _ptr(landmark_chunk_ids), _ptr(value_store),
                                        _stream_ptr(stream)))
+
+
+def argtopk(scores: torch.Tensor, k: int, largest: bool = True, stream=None) -> torch.Tensor:
+    """Indices of the k largest (or smallest) of each row of ``scores [units, n]`` (fp64, device), ties to the
+    lower index, in ascending index order: ``[units, k]`` int32."""
+    assert scores.dtype == torch.float64 and scores.dim() == 2
+    units, n = scores.shape
+    need = int(lib().shadowkv_argtopk_workspace_bytes(units, n, k))
+    ws = alloc_workspace(max(need, 256), scores.device)
+    out = torch.empty(units, k, dtype=torch.int32, device=scores.device)
+    _check(lib().shadowkv_argtopk(_ptr(scores), units, n, k, 1.0 if largest else -1.0, _ptr(out), _ptr(ws), ws.numel(),
+                                  _stream_ptr(stream)))
+    return out
 
 
 class ValueCache:
