@@ -253,7 +253,7 @@ int shadowkv_profile_end(double* stage_ms, int* n_steps) {
   return rc;
 }
 
-int shadowkv_version(void) { return 100; }
+int shadowkv_version(void) { return 200; }
 
 const char* shadowkv_status_string(int status) {
   switch (status) {
