@@ -11,7 +11,8 @@
  *
  * Rules this file keeps:
  *   - it shares nothing with the HIP path (no header, no helper, no table);
- *   - inputs are the same bf16 bit patterns the GPU gets, widened exactly to
+ *   - inputs are the same bit patterns the GPU gets (bf16, or FP8 E5M2 bytes for
+ *     the KV-cache tensors in the FP8 storage mode), widened exactly to
  *     fp64; every sum, norm, exponential and angle is fp64; nothing is rounded
  *     on the way except the chunk logits of the decode step (once, to fp32:
  *     the paper forms them in bf16) and the bf16 outputs (round-to-nearest-even
@@ -27,7 +28,10 @@
  * to token top-k, closed forms for the cosine criterion; for the cache model
  * hand-worked cases, an independent simulation and its invariants; for the
  * append exact projection inside the subspace and "append == longer
- * prefill"; planted mistakes (mutants) must fail these pins.  What is NOT pinned
+ * prefill"; for the FP8 storage mode the format's definition in exact fractions,
+ * a brute-force nearest-code search, a library's own E5M2 type, and bit equality
+ * with the bf16 mode on widened inputs; planted mistakes (mutants) must fail
+ * these pins.  What is NOT pinned
  * anywhere ("parity unpinned"): how well the method approximates dense
  * attention on a trained model -- that needs weights and evaluation suites.
  *
@@ -52,6 +56,7 @@ typedef struct oracle_params {
   const float *inv_freq;  /* optional [d/2]; replaces theta^(-2i/d) */
   double softmax_scale;   /* 0 => 1/sqrt(d) */
   int32_t ctx_capacity;   /* tokens the context arrays are laid out for (0 => ctx_len); see below */
+  int32_t kv_dtype;       /* storage type of the KV-cache tensors: 0 = bf16, 1 = FP8 E5M2; see below */
 } oracle_params;
 
 /* Room to grow (generated tokens are appended chunk by chunk, oracle_append_chunk): the arrays that
@@ -101,6 +106,60 @@ uint16_t oracle_f64_to_bf16(double x) {
   return sign | (uint16_t)(u >> 16);
 }
 
+/* ---- FP8 (E5M2) storage of the KV cache ----------------------------------
+ * Section "Precision Sensitivity": besides bf16 the paper runs the method with the
+ * KV cache held in FP8, the E5M2 format: one byte per element -- sign, 5 exponent
+ * bits (bias 15), 2 fraction bits, with subnormals, infinities and NaNs as in
+ * IEEE 754.  The reading taken: with kv_dtype = 1 every tensor that is KV-cache
+ * state (A, B, landmarks, outlier and recent K,V, the value store, and the keys and
+ * values handed to the pre-filling step and to the append) holds such bytes; the
+ * query and the attention output are activations and stay bf16.  The arithmetic
+ * does not change: stored elements are widened exactly to fp64, and what the
+ * method stores itself (landmarks, low-rank states of generated tokens) is rounded
+ * once, to nearest-even, from the fp64 value; beyond the largest finite value
+ * (57344) that rounding gives infinity, as IEEE 754 does.                      */
+double oracle_e5m2_to_f64(uint8_t v) {
+  const int sign = v >> 7, e = (v >> 2) & 31, m = v & 3;
+  double a;
+  if (e == 31) a = m ? NAN : INFINITY;
+  else if (e == 0) a = ldexp((double)m, -16);            /* subnormal: m/4 * 2^-14 */
+  else a = ldexp(1.0 + (double)m / 4.0, e - 15);
+  return sign ? -a : a;
+}
+
+uint8_t oracle_f64_to_e5m2(double x) {
+  if (isnan(x)) return 0x7f;
+  const uint8_t sign = signbit(x) ? 0x80 : 0;
+  const double a = fabs(x);
+  if (a == 0.0) return sign;
+  if (isinf(a)) return sign | 0x7c;
+  int e;
+  (void)frexp(a, &e);
+  int E = e - 1;                       /* floor(log2 a) */
+  if (E < -14) E = -14;                /* subnormal range: fixed spacing 2^-16 */
+  const double ulp = ldexp(1.0, E - 2);  /* 2 fraction bits */
+  const double r = nearbyint(a / ulp) * ulp; /* ties to even; may carry into the next binade */
+  if (r > 57344.0) return sign | 0x7c;
+  if (r < ldexp(1.0, -14)) return sign | (uint8_t)(r / ldexp(1.0, -16));
+  int er;
+  const double fr = frexp(r, &er);     /* r = fr * 2^er, fr in [0.5, 1) */
+  const int m = (int)((fr * 2.0 - 1.0) * 4.0);
+  return sign | (uint8_t)(((er - 1 + 15) << 2) | m);
+}
+
+/* element i of a KV-cache tensor, widened exactly; bytes per element; store with one rounding */
+static double kv_get(const oracle_params *p, const void *base, int64_t i) {
+  return p->kv_dtype == 1 ? oracle_e5m2_to_f64(((const uint8_t *)base)[i]) : bf16_to_f64(((const uint16_t *)base)[i]);
+}
+static size_t kv_size(const oracle_params *p) { return p->kv_dtype == 1 ? 1 : 2; }
+static void kv_put(const oracle_params *p, void *base, int64_t i, double x) {
+  if (p->kv_dtype == 1) ((uint8_t *)base)[i] = oracle_f64_to_e5m2(x);
+  else ((uint16_t *)base)[i] = oracle_f64_to_bf16(x);
+}
+static void kv_copy(const oracle_params *p, void *dst, int64_t di, const void *src, int64_t si, int64_t n) {
+  memcpy((char *)dst + di * kv_size(p), (const char *)src + si * kv_size(p), (size_t)n * kv_size(p));
+}
+
 /* ---- rotary position embedding ------------------------------------------
  * Rotate-half pairing over the full head dimension: coordinate i < d/2 is
  * paired with i + d/2, frequency theta^(-2i/d), angle = position * frequency
@@ -148,11 +207,11 @@ static int cmp_desc(const void *a, const void *b) {
  *   outlier_chunk_ids [o] most-outlying first, k_outlier/v_outlier [o*c, d].
  * Optional fp64 diagnostics: chunk_min_cos [b,h_kv,n_ch], chunk_mean
  * [b,h_kv,n_ch,d] (pass NULL to skip).  v / v_outlier may be NULL.         */
-int oracle_build_landmarks(const oracle_params *p, const uint16_t *k_rope,
-                           const uint16_t *v, uint16_t *landmarks,
+int oracle_build_landmarks(const oracle_params *p, const void *k_rope,
+                           const void *v, void *landmarks,
                            int32_t *landmark_chunk_ids,
-                           int32_t *outlier_chunk_ids, uint16_t *k_outlier,
-                           uint16_t *v_outlier, double *chunk_min_cos,
+                           int32_t *outlier_chunk_ids, void *k_outlier,
+                           void *v_outlier, double *chunk_min_cos,
                            double *chunk_mean) {
   const int d = p->head_dim, c = p->chunk_size, o = p->n_outlier_chunks;
   const int64_t s = p->ctx_len;
@@ -168,7 +227,7 @@ int oracle_build_landmarks(const oracle_params *p, const uint16_t *k_rope,
 
 #pragma omp parallel for schedule(dynamic, 1)
   for (int64_t u = 0; u < units; ++u) {
-    const uint16_t *K = k_rope + u * s * d;
+    const int64_t K0 = u * s * d;  /* first element of this unit's keys */
     double *C = malloc(sizeof(double) * n_ch * d);      /* chunk means */
     keyed *m = malloc(sizeof(keyed) * (n_ch ? n_ch : 1)); /* -min cos   */
     char *is_out = calloc(n_ch ? n_ch : 1, 1);
@@ -179,7 +238,7 @@ int oracle_build_landmarks(const oracle_params *p, const uint16_t *k_rope,
     for (int64_t j = 0; j < n_ch; ++j)
       for (int x = 0; x < d; ++x) {
         double acc = 0.0;
-        for (int t = 0; t < c; ++t) acc += bf16_to_f64(K[(j * c + t) * d + x]);
+        for (int t = 0; t < c; ++t) acc += kv_get(p, k_rope, K0 + (j * c + t) * d + x);
         C[j * d + x] = acc / (double)c;
       }
     /* S <- CosineSimilarity(C, K^RoPE); Min over the chunk's tokens */
@@ -191,7 +250,7 @@ int oracle_build_landmarks(const oracle_params *p, const uint16_t *k_rope,
       for (int t = 0; t < c; ++t) {
         double dot = 0.0, kn = 0.0;
         for (int x = 0; x < d; ++x) {
-          double kv = bf16_to_f64(K[(j * c + t) * d + x]);
+          double kv = kv_get(p, k_rope, K0 + (j * c + t) * d + x);
           dot += C[j * d + x] * kv;
           kn += kv * kv;
         }
@@ -210,10 +269,9 @@ int oracle_build_landmarks(const oracle_params *p, const uint16_t *k_rope,
       int64_t j = m[i].idx;
       is_out[j] = 1;
       outlier_chunk_ids[u * o + i] = (int32_t)j;
-      memcpy(k_outlier + (u * o + i) * c * d, K + j * c * d, sizeof(uint16_t) * c * d);
+      kv_copy(p, k_outlier, (u * o + i) * c * d, k_rope, K0 + j * c * d, (int64_t)c * d);
       if (v && v_outlier)
-        memcpy(v_outlier + (u * o + i) * c * d, v + (u * cap + j * c) * d,
-               sizeof(uint16_t) * c * d);
+        kv_copy(p, v_outlier, (u * o + i) * c * d, v, (u * cap + j * c) * d, (int64_t)c * d);
     }
     /* L <- C without the outlier rows, in ascending chunk order */
     int64_t slot = 0;
@@ -221,7 +279,7 @@ int oracle_build_landmarks(const oracle_params *p, const uint16_t *k_rope,
       if (is_out[j]) continue;
       landmark_chunk_ids[u * nc_cap + slot] = (int32_t)j;
       for (int x = 0; x < d; ++x)
-        landmarks[(u * nc_cap + slot) * d + x] = oracle_f64_to_bf16(C[j * d + x]);
+        kv_put(p, landmarks, (u * nc_cap + slot) * d + x, C[j * d + x]);
       ++slot;
     }
     free(C); free(m); free(is_out);
@@ -238,12 +296,12 @@ int oracle_build_landmarks(const oracle_params *p, const uint16_t *k_rope,
  * z2 [b,h_kv,n_c] (log-domain group score per landmark slot),
  * k_sparse [b,h_kv,k*c,d] fp64 (rebuilt, rotated keys in chunk_ids order).   */
 int oracle_decode_step(const oracle_params *p, const uint16_t *q,
-                       const uint16_t *A, const uint16_t *B,
-                       const uint16_t *landmarks,
+                       const void *A, const void *B,
+                       const void *landmarks,
                        const int32_t *landmark_chunk_ids,
-                       const uint16_t *k_outlier, const uint16_t *v_outlier,
-                       const uint16_t *k_local, const uint16_t *v_local,
-                       const uint16_t *value_store, const int32_t *pos_offset,
+                       const void *k_outlier, const void *v_outlier,
+                       const void *k_local, const void *v_local,
+                       const void *value_store, const int32_t *pos_offset,
                        uint16_t *out_bf16, double *out_f64, int32_t *chunk_ids,
                        double *z2_out, double *k_sparse_out) {
   const int d = p->head_dim, c = p->chunk_size, r = p->rank;
@@ -265,7 +323,7 @@ int oracle_decode_step(const oracle_params *p, const uint16_t *q,
 #pragma omp parallel for schedule(dynamic, 1)
   for (int64_t u = 0; u < units; ++u) {
     const int64_t bi = u / hkv, h = u % hkv;
-    const uint16_t *L = landmarks + u * nc_cap * d;
+    const int64_t L0 = u * nc_cap * d; /* first element of this unit's landmarks */
     const int32_t *Lid = landmark_chunk_ids + u * nc_cap;
     double *P = malloc(sizeof(double) * (size_t)G * (n_c ? n_c : 1));
     keyed *z2 = malloc(sizeof(keyed) * (n_c ? n_c : 1));
@@ -289,7 +347,7 @@ int oracle_decode_step(const oracle_params *p, const uint16_t *q,
       double mx = -INFINITY;
       for (int64_t j = 0; j < n_c; ++j) {
         double dot = 0.0;
-        for (int x = 0; x < d; ++x) dot += bf16_to_f64(qg[x]) * bf16_to_f64(L[j * d + x]);
+        for (int x = 0; x < d; ++x) dot += bf16_to_f64(qg[x]) * kv_get(p, landmarks, L0 + j * d + x);
         P[g * n_c + j] = (double)(float)(dot * scale); /* the chunk logit, kept in fp32 (see above) */
         if (P[g * n_c + j] > mx) mx = P[g * n_c + j];
       }
@@ -315,8 +373,8 @@ int oracle_decode_step(const oracle_params *p, const uint16_t *q,
     int64_t row = 0;
     for (int64_t i = 0; i < (int64_t)o * c; ++i, ++row)
       for (int x = 0; x < d; ++x) {
-        Kt[row * d + x] = bf16_to_f64(k_outlier[(u * o * c + i) * d + x]);
-        Vt[row * d + x] = bf16_to_f64(v_outlier[(u * o * c + i) * d + x]);
+        Kt[row * d + x] = kv_get(p, k_outlier, (u * o * c + i) * d + x);
+        Vt[row * d + x] = kv_get(p, v_outlier, (u * o * c + i) * d + x);
       }
     const double pos0 = pos_offset ? (double)pos_offset[bi] : 0.0;
     for (int i = 0; i < k; ++i) {
@@ -324,24 +382,24 @@ int oracle_decode_step(const oracle_params *p, const uint16_t *q,
       if (chunk_ids) chunk_ids[u * k + i] = (int32_t)ch;
       for (int t = 0; t < c; ++t, ++row) {
         const int64_t n = ch * c + t; /* token index inside the context */
-        const uint16_t *Arow = A + (bi * cap + n) * r;
+        const int64_t Arow = (bi * cap + n) * r; /* first element of the token's row of A */
         for (int x = 0; x < d; ++x) {
           double acc = 0.0;
           for (int rho = 0; rho < r; ++rho)
-            acc += bf16_to_f64(Arow[rho]) * bf16_to_f64(B[((u * r) + rho) * d + x]);
+            acc += kv_get(p, A, Arow + rho) * kv_get(p, B, ((u * r) + rho) * d + x);
           Kt[row * d + x] = acc;
         }
         rope_inplace(p, Kt + row * d, pos0 + (double)n);
         if (k_sparse_out)
           memcpy(k_sparse_out + ((u * k + i) * c + t) * d, Kt + row * d, sizeof(double) * d);
         for (int x = 0; x < d; ++x)
-          Vt[row * d + x] = bf16_to_f64(value_store[(u * cap + n) * d + x]);
+          Vt[row * d + x] = kv_get(p, value_store, (u * cap + n) * d + x);
       }
     }
     for (int64_t i = 0; i < w; ++i, ++row)
       for (int x = 0; x < d; ++x) {
-        Kt[row * d + x] = bf16_to_f64(k_local[(u * w + i) * d + x]);
-        Vt[row * d + x] = bf16_to_f64(v_local[(u * w + i) * d + x]);
+        Kt[row * d + x] = kv_get(p, k_local, (u * w + i) * d + x);
+        Vt[row * d + x] = kv_get(p, v_local, (u * w + i) * d + x);
       }
 
     /* standard softmax attention of each query head of the group over K, V */
@@ -458,10 +516,10 @@ int oracle_cache_update(int64_t units, int k, int S, const int32_t *sel_ids,
  * in/out (laid out for cap tokens, valid up to s before / s + c after):
  * A, landmarks, landmark_chunk_ids, value_store.  Needs s + c <= cap.
  * The caller then continues with ctx_len = s + c.                          */
-int oracle_append_chunk(const oracle_params *p, const uint16_t *k_pre,
-                        const uint16_t *k_rope, const uint16_t *v,
-                        const uint16_t *B, uint16_t *A, uint16_t *landmarks,
-                        int32_t *landmark_chunk_ids, uint16_t *value_store) {
+int oracle_append_chunk(const oracle_params *p, const void *k_pre,
+                        const void *k_rope, const void *v,
+                        const void *B, void *A, void *landmarks,
+                        int32_t *landmark_chunk_ids, void *value_store) {
   const int d = p->head_dim, c = p->chunk_size, r = p->rank, o = p->n_outlier_chunks;
   const int hkv = p->n_kv_heads;
   const int64_t s = p->ctx_len, cap = capacity_of(p);
@@ -474,18 +532,18 @@ int oracle_append_chunk(const oracle_params *p, const uint16_t *k_pre,
         double acc = 0.0;
         for (int h = 0; h < hkv; ++h)
           for (int x = 0; x < d; ++x)
-            acc += bf16_to_f64(k_pre[((bi * c + t) * hkv + h) * d + x]) *
-                   bf16_to_f64(B[(((bi * hkv + h) * r) + rho) * d + x]);
-        A[(bi * cap + s + t) * r + rho] = oracle_f64_to_bf16(acc);
+            acc += kv_get(p, k_pre, ((bi * c + t) * hkv + h) * d + x) *
+                   kv_get(p, B, (((bi * hkv + h) * r) + rho) * d + x);
+        kv_put(p, A, (bi * cap + s + t) * r + rho, acc);
       }
   for (int64_t u = 0; u < (int64_t)p->batch * hkv; ++u) {
     for (int x = 0; x < d; ++x) {                /* landmark = mean of the chunk */
       double acc = 0.0;
-      for (int t = 0; t < c; ++t) acc += bf16_to_f64(k_rope[(u * c + t) * d + x]);
-      landmarks[(u * nc_cap + n_c) * d + x] = oracle_f64_to_bf16(acc / (double)c);
+      for (int t = 0; t < c; ++t) acc += kv_get(p, k_rope, (u * c + t) * d + x);
+      kv_put(p, landmarks, (u * nc_cap + n_c) * d + x, acc / (double)c);
     }
     landmark_chunk_ids[u * nc_cap + n_c] = (int32_t)n_ch;
-    memcpy(value_store + (u * cap + s) * d, v + u * c * d, sizeof(uint16_t) * c * d);
+    kv_copy(p, value_store, (u * cap + s) * d, v, u * c * d, (int64_t)c * d);
   }
   return 0;
 }

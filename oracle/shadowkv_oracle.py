@@ -2,7 +2,8 @@
 
 Builds ``shadowkv_oracle.c`` with gcc (``-O2 -fopenmp``, no intrinsics) into
 ``liboracle_shadowkv.so`` beside it and exposes the two operations as numpy
-functions.  bf16 tensors travel as ``uint16`` arrays holding the raw bits.
+functions.  bf16 tensors travel as ``uint16`` arrays holding the raw bits, FP8 (E5M2) tensors of the
+KV cache (``OracleParams.kv_dtype = 1``) as ``uint8`` arrays.
 
 Only tests, the smoke check and the benchmark's ``cpu_baseline`` leg may import
 this module; the GPU library never does.
@@ -44,7 +45,7 @@ class _Params(C.Structure):
         ("head_dim", C.c_int32), ("ctx_len", C.c_int32), ("chunk_size", C.c_int32),
         ("rank", C.c_int32), ("n_outlier_chunks", C.c_int32), ("topk_chunks", C.c_int32),
         ("local_len", C.c_int32), ("rope_theta", C.c_double), ("inv_freq", C.c_void_p),
-        ("softmax_scale", C.c_double), ("ctx_capacity", C.c_int32),
+        ("softmax_scale", C.c_double), ("ctx_capacity", C.c_int32), ("kv_dtype", C.c_int32),
     ]
 
 
@@ -64,6 +65,11 @@ class OracleParams:
     inv_freq: Optional[np.ndarray] = None  # float32 [head_dim/2]
     softmax_scale: float = 0.0
     ctx_capacity: int = 0  # tokens the context arrays are laid out for (0 => ctx_len)
+    kv_dtype: int = 0      # storage of the KV-cache tensors: 0 = bf16 (uint16 bits), 1 = FP8 E5M2 (uint8 bits)
+
+    @property
+    def kv_numpy(self):
+        return np.uint8 if self.kv_dtype == 1 else np.uint16
 
     @property
     def n_chunks(self) -> int:
@@ -90,7 +96,7 @@ class OracleParams:
                      self.chunk_size, self.rank, self.n_outlier_chunks, self.topk_chunks,
                      self.local_len, float(self.rope_theta),
                      inv.ctypes.data if inv is not None else None, float(self.softmax_scale),
-                     int(self.ctx_capacity))
+                     int(self.ctx_capacity), int(self.kv_dtype))
         return st, inv  # keep `inv` alive while the struct is in use
 
 
@@ -102,6 +108,10 @@ def _load():
         _lib.oracle_num_threads.restype = C.c_int
         _lib.oracle_f64_to_bf16.restype = C.c_uint16
         _lib.oracle_f64_to_bf16.argtypes = [C.c_double]
+        _lib.oracle_f64_to_e5m2.restype = C.c_uint8
+        _lib.oracle_f64_to_e5m2.argtypes = [C.c_double]
+        _lib.oracle_e5m2_to_f64.restype = C.c_double
+        _lib.oracle_e5m2_to_f64.argtypes = [C.c_uint8]
         _lib.oracle_rope.restype = None
         _lib.oracle_rope.argtypes = [C.c_void_p] * 3 + [C.c_int64, C.c_void_p]
         _lib.oracle_build_landmarks.restype = C.c_int
@@ -119,13 +129,19 @@ def num_threads() -> int:
     return int(_load().oracle_num_threads())
 
 
-def as_bits(x) -> np.ndarray:
-    """bf16 torch tensor (CPU) or uint16 ndarray -> contiguous uint16 ndarray of raw bits."""
+def as_bits(x, kv_dtype: int = 0) -> np.ndarray:
+    """bf16 torch tensor (CPU) or uint16 ndarray -> contiguous uint16 ndarray of raw bits; with
+    ``kv_dtype = 1`` an E5M2 torch tensor, a uint8 torch tensor or a uint8 ndarray -> uint8 ndarray."""
+    want = np.uint8 if kv_dtype == 1 else np.uint16
     if isinstance(x, np.ndarray):
-        assert x.dtype == np.uint16, x.dtype
+        assert x.dtype == want, (x.dtype, want)
         return np.ascontiguousarray(x)
     import torch
-    assert x.dtype == torch.bfloat16 and x.device.type == "cpu"
+    assert x.device.type == "cpu"
+    if kv_dtype == 1:
+        assert x.dtype in (torch.float8_e5m2, torch.uint8), x.dtype
+        return x.contiguous().view(torch.uint8).numpy()
+    assert x.dtype == torch.bfloat16
     return x.contiguous().view(torch.int16).numpy().view(np.uint16)
 
 
@@ -139,6 +155,21 @@ def f64_to_bits(x: np.ndarray) -> np.ndarray:
     lib = _load()
     flat = np.asarray(x, dtype=np.float64).ravel()
     out = np.fromiter((lib.oracle_f64_to_bf16(float(v)) for v in flat), dtype=np.uint16, count=flat.size)
+    return out.reshape(np.shape(x))
+
+
+def e5m2_bits_to_f64(bits: np.ndarray) -> np.ndarray:
+    """Exact widening of E5M2 bytes to float64, elementwise through the C routine's table of 256 values."""
+    lib = _load()
+    table = np.array([lib.oracle_e5m2_to_f64(i) for i in range(256)], dtype=np.float64)
+    return table[np.asarray(bits, dtype=np.uint8)]
+
+
+def f64_to_e5m2_bits(x: np.ndarray) -> np.ndarray:
+    """Single-rounding (nearest-even) fp64 -> E5M2 bytes, elementwise through the C routine."""
+    lib = _load()
+    flat = np.asarray(x, dtype=np.float64).ravel()
+    out = np.fromiter((lib.oracle_f64_to_e5m2(float(v)) for v in flat), dtype=np.uint8, count=flat.size)
     return out.reshape(np.shape(x))
 
 
@@ -164,17 +195,18 @@ def build_landmarks(p: OracleParams, k_rope, v=None, diagnostics: bool = False) 
     lib = _load()
     b, h, s, d, c, o = p.batch, p.n_kv_heads, p.ctx_len, p.head_dim, p.chunk_size, p.n_outlier_chunks
     n_ch, n_c = p.n_chunks, p.landmark_capacity
-    k_rope = as_bits(k_rope)
+    k_rope = as_bits(k_rope, p.kv_dtype)
     assert k_rope.shape == (b, h, s, d), k_rope.shape
     if v is not None:
-        v = as_bits(v)
+        v = as_bits(v, p.kv_dtype)
         assert v.shape == (b, h, p.capacity, d)
+    kvt = p.kv_numpy
     res = {
-        "landmarks": np.zeros((b, h, n_c, d), np.uint16),
+        "landmarks": np.zeros((b, h, n_c, d), kvt),
         "landmark_chunk_ids": np.zeros((b, h, n_c), np.int32),
         "outlier_chunk_ids": np.zeros((b, h, o), np.int32),
-        "k_outlier": np.zeros((b, h, o * c, d), np.uint16),
-        "v_outlier": np.zeros((b, h, o * c, d), np.uint16) if v is not None else None,
+        "k_outlier": np.zeros((b, h, o * c, d), kvt),
+        "v_outlier": np.zeros((b, h, o * c, d), kvt) if v is not None else None,
         "chunk_min_cos": np.zeros((b, h, n_ch), np.float64) if diagnostics else None,
         "chunk_mean": np.zeros((b, h, n_ch, d), np.float64) if diagnostics else None,
     }
@@ -196,10 +228,11 @@ def decode_step(p: OracleParams, q, A, B, landmarks, landmark_chunk_ids, k_outli
     b, hq, h, s, d = p.batch, p.n_q_heads, p.n_kv_heads, p.ctx_len, p.head_dim
     c, r, o, k, w, n_c = p.chunk_size, p.rank, p.n_outlier_chunks, p.topk_chunks, p.local_len, p.n_landmarks
     cap, nc_cap = p.capacity, p.landmark_capacity
-    q, A, B = as_bits(q), as_bits(A), as_bits(B)
-    landmarks, value_store = as_bits(landmarks), as_bits(value_store)
-    k_outlier, v_outlier = as_bits(k_outlier), as_bits(v_outlier)
-    k_local, v_local = as_bits(k_local), as_bits(v_local)
+    t = p.kv_dtype
+    q, A, B = as_bits(q), as_bits(A, t), as_bits(B, t)
+    landmarks, value_store = as_bits(landmarks, t), as_bits(value_store, t)
+    k_outlier, v_outlier = as_bits(k_outlier, t), as_bits(v_outlier, t)
+    k_local, v_local = as_bits(k_local, t), as_bits(v_local, t)
     ids = np.ascontiguousarray(landmark_chunk_ids, dtype=np.int32)
     assert q.shape == (b, hq, d) and A.shape == (b, cap, r) and B.shape == (b, h, r, d)
     assert landmarks.shape == (b, h, nc_cap, d) and ids.shape == (b, h, nc_cap)
@@ -254,16 +287,17 @@ def cache_update(sel_ids: np.ndarray, cache_ids: np.ndarray, stamps: Optional[np
 
 def append_chunk(p: OracleParams, k_pre, k_rope, v, B, A, landmarks, landmark_chunk_ids, value_store) -> None:
     """One more chunk of context from generated tokens (low-rank states K' Psi, landmark, values), written in
-    place into ``A``, ``landmarks``, ``landmark_chunk_ids`` (int32) and ``value_store`` (uint16 ndarrays laid
-    out for ``p.capacity`` tokens).  ``p.ctx_len`` is the length BEFORE the call."""
+    place into ``A``, ``landmarks``, ``landmark_chunk_ids`` (int32) and ``value_store`` (uint16 ndarrays, uint8
+    with E5M2 storage, laid out for ``p.capacity`` tokens).  ``p.ctx_len`` is the length BEFORE the call."""
     lib = _load()
     b, h, d, c, r = p.batch, p.n_kv_heads, p.head_dim, p.chunk_size, p.rank
     cap, nc_cap = p.capacity, p.landmark_capacity
-    k_pre, k_rope, v, B = as_bits(k_pre), as_bits(k_rope), as_bits(v), as_bits(B)
+    t, kvt = p.kv_dtype, p.kv_numpy
+    k_pre, k_rope, v, B = as_bits(k_pre, t), as_bits(k_rope, t), as_bits(v, t), as_bits(B, t)
     assert k_pre.shape == (b, c, h * d) and k_rope.shape == (b, h, c, d) and v.shape == (b, h, c, d)
     assert B.shape == (b, h, r, d)
-    for arr, shape, dt in ((A, (b, cap, r), np.uint16), (landmarks, (b, h, nc_cap, d), np.uint16),
-                           (landmark_chunk_ids, (b, h, nc_cap), np.int32), (value_store, (b, h, cap, d), np.uint16)):
+    for arr, shape, dt in ((A, (b, cap, r), kvt), (landmarks, (b, h, nc_cap, d), kvt),
+                           (landmark_chunk_ids, (b, h, nc_cap), np.int32), (value_store, (b, h, cap, d), kvt)):
         assert isinstance(arr, np.ndarray) and arr.dtype == dt and arr.shape == shape and arr.flags.c_contiguous
     st, keep = p._c()
     rc = lib.oracle_append_chunk(C.addressof(st), _ptr(k_pre), _ptr(k_rope), _ptr(v), _ptr(B), _ptr(A),
