@@ -26,7 +26,9 @@
  * Conventions for every pointer argument:
  *   - "dev"  = device (HBM) memory, "dev|pinned" = HBM or device-readable
  *     pinned host memory.  All tensors are dense, row-major in the layout
- *     written next to them, 16-byte aligned.  bf16 = raw 16-bit patterns.
+ *     written next to them, 16-byte aligned.  bf16 = raw 16-bit patterns;
+ *     where a tensor is marked bf16 below and belongs to the KV cache it is
+ *     E5M2 bytes instead when params->kv_dtype says so (see shadowkv_kv).
  *   - The caller owns every buffer (workspace included) and both streams.
  *     The library allocates no device memory; it keeps two HIP events per
  *     device for the side-stream fork/join, released by shadowkv_shutdown().
@@ -60,6 +62,18 @@ extern "C" {
 #define SHADOWKV_FLAG_KEEP_REBUILT_KEYS 2u /* also write RoPE(Gather(A,I) B) to the workspace (tests) */
 
 typedef uint16_t shadowkv_bf16;
+/* Element of a KV-cache tensor (A, B, landmarks, outlier / recent K,V, value store, value cache, and the keys
+ * and values handed to build_landmarks / append_chunk): bf16 (2 bytes) or FP8 E5M2 (1 byte), chosen for all of
+ * them at once by params->kv_dtype.  Written "kv" next to the arguments below.  The query and the attention
+ * output are activations and are always bf16. */
+typedef void shadowkv_kv;
+
+#define SHADOWKV_KV_BF16 0
+#define SHADOWKV_KV_FP8_E5M2 1   /* section "Precision Sensitivity": sign, 5 exponent bits (bias 15), 2 fraction bits,
+                                    subnormals / infinities / NaNs as in IEEE 754 (the upper byte of a half).  Stored
+                                    elements are widened exactly; the arithmetic is the bf16 mode's; what the library
+                                    stores itself (landmarks, low-rank states of appended tokens) is rounded once, to
+                                    nearest-even, from the fp64 value, overflow to infinity. */
 
 typedef struct shadowkv_params {
   int32_t batch;            /* b  >= 1 */
@@ -79,6 +93,7 @@ typedef struct shadowkv_params {
   const float *inv_freq;    /* optional dev [d/2]: replaces theta^(-2i/d) (scaled-RoPE models) */
   int32_t ctx_capacity;     /* cap: tokens the context arrays are laid out for; 0 => ctx_len.  Multiple of
                                chunk_size, >= ctx_len.  Room for shadowkv_append_chunk to grow the context. */
+  int32_t kv_dtype;         /* SHADOWKV_KV_BF16 | SHADOWKV_KV_FP8_E5M2: storage type of every "kv" tensor */
 } shadowkv_params;
 
 /*
@@ -108,10 +123,10 @@ typedef struct shadowkv_params {
  *   workspace           dev        >= shadowkv_build_workspace_bytes(), 256-byte aligned
  * The fields rank, topk_chunks, local_len of params are ignored here.
  */
-int shadowkv_build_landmarks(const shadowkv_params *params, const shadowkv_bf16 *k_rope,
-                             const shadowkv_bf16 *v, shadowkv_bf16 *landmarks,
+int shadowkv_build_landmarks(const shadowkv_params *params, const shadowkv_kv *k_rope,
+                             const shadowkv_kv *v, shadowkv_kv *landmarks,
                              int32_t *landmark_chunk_ids, int32_t *outlier_chunk_ids,
-                             shadowkv_bf16 *k_outlier, shadowkv_bf16 *v_outlier, void *workspace,
+                             shadowkv_kv *k_outlier, shadowkv_kv *v_outlier, void *workspace,
                              size_t workspace_bytes, void *stream);
 
 /*
@@ -138,11 +153,11 @@ int shadowkv_build_landmarks(const shadowkv_params *params, const shadowkv_bf16 
  * fp32; normaliser and comparison are fp64; ties go to the lower slot.
  */
 int shadowkv_decode_step(const shadowkv_params *params, const shadowkv_bf16 *q,
-                         const shadowkv_bf16 *A, const shadowkv_bf16 *B,
-                         const shadowkv_bf16 *landmarks, const int32_t *landmark_chunk_ids,
-                         const shadowkv_bf16 *k_outlier, const shadowkv_bf16 *v_outlier,
-                         const shadowkv_bf16 *k_local, const shadowkv_bf16 *v_local,
-                         const shadowkv_bf16 *value_store, const int32_t *pos_offset,
+                         const shadowkv_kv *A, const shadowkv_kv *B,
+                         const shadowkv_kv *landmarks, const int32_t *landmark_chunk_ids,
+                         const shadowkv_kv *k_outlier, const shadowkv_kv *v_outlier,
+                         const shadowkv_kv *k_local, const shadowkv_kv *v_local,
+                         const shadowkv_kv *value_store, const int32_t *pos_offset,
                          shadowkv_bf16 *out, int32_t *out_chunk_ids, void *workspace,
                          size_t workspace_bytes, void *stream, void *side_stream);
 
@@ -172,12 +187,12 @@ int shadowkv_decode_step(const shadowkv_params *params, const shadowkv_bf16 *q,
  * owns the buffers and keeps them between steps; the library keeps no pointer to them.
  */
 int shadowkv_decode_step_cached(const shadowkv_params *params, const shadowkv_bf16 *q,
-                                const shadowkv_bf16 *A, const shadowkv_bf16 *B,
-                                const shadowkv_bf16 *landmarks, const int32_t *landmark_chunk_ids,
-                                const shadowkv_bf16 *k_outlier, const shadowkv_bf16 *v_outlier,
-                                const shadowkv_bf16 *k_local, const shadowkv_bf16 *v_local,
-                                const shadowkv_bf16 *value_store, const int32_t *pos_offset,
-                                int32_t cache_slots, shadowkv_bf16 *value_cache,
+                                const shadowkv_kv *A, const shadowkv_kv *B,
+                                const shadowkv_kv *landmarks, const int32_t *landmark_chunk_ids,
+                                const shadowkv_kv *k_outlier, const shadowkv_kv *v_outlier,
+                                const shadowkv_kv *k_local, const shadowkv_kv *v_local,
+                                const shadowkv_kv *value_store, const int32_t *pos_offset,
+                                int32_t cache_slots, shadowkv_kv *value_cache,
                                 int32_t *cache_chunk_ids, int32_t *cache_stamps,
                                 int32_t *out_miss_count, shadowkv_bf16 *out, int32_t *out_chunk_ids,
                                 void *workspace, size_t workspace_bytes, void *stream,
@@ -202,10 +217,10 @@ int shadowkv_decode_step_cached(const shadowkv_params *params, const shadowkv_bf
  * BEFORE the call; the caller continues with ctx_len + chunk_size.  The fields topk_chunks and local_len
  * are ignored.  A value cache (shadowkv_decode_step_cached) stays valid: existing chunks do not change.
  */
-int shadowkv_append_chunk(const shadowkv_params *params, const shadowkv_bf16 *k_pre,
-                          const shadowkv_bf16 *k_rope, const shadowkv_bf16 *v, const shadowkv_bf16 *B,
-                          shadowkv_bf16 *A, shadowkv_bf16 *landmarks, int32_t *landmark_chunk_ids,
-                          shadowkv_bf16 *value_store, void *stream);
+int shadowkv_append_chunk(const shadowkv_params *params, const shadowkv_kv *k_pre,
+                          const shadowkv_kv *k_rope, const shadowkv_kv *v, const shadowkv_kv *B,
+                          shadowkv_kv *A, shadowkv_kv *landmarks, int32_t *landmark_chunk_ids,
+                          shadowkv_kv *value_store, void *stream);
 
 /* Bytes of `value_cache` for the given shape and slot count (0 if either is invalid). */
 size_t shadowkv_value_cache_bytes(const shadowkv_params *params, int32_t cache_slots);

@@ -24,17 +24,47 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
-def build_library(verbose: bool = True) -> str:
-    cmd = [HIPCC] + FLAGS + ["-I", os.path.join(_HERE, "..", "include"), "-o", LIB] + sources()
+def _filter(text: str) -> str:
+    noise = "is not a recognized feature for this target"
+    return "\n".join(l for l in text.splitlines() if noise not in l)
+
+
+def build_library(verbose: bool = True, jobs: int = 0) -> str:
+    """Compile every csrc/*.hip to an object (in parallel, ``jobs`` at a time; default: one per source, at most
+    8) under ``_build/`` and link them into libshadowkv.so."""
+    from concurrent.futures import ThreadPoolExecutor
+    srcs = sources()
+    obj_dir = os.path.join(_HERE, "_build")
+    os.makedirs(obj_dir, exist_ok=True)
+    inc = ["-I", os.path.join(_HERE, "..", "include")]
+    cflags = [f for f in FLAGS if f != "-shared"]
+
+    def compile_one(src):
+        obj = os.path.join(obj_dir, os.path.basename(src)[:-4] + ".o")
+        cmd = [HIPCC] + cflags + inc + ["-c", src, "-o", obj]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        return obj, res.returncode, _filter(res.stdout)
+
+    with ThreadPoolExecutor(max_workers=jobs or min(8, len(srcs))) as pool:
+        results = list(pool.map(compile_one, srcs))
+    failed = False
+    for obj, rc, out in results:
+        if out.strip() and (verbose or rc):
+            print(out)
+        failed |= rc != 0
+    if failed:
+        raise RuntimeError("hipcc failed")
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + [r[0] for r in results]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    noise = "is not a recognized feature for this target"
-    out = "\n".join(l for l in res.stdout.splitlines() if noise not in l)
+    out = _filter(res.stdout)
     if out.strip() and (verbose or res.returncode):
         print(out)
     if res.returncode:
-        raise RuntimeError("hipcc failed")
+        raise RuntimeError("hipcc link failed")
     return LIB
 
 

@@ -31,6 +31,45 @@ __device__ __forceinline__ bf16_t f64_to_bf16(double x) {
   return f32_to_bf16(f);
 }
 
+// ---- FP8 E5M2 storage of the KV cache (section "Precision Sensitivity") --------------------
+// One byte per element: sign, 5 exponent bits (bias 15), 2 fraction bits, subnormals, infinities and
+// NaNs as in IEEE 754 -- the upper byte of a half.  Widening is exact; the conversion unit takes two
+// bytes of a 32-bit word at a time (v_cvt_pk_f32_bf8; checked on the chip against the format's
+// definition for all 256 codes).
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void e5m2x4_to_f32(uint32_t w, float* x) {
+  const f32x2_t lo = __builtin_amdgcn_cvt_pk_f32_bf8((int)w, false);
+  const f32x2_t hi = __builtin_amdgcn_cvt_pk_f32_bf8((int)w, true);
+  x[0] = lo[0]; x[1] = lo[1]; x[2] = hi[0]; x[3] = hi[1];
+}
+__device__ __forceinline__ float e5m2_to_f32(uint8_t v) { return __builtin_amdgcn_cvt_f32_bf8((int)v, 0); }
+// two E5M2 values (bytes 2*PAIR and 2*PAIR+1 of w) as a pair of bf16 bit patterns: every E5M2 value is
+// exact in bf16, so the upper halves of the fp32 patterns are the answer
+template <int PAIR>
+__device__ __forceinline__ uint32_t e5m2x2_to_bf16x2(uint32_t w) {
+  const f32x2_t f = __builtin_amdgcn_cvt_pk_f32_bf8((int)w, PAIR != 0);
+  return (__float_as_uint(f[0]) >> 16) | (__float_as_uint(f[1]) & 0xffff0000u);
+}
+
+// fp64 -> E5M2 with a single rounding (nearest, ties to even; beyond the largest finite value 57344
+// the result is infinity, as in IEEE 754): fp64 -> fp32 by truncation with a sticky last bit, then
+// the fp32 is rounded at its 21st fraction bit, in integer arithmetic so that a carry moves into the
+// exponent by itself; below 2^-14 the codes are equally spaced (2^-16).
+__device__ __forceinline__ uint8_t f64_to_e5m2(double x) {
+  float f = __double2float_rz(x);
+  if ((double)f != x) f = __uint_as_float(__float_as_uint(f) | 1u);
+  const uint32_t u = __float_as_uint(f);
+  const uint32_t sign = (u >> 24) & 0x80u, a = u & 0x7fffffffu;
+  if (a > 0x7f800000u) return (uint8_t)(sign | 0x7fu);
+  if (a >= 0x38800000u) {  // |f| >= 2^-14: a normal E5M2 number, or overflow
+    const uint32_t r = (a + 0xfffffu + ((a >> 21) & 1u)) >> 21;  // 8 exponent bits | 2 fraction bits
+    const int e = (int)(r >> 2) - 127 + 15;
+    if (e >= 31) return (uint8_t)(sign | 0x7cu);
+    return (uint8_t)(sign | ((uint32_t)e << 2) | (r & 3u));
+  }
+  return (uint8_t)(sign | (uint32_t)rintf(__uint_as_float(a) * 65536.0f));  // 0..4; 4 is the smallest normal
+}
+
 // ---- order-preserving key of a double (larger value <=> larger key, never 0 for
 // finite or infinite inputs).  -0.0 is folded onto +0.0 first.
 __device__ __forceinline__ uint64_t f64_key(double x) {
@@ -98,6 +137,84 @@ __device__ __forceinline__ void load_bf16_row(const bf16_t* __restrict__ p, floa
     uint2 w = *reinterpret_cast<const uint2*>(p);
     x[0] = bf16_lo(w.x); x[1] = bf16_hi(w.x); x[2] = bf16_lo(w.y); x[3] = bf16_hi(w.y);
   }
+}
+
+// 32-bit words that hold EPL consecutive elements of EB bytes
+template <int EPL, int EB>
+struct RawWords { static constexpr int n = (EPL * EB + 3) / 4; };
+
+// EPL consecutive stored elements (EPL in {4, 6, 8}) as fp32
+template <int EPL, int EB>
+__device__ __forceinline__ void unpack_kv(const uint32_t (&w)[RawWords<EPL, EB>::n], float (&x)[EPL]) {
+  if constexpr (EB == 2) {
+#pragma unroll
+    for (int i = 0; i < EPL / 2; ++i) { x[2 * i] = bf16_lo(w[i]); x[2 * i + 1] = bf16_hi(w[i]); }
+  } else {
+    e5m2x4_to_f32(w[0], x);
+    if constexpr (EPL == 8) e5m2x4_to_f32(w[1], x + 4);
+    if constexpr (EPL == 6) {
+      const f32x2_t t = __builtin_amdgcn_cvt_pk_f32_bf8((int)w[1], false);
+      x[4] = t[0]; x[5] = t[1];
+    }
+  }
+}
+// p: address of the first of the EPL elements (EPL * EB bytes apart from lane to lane)
+template <int EPL, int EB>
+__device__ __forceinline__ void load_raw(const uint8_t* __restrict__ p, uint32_t (&w)[RawWords<EPL, EB>::n]) {
+  if constexpr (EPL * EB == 16) {
+    const uint4 v = *reinterpret_cast<const uint4*>(p);
+    w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
+  } else if constexpr (EPL * EB == 12) {
+    const uint32_t* q = reinterpret_cast<const uint32_t*>(p);
+    w[0] = q[0]; w[1] = q[1]; w[2] = q[2];
+  } else if constexpr (EPL * EB == 8) {
+    const uint2 v = *reinterpret_cast<const uint2*>(p);
+    w[0] = v.x; w[1] = v.y;
+  } else if constexpr (EPL * EB == 6) {   // 2-byte aligned only
+    const uint16_t* q = reinterpret_cast<const uint16_t*>(p);
+    w[0] = (uint32_t)q[0] | ((uint32_t)q[1] << 16); w[1] = q[2];
+  } else {
+    w[0] = *reinterpret_cast<const uint32_t*>(p);
+  }
+}
+// Raw words of EPL stored elements back to memory (same alignment rules as load_raw).
+template <int EPL, int EB>
+__device__ __forceinline__ void store_raw(uint8_t* __restrict__ p, const uint32_t (&w)[RawWords<EPL, EB>::n]) {
+  if constexpr (EPL * EB == 16) {
+    *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
+  } else if constexpr (EPL * EB == 12) {
+    uint32_t* q = reinterpret_cast<uint32_t*>(p);
+    q[0] = w[0]; q[1] = w[1]; q[2] = w[2];
+  } else if constexpr (EPL * EB == 8) {
+    *reinterpret_cast<uint2*>(p) = make_uint2(w[0], w[1]);
+  } else if constexpr (EPL * EB == 6) {
+    uint16_t* q = reinterpret_cast<uint16_t*>(p);
+    q[0] = (uint16_t)w[0]; q[1] = (uint16_t)(w[0] >> 16); q[2] = (uint16_t)w[1];
+  } else {
+    *reinterpret_cast<uint32_t*>(p) = w[0];
+  }
+}
+// EPL fp64 values rounded once to the storage type, packed as raw words
+template <int EPL, int EB>
+__device__ __forceinline__ void pack_kv(const double (&x)[EPL], uint32_t (&w)[RawWords<EPL, EB>::n]) {
+#pragma unroll
+  for (int i = 0; i < RawWords<EPL, EB>::n; ++i) w[i] = 0u;
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) {
+    if constexpr (EB == 2) w[e / 2] |= (uint32_t)f64_to_bf16(x[e]) << (16 * (e & 1));
+    else w[e / 4] |= (uint32_t)f64_to_e5m2(x[e]) << (8 * (e & 3));
+  }
+}
+// one stored element as fp32 / one fp64 value rounded once into its place
+template <int EB>
+__device__ __forceinline__ float kv_elem(const void* base, size_t i) {
+  if constexpr (EB == 2) return bf16_to_f32(static_cast<const bf16_t*>(base)[i]);
+  else return e5m2_to_f32(static_cast<const uint8_t*>(base)[i]);
+}
+template <int EB>
+__device__ __forceinline__ void kv_store_elem(void* base, size_t i, double x) {
+  if constexpr (EB == 2) static_cast<bf16_t*>(base)[i] = f64_to_bf16(x);
+  else static_cast<uint8_t*>(base)[i] = f64_to_e5m2(x);
 }
 
 // Store ELEMS consecutive bf16 given as fp32 (round to nearest even).

@@ -20,7 +20,8 @@ struct RopeFreqs {
 // logits [b*h_q, n_c] fp32 (exact dot product rounded once); partials [b*h_q, n_tiles] (max, sum exp(p - max))
 // per tile, fp64.
 // landmarks [units, nc_stride, d]: n_c valid rows per unit.
-hipError_t launch_score(const bf16_t* q, const bf16_t* landmarks, float* logits, double2* partials,
+// kv_bytes (here and below): bytes per element of the KV-cache tensors, 2 = bf16, 1 = FP8 E5M2.
+hipError_t launch_score(const bf16_t* q, const void* landmarks, int kv_bytes, float* logits, double2* partials,
                         int batch, int hq, int hkv, int d, int n_c, int nc_stride, double scale, hipStream_t st);
 
 // ---- ArgTopK -------------------------------------------------------------------
@@ -54,8 +55,8 @@ hipError_t launch_select(const SelectArgs& a, const SelectPlan& plan, int src, i
 
 // ---- value chunk gather (V_sparse = Gather(V_store, I)) -----------------------------
 // store [units, s_cap, d] of which s tokens are valid
-hipError_t launch_gather_values(const bf16_t* store, const int32_t* sel_ids, bf16_t* v_sparse, int units, int d,
-                                int s, int s_cap, int c, int k, hipStream_t st);
+hipError_t launch_gather_values(const void* store, const int32_t* sel_ids, void* v_sparse, int kv_bytes, int units,
+                                int d, int s, int s_cap, int c, int k, hipStream_t st);
 
 // ---- chunk cache of the offloaded values: index scan, fetch of the missing chunks ------
 constexpr int kMaxCacheSlots = 8192;  // slots per unit the index-scan kernel handles (256 threads x 32, LDS)
@@ -63,9 +64,9 @@ constexpr int kMaxCacheSlots = 8192;  // slots per unit the index-scan kernel ha
 hipError_t launch_cache_update(const int32_t* sel_ids, int32_t* cache_ids, int32_t* stamps, int32_t* sel_slots,
                                int32_t* miss_slots, int32_t* n_miss, int32_t* n_miss_copy, int units, int k, int S,
                                hipStream_t st);
-hipError_t launch_gather_missing(const bf16_t* store, const int32_t* cache_ids, const int32_t* miss_slots,
-                                 const int32_t* n_miss, bf16_t* v_cache, int units, int d, int s, int s_cap, int c,
-                                 int k, int S, hipStream_t st);
+hipError_t launch_gather_missing(const void* store, const int32_t* cache_ids, const int32_t* miss_slots,
+                                 const int32_t* n_miss, void* v_cache, int kv_bytes, int units, int d, int s, int s_cap,
+                                 int c, int k, int S, hipStream_t st);
 hipError_t launch_fill_i32(int32_t* p, size_t n, int32_t value, hipStream_t st);
 
 // ---- attention over [outliers ; recent] and [selected chunks], keys rebuilt in-kernel ----
@@ -74,16 +75,17 @@ hipError_t launch_fill_i32(int32_t* p, size_t n, int32_t value, hipStream_t st);
 // [i*res_split_len, ...); a combine kernel merges the splits into `out`.
 struct AttnArgs {
   const bf16_t* q;          // [b, h_q, d]
-  const bf16_t* A;          // [b, s_cap, r]
-  const bf16_t* B;          // [units, r, d]
-  const bf16_t* k_outlier;  // [units, o*c, d]
-  const bf16_t* v_outlier;
-  const bf16_t* k_local;    // [units, w, d]
-  const bf16_t* v_local;
-  const bf16_t* v_sparse;   // staged [units, v_unit_rows, d], or NULL: read v_store through sel_ids
+  int kv_bytes;             // storage of the tensors below that are void*: 2 = bf16, 1 = FP8 E5M2
+  const void* A;            // [b, s_cap, r]
+  const void* B;            // [units, r, d]
+  const void* k_outlier;    // [units, o*c, d]
+  const void* v_outlier;
+  const void* k_local;      // [units, w, d]
+  const void* v_local;
+  const void* v_sparse;     // staged [units, v_unit_rows, d], or NULL: read v_store through sel_ids
   const int32_t* v_slots;   // optional [units, k]: chunk slot of selected chunk i inside v_sparse (NULL: slot i)
   int v_unit_rows;          // rows per unit of v_sparse (k*c, or slots*c of a value cache)
-  const bf16_t* v_store;    // [units, s_cap, d] (HBM, or device-readable pinned host memory)
+  const void* v_store;      // [units, s_cap, d] (HBM, or device-readable pinned host memory)
   const int32_t* sel_ids;   // [units, k] true chunk ids
   const int32_t* pos_offset;  // [b] or NULL
   const float* inv_freq_dev;  // optional [d/2]
@@ -107,18 +109,18 @@ hipError_t launch_attention_keys(const AttnArgs& a, hipStream_t st);    // two-p
 hipError_t launch_attention_values(const AttnArgs& a, hipStream_t st);  // two-phase path, after
 
 // ---- pre-filling algorithm: chunk means, min cosine, compaction, outlier gather -------
-hipError_t launch_chunk_stats(const bf16_t* k_rope, bf16_t* chunk_mean, double* chunk_min_cos, int units, int d,
+hipError_t launch_chunk_stats(const void* k_rope, int kv_bytes, void* chunk_mean, double* chunk_min_cos, int units, int d,
                               int s, int c, hipStream_t st);
-hipError_t launch_compact_landmarks(const bf16_t* chunk_mean, const int32_t* outlier_ids, bf16_t* landmarks,
+hipError_t launch_compact_landmarks(const void* chunk_mean, int kv_bytes, const int32_t* outlier_ids, void* landmarks,
                                     int32_t* landmark_chunk_ids, int units, int d, int n_ch, int o, int nc_stride,
                                     hipStream_t st);
-hipError_t launch_gather_outliers(const bf16_t* k_rope, const bf16_t* v, const int32_t* outlier_ids,
-                                  bf16_t* k_outlier, bf16_t* v_outlier, int units, int d, int s, int s_cap, int c,
+hipError_t launch_gather_outliers(const void* k_rope, const void* v, int kv_bytes, const int32_t* outlier_ids,
+                                  void* k_outlier, void* v_outlier, int units, int d, int s, int s_cap, int c,
                                   int o, hipStream_t st);
 
 // ---- generated tokens: one more chunk of context (low-rank states K' Psi, landmark, values) ----
-hipError_t launch_append_chunk(const bf16_t* k_pre, const bf16_t* k_rope, const bf16_t* v, const bf16_t* B, bf16_t* A,
-                               bf16_t* landmarks, int32_t* landmark_chunk_ids, bf16_t* value_store, int batch, int hkv,
-                               int d, int s, int s_cap, int c, int r, int o, hipStream_t st);
+hipError_t launch_append_chunk(const void* k_pre, const void* k_rope, const void* v, const void* B, void* A,
+                               void* landmarks, int32_t* landmark_chunk_ids, void* value_store, int kv_bytes, int batch,
+                               int hkv, int d, int s, int s_cap, int c, int r, int o, hipStream_t st);
 
 }  // namespace skv

@@ -10,28 +10,32 @@
 namespace skv {
 
 // grid (c, batch), 256 threads: 16 lanes share one rank index, 16 rank indices per pass.
-__global__ __launch_bounds__(256) void append_project_kernel(const bf16_t* __restrict__ k_pre,
-                                                             const bf16_t* __restrict__ B, bf16_t* __restrict__ A,
+// EB: bytes per stored element (2 = bf16, 1 = FP8 E5M2), inputs and outputs alike.
+template <int EB>
+__global__ __launch_bounds__(256) void append_project_kernel(const void* __restrict__ k_pre,
+                                                             const void* __restrict__ B, void* __restrict__ A,
                                                              int hkv, int d, int s, int s_cap, int c, int r) {
   const int t = blockIdx.x, b = blockIdx.y;
   const int sub = threadIdx.x & 15, grp = threadIdx.x >> 4;
-  const bf16_t* kp = k_pre + ((size_t)b * c + t) * hkv * d;
+  const size_t kp = ((size_t)b * c + t) * hkv * d;
   for (int rho0 = 0; rho0 < r; rho0 += 16) {
     const int rho = rho0 + grp;
     double acc = 0.0;
     if (rho < r)
       for (int h = 0; h < hkv; ++h) {
-        const bf16_t* brow = B + (((size_t)b * hkv + h) * r + rho) * d;
-        for (int x = sub; x < d; x += 16) acc = fma((double)bf16_to_f32(kp[h * d + x]), (double)bf16_to_f32(brow[x]), acc);
+        const size_t brow = (((size_t)b * hkv + h) * r + rho) * d;
+        for (int x = sub; x < d; x += 16)
+          acc = fma((double)kv_elem<EB>(k_pre, kp + h * d + x), (double)kv_elem<EB>(B, brow + x), acc);
       }
     acc = sum16_f64(acc);
-    if (rho < r && sub == 0) A[((size_t)b * s_cap + s + t) * r + rho] = f64_to_bf16(acc);
+    if (rho < r && sub == 0) kv_store_elem<EB>(A, ((size_t)b * s_cap + s + t) * r + rho, acc);
   }
 }
 
 // grid (units), 256 threads: landmark row, its chunk id, and the copy of the chunk's values.
-__global__ __launch_bounds__(256) void append_landmark_kernel(const bf16_t* __restrict__ k_rope,
-                                                              const uint4* __restrict__ v, bf16_t* __restrict__ landmarks,
+template <int EB>
+__global__ __launch_bounds__(256) void append_landmark_kernel(const void* __restrict__ k_rope,
+                                                              const uint4* __restrict__ v, void* __restrict__ landmarks,
                                                               int32_t* __restrict__ landmark_chunk_ids,
                                                               uint4* __restrict__ value_store, int d, int s, int s_cap,
                                                               int c, int o) {
@@ -39,25 +43,35 @@ __global__ __launch_bounds__(256) void append_landmark_kernel(const bf16_t* __re
   const int n_ch = s / c, n_c = n_ch - o, nc_stride = s_cap / c - o;
   for (int x = threadIdx.x; x < d; x += 256) {
     double acc = 0.0;
-    for (int t = 0; t < c; ++t) acc += (double)bf16_to_f32(k_rope[((size_t)unit * c + t) * d + x]);
-    landmarks[((size_t)unit * nc_stride + n_c) * d + x] = f64_to_bf16(acc / (double)c);
+    for (int t = 0; t < c; ++t) acc += (double)kv_elem<EB>(k_rope, ((size_t)unit * c + t) * d + x);
+    kv_store_elem<EB>(landmarks, ((size_t)unit * nc_stride + n_c) * d + x, acc / (double)c);
   }
   if (threadIdx.x == 0) landmark_chunk_ids[(size_t)unit * nc_stride + n_c] = n_ch;
-  const int vec = c * d * 2 / 16;
-  uint4* dst = value_store + ((size_t)unit * s_cap + s) * d * 2 / 16;
+  const int vec = c * d * EB / 16;
+  uint4* dst = value_store + ((size_t)unit * s_cap + s) * d * EB / 16;
   for (int i = threadIdx.x; i < vec; i += 256) dst[i] = v[(size_t)unit * vec + i];
 }
 
-hipError_t launch_append_chunk(const bf16_t* k_pre, const bf16_t* k_rope, const bf16_t* v, const bf16_t* B, bf16_t* A,
-                               bf16_t* landmarks, int32_t* landmark_chunk_ids, bf16_t* value_store, int batch, int hkv,
-                               int d, int s, int s_cap, int c, int r, int o, hipStream_t st) {
-  hipLaunchKernelGGL(append_project_kernel, dim3(c, batch), dim3(256), 0, st, k_pre, B, A, hkv, d, s, s_cap, c, r);
+template <int EB>
+static hipError_t launch_append_eb(const void* k_pre, const void* k_rope, const void* v, const void* B, void* A,
+                                   void* landmarks, int32_t* landmark_chunk_ids, void* value_store, int batch, int hkv,
+                                   int d, int s, int s_cap, int c, int r, int o, hipStream_t st) {
+  hipLaunchKernelGGL(append_project_kernel<EB>, dim3(c, batch), dim3(256), 0, st, k_pre, B, A, hkv, d, s, s_cap, c, r);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(append_landmark_kernel, dim3(batch * hkv), dim3(256), 0, st, k_rope,
+  hipLaunchKernelGGL(append_landmark_kernel<EB>, dim3(batch * hkv), dim3(256), 0, st, k_rope,
                      reinterpret_cast<const uint4*>(v), landmarks, landmark_chunk_ids,
                      reinterpret_cast<uint4*>(value_store), d, s, s_cap, c, o);
   return hipGetLastError();
+}
+
+hipError_t launch_append_chunk(const void* k_pre, const void* k_rope, const void* v, const void* B, void* A,
+                               void* landmarks, int32_t* landmark_chunk_ids, void* value_store, int kv_bytes, int batch,
+                               int hkv, int d, int s, int s_cap, int c, int r, int o, hipStream_t st) {
+  return kv_bytes == 1 ? launch_append_eb<1>(k_pre, k_rope, v, B, A, landmarks, landmark_chunk_ids, value_store, batch,
+                                             hkv, d, s, s_cap, c, r, o, st)
+                       : launch_append_eb<2>(k_pre, k_rope, v, B, A, landmarks, landmark_chunk_ids, value_store, batch,
+                                             hkv, d, s, s_cap, c, r, o, st);
 }
 
 }  // namespace skv

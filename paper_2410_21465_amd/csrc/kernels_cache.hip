@@ -186,16 +186,16 @@ hipError_t launch_cache_update(const int32_t* sel_ids, int32_t* cache_ids, int32
 #undef SKV_CU
 }
 
-hipError_t launch_gather_missing(const bf16_t* store, const int32_t* cache_ids, const int32_t* miss_slots,
-                                 const int32_t* n_miss, bf16_t* v_cache, int units, int d, int s, int s_cap, int c,
-                                 int k, int S, hipStream_t st) {
-  const int vec_per_chunk = c * d * 2 / 16;
+hipError_t launch_gather_missing(const void* store, const int32_t* cache_ids, const int32_t* miss_slots,
+                                 const int32_t* n_miss, void* v_cache, int kv_bytes, int units, int d, int s, int s_cap,
+                                 int c, int k, int S, hipStream_t st) {
+  const int vec_per_chunk = c * d * kv_bytes / 16;
   const int total = k * vec_per_chunk;
   int gx = (total + 256 * kMissUnroll - 1) / (256 * kMissUnroll);
   if (gx < 1) gx = 1;
   hipLaunchKernelGGL(gather_missing_kernel, dim3(gx, units), dim3(256), 0, st, reinterpret_cast<const uint4*>(store),
                      cache_ids, miss_slots, n_miss, reinterpret_cast<uint4*>(v_cache), k, S, vec_per_chunk,
-                     (size_t)s_cap * d * 2 / 16, s / c - 1);
+                     (size_t)s_cap * d * kv_bytes / 16, s / c - 1);
   return hipGetLastError();
 }
 

@@ -1,6 +1,6 @@
 // Value chunk gather: V_sparse = Gather(V_store, I) (decoding algorithm, "gather value
 // cache" line).  The store may live in pinned host memory that the GPU reads over PCIe,
-// so the kernel is a zero-copy reader: every chunk is c*d*2 contiguous bytes, lanes take
+// so the kernel is a zero-copy reader: every chunk is c*d*(2 or 1) contiguous bytes, lanes take
 // 16 bytes each, and each thread keeps four independent loads in flight before it
 // stores, which is what keeps a high-latency link busy.  The same kernel serves an HBM
 // store when staging is requested.
@@ -38,15 +38,15 @@ __global__ __launch_bounds__(256) void gather_values_kernel(const uint4* __restr
   }
 }
 
-hipError_t launch_gather_values(const bf16_t* store, const int32_t* sel_ids, bf16_t* v_sparse, int units, int d,
-                                int s, int s_cap, int c, int k, hipStream_t st) {
-  const int vec_per_chunk = c * d * 2 / 16;
+hipError_t launch_gather_values(const void* store, const int32_t* sel_ids, void* v_sparse, int kv_bytes, int units,
+                                int d, int s, int s_cap, int c, int k, hipStream_t st) {
+  const int vec_per_chunk = c * d * kv_bytes / 16;
   const int total = k * vec_per_chunk;
   int gx = (total + 256 * kGatherUnroll - 1) / (256 * kGatherUnroll);
   if (gx < 1) gx = 1;
   dim3 grid(gx, units), block(256);
   hipLaunchKernelGGL(gather_values_kernel, grid, block, 0, st, reinterpret_cast<const uint4*>(store), sel_ids,
-                     reinterpret_cast<uint4*>(v_sparse), k, vec_per_chunk, (size_t)s_cap * d * 2 / 16, s / c - 1);
+                     reinterpret_cast<uint4*>(v_sparse), k, vec_per_chunk, (size_t)s_cap * d * kv_bytes / 16, s / c - 1);
   return hipGetLastError();
 }
 

@@ -62,20 +62,22 @@ __device__ __forceinline__ double reduce_scatter16_f64(const double (&v)[16], in
 }
 
 // REG: the chunk's rows are kept in registers (c <= 8); otherwise they are read twice.
-template <int D, bool REG>
-__global__ __launch_bounds__(256) void chunk_stats_kernel(const bf16_t* __restrict__ k_rope,
-                                                          bf16_t* __restrict__ chunk_mean,
+// EB: bytes per stored element (2 = bf16, 1 = FP8 E5M2); the means are written in the same type.
+template <int D, bool REG, int EB>
+__global__ __launch_bounds__(256) void chunk_stats_kernel(const uint8_t* __restrict__ k_rope,
+                                                          uint8_t* __restrict__ chunk_mean,
                                                           double* __restrict__ chunk_min_cos, int s, int c,
                                                           int n_ch) {
   constexpr int EPL = D / 16;
+  constexpr int RW = RawWords<EPL, EB>::n;
   const int unit = blockIdx.y;
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int sub = lane & 15, cg = lane >> 4;
   const int j = blockIdx.x * 16 + wave * 4 + cg;
   const bool ok = j < n_ch;
-  const bf16_t* base = k_rope + ((size_t)unit * s + (size_t)(ok ? j : 0) * c) * D + sub * EPL;
+  const uint8_t* base = k_rope + (((size_t)unit * s + (size_t)(ok ? j : 0) * c) * D + sub * EPL) * EB;
 
-  uint32_t raw[REG ? 8 : 1][EPL / 2];
+  uint32_t raw[REG ? 8 : 1][RW];
   double mean[EPL];
 #pragma unroll
   for (int e = 0; e < EPL; ++e) mean[e] = 0.0;
@@ -83,29 +85,21 @@ __global__ __launch_bounds__(256) void chunk_stats_kernel(const bf16_t* __restri
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
 #pragma unroll
-      for (int e = 0; e < EPL / 2; ++e) raw[t][e] = 0u;
-      if (t < c) {
-        if constexpr (EPL == 8) {
-          const uint4 w = *reinterpret_cast<const uint4*>(base + (size_t)t * D);
-          raw[t][0] = w.x; raw[t][1] = w.y; raw[t][2] = w.z; raw[t][3] = w.w;
-        } else {
-          const uint32_t* q = reinterpret_cast<const uint32_t*>(base + (size_t)t * D);
-#pragma unroll
-          for (int e = 0; e < EPL / 2; ++e) raw[t][e] = q[e];
-        }
-      }
+      for (int e = 0; e < RW; ++e) raw[t][e] = 0u;   // all-zero bits are 0.0 in either type
+      if (t < c) load_raw<EPL, EB>(base + (size_t)t * D * EB, raw[t]);
     }
 #pragma unroll
-    for (int t = 0; t < 8; ++t)
+    for (int t = 0; t < 8; ++t) {
+      float x[EPL];
+      unpack_kv<EPL, EB>(raw[t], x);
 #pragma unroll
-      for (int e = 0; e < EPL / 2; ++e) {
-        mean[2 * e] += (double)bf16_lo(raw[t][e]);
-        mean[2 * e + 1] += (double)bf16_hi(raw[t][e]);
-      }
+      for (int e = 0; e < EPL; ++e) mean[e] += (double)x[e];
+    }
   } else {
     for (int t = 0; t < c; ++t) {
       float x[EPL];
-      load_bf16_row<EPL>(base + (size_t)t * D, x);
+      load_raw<EPL, EB>(base + (size_t)t * D * EB, raw[0]);
+      unpack_kv<EPL, EB>(raw[0], x);
 #pragma unroll
       for (int e = 0; e < EPL; ++e) mean[e] += (double)x[e];
     }
@@ -127,11 +121,13 @@ __global__ __launch_bounds__(256) void chunk_stats_kernel(const bf16_t* __restri
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
       double dot = 0.0, kn2 = 0.0;
+      float x[EPL];
+      unpack_kv<EPL, EB>(raw[t], x);
 #pragma unroll
-      for (int e = 0; e < EPL / 2; ++e) {
-        const double x0 = (double)bf16_lo(raw[t][e]), x1 = (double)bf16_hi(raw[t][e]);
-        dot = fma(mean[2 * e], x0, dot); dot = fma(mean[2 * e + 1], x1, dot);
-        kn2 = fma(x0, x0, kn2); kn2 = fma(x1, x1, kn2);
+      for (int e = 0; e < EPL; ++e) {
+        const double xd = (double)x[e];
+        dot = fma(mean[e], xd, dot);
+        kn2 = fma(xd, xd, kn2);
       }
       v[t] = dot; v[8 + t] = kn2;
     }
@@ -143,7 +139,8 @@ __global__ __launch_bounds__(256) void chunk_stats_kernel(const bf16_t* __restri
   } else {
     for (int t = 0; t < c; ++t) {
       float x[EPL];
-      load_bf16_row<EPL>(base + (size_t)t * D, x);
+      load_raw<EPL, EB>(base + (size_t)t * D * EB, raw[0]);
+      unpack_kv<EPL, EB>(raw[0], x);
       double dot = 0.0, kn2 = 0.0;
 #pragma unroll
       for (int e = 0; e < EPL; ++e) {
@@ -157,20 +154,19 @@ __global__ __launch_bounds__(256) void chunk_stats_kernel(const bf16_t* __restri
     }
   }
   if (ok) {
-    bf16_t hm[EPL];
-#pragma unroll
-    for (int e = 0; e < EPL; ++e) hm[e] = f64_to_bf16(mean[e]);
-    store_bf16_row<EPL>(chunk_mean + ((size_t)unit * n_ch + j) * D + sub * EPL, hm);
+    uint32_t hm[RW];
+    pack_kv<EPL, EB>(mean, hm);
+    store_raw<EPL, EB>(chunk_mean + (((size_t)unit * n_ch + j) * D + sub * EPL) * EB, hm);
     if (sub == 0) chunk_min_cos[(size_t)unit * n_ch + j] = mn;
   }
 }
 
 // L <- C \ Gather(C, I): landmark slot s -> chunk s + t, t = number of outliers i with id_i - i <= s
 // (ids ascending), found by bisection.  A workgroup copies 128 consecutive slots.
-template <int D>
-__global__ __launch_bounds__(256) void compact_landmarks_kernel(const bf16_t* __restrict__ chunk_mean,
+template <int D, int EB>
+__global__ __launch_bounds__(256) void compact_landmarks_kernel(const uint8_t* __restrict__ chunk_mean,
                                                                 const int32_t* __restrict__ outlier_ids,
-                                                                bf16_t* __restrict__ landmarks,
+                                                                uint8_t* __restrict__ landmarks,
                                                                 int32_t* __restrict__ landmark_chunk_ids, int n_ch,
                                                                 int o, int nc_stride) {
   constexpr int EPL = D / 16;
@@ -189,14 +185,9 @@ __global__ __launch_bounds__(256) void compact_landmarks_kernel(const bf16_t* __
       if (oid[mid] <= slot) lo = mid + 1; else hi = mid;
     }
     const int j = slot + lo;
-    const uint32_t* s32 = reinterpret_cast<const uint32_t*>(chunk_mean + ((size_t)unit * n_ch + j) * D + sub * EPL);
-    uint32_t* d32 = reinterpret_cast<uint32_t*>(landmarks + ((size_t)unit * nc_stride + slot) * D + sub * EPL);
-    if constexpr (EPL == 8) {
-      *reinterpret_cast<uint4*>(d32) = *reinterpret_cast<const uint4*>(s32);
-    } else {
-#pragma unroll
-      for (int e = 0; e < EPL / 2; ++e) d32[e] = s32[e];
-    }
+    uint32_t row[RawWords<EPL, EB>::n];
+    load_raw<EPL, EB>(chunk_mean + (((size_t)unit * n_ch + j) * D + sub * EPL) * EB, row);
+    store_raw<EPL, EB>(landmarks + (((size_t)unit * nc_stride + slot) * D + sub * EPL) * EB, row);
     if (sub == 0) landmark_chunk_ids[(size_t)unit * nc_stride + slot] = j;
   }
 }
@@ -219,49 +210,63 @@ __global__ __launch_bounds__(256) void gather_outliers_kernel(const uint4* __res
   }
 }
 
-hipError_t launch_chunk_stats(const bf16_t* k_rope, bf16_t* chunk_mean, double* chunk_min_cos, int units, int d,
+hipError_t launch_chunk_stats(const void* k_rope, int kv_bytes, void* chunk_mean, double* chunk_min_cos, int units, int d,
                               int s, int c, hipStream_t st) {
   const int n_ch = s / c;
   dim3 grid((n_ch + 15) / 16, units), block(256);
-#define SKV_STATS(D_)                                                                                              \
+  const uint8_t* kr = static_cast<const uint8_t*>(k_rope);
+  uint8_t* cm = static_cast<uint8_t*>(chunk_mean);
+#define SKV_STATS(D_, EB_)                                                                                         \
   do {                                                                                                             \
-    if (c <= 8) hipLaunchKernelGGL((chunk_stats_kernel<D_, true>), grid, block, 0, st, k_rope, chunk_mean, chunk_min_cos, s, c, n_ch); \
-    else hipLaunchKernelGGL((chunk_stats_kernel<D_, false>), grid, block, 0, st, k_rope, chunk_mean, chunk_min_cos, s, c, n_ch);       \
+    if (c <= 8) hipLaunchKernelGGL((chunk_stats_kernel<D_, true, EB_>), grid, block, 0, st, kr, cm, chunk_min_cos, s, c, n_ch); \
+    else hipLaunchKernelGGL((chunk_stats_kernel<D_, false, EB_>), grid, block, 0, st, kr, cm, chunk_min_cos, s, c, n_ch);       \
   } while (0)
-  switch (d) {
-    case 64: SKV_STATS(64); break;
-    case 96: SKV_STATS(96); break;
-    case 128: SKV_STATS(128); break;
+  switch (d * 4 + kv_bytes) {
+    case 64 * 4 + 2: SKV_STATS(64, 2); break;
+    case 96 * 4 + 2: SKV_STATS(96, 2); break;
+    case 128 * 4 + 2: SKV_STATS(128, 2); break;
+    case 64 * 4 + 1: SKV_STATS(64, 1); break;
+    case 96 * 4 + 1: SKV_STATS(96, 1); break;
+    case 128 * 4 + 1: SKV_STATS(128, 1); break;
     default: return hipErrorInvalidValue;
   }
 #undef SKV_STATS
   return hipGetLastError();
 }
 
-hipError_t launch_compact_landmarks(const bf16_t* chunk_mean, const int32_t* outlier_ids, bf16_t* landmarks,
+hipError_t launch_compact_landmarks(const void* chunk_mean, int kv_bytes, const int32_t* outlier_ids, void* landmarks,
                                     int32_t* landmark_chunk_ids, int units, int d, int n_ch, int o, int nc_stride,
                                     hipStream_t st) {
   const int n_c = n_ch - o;
   if (n_c <= 0) return hipSuccess;
   dim3 grid((n_c + 127) / 128, units), block(256);
-  switch (d) {
-    case 64: hipLaunchKernelGGL((compact_landmarks_kernel<64>), grid, block, 0, st, chunk_mean, outlier_ids, landmarks, landmark_chunk_ids, n_ch, o, nc_stride); break;
-    case 96: hipLaunchKernelGGL((compact_landmarks_kernel<96>), grid, block, 0, st, chunk_mean, outlier_ids, landmarks, landmark_chunk_ids, n_ch, o, nc_stride); break;
-    case 128: hipLaunchKernelGGL((compact_landmarks_kernel<128>), grid, block, 0, st, chunk_mean, outlier_ids, landmarks, landmark_chunk_ids, n_ch, o, nc_stride); break;
+  const uint8_t* cm = static_cast<const uint8_t*>(chunk_mean);
+  uint8_t* lm = static_cast<uint8_t*>(landmarks);
+#define SKV_COMPACT(D_, EB_)                                                                                     \
+  hipLaunchKernelGGL((compact_landmarks_kernel<D_, EB_>), grid, block, 0, st, cm, outlier_ids, lm, landmark_chunk_ids, \
+                     n_ch, o, nc_stride)
+  switch (d * 4 + kv_bytes) {
+    case 64 * 4 + 2: SKV_COMPACT(64, 2); break;
+    case 96 * 4 + 2: SKV_COMPACT(96, 2); break;
+    case 128 * 4 + 2: SKV_COMPACT(128, 2); break;
+    case 64 * 4 + 1: SKV_COMPACT(64, 1); break;
+    case 96 * 4 + 1: SKV_COMPACT(96, 1); break;
+    case 128 * 4 + 1: SKV_COMPACT(128, 1); break;
     default: return hipErrorInvalidValue;
   }
+#undef SKV_COMPACT
   return hipGetLastError();
 }
 
-hipError_t launch_gather_outliers(const bf16_t* k_rope, const bf16_t* v, const int32_t* outlier_ids,
-                                  bf16_t* k_outlier, bf16_t* v_outlier, int units, int d, int s, int s_cap, int c,
+hipError_t launch_gather_outliers(const void* k_rope, const void* v, int kv_bytes, const int32_t* outlier_ids,
+                                  void* k_outlier, void* v_outlier, int units, int d, int s, int s_cap, int c,
                                   int o, hipStream_t st) {
   if (o <= 0) return hipSuccess;
   dim3 grid(o, units), block(256);
   hipLaunchKernelGGL(gather_outliers_kernel, grid, block, 0, st, reinterpret_cast<const uint4*>(k_rope),
                      reinterpret_cast<const uint4*>(v), outlier_ids, reinterpret_cast<uint4*>(k_outlier),
-                     reinterpret_cast<uint4*>(v_outlier), o, c * d * 2 / 16, (size_t)s * d * 2 / 16,
-                     (size_t)s_cap * d * 2 / 16);
+                     reinterpret_cast<uint4*>(v_outlier), o, c * d * kv_bytes / 16, (size_t)s * d * kv_bytes / 16,
+                     (size_t)s_cap * d * kv_bytes / 16);
   return hipGetLastError();
 }
 

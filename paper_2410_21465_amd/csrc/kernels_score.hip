@@ -36,11 +36,16 @@ __device__ __forceinline__ void lse_merge(double& m, double& s, double m2, doubl
   if (m2 > m) { s = s * e + s2; m = m2; } else { s += s2 * e; }
 }
 
-template <int D>
-__global__ __launch_bounds__(256) void score_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ L,
+// EB = bytes per landmark element: 2 (bf16) or 1 (FP8 E5M2 storage; a row is then d bytes and a lane's
+// piece holds twice as many elements, or the same number in 8 bytes when d is not a multiple of 64).
+template <int D, int EB>
+__global__ __launch_bounds__(256) void score_kernel(const bf16_t* __restrict__ q, const uint8_t* __restrict__ L,
                                                     float* __restrict__ logits, double2* __restrict__ partials,
                                                     int hq, int hkv, int G, int n_c, int nc_stride, int n_tiles, double scale) {
-  constexpr int NI = D / 32;  // 16-byte pieces per lane per row
+  constexpr int PB = (EB == 2 || D % 64 == 0) ? 16 : 8;  // bytes per piece
+  constexpr int PE = PB / EB;                             // elements per piece
+  constexpr int NI = D / (4 * PE);                        // pieces per lane per row
+  constexpr int PW = PB / 4;                              // 32-bit words per piece
   __shared__ double2 wred[4][4];
   const int unit = blockIdx.y, tile = blockIdx.x, g0 = blockIdx.z * 4;
   const int b = unit / hkv, h = unit % hkv;
@@ -48,31 +53,43 @@ __global__ __launch_bounds__(256) void score_kernel(const bf16_t* __restrict__ q
   const int kq = lane >> 4, blk = (lane >> 2) & 3, ij = lane & 3;
   const size_t head0 = (size_t)b * hq + (size_t)h * G + g0;
 
-  const bf16_t* Lu = L + (size_t)unit * nc_stride * D;  // the landmark array may have room to grow
+  const uint8_t* Lu = L + (size_t)unit * nc_stride * D * EB;  // the landmark array may have room to grow
   const int row0 = tile * kScoreTile + wave * kWave;
-  uint4 w[4][NI];  // requested before q: the landmark rows are the long-latency loads
+  uint32_t w[4][NI][PW];  // requested before q: the landmark rows are the long-latency loads
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
     const int r = row0 + t * 16 + blk * 4 + ij;
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
-      w[t][i] = make_uint4(0u, 0u, 0u, 0u);
-      if (r < n_c) w[t][i] = *reinterpret_cast<const uint4*>(Lu + (size_t)r * D + 32 * i + 8 * kq);
+#pragma unroll
+      for (int x = 0; x < PW; ++x) w[t][i][x] = 0u;
+      if (r < n_c) {
+        const uint8_t* src = Lu + (size_t)r * D * EB + (size_t)(4 * PE * i + PE * kq) * EB;
+        if constexpr (PW == 4) {
+          const uint4 v = *reinterpret_cast<const uint4*>(src);
+          w[t][i][0] = v.x; w[t][i][1] = v.y; w[t][i][2] = v.z; w[t][i][3] = v.w;
+        } else {
+          const uint2 v = *reinterpret_cast<const uint2*>(src);
+          w[t][i][0] = v.x; w[t][i][1] = v.y;
+        }
+      }
     }
   }
 
   // A operand: q of head g0 + ij, the elements this lane's k-slot meets, as fp64
-  double qa[NI][8];
+  double qa[NI][PE];
   {
     const bool hv = g0 + ij < G;
-    const bf16_t* qp = q + (head0 + (hv ? ij : 0)) * D + 8 * kq;
+    const bf16_t* qp = q + (head0 + (hv ? ij : 0)) * D + PE * kq;
 #pragma unroll
-    for (int i = 0; i < NI; ++i) {
-      float x[8];
-      load_bf16_row<8>(qp + 32 * i, x);
+    for (int i = 0; i < NI; ++i)
 #pragma unroll
-      for (int e = 0; e < 8; ++e) qa[i][e] = hv ? (double)x[e] : 0.0;
-    }
+      for (int e8 = 0; e8 < PE / 8; ++e8) {
+        float x[8];
+        load_bf16_row<8>(qp + 4 * PE * i + 8 * e8, x);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qa[i][8 * e8 + e] = hv ? (double)x[e] : 0.0;
+      }
   }
 
   const int hd = g0 + (lane >> 4);  // head of this lane's results
@@ -82,11 +99,18 @@ __global__ __launch_bounds__(256) void score_kernel(const bf16_t* __restrict__ q
     double acc = 0.0;
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
-      const uint32_t u4[4] = {w[t][i].x, w[t][i].y, w[t][i].z, w[t][i].w};
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        acc = __builtin_amdgcn_mfma_f64_4x4x4f64(qa[i][2 * e], (double)bf16_lo(u4[e]), acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f64_4x4x4f64(qa[i][2 * e + 1], (double)bf16_hi(u4[e]), acc, 0, 0, 0);
+      for (int x = 0; x < PW; ++x) {
+        if constexpr (EB == 2) {
+          acc = __builtin_amdgcn_mfma_f64_4x4x4f64(qa[i][2 * x], (double)bf16_lo(w[t][i][x]), acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f64_4x4x4f64(qa[i][2 * x + 1], (double)bf16_hi(w[t][i][x]), acc, 0, 0, 0);
+        } else {
+          float f[4];
+          e5m2x4_to_f32(w[t][i][x], f);
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            acc = __builtin_amdgcn_mfma_f64_4x4x4f64(qa[i][4 * x + e], (double)f[e], acc, 0, 0, 0);
+        }
       }
     }
     const int r = row0 + t * 16 + (lane & 15);
@@ -111,17 +135,25 @@ __global__ __launch_bounds__(256) void score_kernel(const bf16_t* __restrict__ q
   }
 }
 
-hipError_t launch_score(const bf16_t* q, const bf16_t* landmarks, float* logits, double2* partials, int batch,
-                        int hq, int hkv, int d, int n_c, int nc_stride, double scale, hipStream_t st) {
+hipError_t launch_score(const bf16_t* q, const void* landmarks, int kv_bytes, float* logits, double2* partials,
+                        int batch, int hq, int hkv, int d, int n_c, int nc_stride, double scale, hipStream_t st) {
   const int G = hq / hkv;
   const int n_tiles = (n_c + kScoreTile - 1) / kScoreTile;
   dim3 grid(n_tiles, batch * hkv, (G + 3) / 4), block(256);
-  switch (d) {
-    case 64: hipLaunchKernelGGL((score_kernel<64>), grid, block, 0, st, q, landmarks, logits, partials, hq, hkv, G, n_c, nc_stride, n_tiles, scale); break;
-    case 96: hipLaunchKernelGGL((score_kernel<96>), grid, block, 0, st, q, landmarks, logits, partials, hq, hkv, G, n_c, nc_stride, n_tiles, scale); break;
-    case 128: hipLaunchKernelGGL((score_kernel<128>), grid, block, 0, st, q, landmarks, logits, partials, hq, hkv, G, n_c, nc_stride, n_tiles, scale); break;
+  const uint8_t* L = static_cast<const uint8_t*>(landmarks);
+#define SKV_SCORE(D_, EB_)                                                                                       \
+  hipLaunchKernelGGL((score_kernel<D_, EB_>), grid, block, 0, st, q, L, logits, partials, hq, hkv, G, n_c, nc_stride, \
+                     n_tiles, scale)
+  switch (d * 4 + kv_bytes) {
+    case 64 * 4 + 2: SKV_SCORE(64, 2); break;
+    case 96 * 4 + 2: SKV_SCORE(96, 2); break;
+    case 128 * 4 + 2: SKV_SCORE(128, 2); break;
+    case 64 * 4 + 1: SKV_SCORE(64, 1); break;
+    case 96 * 4 + 1: SKV_SCORE(96, 1); break;
+    case 128 * 4 + 1: SKV_SCORE(128, 1); break;
     default: return hipErrorInvalidValue;
   }
+#undef SKV_SCORE
   return hipGetLastError();
 }
 

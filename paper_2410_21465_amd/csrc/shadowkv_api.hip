@@ -46,6 +46,7 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 struct Shape {
   int b, hq, hkv, G, d, s, c, r, o, k, w, n_ch, n_c, units;
   int cap, nc_cap;  // tokens / landmark rows the context arrays are laid out for
+  int eb;           // bytes per element of the KV-cache tensors (2 = bf16, 1 = FP8 E5M2)
   bool stage, keep_keys;
 };
 
@@ -68,6 +69,9 @@ int check_params(const shadowkv_params* p, bool decode, Shape* sh) {
   if (units > 65535) return fail_inval("batch * n_kv_heads above 65535 is not supported");
   if (p->value_location != SHADOWKV_VALUES_DEVICE && p->value_location != SHADOWKV_VALUES_HOST)
     return fail_inval("value_location must be SHADOWKV_VALUES_DEVICE or SHADOWKV_VALUES_HOST");
+  if (p->kv_dtype != SHADOWKV_KV_BF16 && p->kv_dtype != SHADOWKV_KV_FP8_E5M2)
+    return fail_inval("kv_dtype must be SHADOWKV_KV_BF16 or SHADOWKV_KV_FP8_E5M2");
+  sh->eb = p->kv_dtype == SHADOWKV_KV_FP8_E5M2 ? 1 : 2;
   sh->b = p->batch; sh->hq = p->n_q_heads; sh->hkv = p->n_kv_heads; sh->G = sh->hq / sh->hkv;
   sh->d = p->head_dim; sh->s = p->ctx_len; sh->c = p->chunk_size; sh->o = p->n_outlier_chunks;
   sh->n_ch = (int)n_ch; sh->n_c = (int)n_ch - sh->o; sh->units = (int)units;
@@ -143,7 +147,7 @@ DecodeLayout decode_layout(const Shape& sh) {
   L.n_miss = off; off += up((size_t)sh.units * sizeof(int32_t));
   L.logit_buf = off; off += up(heads * rows / sh.units * sizeof(float));  // two-phase path: [b*h_q, k*c]
   L.k_sparse = off; off += sh.keep_keys ? up(rows * sh.d * sizeof(float)) : 0;
-  L.v_sparse = off; off += sh.stage ? up(rows * sh.d * sizeof(bf16_t)) : 0;
+  L.v_sparse = off; off += sh.stage ? up(rows * sh.d * sh.eb) : 0;
   const size_t n_part = (size_t)L.attn.n_splits + L.attn.n_pv_splits;
   L.part_acc = off; off += up(heads * n_part * sh.d * sizeof(float));
   L.part_ml = off; off += up(heads * n_part * sizeof(float2));
@@ -159,7 +163,7 @@ bool build_layout(const Shape& sh, BuildLayout* L) {
   *L = BuildLayout{};
   if (sh.o > 0 && !plan_select(sh.n_ch, sh.o, &L->sel)) return false;
   size_t off = 0;
-  L->chunk_mean = off; off += up((size_t)sh.units * sh.n_ch * sh.d * sizeof(bf16_t));
+  L->chunk_mean = off; off += up((size_t)sh.units * sh.n_ch * sh.d * sh.eb);
   L->min_cos = off; off += up((size_t)sh.units * sh.n_ch * sizeof(double));
   L->cand_key = off; off += up((size_t)sh.units * L->sel.cand_stride * sizeof(uint64_t));
   L->cand_idx = off; off += up((size_t)sh.units * L->sel.cand_stride * sizeof(int32_t));
@@ -253,7 +257,7 @@ int shadowkv_profile_end(double* stage_ms, int* n_steps) {
   return rc;
 }
 
-int shadowkv_version(void) { return 200; }
+int shadowkv_version(void) { return 300; }
 
 const char* shadowkv_status_string(int status) {
   switch (status) {
@@ -313,9 +317,9 @@ void* shadowkv_decode_workspace_view(const shadowkv_params* params, void* worksp
   }
 }
 
-int shadowkv_build_landmarks(const shadowkv_params* params, const shadowkv_bf16* k_rope, const shadowkv_bf16* v,
-                             shadowkv_bf16* landmarks, int32_t* landmark_chunk_ids, int32_t* outlier_chunk_ids,
-                             shadowkv_bf16* k_outlier, shadowkv_bf16* v_outlier, void* workspace,
+int shadowkv_build_landmarks(const shadowkv_params* params, const shadowkv_kv* k_rope, const shadowkv_kv* v,
+                             shadowkv_kv* landmarks, int32_t* landmark_chunk_ids, int32_t* outlier_chunk_ids,
+                             shadowkv_kv* k_outlier, shadowkv_kv* v_outlier, void* workspace,
                              size_t workspace_bytes, void* stream) {
   Shape sh;
   int rc = check_params(params, false, &sh);
@@ -333,9 +337,9 @@ int shadowkv_build_landmarks(const shadowkv_params* params, const shadowkv_bf16*
 
   hipStream_t st = static_cast<hipStream_t>(stream);
   char* ws = static_cast<char*>(workspace);
-  bf16_t* chunk_mean = reinterpret_cast<bf16_t*>(ws + L.chunk_mean);
+  void* chunk_mean = ws + L.chunk_mean;
   double* min_cos = reinterpret_cast<double*>(ws + L.min_cos);
-  hipError_t e = launch_chunk_stats(k_rope, chunk_mean, min_cos, sh.units, sh.d, sh.s, sh.c, st);
+  hipError_t e = launch_chunk_stats(k_rope, sh.eb, chunk_mean, min_cos, sh.units, sh.d, sh.s, sh.c, st);
   if (e != hipSuccess) return fail_hip("chunk_stats", e);
   if (sh.o > 0) {
     SelectArgs a{};
@@ -347,12 +351,12 @@ int shadowkv_build_landmarks(const shadowkv_params* params, const shadowkv_bf16*
     a.out_ids = outlier_chunk_ids;
     e = launch_select(a, L.sel, kSrcArray, sh.units, st);
     if (e != hipSuccess) return fail_hip("select outliers", e);
-    e = launch_gather_outliers(k_rope, v, outlier_chunk_ids, k_outlier, v_outlier, sh.units, sh.d, sh.s, sh.cap, sh.c,
-                               sh.o, st);
+    e = launch_gather_outliers(k_rope, v, sh.eb, outlier_chunk_ids, k_outlier, v_outlier, sh.units, sh.d, sh.s, sh.cap,
+                               sh.c, sh.o, st);
     if (e != hipSuccess) return fail_hip("gather outliers", e);
   }
-  e = launch_compact_landmarks(chunk_mean, outlier_chunk_ids, landmarks, landmark_chunk_ids, sh.units, sh.d, sh.n_ch,
-                               sh.o, sh.nc_cap, st);
+  e = launch_compact_landmarks(chunk_mean, sh.eb, outlier_chunk_ids, landmarks, landmark_chunk_ids, sh.units, sh.d,
+                               sh.n_ch, sh.o, sh.nc_cap, st);
   if (e != hipSuccess) return fail_hip("compact landmarks", e);
   return SHADOWKV_OK;
 }
@@ -360,17 +364,17 @@ int shadowkv_build_landmarks(const shadowkv_params* params, const shadowkv_bf16*
 // Value cache handed to a cached step (all device pointers).
 struct CacheIO {
   int slots;             // S >= k slots per unit
-  bf16_t* values;        // [units, S*c, d]
+  void* values;          // [units, S*c, d] in the storage type of the KV cache
   int32_t* chunk_ids;    // [units, S], -1 = empty
   int32_t* stamps;       // [units, S + 1]: last use of each slot, then the unit's clock
   int32_t* miss_count;   // optional [units]
 };
 
-static int decode_impl(const shadowkv_params* params, const shadowkv_bf16* q, const shadowkv_bf16* A,
-                       const shadowkv_bf16* B, const shadowkv_bf16* landmarks, const int32_t* landmark_chunk_ids,
-                       const shadowkv_bf16* k_outlier, const shadowkv_bf16* v_outlier,
-                       const shadowkv_bf16* k_local, const shadowkv_bf16* v_local,
-                       const shadowkv_bf16* value_store, const int32_t* pos_offset, const CacheIO* cache,
+static int decode_impl(const shadowkv_params* params, const shadowkv_bf16* q, const shadowkv_kv* A,
+                       const shadowkv_kv* B, const shadowkv_kv* landmarks, const int32_t* landmark_chunk_ids,
+                       const shadowkv_kv* k_outlier, const shadowkv_kv* v_outlier,
+                       const shadowkv_kv* k_local, const shadowkv_kv* v_local,
+                       const shadowkv_kv* value_store, const int32_t* pos_offset, const CacheIO* cache,
                        shadowkv_bf16* out, int32_t* out_chunk_ids, void* workspace, size_t workspace_bytes,
                        void* stream, void* side_stream) {
   Shape sh;
@@ -401,7 +405,7 @@ static int decode_impl(const shadowkv_params* params, const shadowkv_bf16* q, co
   float* logits = reinterpret_cast<float*>(ws + L.logits);
   double2* partials = reinterpret_cast<double2*>(ws + L.partials);
   int32_t* sel_ids = reinterpret_cast<int32_t*>(ws + L.sel_ids);
-  bf16_t* v_sparse = sh.stage ? reinterpret_cast<bf16_t*>(ws + L.v_sparse) : nullptr;
+  void* v_sparse = sh.stage ? ws + L.v_sparse : nullptr;
   const double scale = params->softmax_scale != 0.0 ? params->softmax_scale : 1.0 / std::sqrt((double)sh.d);
 
   RopeFreqs freqs;
@@ -419,7 +423,7 @@ static int decode_impl(const shadowkv_params* params, const shadowkv_bf16* q, co
   const int pstep = (g_prof.on && g_prof.n_steps < g_prof.max_steps) ? g_prof.n_steps++ : -1;
   prof_mark(st, pstep, 0);
   // 1. P = Q L^T / sqrt(d), per-tile softmax statistics
-  hipError_t e = launch_score(q, landmarks, logits, partials, sh.b, sh.hq, sh.hkv, sh.d, sh.n_c, sh.nc_cap, scale, st);
+  hipError_t e = launch_score(q, landmarks, sh.eb, logits, partials, sh.b, sh.hq, sh.hkv, sh.d, sh.n_c, sh.nc_cap, scale, st);
   if (e != hipSuccess) return fail_hip("score", e);
   prof_mark(st, pstep, 1);
   // 2. softmax normaliser per head, max over the group, ArgTopK -> true chunk ids
@@ -435,6 +439,7 @@ static int decode_impl(const shadowkv_params* params, const shadowkv_bf16* q, co
   if (e != hipSuccess) return fail_hip("select chunks", e);
   prof_mark(st, pstep, 2);
   AttnArgs t{};
+  t.kv_bytes = sh.eb;
   t.q = q; t.A = A; t.B = B; t.k_outlier = k_outlier; t.v_outlier = v_outlier;
   t.k_local = k_local; t.v_local = v_local; t.v_store = value_store;
   t.sel_ids = sel_ids; t.pos_offset = pos_offset; t.inv_freq_dev = params->inv_freq;
@@ -483,11 +488,11 @@ static int decode_impl(const shadowkv_params* params, const shadowkv_bf16* q, co
     gs = side;
   }
   if (cache) {
-    e = launch_gather_missing(value_store, cache->chunk_ids, miss_slots, n_miss, cache->values, sh.units, sh.d, sh.s,
-                              sh.cap, sh.c, sh.k, cache->slots, gs);
+    e = launch_gather_missing(value_store, cache->chunk_ids, miss_slots, n_miss, cache->values, sh.eb, sh.units, sh.d,
+                              sh.s, sh.cap, sh.c, sh.k, cache->slots, gs);
     t.v_sparse = cache->values; t.v_slots = sel_slots; t.v_unit_rows = cache->slots * sh.c;
   } else {
-    e = launch_gather_values(value_store, sel_ids, v_sparse, sh.units, sh.d, sh.s, sh.cap, sh.c, sh.k, gs);
+    e = launch_gather_values(value_store, sel_ids, v_sparse, sh.eb, sh.units, sh.d, sh.s, sh.cap, sh.c, sh.k, gs);
     t.v_sparse = v_sparse;
   }
   if (e != hipSuccess) return fail_hip("gather values", e);
@@ -506,11 +511,11 @@ static int decode_impl(const shadowkv_params* params, const shadowkv_bf16* q, co
   return SHADOWKV_OK;
 }
 
-int shadowkv_decode_step(const shadowkv_params* params, const shadowkv_bf16* q, const shadowkv_bf16* A,
-                         const shadowkv_bf16* B, const shadowkv_bf16* landmarks, const int32_t* landmark_chunk_ids,
-                         const shadowkv_bf16* k_outlier, const shadowkv_bf16* v_outlier,
-                         const shadowkv_bf16* k_local, const shadowkv_bf16* v_local,
-                         const shadowkv_bf16* value_store, const int32_t* pos_offset, shadowkv_bf16* out,
+int shadowkv_decode_step(const shadowkv_params* params, const shadowkv_bf16* q, const shadowkv_kv* A,
+                         const shadowkv_kv* B, const shadowkv_kv* landmarks, const int32_t* landmark_chunk_ids,
+                         const shadowkv_kv* k_outlier, const shadowkv_kv* v_outlier,
+                         const shadowkv_kv* k_local, const shadowkv_kv* v_local,
+                         const shadowkv_kv* value_store, const int32_t* pos_offset, shadowkv_bf16* out,
                          int32_t* out_chunk_ids, void* workspace, size_t workspace_bytes, void* stream,
                          void* side_stream) {
   return decode_impl(params, q, A, B, landmarks, landmark_chunk_ids, k_outlier, v_outlier, k_local, v_local,
@@ -518,12 +523,12 @@ int shadowkv_decode_step(const shadowkv_params* params, const shadowkv_bf16* q, 
                      side_stream);
 }
 
-int shadowkv_decode_step_cached(const shadowkv_params* params, const shadowkv_bf16* q, const shadowkv_bf16* A,
-                                const shadowkv_bf16* B, const shadowkv_bf16* landmarks,
-                                const int32_t* landmark_chunk_ids, const shadowkv_bf16* k_outlier,
-                                const shadowkv_bf16* v_outlier, const shadowkv_bf16* k_local,
-                                const shadowkv_bf16* v_local, const shadowkv_bf16* value_store,
-                                const int32_t* pos_offset, int32_t cache_slots, shadowkv_bf16* value_cache,
+int shadowkv_decode_step_cached(const shadowkv_params* params, const shadowkv_bf16* q, const shadowkv_kv* A,
+                                const shadowkv_kv* B, const shadowkv_kv* landmarks,
+                                const int32_t* landmark_chunk_ids, const shadowkv_kv* k_outlier,
+                                const shadowkv_kv* v_outlier, const shadowkv_kv* k_local,
+                                const shadowkv_kv* v_local, const shadowkv_kv* value_store,
+                                const int32_t* pos_offset, int32_t cache_slots, shadowkv_kv* value_cache,
                                 int32_t* cache_chunk_ids, int32_t* cache_stamps, int32_t* out_miss_count,
                                 shadowkv_bf16* out, int32_t* out_chunk_ids, void* workspace, size_t workspace_bytes,
                                 void* stream, void* side_stream) {
@@ -532,9 +537,9 @@ int shadowkv_decode_step_cached(const shadowkv_params* params, const shadowkv_bf
                      value_store, pos_offset, &c, out, out_chunk_ids, workspace, workspace_bytes, stream, side_stream);
 }
 
-int shadowkv_append_chunk(const shadowkv_params* params, const shadowkv_bf16* k_pre, const shadowkv_bf16* k_rope,
-                          const shadowkv_bf16* v, const shadowkv_bf16* B, shadowkv_bf16* A, shadowkv_bf16* landmarks,
-                          int32_t* landmark_chunk_ids, shadowkv_bf16* value_store, void* stream) {
+int shadowkv_append_chunk(const shadowkv_params* params, const shadowkv_kv* k_pre, const shadowkv_kv* k_rope,
+                          const shadowkv_kv* v, const shadowkv_kv* B, shadowkv_kv* A, shadowkv_kv* landmarks,
+                          int32_t* landmark_chunk_ids, shadowkv_kv* value_store, void* stream) {
   Shape sh;
   int rc = check_params(params, false, &sh);
   if (rc != SHADOWKV_OK) return rc;
@@ -547,8 +552,8 @@ int shadowkv_append_chunk(const shadowkv_params* params, const shadowkv_bf16* k_
   if (!aligned16(k_pre) || !aligned16(k_rope) || !aligned16(v) || !aligned16(B) || !aligned16(A) ||
       !aligned16(landmarks) || !aligned16(value_store))
     return fail_inval("tensor pointers must be 16-byte aligned");
-  hipError_t e = launch_append_chunk(k_pre, k_rope, v, B, A, landmarks, landmark_chunk_ids, value_store, sh.b, sh.hkv,
-                                     sh.d, sh.s, sh.cap, sh.c, sh.r, sh.o, static_cast<hipStream_t>(stream));
+  hipError_t e = launch_append_chunk(k_pre, k_rope, v, B, A, landmarks, landmark_chunk_ids, value_store, sh.eb, sh.b,
+                                     sh.hkv, sh.d, sh.s, sh.cap, sh.c, sh.r, sh.o, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) return fail_hip("append chunk", e);
   return SHADOWKV_OK;
 }
@@ -586,7 +591,7 @@ size_t shadowkv_value_cache_bytes(const shadowkv_params* params, int32_t cache_s
   Shape sh;
   if (check_params(params, true, &sh) != SHADOWKV_OK) return 0;
   if (cache_slots < sh.k || cache_slots > kMaxCacheSlots) return 0;
-  return (size_t)sh.units * cache_slots * sh.c * sh.d * sizeof(bf16_t);
+  return (size_t)sh.units * cache_slots * sh.c * sh.d * sh.eb;
 }
 
 int shadowkv_value_cache_reset(const shadowkv_params* params, int32_t cache_slots, int32_t* cache_chunk_ids,

@@ -20,6 +20,7 @@ OK, EINVAL, EWORKSPACE, EHIP = 0, -1, -2, -3
 VALUES_DEVICE, VALUES_HOST = 0, 1
 FLAG_STAGE_VALUES = 1
 FLAG_KEEP_REBUILT_KEYS = 2
+KV_BF16, KV_FP8_E5M2 = 0, 1     # storage type of the KV-cache tensors (Params.kv_dtype)
 
 EXPORTS = (
     "shadowkv_build_landmarks", "shadowkv_decode_step", "shadowkv_build_workspace_bytes",
@@ -38,7 +39,7 @@ class CParams(C.Structure):
         ("n_outlier_chunks", C.c_int32), ("topk_chunks", C.c_int32), ("local_len", C.c_int32),
         ("value_location", C.c_int32), ("flags", C.c_uint32),
         ("rope_theta", C.c_double), ("softmax_scale", C.c_double), ("inv_freq", C.c_void_p),
-        ("ctx_capacity", C.c_int32),
+        ("ctx_capacity", C.c_int32), ("kv_dtype", C.c_int32),
     ]
 
 
@@ -147,6 +148,15 @@ class Params:
     softmax_scale: float = 0.0
     inv_freq: Optional[torch.Tensor] = None   # device float32 [head_dim/2]
     ctx_capacity: int = 0                     # tokens the context arrays are laid out for (0 => ctx_len)
+    kv_dtype: int = KV_BF16                   # KV_BF16 | KV_FP8_E5M2: storage of every KV-cache tensor
+
+    @property
+    def kv_torch_dtype(self) -> torch.dtype:
+        return torch.float8_e5m2 if self.kv_dtype == KV_FP8_E5M2 else torch.bfloat16
+
+    @property
+    def kv_bytes(self) -> int:
+        return 1 if self.kv_dtype == KV_FP8_E5M2 else 2
 
     @property
     def n_chunks(self) -> int:
@@ -171,7 +181,8 @@ class Params:
             inv = self.inv_freq.data_ptr()
         return CParams(self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim, self.ctx_len, self.chunk_size,
                        self.rank, self.n_outlier_chunks, self.topk_chunks, self.local_len, self.value_location,
-                       self.flags, float(self.rope_theta), float(self.softmax_scale), inv, int(self.ctx_capacity))
+                       self.flags, float(self.rope_theta), float(self.softmax_scale), inv, int(self.ctx_capacity),
+                       int(self.kv_dtype))
 
     @classmethod
     def from_workload(cls, wl, **kw) -> "Params":
@@ -224,10 +235,10 @@ def build_landmarks(p: Params, k_rope: torch.Tensor, v: Optional[torch.Tensor] =
     b, h, s, d, c, o = p.batch, p.n_kv_heads, p.ctx_len, p.head_dim, p.chunk_size, p.n_outlier_chunks
     n_c = p.landmark_capacity      # rows allocated; the first p.n_landmarks are written
     dev = k_rope.device
-    assert k_rope.dtype == torch.bfloat16 and tuple(k_rope.shape) == (b, h, s, d)
+    assert k_rope.dtype == p.kv_torch_dtype and tuple(k_rope.shape) == (b, h, s, d)
     if v is not None:
-        assert v.dtype == torch.bfloat16 and tuple(v.shape) == (b, h, p.capacity, d)
-    bf, i32 = torch.bfloat16, torch.int32
+        assert v.dtype == p.kv_torch_dtype and tuple(v.shape) == (b, h, p.capacity, d)
+    bf, i32 = p.kv_torch_dtype, torch.int32
     out = {
         "landmarks": torch.empty(b, h, max(n_c, 0), d, dtype=bf, device=dev),
         "landmark_chunk_ids": torch.empty(b, h, max(n_c, 0), dtype=i32, device=dev),
@@ -291,7 +302,7 @@ def argtopk(scores: torch.Tensor, k: int, largest: bool = True, stream=None) -> 
 
 class ValueCache:
     """Device buffers of the chunk cache of the value store with ``slots`` >= k slots per (batch, KV head):
-    ``values [b,h_kv,slots*c,d]`` bf16, ``chunk_ids [b,h_kv,slots]`` int32 (-1 = empty), ``stamps
+    ``values [b,h_kv,slots*c,d]`` in the storage type of the KV cache, ``chunk_ids [b,h_kv,slots]`` int32 (-1 = empty), ``stamps
     [b,h_kv,slots+1]`` int32 (last use per slot, then the unit's clock), ``miss_count [b,h_kv]`` of the last step."""
 
     def __init__(self, p: Params, slots: Optional[int] = None, device="cuda", stream=None):
@@ -302,8 +313,8 @@ class ValueCache:
             _check(lib().shadowkv_validate_params(C.addressof(st), 1))
             raise ValueError(f"cache slots {self.slots} outside [topk_chunks, 8192]")
         self.values = torch.empty(p.batch, p.n_kv_heads, self.slots * p.chunk_size, p.head_dim,
-                                  dtype=torch.bfloat16, device=device)
-        assert self.values.numel() * 2 == n
+                                  dtype=p.kv_torch_dtype, device=device)
+        assert self.values.numel() * p.kv_bytes == n
         self.chunk_ids = torch.empty(p.batch, p.n_kv_heads, self.slots, dtype=torch.int32, device=device)
         self.stamps = torch.empty(p.batch, p.n_kv_heads, self.slots + 1, dtype=torch.int32, device=device)
         self.miss_count = torch.zeros(p.batch, p.n_kv_heads, dtype=torch.int32, device=device)
@@ -342,7 +353,7 @@ def decode_step_cached(p: Params, q, A, B, landmarks, landmark_chunk_ids, k_outl
 def workspace_view(p: Params, workspace: torch.Tensor, which: str) -> Optional[torch.Tensor]:
     """Intermediate of the last decode step as a tensor aliasing ``workspace``.
 
-    ``"k_sparse"`` fp32 [b,h_kv,k*c,d]; ``"v_sparse"`` bf16 (staged runs only); ``"logits"`` fp32 [b,h_q,n_c].
+    ``"k_sparse"`` fp32 [b,h_kv,k*c,d]; ``"v_sparse"`` in the KV storage type (staged runs only); ``"logits"`` fp32 [b,h_q,n_c].
     """
     code = {"k_sparse": 0, "v_sparse": 1, "sel_ids": 2, "logits": 3, "miss_slots": 4, "sel_slots": 5}[which]
     st = p.c_struct()
@@ -356,7 +367,7 @@ def workspace_view(p: Params, workspace: torch.Tensor, which: str) -> Optional[t
         return workspace[off:off + 4 * n].view(torch.float32).view(rows)
     if which == "v_sparse":
         n = rows[0] * rows[1] * rows[2] * rows[3]
-        return workspace[off:off + 2 * n].view(torch.bfloat16).view(rows)
+        return workspace[off:off + p.kv_bytes * n].view(p.kv_torch_dtype).view(rows)
     if which in ("sel_ids", "miss_slots", "sel_slots"):
         n = p.batch * p.n_kv_heads * p.topk_chunks
         return workspace[off:off + 4 * n].view(torch.int32).view(p.batch, p.n_kv_heads, p.topk_chunks)

@@ -233,6 +233,32 @@ def generate(wl: Workload, device: Optional[str] = None, want_prefill: bool = Tr
     return out
 
 
+KV_TENSORS = ("A", "B", "k_rope", "v", "k_local", "v_local")
+
+
+def to_fp8_storage(t: Dict[str, torch.Tensor]) -> Dict[str, torch.Tensor]:
+    """The same workload with its KV-cache tensors (``KV_TENSORS``) stored as FP8 E5M2 (torch's cast, round to
+    nearest even): the second storage precision the paper evaluates (section "Precision Sensitivity").  Queries
+    stay bf16.  Pinned host memory is kept pinned.  A cast of inputs, not a step of the method: oracle and
+    library are handed these bytes."""
+    out = dict(t)
+    for name in KV_TENSORS:
+        if name not in t:
+            continue
+        x = t[name]
+        if x.device.type == "cpu" and x.is_pinned():
+            y = _alloc(tuple(x.shape), torch.float8_e5m2, "cpu", pinned=True)
+            step = max(1, (1 << 26) // max(1, x[0].numel()))
+            for i in range(0, x.shape[0], step):
+                y[i:i + step].copy_(x[i:i + step].to(torch.float8_e5m2))
+        else:
+            y = torch.empty(x.shape, dtype=torch.float8_e5m2, device=x.device)
+            for i in range(x.shape[0]):          # per batch item: bounds the temporary of the cast
+                y[i].copy_(x[i].to(torch.float8_e5m2))
+        out[name] = y
+    return out
+
+
 def query_sequence(wl: Workload, n_steps: int, rho_q: float = 0.9, device: Optional[str] = None) -> torch.Tensor:
     """Queries of ``n_steps`` consecutive decode steps, ``[n_steps, b, h_q, d]`` bf16, correlated from step to
     step so that consecutive selections overlap (the temporal locality the chunk cache of the value store

@@ -27,14 +27,30 @@ TIE_REL = 1e-6
 KSPARSE_REL = 2e-4
 
 
-def oracle_params(wl: Workload, inv_freq=None, softmax_scale=0.0) -> O.OracleParams:
+def oracle_params(wl: Workload, inv_freq=None, softmax_scale=0.0, kv_dtype=0) -> O.OracleParams:
     return O.OracleParams(wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ctx_len, wl.chunk_size, wl.rank,
                           wl.n_outlier_chunks, wl.topk_chunks, wl.local_len, rope_theta=wl.rope_theta,
-                          inv_freq=inv_freq, softmax_scale=softmax_scale)
+                          inv_freq=inv_freq, softmax_scale=softmax_scale, kv_dtype=kv_dtype)
 
 
-def to_bits(t: torch.Tensor) -> np.ndarray:
-    return O.as_bits(t.detach().cpu())
+def to_bits(t: torch.Tensor, kv_dtype: int = 0) -> np.ndarray:
+    """Raw bits of a bf16 tensor (uint16), or of an E5M2 tensor of the KV cache with kv_dtype = 1 (uint8)."""
+    return O.as_bits(t.detach().cpu(), kv_dtype)
+
+
+def kv_from_bits(bits: np.ndarray, device="cuda") -> torch.Tensor:
+    """Oracle-side raw bits (uint16 = bf16, uint8 = E5M2) as a device tensor of that type."""
+    if bits.dtype == np.uint8:
+        return torch.from_numpy(bits).view(torch.float8_e5m2).to(device)
+    return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(device)
+
+
+def kv_to_f64(bits: np.ndarray) -> np.ndarray:
+    return O.e5m2_bits_to_f64(bits) if bits.dtype == np.uint8 else O.bits_to_f64(bits)
+
+
+def kv_round(x: np.ndarray, kv_dtype: int) -> np.ndarray:
+    return O.f64_to_e5m2_bits(x) if kv_dtype == 1 else O.f64_to_bits(x)
 
 
 def check_index_sets(got: np.ndarray, want_best_first: np.ndarray, score_of_id, what: str):
@@ -56,12 +72,12 @@ def check_index_sets(got: np.ndarray, want_best_first: np.ndarray, score_of_id, 
     return n_tied
 
 
-def run_build_parity(wl: Workload, t: dict, device="cuda"):
+def run_build_parity(wl: Workload, t: dict, device="cuda", kv_dtype: int = 0):
     """shadowkv_build_landmarks against the oracle.  Returns (oracle result, gpu result)."""
-    op = oracle_params(wl)
-    k_bits, v_bits = to_bits(t["k_rope"]), to_bits(t["v"])
+    op = oracle_params(wl, kv_dtype=kv_dtype)
+    k_bits, v_bits = to_bits(t["k_rope"], kv_dtype), to_bits(t["v"], kv_dtype)
     ref = O.build_landmarks(op, k_bits, v_bits, diagnostics=True)
-    gp = S.Params.from_workload(wl)
+    gp = S.Params.from_workload(wl, kv_dtype=kv_dtype)
     v_dev = t["v"]
     got = S.build_landmarks(gp, t["k_rope"], v_dev)
     torch.cuda.synchronize()
@@ -77,8 +93,8 @@ def run_build_parity(wl: Workload, t: dict, device="cuda"):
         ties = 0
     # gathered rows: bit-exact copies of the chunks the GPU chose
     if o:
-        gk = to_bits(got["k_outlier"]).reshape(units, o, c, d)
-        gv = to_bits(got["v_outlier"]).reshape(units, o, c, d)
+        gk = to_bits(got["k_outlier"], kv_dtype).reshape(units, o, c, d)
+        gv = to_bits(got["v_outlier"], kv_dtype).reshape(units, o, c, d)
         kk = k_bits.reshape(units, -1, c, d)
         vv = v_bits.reshape(units, -1, c, d)
         for u in range(units):
@@ -86,34 +102,35 @@ def run_build_parity(wl: Workload, t: dict, device="cuda"):
             np.testing.assert_array_equal(gv[u], vv[u, g_out[u]])
     if ties == 0:
         np.testing.assert_array_equal(got["landmark_chunk_ids"].cpu().numpy(), ref["landmark_chunk_ids"])
-        np.testing.assert_array_equal(to_bits(got["landmarks"]), ref["landmarks"])
+        np.testing.assert_array_equal(to_bits(got["landmarks"], kv_dtype), ref["landmarks"])
     else:  # compare the landmarks chunk by chunk through the ids
         gid = got["landmark_chunk_ids"].cpu().numpy().reshape(units, -1)
-        gl = to_bits(got["landmarks"]).reshape(units, -1, d)
+        gl = to_bits(got["landmarks"], kv_dtype).reshape(units, -1, d)
         means = ref["chunk_mean"].reshape(units, -1, d)
         for u in range(units):
-            np.testing.assert_array_equal(gl[u], O.f64_to_bits(means[u, gid[u]]))
+            np.testing.assert_array_equal(gl[u], kv_round(means[u, gid[u]], kv_dtype))
     return ref, got
 
 
 def run_decode_parity(wl: Workload, t: dict, ref_build: dict, qi: int = 0, side_stream: bool = True, flags: int = 0,
                       inv_freq=None, softmax_scale: float = 0.0, pos_offset=None, device="cuda",
-                      check_keys: bool = True):
+                      check_keys: bool = True, kv_dtype: int = 0):
     """shadowkv_decode_step against the oracle, both fed the ORACLE's landmarks and outliers."""
     b, hq, h, d, c, k = wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.chunk_size, wl.topk_chunks
     units = b * h
-    op = oracle_params(wl, inv_freq=inv_freq, softmax_scale=softmax_scale)
+    op = oracle_params(wl, inv_freq=inv_freq, softmax_scale=softmax_scale, kv_dtype=kv_dtype)
     q = t["q_pool"][qi]
     pos = t["pos_offset"] if pos_offset is None else pos_offset
-    ref = O.decode_step(op, to_bits(q), to_bits(t["A"]), to_bits(t["B"]), ref_build["landmarks"],
+    kd = kv_dtype
+    ref = O.decode_step(op, to_bits(q), to_bits(t["A"], kd), to_bits(t["B"], kd), ref_build["landmarks"],
                         ref_build["landmark_chunk_ids"], ref_build["k_outlier"], ref_build["v_outlier"],
-                        to_bits(t["k_local"]), to_bits(t["v_local"]), to_bits(t["v"]), pos.cpu().numpy())
+                        to_bits(t["k_local"], kd), to_bits(t["v_local"], kd), to_bits(t["v"], kd), pos.cpu().numpy())
 
     def dev_bf16(bits):
-        return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(device)
+        return kv_from_bits(bits, device)
 
     gp = S.Params.from_workload(wl, flags=flags | (S.FLAG_KEEP_REBUILT_KEYS if check_keys else 0),
-                                softmax_scale=softmax_scale,
+                                softmax_scale=softmax_scale, kv_dtype=kv_dtype,
                                 inv_freq=None if inv_freq is None else torch.from_numpy(inv_freq).to(device))
     lm = dev_bf16(ref_build["landmarks"])
     lm_ids = torch.from_numpy(ref_build["landmark_chunk_ids"]).to(device)
@@ -154,8 +171,8 @@ def run_decode_parity(wl: Workload, t: dict, ref_build: dict, qi: int = 0, side_
     # --- staged values: bit-exact copies ---
     vs = S.workspace_view(gp, ws, "v_sparse")
     if vs is not None:
-        vbits = to_bits(t["v"]).reshape(units, -1, c, d)
-        gv = to_bits(vs).reshape(units, k, c, d)
+        vbits = to_bits(t["v"], kd).reshape(units, -1, c, d)
+        gv = to_bits(vs, kd).reshape(units, k, c, d)
         for u in range(units):
             np.testing.assert_array_equal(gv[u], vbits[u, g_ids[u]])
 
