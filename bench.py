@@ -22,16 +22,17 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E bandwidth
 
 
-def algorithmic_bytes(wl) -> dict:
-    """Bytes the method itself has to move per decode step (bf16 everywhere), by consumer."""
+def algorithmic_bytes(wl, kv_bytes: int = 2) -> dict:
+    """Bytes the method itself has to move per decode step, by consumer: ``kv_bytes`` per element of the KV-cache
+    tensors (2 = bf16, 1 = FP8 E5M2), 2 per element of the query and the output."""
     d, c, r, k, o, w, G = wl.head_dim, wl.chunk_size, wl.rank, wl.topk_chunks, wl.n_outlier_chunks, wl.local_len, wl.group
-    u = wl.units
+    u, e = wl.units, kv_bytes
     per = {
-        "landmarks": 2 * d * wl.n_landmarks,            # read once for all G heads of the group
-        "A_rows": 2 * r * k * c,                        # gathered rows of the left factor
-        "B": 2 * r * d,
-        "values": 2 * d * k * c,                        # selected chunks' values, read once
-        "resident_kv": 2 * 2 * d * (o * c + w),         # outlier + recent keys and values
+        "landmarks": e * d * wl.n_landmarks,            # read once for all G heads of the group
+        "A_rows": e * r * k * c,                        # gathered rows of the left factor
+        "B": e * r * d,
+        "values": e * d * k * c,                        # selected chunks' values, read once
+        "resident_kv": 2 * e * d * (o * c + w),         # outlier + recent keys and values
         "q_out": 2 * 2 * d * G,
     }
     tot = {n: v * u for n, v in per.items()}
@@ -68,6 +69,8 @@ def main() -> int:
     ap.add_argument("--append", type=int, default=0, metavar="N",
                     help="lay the context arrays out with room for N more chunks and time N shadowkv_append_chunk calls "
                          "after the decode measurement (reported as append_chunk_ms)")
+    ap.add_argument("--kv-dtype", choices=["bf16", "fp8"], default="bf16",
+                    help="storage type of the KV-cache tensors: bf16, or FP8 E5M2 (the paper's second precision)")
     ap.add_argument("--stage-values", action="store_true",
                     help="stage the selected values with the gather kernel even for an HBM store "
                          "(gives profiles a plain copy kernel of known size: k*c*d*2 bytes per unit each way)")
@@ -78,7 +81,8 @@ def main() -> int:
 
     import torch
     from paper_2410_21465_amd import shadowkv as S
-    from paper_2410_21465_amd.workloads import CONFIGS, generate, generated_chunk, query_sequence, with_capacity
+    from paper_2410_21465_amd.workloads import (CONFIGS, generate, generated_chunk, query_sequence, to_fp8_storage,
+                                                with_capacity)
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -91,9 +95,15 @@ def main() -> int:
     ctx_cap = wl.ctx_len + args.append * wl.chunk_size
     if args.append:
         t = with_capacity(t, wl, ctx_cap)
+    fp8 = args.kv_dtype == "fp8"
+    kv_dtype = S.KV_FP8_E5M2 if fp8 else S.KV_BF16
+    t_bf16 = t
+    if fp8:
+        t = to_fp8_storage(t)
+        t_bf16 = {"A": t_bf16["A"], "B": t_bf16["B"]} if args.append else None   # generated_chunk draws from these
     print("[bench] inputs drawn", file=sys.stderr, flush=True)
     p = S.Params.from_workload(wl, flags=S.FLAG_STAGE_VALUES if args.stage_values else 0,
-                               ctx_capacity=ctx_cap if args.append else 0)
+                               ctx_capacity=ctx_cap if args.append else 0, kv_dtype=kv_dtype)
     # pre-filling algorithm (after the SVD) through the library itself
     torch.cuda.synchronize()
     tb = time.time()
@@ -186,12 +196,14 @@ def main() -> int:
 
     append_ms = None
     if args.append:   # grow the context chunk by chunk (the step after decode once c tokens left the window)
-        chunks = [generated_chunk(wl, t, i, device=dev) for i in range(min(args.append, 4))]
+        chunks = [generated_chunk(wl, t_bf16, i, device=dev) for i in range(min(args.append, 4))]
+        if fp8:
+            chunks = [tuple(x.to(torch.float8_e5m2) for x in ch) for ch in chunks]
         torch.cuda.synchronize()
         ev0.record()
         for i in range(args.append):
             kp, kr, vv = chunks[i % len(chunks)]
-            pa = S.Params.from_workload(wl, ctx_len=wl.ctx_len + i * wl.chunk_size, ctx_capacity=ctx_cap)
+            pa = S.Params.from_workload(wl, ctx_len=wl.ctx_len + i * wl.chunk_size, ctx_capacity=ctx_cap, kv_dtype=kv_dtype)
             S.append_chunk(pa, kp, kr, vv, t["B"], t["A"], bl["landmarks"], bl["landmark_chunk_ids"], t["v"])
         ev1.record()
         torch.cuda.synchronize()
@@ -221,12 +233,13 @@ def main() -> int:
         h2d_gbps = 4 * hsrc.numel() / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
         del hsrc, ddst
 
-    ab = algorithmic_bytes(wl)
+    ab = algorithmic_bytes(wl, 1 if fp8 else 2)
     score_ms = prof["ms"]["score"]
     score_bytes = ab["landmarks"] + ab["q_out"] // 2
     achieved = score_bytes / (score_ms * 1e-3) / 1e9
     traffic = None
-    pmc = os.path.join(ROOT, "profiles", f"score_kernel_{wl.name}_traffic.txt")   # committed rocprofv3 --pmc summary
+    tag = wl.name + ("-fp8" if fp8 else "")
+    pmc = os.path.join(ROOT, "profiles", f"score_kernel_{tag}_traffic.txt")   # committed rocprofv3 --pmc summary
     if os.path.exists(pmc):
         for line in open(pmc):
             if line.startswith("hbm_bytes_per_launch:"):
@@ -237,11 +250,17 @@ def main() -> int:
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{wl.name}: batch {wl.batch} x context {wl.ctx_len}, {wl.n_q_heads}q/{wl.n_kv_heads}kv "
                                f"heads, d={wl.head_dim}, c={wl.chunk_size}, r={wl.rank}, k={wl.topk_chunks}, "
-                               f"o={wl.n_outlier_chunks}, w={wl.local_len}, values in {wl.value_location}",
-                   "layers": 1, "side_stream": side is not None},
+                               f"o={wl.n_outlier_chunks}, w={wl.local_len}, values in {wl.value_location}"
+                               + (", KV cache stored as FP8 E5M2" if fp8 else ""),
+                   "layers": 1, "side_stream": side is not None, "kv_storage": "fp8_e5m2" if fp8 else "bf16"},
         "roofline": {"kernel": "score_kernel (landmark scoring, P = Q L^T)", "bound": "hbm", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
-                     "algorithmic_bytes_per_launch": score_bytes, "avg_launch_ms": score_ms},
+                     "algorithmic_bytes_per_launch": score_bytes, "avg_launch_ms": score_ms,
+                     # the same launch priced on the fp64 matrix pipe it computes on (4 heads x d FMAs per landmark row
+                     # and head group): what bounds it once the landmarks are one byte per element
+                     "fp64_mfma_tflops": 2.0 * wl.units * ((wl.group + 3) // 4) * 4 * wl.n_landmarks * wl.head_dim
+                                         / (score_ms * 1e-3) / 1e12,
+                     "fp64_mfma_peak_tflops": 78.6},
         "stage_ms": prof["ms"],
         "timed_region": "hip-graph replay" if graph is not None else "eager",
         "eager_ms_per_step_with_events": eager_ms_per_step,
@@ -270,12 +289,12 @@ def main() -> int:
             res["value_gather_pcie_gbps"] = res["value_gather_pcie_bytes"] / (prof["ms"]["gather_values"] * 1e-3) / 1e9
 
     if not args.no_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline(wl, t, args.cpu_seconds)
+        res["cpu_baseline"] = cpu_baseline(wl, t, args.cpu_seconds, 1 if fp8 else 0)
     print(json.dumps(res), flush=True)
     return 0
 
 
-def cpu_baseline(wl, t, budget_s: float) -> dict:
+def cpu_baseline(wl, t, budget_s: float, kv_dtype: int = 0) -> dict:
     """The CPU oracle, as it stands, on the first sequences of the same workload."""
     import numpy as np
     from oracle import shadowkv_oracle as O
@@ -283,10 +302,10 @@ def cpu_baseline(wl, t, budget_s: float) -> dict:
     bs = min(wl.batch, 4)
     sub = wl.scaled(batch=bs)
     op = O.OracleParams(bs, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ctx_len, wl.chunk_size, wl.rank,
-                        wl.n_outlier_chunks, wl.topk_chunks, wl.local_len, rope_theta=wl.rope_theta)
+                        wl.n_outlier_chunks, wl.topk_chunks, wl.local_len, rope_theta=wl.rope_theta, kv_dtype=kv_dtype)
 
     def bits(x):
-        return O.as_bits(x[:bs].detach().cpu())
+        return O.as_bits(x[:bs].detach().cpu(), kv_dtype)
 
     s_len = wl.ctx_len      # the oracle gets the dense layout (the arrays may have room to grow)
     t = dict(t, A=t["A"][:bs, :s_len].contiguous(), v=t["v"][:bs, :, :s_len].contiguous())

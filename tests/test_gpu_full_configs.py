@@ -59,3 +59,36 @@ def test_config4_one_million_tokens_needles():
 
 def test_config5_mha_d96():
     _run("c5")
+
+
+# ---- the same configurations with the KV cache stored as FP8 E5M2 (section "Precision Sensitivity") ----
+def _run_fp8(name, n_queries=2, move_values_to=None):
+    from paper_2410_21465_amd.workloads import to_fp8_storage
+    wl = CONFIGS[name]
+    print(f"\n[config] fp8 {wl}", flush=True)
+    t = to_fp8_storage(PU.draw(wl))
+    if move_values_to is not None:
+        t["v"] = t["v"].to(move_values_to)
+    print("[config] inputs drawn and cast", flush=True)
+    ref_b, _ = PU.run_build_parity(wl, t, kv_dtype=1)
+    print("[config] build parity ok", flush=True)
+    for qi in range(n_queries):
+        stats, ref_d, got = PU.run_decode_parity(wl, t, ref_b, qi=qi, check_keys=(qi == 0), kv_dtype=1)
+        print(f"[decode] fp8 {name} q{qi}: {stats}", flush=True)
+    return wl, t, ref_b, (stats, ref_d, got)
+
+
+def test_fp8_config3_values_in_hbm():
+    _run_fp8("c3-hbm")
+
+
+def test_fp8_config2_host_values():
+    _run_fp8("c2", n_queries=1)
+
+
+def test_fp8_config4_one_million_tokens():
+    _run_fp8("c4", n_queries=1)
+
+
+def test_fp8_config5_mha_d96():
+    _run_fp8("c5", n_queries=1)
