@@ -6,7 +6,7 @@ import torch
 
 from oracle import shadowkv_oracle as O
 from paper_2410_21465_amd import shadowkv as S
-from paper_2410_21465_amd.workloads import Workload, generate, query_sequence
+from paper_2410_21465_amd.workloads import Workload, generate, query_sequence, to_fp8_storage
 
 import parity_util as PU
 
@@ -30,22 +30,24 @@ def draw_shape(seed: int) -> Workload:
                     value_location=str(rng.choice(["hbm", "host"])), n_queries=2)
 
 
-@pytest.mark.parametrize("seed", range(14))
-def test_random_shape(seed):
+# every shape with bf16 storage of the KV cache; every other one also with FP8 E5M2 storage (seeds 100 + ...)
+@pytest.mark.parametrize("seed,kd", [(s, 0) for s in range(14)] + [(s, 1) for s in range(0, 14, 2)] + [(s, 1) for s in range(14, 20)],
+                         ids=lambda v: str(v))
+def test_random_shape(seed, kd):
     wl = draw_shape(seed)
-    print(f"\n[case] {wl}", flush=True)
+    print(f"\n[case] kv_dtype {kd} {wl}", flush=True)
     t = PU.draw(wl)
-    ref_b, _ = PU.run_build_parity(wl, t)
-    stats, _, _ = PU.run_decode_parity(wl, t, ref_b, qi=0, check_keys=True)
+    if kd:
+        t = to_fp8_storage(t)
+    ref_b, _ = PU.run_build_parity(wl, t, kv_dtype=kd)
+    stats, _, _ = PU.run_decode_parity(wl, t, ref_b, qi=0, check_keys=True, kv_dtype=kd)
     print(f"[decode] {wl.name}: {stats}", flush=True)
     # two cached steps with a cache a little larger than the budget
     rng = np.random.default_rng(2000 + seed)
     slots = wl.topk_chunks + int(rng.integers(0, 2 * wl.topk_chunks + 1))
-    op = PU.oracle_params(wl)
-    p = S.Params.from_workload(wl)
-
-    def dev(bits):
-        return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).cuda()
+    op = PU.oracle_params(wl, kv_dtype=kd)
+    p = S.Params.from_workload(wl, kv_dtype=kd)
+    dev = PU.kv_from_bits
 
     lm, ids = dev(ref_b["landmarks"]), torch.from_numpy(ref_b["landmark_chunk_ids"]).cuda()
     ko, vo = dev(ref_b["k_outlier"]), dev(ref_b["v_outlier"])
@@ -53,9 +55,9 @@ def test_random_shape(seed):
     qs = query_sequence(wl, 2, 0.9)
     units, k = wl.batch * wl.n_kv_heads, wl.topk_chunks
     ocache, ostamps = -np.ones((units, slots), np.int32), None
-    fixed = (PU.to_bits(t["A"]), PU.to_bits(t["B"]), ref_b["landmarks"], ref_b["landmark_chunk_ids"], ref_b["k_outlier"],
-             ref_b["v_outlier"], PU.to_bits(t["k_local"]), PU.to_bits(t["v_local"]), PU.to_bits(t["v"]),
-             t["pos_offset"].cpu().numpy())
+    fixed = (PU.to_bits(t["A"], kd), PU.to_bits(t["B"], kd), ref_b["landmarks"], ref_b["landmark_chunk_ids"],
+             ref_b["k_outlier"], ref_b["v_outlier"], PU.to_bits(t["k_local"], kd), PU.to_bits(t["v_local"], kd),
+             PU.to_bits(t["v"], kd), t["pos_offset"].cpu().numpy())
     for step in range(2):
         out, sel, _ = S.decode_step_cached(p, qs[step], t["A"], t["B"], lm, ids, ko, vo, t["k_local"], t["v_local"], t["v"],
                                            cache, t["pos_offset"], side_stream=torch.cuda.Stream())
