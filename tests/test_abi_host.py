@@ -57,13 +57,30 @@ def test_valid_params_and_workspace_sizes():
     dict(batch=0), dict(n_q_heads=9), dict(head_dim=80), dict(head_dim=127), dict(chunk_size=0), dict(chunk_size=65),
     dict(ctx_len=4100), dict(ctx_len=0), dict(rank=12), dict(rank=0), dict(rank=264), dict(topk_chunks=0),
     dict(topk_chunks=509), dict(n_outlier_chunks=-1), dict(n_outlier_chunks=2000), dict(local_len=-1),
-    dict(value_location=7), dict(softmax_scale=-1.0), dict(rope_theta=0.0), dict(n_q_heads=2 * 65, n_kv_heads=2),
+    dict(value_location=7), dict(kv_dtype=2), dict(kv_dtype=-1), dict(softmax_scale=-1.0), dict(rope_theta=0.0), dict(n_q_heads=2 * 65, n_kv_heads=2),
 ])
 def test_invalid_params_are_rejected(bad):
     p = S.Params(**{**GOOD, **bad})
     assert S.validate_params(p) == S.EINVAL
     assert S.last_error()
     assert S.decode_workspace_bytes(p) == 0
+
+
+def test_fp8_storage_halves_the_value_buffers():
+    """kv_dtype = FP8 E5M2: one byte per stored element in every size the library reports."""
+    host16 = S.Params(**{**GOOD, "value_location": S.VALUES_HOST})
+    host8 = S.Params(**{**GOOD, "value_location": S.VALUES_HOST, "kv_dtype": S.KV_FP8_E5M2})
+    assert S.validate_params(host8) == S.OK and S.validate_params(host8, for_decode=False) == S.OK
+    rows = 2 * 2 * 16 * 8 * 128                    # units * k * c * d staged value elements
+    assert S.decode_workspace_bytes(host16) - S.decode_workspace_bytes(host8) == rows
+    assert S.decode_workspace_bytes(S.Params(**{**GOOD, "kv_dtype": S.KV_FP8_E5M2})) == S.decode_workspace_bytes(S.Params(**GOOD))
+    st16, st8 = host16.c_struct(), host8.c_struct()
+    import ctypes as C
+    n16 = S.lib().shadowkv_value_cache_bytes(C.addressof(st16), 64)
+    n8 = S.lib().shadowkv_value_cache_bytes(C.addressof(st8), 64)
+    assert n16 == 2 * n8 == 2 * 2 * 64 * 8 * 128 * 2
+    # chunk means of the pre-filling step are kept in the storage type
+    assert S.build_workspace_bytes(S.Params(**GOOD)) - S.build_workspace_bytes(S.Params(**{**GOOD, "kv_dtype": 1})) == 2 * 2 * 512 * 128
 
 
 def test_build_ignores_decode_only_fields():
