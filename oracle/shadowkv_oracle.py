@@ -305,3 +305,37 @@ def append_chunk(p: OracleParams, k_pre, k_rope, v, B, A, landmarks, landmark_ch
     del keep
     if rc != 0:
         raise ValueError(f"oracle_append_chunk rejected its arguments (rc={rc})")
+
+
+def factorize_keys(p: OracleParams, k_pre) -> dict:
+    """First line of the pre-filling algorithm, A, B <- SVD(K): per sequence the thin singular value decomposition
+    K = Phi Sigma Psi^T of the pre-RoPE keys ``k_pre [b, s, h_kv*d]`` (stored bits, widened exactly to fp64; numpy's
+    LAPACK SVD is the library step), truncated to the ``p.rank`` largest singular values.  ``B = Psi^T`` laid out
+    ``[b, h_kv, r, d]`` (``B[h, rho, x] = Psi[h*d + x, rho]``), ``A = K Psi`` (``[b, capacity, r]``, rows beyond
+    ``ctx_len`` left zero), both rounded once to the storage type.  Sign convention (an SVD leaves the sign of each
+    singular pair open): the component of largest magnitude of every right singular vector is positive, ties to the
+    lowest index.  Also returns ``psi [b, r, D]`` (rows = right singular vectors), ``sigma [b, r]`` and the unrounded
+    ``A_f64 [b, s, r]``."""
+    b, h, d, s, r = p.batch, p.n_kv_heads, p.head_dim, p.ctx_len, p.rank
+    D = h * d
+    bits = as_bits(k_pre, p.kv_dtype)
+    assert bits.shape == (b, s, D), bits.shape
+    assert 1 <= r <= min(s, D)
+    widen = e5m2_bits_to_f64 if p.kv_dtype == 1 else bits_to_f64
+    rnd = f64_to_e5m2_bits if p.kv_dtype == 1 else f64_to_bits
+    psi = np.zeros((b, r, D))
+    sigma = np.zeros((b, r))
+    A64 = np.zeros((b, s, r))
+    for bi in range(b):
+        K = widen(bits[bi])
+        _, sv, vt = np.linalg.svd(K, full_matrices=False)      # singular values in descending order
+        v = vt[:r].copy()
+        lead = np.argmax(np.abs(v), axis=1)                    # first index of the largest magnitude
+        sign = np.where(v[np.arange(r), lead] < 0.0, -1.0, 1.0)
+        v *= sign[:, None]
+        psi[bi], sigma[bi] = v, sv[:r]
+        A64[bi] = K @ v.T
+    A = np.zeros((b, p.capacity, r), p.kv_numpy)
+    A[:, :s] = rnd(A64)
+    B = rnd(psi.reshape(b, r, h, d).transpose(0, 2, 1, 3))
+    return {"A": A, "B": np.ascontiguousarray(B), "psi": psi, "sigma": sigma, "A_f64": A64}

@@ -125,7 +125,7 @@ def _alloc(shape, dtype, device, pinned: bool) -> torch.Tensor:
 
 
 def generate(wl: Workload, device: Optional[str] = None, want_prefill: bool = True,
-             value_device: Optional[str] = None) -> Dict[str, torch.Tensor]:
+             value_device: Optional[str] = None, want_k_pre: bool = False) -> Dict[str, torch.Tensor]:
     """Draw one workload.  Returns bf16 tensors (ids int32):
 
     ``q_pool [n_queries, b, h_q, d]``, ``A [b, s, r]``, ``B [b, h_kv, r, d]``,
@@ -160,6 +160,8 @@ def generate(wl: Workload, device: Optional[str] = None, want_prefill: bool = Tr
     }
     if want_prefill:
         out["k_rope"] = torch.empty(b, hkv, s, d, dtype=bf, device=dev)
+    if want_k_pre:
+        out["k_pre"] = torch.empty(b, s, D, dtype=bf, device=dev)
     needle_dirs = None
     n_plant = max(1, (s // c) // 100)
     if wl.plant == "outliers" and want_prefill:
@@ -192,6 +194,8 @@ def generate(wl: Workload, device: Optional[str] = None, want_prefill: bool = Tr
             needle_dirs[bi] = dirs
         # 2. rank-r factors of the context keys (pre-filling algorithm, SVD line)
         ctx = k_pre[:s]
+        if want_k_pre:
+            out["k_pre"][bi] = ctx.to(bf)
         gram = (ctx.t() @ ctx).to(torch.float64)
         evals, evecs = torch.linalg.eigh(gram)
         psi = evecs[:, -r:].flip(-1).to(torch.float32)                  # [D, r], strongest first
