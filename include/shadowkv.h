@@ -222,6 +222,30 @@ int shadowkv_append_chunk(const shadowkv_params *params, const shadowkv_kv *k_pr
                           shadowkv_kv *A, shadowkv_kv *landmarks, int32_t *landmark_chunk_ids,
                           shadowkv_kv *value_store, void *stream);
 
+/*
+ * Alg. 1, first line: A, B <- SVD(K), the rank-r factors of the pre-RoPE keys of every sequence.  With
+ * K = Phi Sigma Psi^T the thin SVD of the [s, D = h_kv*d] key matrix of one sequence, truncated to the r largest
+ * singular values: B = Psi^T (reshaped [h_kv, r, d]: B[h, rho, x] = Psi[h*d + x, rho]) and A = K Psi = Phi Sigma
+ * (the low-rank states of section "High-throughput Decoding": keys are kept as K Psi and projected back with Psi^T).
+ * Singular vectors are defined up to sign; the convention here makes the component of largest magnitude of every
+ * right singular vector positive (ties: lowest index).  Computed from the Gram matrix K^T K (fp64) by subspace
+ * iteration with `n_iter` steps (0 => 16) on r + 32 vectors and a Rayleigh-Ritz step; accurate when sigma_r and
+ * sigma_(r+33) are apart (the convergence factor per step is (sigma_(r+33) / sigma_r)^2).
+ *
+ *   k_pre      dev      [b, s, h_kv*d] kv   pre-RoPE keys, heads side by side
+ *   A          dev out  [b, cap, r] kv      rows 0 .. s-1 written (fp64 accumulate, rounded once)
+ *   B          dev out  [b, h_kv, r, d] kv
+ *   psi_out    dev out  [b, r, h_kv*d] fp64 optional (NULL): the right singular vectors before rounding, as rows
+ *   sigma_out  dev out  [b, r] fp64         optional (NULL): singular values, largest first
+ *   workspace  dev      >= shadowkv_factorize_workspace_bytes(), 256-byte aligned
+ * Needs rank <= h_kv*d.  topk_chunks, local_len, n_outlier_chunks are ignored.  Enqueues several thousand small
+ * launches (one per dependent step of the orthogonalisation and of the Jacobi sweeps).
+ */
+int shadowkv_factorize_keys(const shadowkv_params *params, const shadowkv_kv *k_pre, shadowkv_kv *A,
+                            shadowkv_kv *B, double *psi_out, double *sigma_out, int32_t n_iter,
+                            void *workspace, size_t workspace_bytes, void *stream);
+size_t shadowkv_factorize_workspace_bytes(const shadowkv_params *params);
+
 /* Bytes of `value_cache` for the given shape and slot count (0 if either is invalid). */
 size_t shadowkv_value_cache_bytes(const shadowkv_params *params, int32_t cache_slots);
 

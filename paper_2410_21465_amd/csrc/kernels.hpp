@@ -123,4 +123,18 @@ hipError_t launch_append_chunk(const void* k_pre, const void* k_rope, const void
                                void* landmarks, int32_t* landmark_chunk_ids, void* value_store, int kv_bytes, int batch,
                                int hkv, int d, int s, int s_cap, int c, int r, int o, hipStream_t st);
 
+// ---- pre-filling algorithm, first line: A, B <- SVD(K) truncated to rank r (kernels_factorize.hip) ----
+struct FactorizePlan {
+  int m, mp;                // subspace width r + oversample (at most D), and the same rounded up to even
+  int nb;                   // 64-column blocks of the Gram matrix
+  int n_splits, tokens_per_split;
+  size_t part, G, Xt, Yt, W, V, Wsel, Psi_t, total;  // workspace offsets (bytes)
+};
+FactorizePlan plan_factorize(int batch, int s, int D, int r, int oversample);
+// k_pre [b, s, h_kv*d]; A [b, s_cap, r]; B [b, h_kv, r, d]; psi_out optional [b, r, D] fp64 (right singular vectors
+// as rows, after the sign convention); sigma_out optional [b, r] fp64 (singular values, strongest first)
+hipError_t launch_factorize(const void* k_pre, int kv_bytes, void* A, void* B, double* psi_out, double* sigma_out,
+                            char* ws, const FactorizePlan& pl, int batch, int hkv, int d, int s, int s_cap, int r,
+                            int n_iter, int n_sweeps, hipStream_t st);
+
 }  // namespace skv

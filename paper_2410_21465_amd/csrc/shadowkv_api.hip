@@ -558,6 +558,40 @@ int shadowkv_append_chunk(const shadowkv_params* params, const shadowkv_kv* k_pr
   return SHADOWKV_OK;
 }
 
+constexpr int kFactorOversample = 32;  // extra vectors carried by the subspace iteration
+constexpr int kFactorSweeps = 12;      // Jacobi sweeps of the Ritz step
+constexpr int kFactorIters = 16;       // default number of subspace iterations
+
+size_t shadowkv_factorize_workspace_bytes(const shadowkv_params* params) {
+  Shape sh;
+  if (check_params(params, false, &sh) != SHADOWKV_OK) return 0;
+  if (params->rank < 8 || params->rank > 256 || params->rank % 8 || params->rank > sh.hkv * sh.d) return 0;
+  return plan_factorize(sh.b, sh.s, sh.hkv * sh.d, params->rank, kFactorOversample).total;
+}
+
+int shadowkv_factorize_keys(const shadowkv_params* params, const shadowkv_kv* k_pre, shadowkv_kv* A, shadowkv_kv* B,
+                            double* psi_out, double* sigma_out, int32_t n_iter, void* workspace, size_t workspace_bytes,
+                            void* stream) {
+  Shape sh;
+  int rc = check_params(params, false, &sh);
+  if (rc != SHADOWKV_OK) return rc;
+  if (params->rank < 8 || params->rank > 256 || params->rank % 8)
+    return fail_inval("rank must be a multiple of 8 in [8, 256]");
+  if (params->rank > sh.hkv * sh.d) return fail_inval("rank %d exceeds the key width %d", params->rank, sh.hkv * sh.d);
+  if (n_iter < 0 || n_iter > 1000) return fail_inval("n_iter must be in [0, 1000] (0 = default)");
+  if (!k_pre || !A || !B) return fail_inval("k_pre, A and B must not be NULL");
+  if (!aligned16(k_pre) || !aligned16(A) || !aligned16(B) || !aligned16(psi_out))
+    return fail_inval("tensor pointers must be 16-byte aligned");
+  const FactorizePlan pl = plan_factorize(sh.b, sh.s, sh.hkv * sh.d, params->rank, kFactorOversample);
+  rc = check_workspace(workspace, workspace_bytes, pl.total);
+  if (rc != SHADOWKV_OK) return rc;
+  hipError_t e = launch_factorize(k_pre, sh.eb, A, B, psi_out, sigma_out, static_cast<char*>(workspace), pl, sh.b, sh.hkv,
+                                  sh.d, sh.s, sh.cap, params->rank, n_iter ? n_iter : kFactorIters, kFactorSweeps,
+                                  static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return fail_hip("factorize keys", e);
+  return SHADOWKV_OK;
+}
+
 size_t shadowkv_argtopk_workspace_bytes(int32_t units, int32_t n, int32_t k) {
   SelectPlan plan;
   if (units < 1 || units > 65535 || n < 1 || k < 1 || k > n || !plan_select(n, k, &plan)) return 0;

@@ -28,6 +28,7 @@ EXPORTS = (
     "shadowkv_status_string", "shadowkv_last_error", "shadowkv_version", "shadowkv_shutdown",
     "shadowkv_profile_begin", "shadowkv_profile_end", "shadowkv_decode_step_cached", "shadowkv_value_cache_bytes",
     "shadowkv_value_cache_reset", "shadowkv_append_chunk", "shadowkv_argtopk", "shadowkv_argtopk_workspace_bytes",
+    "shadowkv_factorize_keys", "shadowkv_factorize_workspace_bytes",
 )
 STAGES = ("score", "select", "gather_values", "attention")
 
@@ -79,6 +80,10 @@ def lib() -> C.CDLL:
         L.shadowkv_argtopk_workspace_bytes.argtypes = [i32, i32, i32]
         L.shadowkv_append_chunk.restype = i32
         L.shadowkv_append_chunk.argtypes = [vp] * 10
+        L.shadowkv_factorize_keys.restype = i32
+        L.shadowkv_factorize_keys.argtypes = [vp] * 6 + [i32, vp, sz, vp]
+        L.shadowkv_factorize_workspace_bytes.restype = sz
+        L.shadowkv_factorize_workspace_bytes.argtypes = [vp]
         L.shadowkv_build_workspace_bytes.restype = sz
         L.shadowkv_build_workspace_bytes.argtypes = [vp]
         L.shadowkv_decode_workspace_bytes.restype = sz
@@ -285,6 +290,32 @@ def append_chunk(p: Params, k_pre, k_rope, v, B, A, landmarks, landmark_chunk_id
     _check(lib().shadowkv_append_chunk(C.addressof(st), _ptr(k_pre), _ptr(k_rope), _ptr(v), _ptr(B), _ptr(A),
                                        _ptr(landmarks), _ptr(landmark_chunk_ids), _ptr(value_store),
                                        _stream_ptr(stream)))
+
+
+def factorize_keys(p: Params, k_pre: torch.Tensor, n_iter: int = 0, want_vectors: bool = False, workspace=None,
+                   stream=None) -> dict:
+    """First line of the pre-filling algorithm: rank-r factors of the pre-RoPE keys ``k_pre [b, s, h_kv*d]``.
+    Returns ``A [b, cap, r]`` and ``B [b, h_kv, r, d]`` in the storage type of the KV cache, and with
+    ``want_vectors`` also ``psi [b, r, h_kv*d]`` and ``sigma [b, r]`` (fp64)."""
+    b, h, d, r = p.batch, p.n_kv_heads, p.head_dim, p.rank
+    dev = k_pre.device
+    assert k_pre.dtype == p.kv_torch_dtype and tuple(k_pre.shape) == (b, p.ctx_len, h * d)
+    out = {"A": torch.empty(b, p.capacity, r, dtype=p.kv_torch_dtype, device=dev),
+           "B": torch.empty(b, h, r, d, dtype=p.kv_torch_dtype, device=dev),
+           "psi": torch.empty(b, r, h * d, dtype=torch.float64, device=dev) if want_vectors else None,
+           "sigma": torch.empty(b, r, dtype=torch.float64, device=dev) if want_vectors else None}
+    st = p.c_struct()
+    if workspace is None:
+        need = int(lib().shadowkv_factorize_workspace_bytes(C.addressof(st)))
+        if need == 0:
+            _check(lib().shadowkv_validate_params(C.addressof(st), 0))
+            raise ValueError("rank must be a multiple of 8 in [8, 256] and at most h_kv * d")
+        workspace = alloc_workspace(need, dev)
+    _check(lib().shadowkv_factorize_keys(C.addressof(st), _ptr(k_pre), _ptr(out["A"]), _ptr(out["B"]), _ptr(out["psi"]),
+                                         _ptr(out["sigma"]), int(n_iter), _ptr(workspace), workspace.numel(),
+                                         _stream_ptr(stream)))
+    out["workspace"] = workspace
+    return out
 
 
 def argtopk(scores: torch.Tensor, k: int, largest: bool = True, stream=None) -> torch.Tensor:
