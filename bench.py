@@ -71,6 +71,9 @@ def main() -> int:
                          "after the decode measurement (reported as append_chunk_ms)")
     ap.add_argument("--kv-dtype", choices=["bf16", "fp8"], default="bf16",
                     help="storage type of the KV-cache tensors: bf16, or FP8 E5M2 (the paper's second precision)")
+    ap.add_argument("--factorize", action="store_true",
+                    help="also time shadowkv_factorize_keys (the SVD line of the pre-filling algorithm) on the workload's "
+                         "pre-RoPE keys (reported as factorize_ms, with the Gram kernel's fp64 matrix rate)")
     ap.add_argument("--stage-values", action="store_true",
                     help="stage the selected values with the gather kernel even for an HBM store "
                          "(gives profiles a plain copy kernel of known size: k*c*d*2 bytes per unit each way)")
@@ -91,7 +94,7 @@ def main() -> int:
     dev = "cuda"
     t0 = time.time()
     print(f"[bench] drawing {wl.name}", file=sys.stderr, flush=True)
-    t = generate(wl, device=dev)
+    t = generate(wl, device=dev, want_k_pre=args.factorize)
     ctx_cap = wl.ctx_len + args.append * wl.chunk_size
     if args.append:
         t = with_capacity(t, wl, ctx_cap)
@@ -194,6 +197,24 @@ def main() -> int:
             miss.append(float(cache.miss_count.float().mean().item()) / wl.topk_chunks)
         hit_rate = 1.0 - sum(miss) / len(miss)
 
+    factorize = None
+    if args.factorize:   # A, B <- SVD(K) through the library (untimed part of set-up in the paper; timed here on request)
+        kp = t["k_pre"].to(torch.float8_e5m2) if fp8 else t["k_pre"]
+        pf = S.Params.from_workload(wl, kv_dtype=kv_dtype)
+        f = S.factorize_keys(pf, kp)
+        torch.cuda.synchronize()
+        ev0.record()
+        for _ in range(2):
+            S.factorize_keys(pf, kp, workspace=f["workspace"])
+        ev1.record()
+        torch.cuda.synchronize()
+        fms = ev0.elapsed_time(ev1) / 2
+        Dk = wl.key_width
+        nb = (Dk + 63) // 64
+        gram_flop = 2.0 * wl.batch * wl.ctx_len * (nb * (nb + 1) // 2) * 64 * 64
+        factorize = {"ms": fms, "gram_fp64_flop": gram_flop, "projection_fp64_flop": 2.0 * wl.batch * wl.ctx_len * Dk * wl.rank}
+        del f, kp
+
     append_ms = None
     if args.append:   # grow the context chunk by chunk (the step after decode once c tokens left the window)
         chunks = [generated_chunk(wl, t_bf16, i, device=dev) for i in range(min(args.append, 4))]
@@ -269,6 +290,7 @@ def main() -> int:
         "build_landmarks_ms": build_ms,
         "device_copy_gbps": copy_gbps,
         "append_chunk_ms": append_ms,
+        "factorize_keys": factorize,
         "setup_s": setup_s,
     }
     if wl.value_location == "host":

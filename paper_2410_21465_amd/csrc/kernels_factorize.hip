@@ -15,6 +15,7 @@
 // Operand layout of v_mfma_f64_16x16x4f64 as measured on gfx950: A lane l holds (m = l % 16, k = l / 16),
 // B lane l holds (n = l % 16, k = l / 16), result register j of lane l is (m = 4 j + l / 16, n = l % 16).
 #include <algorithm>
+#include <type_traits>
 
 #include "kernels.hpp"
 
@@ -22,21 +23,55 @@ namespace skv {
 
 typedef double f64x4 __attribute__((ext_vector_type(4)));
 
-// four consecutive stored elements starting at element index `at` of `base`, as doubles; zero when !ok
+// four consecutive stored elements starting at element index `at` of `base` (zero when !ok), kept as stored and
+// widened to fp64 when they are used: what a prefetch holds
 template <int EB>
-__device__ __forceinline__ void load4_f64(const void* base, size_t at, bool ok, double (&x)[4]) {
-  float f[4] = {0.f, 0.f, 0.f, 0.f};
-  if (ok) {
+struct Raw4 {
+  uint32_t w[EB == 2 ? 2 : 1];
+  __device__ __forceinline__ void load(const void* base, size_t at, bool ok) {
     if constexpr (EB == 2) {
-      const uint2 w = *reinterpret_cast<const uint2*>(static_cast<const bf16_t*>(base) + at);
-      f[0] = bf16_lo(w.x); f[1] = bf16_hi(w.x); f[2] = bf16_lo(w.y); f[3] = bf16_hi(w.y);
+      uint2 v = make_uint2(0u, 0u);
+      if (ok) v = *reinterpret_cast<const uint2*>(static_cast<const bf16_t*>(base) + at);
+      w[0] = v.x; w[1] = v.y;
     } else {
-      e5m2x4_to_f32(*reinterpret_cast<const uint32_t*>(static_cast<const uint8_t*>(base) + at), f);
+      w[0] = ok ? *reinterpret_cast<const uint32_t*>(static_cast<const uint8_t*>(base) + at) : 0u;
     }
   }
+  __device__ __forceinline__ void widen(double (&x)[4]) const {
+    float f[4];
+    if constexpr (EB == 2) { f[0] = bf16_lo(w[0]); f[1] = bf16_hi(w[0]); f[2] = bf16_lo(w[1]); f[3] = bf16_hi(w[1]); }
+    else e5m2x4_to_f32(w[0], f);
 #pragma unroll
-  for (int e = 0; e < 4; ++e) x[e] = (double)f[e];
-}
+    for (int e = 0; e < 4; ++e) x[e] = (double)f[e];
+  }
+};
+
+// sixteen consecutive stored elements (32 or 16 bytes), widened four at a time
+template <int EB>
+struct Raw16 {
+  uint32_t w[EB == 2 ? 8 : 4];
+  __device__ __forceinline__ void load(const void* base, size_t at, bool ok) {
+    uint4 lo = make_uint4(0u, 0u, 0u, 0u), hi = lo;
+    if (ok) {
+      if constexpr (EB == 2) {
+        const uint4* p = reinterpret_cast<const uint4*>(static_cast<const bf16_t*>(base) + at);
+        lo = p[0]; hi = p[1];
+      } else {
+        lo = *reinterpret_cast<const uint4*>(static_cast<const uint8_t*>(base) + at);
+      }
+    }
+    w[0] = lo.x; w[1] = lo.y; w[2] = lo.z; w[3] = lo.w;
+    if constexpr (EB == 2) { w[4] = hi.x; w[5] = hi.y; w[6] = hi.z; w[7] = hi.w; }
+  }
+  template <int U>
+  __device__ __forceinline__ void widen4(double (&x)[4]) const {
+    float f[4];
+    if constexpr (EB == 2) { f[0] = bf16_lo(w[2 * U]); f[1] = bf16_hi(w[2 * U]); f[2] = bf16_lo(w[2 * U + 1]); f[3] = bf16_hi(w[2 * U + 1]); }
+    else e5m2x4_to_f32(w[U], f);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) x[e] = (double)f[e];
+  }
+};
 
 // ---- 1. Gram matrix ---------------------------------------------------------------------------------
 // One wave per (pair of 64-column blocks bi <= bj, token split, sequence).  Tile (mt, nt) of the 64 x 64
@@ -62,24 +97,36 @@ __global__ __launch_bounds__(64) void gram_kernel(const void* __restrict__ K, do
 #pragma unroll
     for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = f64x4{0.0, 0.0, 0.0, 0.0};
 
-  double an[4], bn[4];
-  {
-    const int t = t_begin + kq;
-    load4_f64<EB>(K, base + (size_t)min(t, s - 1) * D + ci, oki && t < t_end, an);
-    load4_f64<EB>(K, base + (size_t)min(t, s - 1) * D + cj, okj && t < t_end, bn);
-  }
-  for (int t0 = t_begin; t0 < t_end; t0 += 4) {
-    double a[4], bb[4];
+  // 16 tokens (four matrix steps) per iteration; the next iteration's rows are requested before this one's 64
+  // matrix instructions, which is about the latency of a load
+  constexpr int PF = 4;
+  Raw4<EB> an[PF], bn[PF];
+  auto request = [&](int t0) {
 #pragma unroll
-    for (int e = 0; e < 4; ++e) { a[e] = an[e]; bb[e] = bn[e]; }
-    const int t = t0 + 4 + kq;  // next step's rows, requested before this step's matrix instructions
-    load4_f64<EB>(K, base + (size_t)min(t, s - 1) * D + ci, oki && t < t_end, an);
-    load4_f64<EB>(K, base + (size_t)min(t, s - 1) * D + cj, okj && t < t_end, bn);
+    for (int u = 0; u < PF; ++u) {
+      const int t = t0 + 4 * u + kq;
+      const size_t row = base + (size_t)min(t, s - 1) * D;
+      an[u].load(K, row + ci, oki && t < t_end);
+      bn[u].load(K, row + cj, okj && t < t_end);
+    }
+  };
+  request(t_begin);
+  for (int t0 = t_begin; t0 < t_end; t0 += 4 * PF) {
+    Raw4<EB> ac[PF], bc[PF];
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt)
+    for (int u = 0; u < PF; ++u) { ac[u] = an[u]; bc[u] = bn[u]; }
+    request(t0 + 4 * PF);
 #pragma unroll
-      for (int nt = 0; nt < 4; ++nt)
-        acc[mt][nt] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[mt], bb[nt], acc[mt][nt], 0, 0, 0);
+    for (int u = 0; u < PF; ++u) {
+      double a[4], bb[4];
+      ac[u].widen(a);
+      bc[u].widen(bb);
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt)
+          acc[mt][nt] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[mt], bb[nt], acc[mt][nt], 0, 0, 0);
+    }
   }
   double* out = part + ((size_t)split * batch + b) * D * D;
 #pragma unroll
@@ -296,19 +343,23 @@ __global__ __launch_bounds__(256) void emit_b_kernel(double* __restrict__ Psi_t,
 }
 
 // ---- 3. A = K Psi -----------------------------------------------------------------------------------------
-// One wave per (16 tokens, up to 80 rank columns, sequence): M = tokens, N = rank index, contraction over the
-// key columns, 16 per step (a lane's four consecutive stored elements are four contraction steps).
+// One wave per (48 tokens, up to 80 rank columns, sequence): M = tokens (three 16-row tiles), N = rank index,
+// contraction over the key columns (a lane's four consecutive stored elements are four contraction steps).  Every fragment of Psi read from L2 serves the three token tiles (120 accumulator registers: a fourth
+// tile makes the compiler move accumulators in and out of the matrix register file every step).
 template <int EB>
 __global__ __launch_bounds__(64) void project_kernel(const void* __restrict__ K, const double* __restrict__ Psi_t,
                                                      void* __restrict__ Aout, int s, int s_cap, int D, int r) {
-  constexpr int NT = 5;
+  constexpr int NT = 5, MT = 3;
   const int lane = threadIdx.x, mrow = lane & 15, kq = lane >> 4;
-  const int tok0 = blockIdx.x * 16, n0 = blockIdx.y * (16 * NT), b = blockIdx.z;
-  const int tok = min(tok0 + mrow, s - 1);
-  const size_t krow = ((size_t)b * s + tok) * D;
-  f64x4 acc[NT];
+  const int tok0 = blockIdx.x * (16 * MT), n0 = blockIdx.y * (16 * NT), b = blockIdx.z;
+  size_t krow[MT];
 #pragma unroll
-  for (int nt = 0; nt < NT; ++nt) acc[nt] = f64x4{0.0, 0.0, 0.0, 0.0};
+  for (int mt = 0; mt < MT; ++mt) krow[mt] = ((size_t)b * s + min(tok0 + 16 * mt + mrow, s - 1)) * D;
+  f64x4 acc[MT][NT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = f64x4{0.0, 0.0, 0.0, 0.0};
   const double* prow[NT];
   bool okn[NT];
 #pragma unroll
@@ -317,29 +368,70 @@ __global__ __launch_bounds__(64) void project_kernel(const void* __restrict__ K,
     okn[nt] = rho < r;
     prow[nt] = Psi_t + ((size_t)b * r + min(rho, r - 1)) * D;
   }
-  for (int c0 = 0; c0 < D; c0 += 16) {
-    const int col = c0 + 4 * kq;
-    double a[4];
-    load4_f64<EB>(K, krow + col, col < D, a);
+  // The contraction runs over 64 key columns per outer step: lane group kq owns columns c0 + 16 kq .. + 15 (one
+  // 32-byte piece of each of its token rows, requested a whole outer step ahead: it comes from HBM) and takes them
+  // four at a time; the Psi fragments of the next inner step (from L2) are requested before the matrix
+  // instructions of the current one.
+  Raw16<EB> kn[MT];
+  double pn[NT][4];
+  auto request_k = [&](int c0) {
+    const int col = c0 + 16 * kq;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) kn[mt].load(K, krow[mt] + col, col < D);
+  };
+  auto request_psi = [&](int col) {   // col = first of this lane group's four columns
+    const bool ok = col < D;
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-      double pb[4] = {0.0, 0.0, 0.0, 0.0};
-      if (okn[nt] && col < D) {
-        const double2 lo = *reinterpret_cast<const double2*>(prow[nt] + col);
-        const double2 hi = *reinterpret_cast<const double2*>(prow[nt] + col + 2);
-        pb[0] = lo.x; pb[1] = lo.y; pb[2] = hi.x; pb[3] = hi.y;
+      double2 lo = make_double2(0.0, 0.0), hi = make_double2(0.0, 0.0);
+      if (okn[nt] && ok) {
+        lo = *reinterpret_cast<const double2*>(prow[nt] + col);
+        hi = *reinterpret_cast<const double2*>(prow[nt] + col + 2);
       }
-#pragma unroll
-      for (int e = 0; e < 4; ++e) acc[nt] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[e], pb[e], acc[nt], 0, 0, 0);
+      pn[nt][0] = lo.x; pn[nt][1] = lo.y; pn[nt][2] = hi.x; pn[nt][3] = hi.y;
     }
+  };
+  request_k(0);
+  request_psi(16 * kq);
+#pragma unroll 1
+  for (int c0 = 0; c0 < D; c0 += 64) {
+    Raw16<EB> kc[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) kc[mt] = kn[mt];
+    request_k(c0 + 64);
+    auto inner = [&](auto u_tag, int next_col) {
+      constexpr int U = decltype(u_tag)::value;
+      double a[MT][4], pb[NT][4];
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) kc[mt].template widen4<U>(a[mt]);
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) pb[nt][e] = pn[nt][e];
+      request_psi(next_col);
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt)
+            acc[mt][nt] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[mt][e], pb[nt][e], acc[mt][nt], 0, 0, 0);
+    };
+    const int cb = c0 + 16 * kq;
+    inner(std::integral_constant<int, 0>{}, cb + 4);
+    inner(std::integral_constant<int, 1>{}, cb + 8);
+    inner(std::integral_constant<int, 2>{}, cb + 12);
+    inner(std::integral_constant<int, 3>{}, cb + 64);
   }
 #pragma unroll
-  for (int nt = 0; nt < NT; ++nt)
+  for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int t = tok0 + 4 * j + kq, rho = n0 + 16 * nt + mrow;
-      if (t < s && rho < r) kv_store_elem<EB>(Aout, ((size_t)b * s_cap + t) * r + rho, acc[nt][j]);
-    }
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int t = tok0 + 16 * mt + 4 * j + kq, rho = n0 + 16 * nt + mrow;
+        if (t < s && rho < r) kv_store_elem<EB>(Aout, ((size_t)b * s_cap + t) * r + rho, acc[mt][nt][j]);
+      }
 }
 
 // ---- launch sequence ----------------------------------------------------------------------------------------
@@ -358,11 +450,11 @@ FactorizePlan plan_factorize(int batch, int s, int D, int r, int oversample) {
   p.nb = (D + 63) / 64;
   const long pairs = (long)p.nb * (p.nb + 1) / 2;
   // enough waves to fill the chip: split the tokens when there are few column-block pairs
-  long splits = (4096 + pairs * batch - 1) / (pairs * batch);
+  long splits = (8192 + pairs * batch - 1) / (pairs * batch);
   const long max_splits = (s + 1023) / 1024;
   if (splits > max_splits) splits = max_splits;
   if (splits < 1) splits = 1;
-  p.tokens_per_split = (int)(((s + splits - 1) / splits + 3) / 4 * 4);
+  p.tokens_per_split = (int)(((s + splits - 1) / splits + 15) / 16 * 16);
   p.n_splits = (s + p.tokens_per_split - 1) / p.tokens_per_split;
   size_t off = 0;
   auto up = [](size_t x) { return (x + 255) / 256 * 256; };
@@ -420,7 +512,9 @@ hipError_t launch_factorize(const void* k_pre, int kv_bytes, void* A, void* B, d
   for (int it = 0; it < n_iter; ++it) {
     // Yt [m x D] = Xt [m x D] G [D x D]   (G is symmetric)
     if ((e = dgemm(Xt, G, Yt, m, D, D, D, 1, D, 1, D, (long)m * D, (long)D * D, (long)m * D, batch, st)) != hipSuccess) return e;
-    if ((e = orthonormalise(Yt)) != hipSuccess) return e;
+    // every second product only: two products square the condition number of the basis (~1e8 at most for the
+    // spectra this is meant for), which modified Gram-Schmidt still handles; the last basis is done twice
+    if (((it & 1) || it + 1 == n_iter) && (e = orthonormalise(Yt)) != hipSuccess) return e;
     if (it + 1 == n_iter && (e = orthonormalise(Yt)) != hipSuccess) return e;  // once more before the Ritz step
     double* tmp = Xt; Xt = Yt; Yt = tmp;
   }
@@ -451,7 +545,7 @@ hipError_t launch_factorize(const void* k_pre, int kv_bytes, void* A, void* B, d
   else hipLaunchKernelGGL(emit_b_kernel<2>, dim3(r, batch), dim3(256), 0, st, Psi_t, B, D, r, hkv, d);
   SKV_CHECK();
   {
-    dim3 grid((s + 15) / 16, (r + 79) / 80, batch);
+    dim3 grid((s + 47) / 48, (r + 79) / 80, batch);
     if (kv_bytes == 1) hipLaunchKernelGGL(project_kernel<1>, grid, dim3(64), 0, st, k_pre, Psi_t, A, s, s_cap, D, r);
     else hipLaunchKernelGGL(project_kernel<2>, grid, dim3(64), 0, st, k_pre, Psi_t, A, s, s_cap, D, r);
     SKV_CHECK();
