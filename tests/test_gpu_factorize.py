@@ -104,35 +104,39 @@ def test_rejects_bad_arguments():
 
 
 @pytest.mark.timeout(900)
-def test_full_size_sequence_by_properties():
-    """One 128K-token sequence of the Llama-3-8B-shaped workload (D = 1024, r = 160): the LAPACK SVD of a 131072 x 1024
-    matrix is out of reach of the test budget, so what holds at any size is checked against fp64 numpy on the same
-    keys: orthonormal right singular vectors, Ritz residuals at rounding level (K^T K psi = sigma^2 psi), the captured
+@pytest.mark.parametrize("name,kd", [("c3-hbm", 0), ("c5", 0), ("c4", 0), ("c2", 1)])
+def test_full_size_sequence_by_properties(name, kd):
+    """One sequence of a benchmark workload at full length (c3: 128K tokens x 1024, c5: 128K x 3072, c4: 1M x 256; c2
+    with FP8 keys), r = 160: the LAPACK SVD of such a matrix is out of reach of the test budget, so what holds at any
+    size is checked against fp64 numpy on the same keys: orthonormal right singular vectors, Ritz residuals at rounding level (K^T K psi = sigma^2 psi), the captured
     energy equal to the sum of the 160 largest eigenvalues of the Gram matrix (Eckart-Young), and sampled rows of A and
     all of B equal to the roundings of K psi and psi."""
     from paper_2410_21465_amd.workloads import CONFIGS
-    wl = CONFIGS["c3-hbm"].scaled(batch=1, n_queries=1)
+    wl = CONFIGS[name].scaled(batch=1, n_queries=1, value_location="hbm")
+    print(f"\n[case] kv_dtype {kd} {wl}", flush=True)
     t = generate(wl, device="cuda", want_prefill=False, want_k_pre=True)
-    gp = S.Params.from_workload(wl)
-    got = S.factorize_keys(gp, t["k_pre"], want_vectors=True)
+    k_pre = t["k_pre"].to(torch.float8_e5m2) if kd else t["k_pre"]
+    gp = S.Params.from_workload(wl, kv_dtype=kd)
+    got = S.factorize_keys(gp, k_pre, want_vectors=True)
     torch.cuda.synchronize()
     psi, sig = got["psi"][0].cpu().numpy(), got["sigma"][0].cpu().numpy()
-    K = PU.kv_to_f64(PU.to_bits(t["k_pre"]))[0]
+    K = PU.kv_to_f64(PU.to_bits(k_pre, kd))[0]
     r = wl.rank
     assert np.abs(psi @ psi.T - np.eye(r)).max() < 1e-12
     G = K.T @ K
     lam = np.linalg.eigvalsh(G)[::-1]
     np.testing.assert_allclose(sig ** 2, lam[:r], rtol=1e-9)
     resid = np.abs(psi @ G - (sig ** 2)[:, None] * psi).max()
-    print(f"[svd] full size: max Ritz residual {resid:.3e} (lambda_1 = {lam[0]:.3e}, lambda_r = {lam[r - 1]:.3e})", flush=True)
+    print(f"[svd] {name}: max Ritz residual {resid:.3e} (lambda_1 = {lam[0]:.3e}, lambda_r = {lam[r - 1]:.3e})", flush=True)
     assert resid <= 1e-9 * lam[0]
     captured = (sig ** 2).sum()
     assert abs(captured - lam[:r].sum()) <= 1e-10 * lam[:r].sum()
     lead = np.argmax(np.abs(psi), axis=1)
     assert np.all(psi[np.arange(r), lead] > 0)
-    np.testing.assert_array_equal(PU.to_bits(got["B"])[0], O.f64_to_bits(psi.reshape(r, wl.n_kv_heads, wl.head_dim).transpose(1, 0, 2)))
+    np.testing.assert_array_equal(PU.to_bits(got["B"], kd)[0],
+                                  PU.kv_round(psi.reshape(r, wl.n_kv_heads, wl.head_dim).transpose(1, 0, 2), kd))
     rows = np.random.default_rng(0).choice(wl.ctx_len, size=512, replace=False)
-    want = O.f64_to_bits(K[rows] @ psi.T)
-    gA = PU.to_bits(got["A"])[0][rows]
+    want = PU.kv_round(K[rows] @ psi.T, kd)
+    gA = PU.to_bits(got["A"], kd)[0][rows]
     diff = gA != want
-    assert diff.mean() < 1e-3 and ulp_distance(gA, want, 0).max() <= 1
+    assert diff.mean() < 1e-3 and ulp_distance(gA, want, kd).max() <= 1
