@@ -257,7 +257,7 @@ int shadowkv_profile_end(double* stage_ms, int* n_steps) {
   return rc;
 }
 
-int shadowkv_version(void) { return 300; }
+int shadowkv_version(void) { return 400; }
 
 const char* shadowkv_status_string(int status) {
   switch (status) {

@@ -120,6 +120,26 @@ def test_calls_reject_null_and_bad_workspace_without_a_gpu():
     assert rc == S.EINVAL
 
 
+def test_factorize_keys_rejects_bad_arguments_without_a_gpu():
+    lib = S.lib()
+    fake = C.c_void_p(0x1000)
+    p = S.Params(**GOOD)
+    st = p.c_struct()
+    need = lib.shadowkv_factorize_workspace_bytes(C.addressof(st))
+    # Gram matrix and its split partials (fp64, 256 x 256 per sequence) are the floor of the size
+    assert need >= 2 * 2 * 256 * 256 * 8 and need % 256 == 0
+    call = lib.shadowkv_factorize_keys
+    assert call(C.addressof(st), None, fake, fake, None, None, 0, fake, need, None) == S.EINVAL           # NULL keys
+    assert call(C.addressof(st), fake, fake, fake, C.c_void_p(0x1008), None, 0, fake, need, None) == S.EINVAL  # misaligned
+    assert call(C.addressof(st), fake, fake, fake, None, None, -1, fake, need, None) == S.EINVAL          # n_iter
+    assert call(C.addressof(st), fake, fake, fake, None, None, 0, None, need, None) == S.EWORKSPACE
+    assert call(C.addressof(st), fake, fake, fake, None, None, 0, fake, need - 256, None) == S.EWORKSPACE
+    wide = S.Params(**{**GOOD, "rank": 256, "n_kv_heads": 1, "n_q_heads": 8}).c_struct()                 # r > h_kv * d
+    assert lib.shadowkv_factorize_workspace_bytes(C.addressof(wide)) == 0
+    assert call(C.addressof(wide), fake, fake, fake, None, None, 0, fake, 1 << 40, None) == S.EINVAL
+    assert "key width" in S.last_error()
+
+
 def test_append_chunk_rejects_a_full_context_and_bad_capacity():
     lib = S.lib()
     fake = C.c_void_p(0x1000)
