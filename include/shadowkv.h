@@ -2,8 +2,8 @@
  * libshadowkv -- ShadowKV decode hot path on one MI355X (gfx950), C ABI.
  *
  * Two main operations, both enqueue-only on caller-owned HIP streams (further down: the decode step
- * with a chunk cache of an offloaded value store, the append of generated tokens to the context, and
- * the ArgTopK primitive on its own):
+ * with a chunk cache of an offloaded value store, the append of generated tokens to the context, the
+ * SVD line of the pre-filling algorithm, and the ArgTopK primitive on its own):
  *
  *   shadowkv_build_landmarks  pre-filling algorithm (Alg. 1) after its SVD
  *                             line: chunk means of the post-RoPE keys,
