@@ -7,7 +7,7 @@
 //      elements are exact, the sum is fp64) -- the dense contraction, 2 s D^2 flops, K streamed once per
 //      column-block pair; only blocks on and above the diagonal are formed, gram_finish sums the token
 //      splits and mirrors;
-//   2. subspace iteration on m = r + oversample vectors (X <- orth(G X), modified Gram-Schmidt), then one
+//   2. subspace iteration on m = r + oversample vectors (X <- orth(G X), modified Gram-Schmidt in groups), then one
 //      Rayleigh-Ritz step: T = X^T G X, eigenvectors of the small T by one-sided Jacobi rotations, the r
 //      largest kept -- all fp64, small, one launch per dependent step;
 //   3. sign convention (largest-magnitude component positive), B written, and project_kernel: A = K Psi on
@@ -225,7 +225,102 @@ __global__ __launch_bounds__(256) void subspace_init_kernel(double* __restrict__
   Xt[i] = (double)(int64_t)(z >> 11) * (1.0 / 4503599627370496.0) - 1.0;  // 53 bits -> [-1, 1)
 }
 
-// modified Gram-Schmidt, step j: every later vector loses its component along vector j (not yet normalised)
+// sums of NV values per thread over the 256 threads of the workgroup (result in every thread)
+template <int NV>
+__device__ __forceinline__ void block_sum_multi(double (&v)[NV], double (*sm)[NV]) {
+  const int wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) v[i] = wave_sum_f64(v[i]);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0)
+#pragma unroll
+    for (int i = 0; i < NV; ++i) sm[wave][i] = v[i];
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < NV; ++i) v[i] = sm[0][i] + sm[1][i] + sm[2][i] + sm[3][i];
+}
+
+// Modified Gram-Schmidt in groups of Q vectors (vectors are not normalised until the end), two launches per group
+// instead of one per vector.  First the Q pivots j .. j+q-1 are made orthogonal among themselves by one workgroup
+// per sequence that keeps them in registers (EPT elements per thread and vector) ...
+template <int Q, int EPT>
+__global__ __launch_bounds__(256) void mgs_pivots_kernel(double* __restrict__ Xt, int D, int m, int j, int q) {
+  __shared__ double sm[4][Q];
+  double* X0 = Xt + ((size_t)blockIdx.x * m + j) * D;
+  double p[Q][EPT];
+#pragma unroll
+  for (int a = 0; a < Q; ++a)
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+      const int x = threadIdx.x + 256 * e;
+      p[a][e] = (a < q && x < D) ? X0[(size_t)a * D + x] : 0.0;
+    }
+#pragma unroll
+  for (int a = 0; a + 1 < Q; ++a) {
+    double v[Q];  // v[a] = |p_a|^2, v[b] = p_a . p_b for b > a
+#pragma unroll
+    for (int bb = 0; bb < Q; ++bb) {
+      v[bb] = 0.0;
+      if (bb >= a)
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) v[bb] = fma(p[a][e], p[bb][e], v[bb]);
+    }
+    block_sum_multi<Q>(v, sm);
+    if (v[a] > 0.0) {
+#pragma unroll
+      for (int bb = a + 1; bb < Q; ++bb) {
+        const double f = v[bb] / v[a];
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) p[bb][e] = fma(-f, p[a][e], p[bb][e]);
+      }
+    }
+  }
+#pragma unroll
+  for (int a = 1; a < Q; ++a)
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+      const int x = threadIdx.x + 256 * e;
+      if (a < q && x < D) X0[(size_t)a * D + x] = p[a][e];
+    }
+}
+// ... then every later vector k loses its components along the q pivots, one after the other
+template <int Q, int EPT>
+__global__ __launch_bounds__(256) void mgs_project_kernel(double* __restrict__ Xt, int D, int m, int j, int q) {
+  __shared__ double sm[4][2];
+  const int k = j + q + blockIdx.x, b = blockIdx.y;
+  const double* P0 = Xt + ((size_t)b * m + j) * D;
+  double* xk = Xt + ((size_t)b * m + k) * D;
+  double x[EPT];
+#pragma unroll
+  for (int e = 0; e < EPT; ++e) {
+    const int c = threadIdx.x + 256 * e;
+    x[e] = c < D ? xk[c] : 0.0;
+  }
+#pragma unroll
+  for (int a = 0; a < Q; ++a) {
+    if (a >= q) break;
+    double pa[EPT], v[2] = {0.0, 0.0};
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+      const int c = threadIdx.x + 256 * e;
+      pa[e] = c < D ? P0[(size_t)a * D + c] : 0.0;
+      v[0] = fma(pa[e], pa[e], v[0]);
+      v[1] = fma(pa[e], x[e], v[1]);
+    }
+    block_sum_multi<2>(v, sm);
+    if (v[0] > 0.0) {
+      const double f = v[1] / v[0];
+#pragma unroll
+      for (int e = 0; e < EPT; ++e) x[e] = fma(-f, pa[e], x[e]);
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < EPT; ++e) {
+    const int c = threadIdx.x + 256 * e;
+    if (c < D) xk[c] = x[e];
+  }
+}
+// key widths beyond what the grouped kernels hold in registers: one launch per vector
 __global__ __launch_bounds__(256) void mgs_step_kernel(double* __restrict__ Xt, int D, int m, int j) {
   __shared__ double sm[4];
   const int k = j + 1 + blockIdx.x, b = blockIdx.y;
@@ -503,11 +598,28 @@ hipError_t launch_factorize(const void* k_pre, int kv_bytes, void* A, void* B, d
   hipLaunchKernelGGL(subspace_init_kernel, dim3((unsigned)((nx + 255) / 256)), dim3(256), 0, st, Xt, nx);
   SKV_CHECK();
   auto orthonormalise = [&](double* X) -> hipError_t {
-    for (int j = 0; j + 1 < m; ++j) {
-      hipLaunchKernelGGL(mgs_step_kernel, dim3(m - 1 - j, batch), dim3(256), 0, st, X, D, m, j);
-      hipError_t err = hipGetLastError();
-      if (err != hipSuccess) return err;
+    hipError_t err = hipSuccess;
+    if (D <= 1024) {          // groups of 8 vectors, 4 elements per thread
+      for (int j = 0; j < m && err == hipSuccess; j += 8) {
+        const int q = std::min(8, m - j);
+        hipLaunchKernelGGL((mgs_pivots_kernel<8, 4>), dim3(batch), dim3(256), 0, st, X, D, m, j, q);
+        if (j + q < m) hipLaunchKernelGGL((mgs_project_kernel<8, 4>), dim3(m - j - q, batch), dim3(256), 0, st, X, D, m, j, q);
+        err = hipGetLastError();
+      }
+    } else if (D <= 3072) {   // groups of 4 vectors, 12 elements per thread
+      for (int j = 0; j < m && err == hipSuccess; j += 4) {
+        const int q = std::min(4, m - j);
+        hipLaunchKernelGGL((mgs_pivots_kernel<4, 12>), dim3(batch), dim3(256), 0, st, X, D, m, j, q);
+        if (j + q < m) hipLaunchKernelGGL((mgs_project_kernel<4, 12>), dim3(m - j - q, batch), dim3(256), 0, st, X, D, m, j, q);
+        err = hipGetLastError();
+      }
+    } else {
+      for (int j = 0; j + 1 < m && err == hipSuccess; ++j) {
+        hipLaunchKernelGGL(mgs_step_kernel, dim3(m - 1 - j, batch), dim3(256), 0, st, X, D, m, j);
+        err = hipGetLastError();
+      }
     }
+    if (err != hipSuccess) return err;
     hipLaunchKernelGGL(normalize_rows_kernel, dim3(batch * m), dim3(256), 0, st, X, D);
     return hipGetLastError();
   };
