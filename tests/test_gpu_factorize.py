@@ -28,6 +28,9 @@ CASES = [
     (_wl("svd-d128x2-r64", head_dim=128, rank=64, ctx_len=4096, batch=1), 0),
     (_wl("svd-d64x3-ragged", n_q_heads=3, n_kv_heads=3, rank=24, ctx_len=1001 * 3, chunk_size=3), 0),
     (_wl("svd-fp8", head_dim=128, rank=48, ctx_len=2048), 1),
+    # key widths above 1024 and above 3072 take the other two orthogonalisation paths
+    (_wl("svd-wide-2048", batch=1, n_q_heads=16, n_kv_heads=16, head_dim=128, rank=64, ctx_len=4096), 0),
+    (_wl("svd-wide-4096", batch=1, n_q_heads=32, n_kv_heads=32, head_dim=128, rank=32, ctx_len=2048), 0),
 ]
 
 
