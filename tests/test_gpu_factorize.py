@@ -143,3 +143,28 @@ def test_full_size_sequence_by_properties(name, kd):
     gA = PU.to_bits(got["A"], kd)[0][rows]
     diff = gA != want
     assert diff.mean() < 1e-3 and ulp_distance(gA, want, kd).max() <= 1
+
+
+def test_degenerate_keys_give_finite_factors():
+    """Keys of rank 8 factored at rank 16, and all-zero keys: no NaN or Inf anywhere, the spare singular values are
+    zero, and A B still reconstructs the keys (up to the rounding of the factors)."""
+    wl = _wl("svd-degenerate", batch=2, rank=16, ctx_len=1024)
+    D = wl.n_kv_heads * wl.head_dim
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    left = torch.randn(wl.ctx_len, 8, generator=gen, device="cuda")
+    right = torch.randn(8, D, generator=gen, device="cuda")
+    k = torch.zeros(2, wl.ctx_len, D, dtype=torch.bfloat16, device="cuda")
+    k[0] = (left @ right).to(torch.bfloat16)                 # rounding adds a little full-rank noise at the 2^-9 level
+    gp = S.Params.from_workload(wl)
+    got = S.factorize_keys(gp, k, want_vectors=True)
+    torch.cuda.synchronize()
+    for name in ("psi", "sigma"):
+        assert torch.isfinite(got[name]).all(), name
+    A, B = got["A"].float(), got["B"].float()
+    assert torch.isfinite(A).all() and torch.isfinite(B).all()
+    sig = got["sigma"].cpu().numpy()
+    assert np.all(sig[1] == 0.0) and not A[1].any()
+    assert sig[0, 7] > 50 * sig[0, 8]                        # eight real directions, then the rounding noise
+    rec = torch.einsum("sr,rx->sx", A[0], B[0].permute(1, 0, 2).reshape(wl.rank, D))
+    err = (rec - k[0].float()).norm() / k[0].float().norm()
+    assert err < 1e-2, float(err)
