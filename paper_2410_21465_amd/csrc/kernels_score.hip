@@ -135,15 +135,120 @@ __global__ __launch_bounds__(256) void score_kernel(const bf16_t* __restrict__ q
   }
 }
 
+// Groups of 16 query heads per KV head (or a multiple): the 16x16x4 form of the fp64 matrix instruction takes all
+// 16 heads at once (A lane l = (head l % 16, k-slot l / 16), B lane l = (row l % 16, k-slot l / 16), result register j
+// of lane l = (head 4 j + l / 16, row l % 16); measured on gfx950), so every landmark element is loaded and widened
+// once instead of once per four heads.  Same tiles, same logits (exact sum, one rounding) and partials as above.
+typedef double f64x4_t __attribute__((ext_vector_type(4)));
+template <int D, int EB>
+__global__ __launch_bounds__(256) void score_kernel_g16(const bf16_t* __restrict__ q, const uint8_t* __restrict__ L,
+                                                        float* __restrict__ logits, double2* __restrict__ partials,
+                                                        int hq, int hkv, int G, int n_c, int nc_stride, int n_tiles,
+                                                        double scale) {
+  constexpr int PB = (EB == 2 || D % 64 == 0) ? 16 : 8;
+  constexpr int PE = PB / EB, NI = D / (4 * PE), PW = PB / 4;
+  __shared__ double2 wred[4][16];
+  const int unit = blockIdx.y, tile = blockIdx.x, g0 = blockIdx.z * 16;
+  const int b = unit / hkv, h = unit % hkv;
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int kq = lane >> 4, rl = lane & 15;
+  const size_t head0 = (size_t)b * hq + (size_t)h * G + g0;
+  const uint8_t* Lu = L + (size_t)unit * nc_stride * D * EB;
+  const int row0 = tile * kScoreTile + wave * kWave;
+  uint32_t w[4][NI][PW];
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    const int r = row0 + t * 16 + rl;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+#pragma unroll
+      for (int x = 0; x < PW; ++x) w[t][i][x] = 0u;
+      if (r < n_c) {
+        const uint8_t* src = Lu + (size_t)r * D * EB + (size_t)(4 * PE * i + PE * kq) * EB;
+        if constexpr (PW == 4) {
+          const uint4 v = *reinterpret_cast<const uint4*>(src);
+          w[t][i][0] = v.x; w[t][i][1] = v.y; w[t][i][2] = v.z; w[t][i][3] = v.w;
+        } else {
+          const uint2 v = *reinterpret_cast<const uint2*>(src);
+          w[t][i][0] = v.x; w[t][i][1] = v.y;
+        }
+      }
+    }
+  }
+  double qa[NI][PE];  // head g0 + rl, the elements this lane's k-slot meets
+  {
+    const bf16_t* qp = q + (head0 + rl) * D + PE * kq;
+#pragma unroll
+    for (int i = 0; i < NI; ++i)
+#pragma unroll
+      for (int e8 = 0; e8 < PE / 8; ++e8) {
+        float x[8];
+        load_bf16_row<8>(qp + 4 * PE * i + 8 * e8, x);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qa[i][8 * e8 + e] = (double)x[e];
+      }
+  }
+  double m[4], s[4];   // heads g0 + 4 j + kq
+#pragma unroll
+  for (int j = 0; j < 4; ++j) { m[j] = -INFINITY; s[j] = 0.0; }
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    f64x4_t acc = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int i = 0; i < NI; ++i)
+#pragma unroll
+      for (int x = 0; x < PW; ++x) {
+        if constexpr (EB == 2) {
+          acc = __builtin_amdgcn_mfma_f64_16x16x4f64(qa[i][2 * x], (double)bf16_lo(w[t][i][x]), acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f64_16x16x4f64(qa[i][2 * x + 1], (double)bf16_hi(w[t][i][x]), acc, 0, 0, 0);
+        } else {
+          float f[4];
+          e5m2x4_to_f32(w[t][i][x], f);
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(qa[i][4 * x + e], (double)f[e], acc, 0, 0, 0);
+        }
+      }
+    const int r = row0 + t * 16 + rl;
+    if (r < n_c) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float p32 = (float)(acc[j] * scale);   // the logit: exact dot product, rounded once to fp32
+        logits[(head0 + 4 * j + kq) * n_c + r] = p32;
+        lse_merge(m[j], s[j], (double)p32, 1.0);
+      }
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+#pragma unroll
+    for (int x = 8; x >= 1; x >>= 1) lse_merge(m[j], s[j], shfl_xor_f64(m[j], x), shfl_xor_f64(s[j], x));
+    if (rl == 0) wred[wave][4 * j + kq] = make_double2(m[j], s[j]);
+  }
+  __syncthreads();
+  if (threadIdx.x < 16) {
+    const int g = threadIdx.x;
+    double M = -INFINITY, S = 0.0;
+#pragma unroll
+    for (int wv = 0; wv < 4; ++wv) lse_merge(M, S, wred[wv][g].x, wred[wv][g].y);
+    partials[(head0 + g) * n_tiles + tile] = make_double2(M, S);
+  }
+}
+
 hipError_t launch_score(const bf16_t* q, const void* landmarks, int kv_bytes, float* logits, double2* partials,
                         int batch, int hq, int hkv, int d, int n_c, int nc_stride, double scale, hipStream_t st) {
   const int G = hq / hkv;
   const int n_tiles = (n_c + kScoreTile - 1) / kScoreTile;
-  dim3 grid(n_tiles, batch * hkv, (G + 3) / 4), block(256);
+  const bool g16 = G % 16 == 0;
+  dim3 grid(n_tiles, batch * hkv, g16 ? G / 16 : (G + 3) / 4), block(256);
   const uint8_t* L = static_cast<const uint8_t*>(landmarks);
-#define SKV_SCORE(D_, EB_)                                                                                       \
-  hipLaunchKernelGGL((score_kernel<D_, EB_>), grid, block, 0, st, q, L, logits, partials, hq, hkv, G, n_c, nc_stride, \
-                     n_tiles, scale)
+#define SKV_SCORE(D_, EB_)                                                                                            \
+  do {                                                                                                                \
+    if (g16) hipLaunchKernelGGL((score_kernel_g16<D_, EB_>), grid, block, 0, st, q, L, logits, partials, hq, hkv, G,   \
+                                n_c, nc_stride, n_tiles, scale);                                                      \
+    else hipLaunchKernelGGL((score_kernel<D_, EB_>), grid, block, 0, st, q, L, logits, partials, hq, hkv, G, n_c,      \
+                            nc_stride, n_tiles, scale);                                                               \
+  } while (0)
   switch (d * 4 + kv_bytes) {
     case 64 * 4 + 2: SKV_SCORE(64, 2); break;
     case 96 * 4 + 2: SKV_SCORE(96, 2); break;
