@@ -625,13 +625,34 @@ __global__ __launch_bounds__(D) void attn_combine_kernel(const float* __restrict
   const size_t head = blockIdx.x;
   const int e = threadIdx.x;
   const float2* ml = part_ml + head * n_splits;
+  const float* pa = part_acc + head * n_splits * D + e;
+  // eight partial states at a time: their loads are issued together, the folding keeps the order of the splits
   float M = -INFINITY;
-  for (int sp = 0; sp < n_splits; ++sp) M = fmaxf(M, ml[sp].x);
+  for (int s0 = 0; s0 < n_splits; s0 += 8) {
+    float mx[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) mx[u] = ml[min(s0 + u, n_splits - 1)].x;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) M = fmaxf(M, mx[u]);
+  }
   float num = 0.f, den = 0.f;
-  for (int sp = 0; sp < n_splits; ++sp) {
-    const float sc = (ml[sp].x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ml[sp].x - M);
-    num = fmaf(part_acc[(head * n_splits + sp) * D + e], sc, num);
-    den = fmaf(ml[sp].y, sc, den);
+  for (int s0 = 0; s0 < n_splits; s0 += 8) {
+    float2 st[8];
+    float av[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int sp = min(s0 + u, n_splits - 1);
+      st[u] = ml[sp];
+      av[u] = pa[(size_t)sp * D];
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      if (s0 + u < n_splits) {
+        const float sc = (st[u].x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(st[u].x - M);
+        num = fmaf(av[u], sc, num);
+        den = fmaf(st[u].y, sc, den);
+      }
+    }
   }
   out[head * D + e] = f32_to_bf16(num / den);
 }
