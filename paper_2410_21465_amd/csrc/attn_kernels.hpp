@@ -5,7 +5,7 @@
 //
 // Split-K flash-decode.  The selected tokens of a (batch, KV head) unit are cut into splits; one
 // workgroup owns one split plus an equal share of the unit's resident tokens (outliers, recent),
-// for up to 8 query heads of the GQA group, so K and V are touched once per group.
+// for up to 4 query heads of the GQA group (8 made the kernel spill), so K and V are touched once per four heads.
 //   * resident rows: K rows are read as stored (bf16);
 //   * selected rows: the keys never exist in memory.  Each wave gathers 16 rows of A straight
 //     into MFMA operand layout, multiplies by B^T staged in LDS (v_mfma_f32_16x16x32_bf16, fp32
@@ -686,7 +686,6 @@ static hipError_t launch_keys_d(const AttnArgs& a, hipStream_t st) {
   const size_t lds = (size_t)D * a.rp * sizeof(bf16_t) + 2 * ((size_t)a.sparse_split_len / a.c + 2) * sizeof(int);
   dim3 grid(a.n_splits, a.batch * a.hkv, G / gh);
   switch (gh) {
-    case 8: return launch_sparse_ks<D, 8, KEYS_ONLY, EB>(a, grid, lds, st);
     case 4: return launch_sparse_ks<D, 4, KEYS_ONLY, EB>(a, grid, lds, st);
     case 2: return launch_sparse_ks<D, 2, KEYS_ONLY, EB>(a, grid, lds, st);
     default: return launch_sparse_ks<D, 1, KEYS_ONLY, EB>(a, grid, lds, st);

@@ -103,7 +103,7 @@ struct AttnArgs {
   float scale_log2;         // softmax scale * log2(e)
   RopeFreqs freqs;
 };
-inline int attention_heads_per_group(int G) { return (G % 8 == 0) ? 8 : (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1; }
+inline int attention_heads_per_group(int G) { return (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1; }
 hipError_t launch_attention(const AttnArgs& a, hipStream_t st);         // values readable now: one fused kernel
 hipError_t launch_attention_keys(const AttnArgs& a, hipStream_t st);    // two-phase path, before the values arrive
 hipError_t launch_attention_values(const AttnArgs& a, hipStream_t st);  // two-phase path, after
