@@ -15,7 +15,8 @@ CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libshadowkv.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
-# Packed fp32 VALU ops are switched off for device code on purpose.
+# Packed fp32 VALU ops are switched off for device code on purpose: some of their forms have given wrong
+# results on this hardware without any error.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
