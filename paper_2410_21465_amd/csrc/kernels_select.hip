@@ -20,15 +20,28 @@ constexpr int kSelNT = 512;
 __device__ __forceinline__ double exp_neg_fast(double x) {
   return (double)__builtin_amdgcn_exp2f((float)(x * 1.4426950408889634074));
 }
+// NB of a lane's pairs are requested together (long contexts have many tiles per head).
+template <int NB>
 __device__ void unit_lse(const double2* __restrict__ part, int n_tiles, int G, double* lse_sm) {
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   for (int g = wave; g < G; g += kSelNT / kWave) {
     const double2* p = part + (size_t)g * n_tiles;
     double m = -INFINITY, s = 0.0;   // running (max, sum exp(. - max)) of this lane's tiles
-    for (int t = lane; t < n_tiles; t += kWave) {
-      const double2 v = p[t];
-      if (v.x > m) { s = s * exp_neg_fast(m - v.x) + v.y; m = v.x; }
-      else if (v.x != -INFINITY) s += v.y * exp_neg_fast(v.x - m);
+    // tiles past the end read the last pair and count as empty; the pairs are folded in the order
+    // lane, lane + 64, ... whatever the batching
+    for (int t0 = lane; t0 < n_tiles; t0 += NB * kWave) {
+      double2 v[NB];
+#pragma unroll
+      for (int u = 0; u < NB; ++u) {
+        const int t = t0 + u * kWave;
+        v[u] = p[min(t, n_tiles - 1)];
+        if (t >= n_tiles) v[u] = make_double2(-INFINITY, 0.0);
+      }
+#pragma unroll
+      for (int u = 0; u < NB; ++u) {
+        if (v[u].x > m) { s = s * exp_neg_fast(m - v[u].x) + v[u].y; m = v[u].x; }
+        else if (v[u].x != -INFINITY) s += v[u].y * exp_neg_fast(v[u].x - m);
+      }
     }
     const double mw = wave_max_f64(m);
     s = (m == -INFINITY) ? 0.0 : s * exp_neg_fast(m - mw);
@@ -38,7 +51,9 @@ __device__ void unit_lse(const double2* __restrict__ part, int n_tiles, int G, d
   __syncthreads();
 }
 
-template <int E, int SRC>
+// WIDE: the variant for more than 4 query heads per KV head or more than 64 score tiles per head (it spends
+// registers on loads in flight that the common case does not need).
+template <int E, int SRC, bool WIDE>
 __global__ __launch_bounds__(kSelNT) void select_slices(SelectArgs a) {
   __shared__ SelectSmem<kSelNT> sm;
   __shared__ double lse_sm[64];
@@ -61,7 +76,7 @@ __global__ __launch_bounds__(kSelNT) void select_slices(SelectArgs a) {
 #pragma unroll
       for (int e = 0; e < E; ++e) pre[g][e] = row[min(j0 + e, a.n - 1)];
     }
-    unit_lse(a.partials + (size_t)unit * a.G * a.n_tiles, a.n_tiles, a.G, lse_sm);
+    unit_lse<WIDE ? 4 : 1>(a.partials + (size_t)unit * a.G * a.n_tiles, a.n_tiles, a.G, lse_sm);
 #pragma unroll
     for (int e = 0; e < E; ++e) key[e] = 0ull;
 #pragma unroll
@@ -76,15 +91,27 @@ __global__ __launch_bounds__(kSelNT) void select_slices(SelectArgs a) {
           }
       }
     }
-    for (int g = GP; g < a.G; ++g) {
-      const double l = lse_sm[g];
-      const float* row = lg + (size_t)g * a.n;
+    // the remaining heads of a large group: with few keys per thread a batch of 32 logits is requested
+    // before it is used; the wide variants have no registers to spare and take one head at a time
+    constexpr int GB = !WIDE ? 1 : E <= 4 ? 8 : E <= 8 ? 4 : 1;
+    for (int gb = GP; gb < a.G; gb += GB) {
+      float more[GB][E];
 #pragma unroll
-      for (int e = 0; e < E; ++e) {
-        const int j = j0 + e;
-        if (j < a.n) {
-          const uint64_t kk = f64_key((double)row[j] - l);
-          key[e] = kk > key[e] ? kk : key[e];
+      for (int g = 0; g < GB; ++g) {
+        const float* row = lg + (size_t)min(gb + g, a.G - 1) * a.n;
+#pragma unroll
+        for (int e = 0; e < E; ++e) more[g][e] = GB > 1 ? row[min(j0 + e, a.n - 1)] : (j0 + e < a.n ? row[j0 + e] : 0.f);
+      }
+#pragma unroll
+      for (int g = 0; g < GB; ++g) {
+        if (gb + g < a.G) {
+          const double l = lse_sm[gb + g];
+#pragma unroll
+          for (int e = 0; e < E; ++e)
+            if (j0 + e < a.n) {
+              const uint64_t kk = f64_key((double)more[g][e] - l);
+              key[e] = kk > key[e] ? kk : key[e];
+            }
         }
       }
     }
@@ -217,17 +244,22 @@ bool plan_select(int n, int k, SelectPlan* plan) {
   return false;
 }
 
-template <int SRC>
-static hipError_t launch_slices(const SelectArgs& a, int e, int units, hipStream_t st) {
+template <int SRC, bool WIDE>
+static hipError_t launch_slices_w(const SelectArgs& a, int e, int units, hipStream_t st) {
   dim3 grid(a.n_slices, units), block(kSelNT);
   switch (e) {
-    case 4: hipLaunchKernelGGL((select_slices<4, SRC>), grid, block, 0, st, a); break;
-    case 8: hipLaunchKernelGGL((select_slices<8, SRC>), grid, block, 0, st, a); break;
-    case 16: hipLaunchKernelGGL((select_slices<16, SRC>), grid, block, 0, st, a); break;
-    case 32: hipLaunchKernelGGL((select_slices<32, SRC>), grid, block, 0, st, a); break;
+    case 4: hipLaunchKernelGGL((select_slices<4, SRC, WIDE>), grid, block, 0, st, a); break;
+    case 8: hipLaunchKernelGGL((select_slices<8, SRC, WIDE>), grid, block, 0, st, a); break;
+    case 16: hipLaunchKernelGGL((select_slices<16, SRC, WIDE>), grid, block, 0, st, a); break;
+    case 32: hipLaunchKernelGGL((select_slices<32, SRC, WIDE>), grid, block, 0, st, a); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
+}
+template <int SRC>
+static hipError_t launch_slices(const SelectArgs& a, int e, int units, hipStream_t st) {
+  if (SRC == kSrcLogits && (a.G > 4 || a.n_tiles > 64)) return launch_slices_w<SRC, true>(a, e, units, st);
+  return launch_slices_w<SRC, false>(a, e, units, st);
 }
 
 template <bool MID>
