@@ -56,10 +56,12 @@ def main() -> int:
     ap.add_argument("--workload", default="c3-hbm", help="c1 | c2 | c3-hbm | c3-host | c4 | c5")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU time budget of the oracle leg")
-    ap.add_argument("--no-side-stream", action="store_true")
+    ap.add_argument("--side-stream", action="store_true",
+                    help="run the value gather as a launch of its own on a second stream (default: it shares the "
+                         "launch of the attention's key phase)")
     ap.add_argument("--no-graph", action="store_true", help="enqueue the timed steps eagerly instead of replaying a HIP graph")
     ap.add_argument("--force-graph", action="store_true",
-                    help="replay a HIP graph also where the default is eager (steps with a value gather on the side stream)")
+                    help="replay a HIP graph also where the default is eager (--side-stream)")
     ap.add_argument("--chunk-cache", action="store_true",
                     help="run shadowkv_decode_step_cached over a ring of correlated queries (values fetched only for "
                          "chunks missing from last step's selection); meant for the host-store workloads")
@@ -126,7 +128,7 @@ def main() -> int:
     ws = S.alloc_workspace(S.decode_workspace_bytes(p))
     out = torch.empty(wl.batch, wl.n_q_heads, wl.head_dim, dtype=torch.bfloat16, device=dev)
     ids = torch.empty(wl.batch, wl.n_kv_heads, wl.topk_chunks, dtype=torch.int32, device=dev)
-    side = None if args.no_side_stream else torch.cuda.Stream()
+    side = torch.cuda.Stream() if args.side_stream else None
     pool = t["q_pool"]
     cache = None
     if args.chunk_cache:
@@ -152,10 +154,10 @@ def main() -> int:
     # host launch gaps between the five kernels of a step; --no-graph enqueues every step eagerly instead.
     n_pool = pool.shape[0]
     graph = None
-    # Steps whose values come through a gather run it on the side stream next to the key phase of the attention;
-    # a replayed HIP graph does not overlap the two branches on this runtime (measured: replay = serial time), so
-    # those workloads are timed with eager enqueues unless --force-graph is given.
-    two_phase = wl.value_location == "host" or args.chunk_cache or args.stage_values
+    # With --side-stream a step whose values come through a gather forks to the second stream; a replayed HIP
+    # graph does not overlap the two branches on this runtime (measured: replay = serial time), so such runs
+    # are timed with eager enqueues unless --force-graph is given.
+    two_phase = side is not None and (wl.value_location == "host" or args.chunk_cache or args.stage_values)
     use_graph = not args.no_graph and (args.force_graph or not two_phase)
     if use_graph and args.steps >= n_pool:
         cap = torch.cuda.Stream()

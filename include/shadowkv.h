@@ -145,7 +145,13 @@ int shadowkv_build_landmarks(const shadowkv_params *params, const shadowkv_kv *k
  *   out_chunk_ids       dev  out   [b, h_kv, k] int32 or NULL: the selected true chunk ids, ascending
  *   workspace           dev        >= shadowkv_decode_workspace_bytes(), 256-byte aligned
  *   stream              HIP stream all work is ordered on
- *   side_stream         HIP stream for the value gather (overlaps the key rebuild); NULL => serial on `stream`
+ *   side_stream         NULL (recommended): a value gather, where one is needed, is done by the first
+ *                       workgroups of the launch that rebuilds the keys, so the two overlap inside one
+ *                       launch and the whole step is ordered on `stream` alone (it can be captured into a
+ *                       HIP graph as it is).  Non-NULL and different from `stream`: the gather is a launch
+ *                       of its own on that stream, forked from and joined back into `stream` with events
+ *                       (the two-stream arrangement the paper describes; slower here by the cost of the
+ *                       events).  Ignored when no gather is needed.
  *
  * Scores are ranked in the log domain: score(slot) = max over the group's heads of
  * (logit_g(slot) - logsumexp_g), which orders slots exactly like softmax-then-max.  The logit is

@@ -128,6 +128,42 @@ struct OnlineSoftmax {
   }
 };
 
+// Value chunks copied by the first workgroups of the key-phase launch (see GatherArgs).  A zero-copy
+// reader like gather_values_kernel: 16 bytes per lane, whole chunks contiguous, four independent loads in
+// flight per thread; a fixed, small number of workgroups loops over the work, so that the rest of the chip
+// is left to the key phase that runs beside it.
+__device__ __forceinline__ void gather_chunks(const GatherArgs& g, int block) {
+  constexpr int U = 4;
+  const int vpc = g.vec_per_chunk;
+  const int sub = block % g.blocks_per_unit;
+  const int stride = g.blocks_per_unit * 256;
+  for (int unit = block / g.blocks_per_unit; unit < g.units; unit += g.unit_step) {
+    const int n_chunks = g.miss_slots ? min(max(g.n_miss[unit], 0), g.k) : g.k;
+    const int total = n_chunks * vpc;
+    const int32_t* ids = g.ids + (size_t)unit * (g.miss_slots ? g.slots_per_unit : g.k);
+    const uint4* src_u = g.store + (size_t)unit * g.vec_per_unit_store;
+    uint4* dst_u = g.dst + (size_t)unit * g.slots_per_unit * vpc;
+    for (int v0 = sub * 256 + (int)threadIdx.x; v0 < total; v0 += stride * U) {
+      uint4 buf[U];
+      int at[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int v = v0 + u * stride;
+        at[u] = -1;
+        if (v < total) {
+          const int i = v / vpc, off = v - i * vpc;
+          const int slot = g.miss_slots ? min(max(g.miss_slots[(size_t)unit * g.k + i], 0), g.slots_per_unit - 1) : i;
+          buf[u] = src_u[(size_t)min(max(ids[slot], 0), g.last_chunk) * vpc + off];
+          at[u] = slot * vpc + off;
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (at[u] >= 0) dst_u[at[u]] = buf[u];
+    }
+  }
+}
+
 // KSMAX = number of 32-wide rank steps the A prefetch buffer is sized for (5: r <= 160, 8: r <= 256).
 // KEYS_ONLY: the selected values are still on their way (a gather on another stream).  The kernel
 // then does everything that needs no selected value -- the resident rows in full, and for the
@@ -141,7 +177,18 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
   extern __shared__ __align__(16) bf16_t Bt[];  // [D][rp], element (n, kk) = B[kk][n]; then int tokb[]
   __shared__ float sm_acc[4][GH][D];
   __shared__ float sm_m[4][GH], sm_l[4][GH];
-  const int unit = blockIdx.y, split = blockIdx.x, g0 = blockIdx.z * GH;
+  // KEYS_ONLY: a flat grid, the gather's workgroups first (they are dispatched first), then (split, unit, head block)
+  int unit = blockIdx.y, split = blockIdx.x, g0 = blockIdx.z * GH;
+  if constexpr (KEYS_ONLY) {
+    if ((int)blockIdx.x < a.gather.n_blocks) {
+      gather_chunks(a.gather, blockIdx.x);
+      return;
+    }
+    const int idx = blockIdx.x - a.gather.n_blocks, units = a.batch * a.hkv;
+    split = idx % a.n_splits;
+    unit = (idx / a.n_splits) % units;
+    g0 = idx / (a.n_splits * units) * GH;
+  }
   const int G = a.hq / a.hkv, b = unit / a.hkv, h = unit % a.hkv;
   const size_t head0 = (size_t)b * a.hq + (size_t)h * G + g0;
   const int lane = threadIdx.x & (kWave - 1);
@@ -685,6 +732,7 @@ static hipError_t launch_keys_d(const AttnArgs& a, hipStream_t st) {
   // B^T (as bf16 whatever the storage), then the first token and the first value row of each chunk a split touches
   const size_t lds = (size_t)D * a.rp * sizeof(bf16_t) + 2 * ((size_t)a.sparse_split_len / a.c + 2) * sizeof(int);
   dim3 grid(a.n_splits, a.batch * a.hkv, G / gh);
+  if (KEYS_ONLY) grid = dim3((unsigned)(a.gather.n_blocks + (long)a.n_splits * a.batch * a.hkv * (G / gh)));
   switch (gh) {
     case 4: return launch_sparse_ks<D, 4, KEYS_ONLY, EB>(a, grid, lds, st);
     case 2: return launch_sparse_ks<D, 2, KEYS_ONLY, EB>(a, grid, lds, st);

@@ -73,6 +73,22 @@ hipError_t launch_fill_i32(int32_t* p, size_t n, int32_t value, hipStream_t st);
 // K_sparse = RoPE(Gather(A, I) B) is formed per 16-row block on the matrix cores and consumed
 // from registers.  Split i covers selected rows [i*sparse_split_len, ...) and resident rows
 // [i*res_split_len, ...); a combine kernel merges the splits into `out`.
+// A gather of value chunks that rides in the same launch as the key phase of the attention (the first
+// `n_blocks` workgroups of that launch do it; 0: none).  Plain: chunk ids[unit][i] of the store goes to
+// slot i of dst.  With a chunk cache (miss_slots != NULL): for i < n_miss[unit], the chunk named by
+// ids[unit][slot], slot = miss_slots[unit][i], goes to that slot of dst.
+struct GatherArgs {
+  const uint4* store;         // [units, vec_per_unit_store] 16-byte vectors (HBM or device-readable pinned host memory)
+  uint4* dst;                 // [units, slots_per_unit, vec_per_chunk]
+  const int32_t* ids;         // plain: [units, k] selected chunk ids; cache: [units, slots_per_unit] chunk id held by each slot
+  const int32_t* miss_slots;  // cache only: [units, k]
+  const int32_t* n_miss;      // cache only: [units]
+  int n_blocks, blocks_per_unit, unit_step;
+  int units, k, slots_per_unit, vec_per_chunk, last_chunk;
+  size_t vec_per_unit_store;
+};
+void plan_gather(GatherArgs* g);  // fills n_blocks, blocks_per_unit, unit_step from the sizes
+
 struct AttnArgs {
   const bf16_t* q;          // [b, h_q, d]
   int kv_bytes;             // storage of the tensors below that are void*: 2 = bf16, 1 = FP8 E5M2
@@ -102,6 +118,7 @@ struct AttnArgs {
   int c_shift;              // log2(c) when c is a power of two, else -1
   float scale_log2;         // softmax scale * log2(e)
   RopeFreqs freqs;
+  GatherArgs gather;        // key phase of the two-phase path only: value gather done by the same launch
 };
 inline int attention_heads_per_group(int G) { return (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1; }
 hipError_t launch_attention(const AttnArgs& a, hipStream_t st);         // values readable now: one fused kernel

@@ -50,4 +50,24 @@ hipError_t launch_gather_values(const void* store, const int32_t* sel_ids, void*
   return hipGetLastError();
 }
 
+// Workgroups of a gather that shares a launch with the key phase: at most one per compute unit, so that the
+// key phase finds the other half of every unit's slots free; whole workgroups per unit when there are few units.
+void plan_gather(GatherArgs* g) {
+  constexpr int kMaxBlocks = 256;
+  const long per_unit = (long)g->k * g->vec_per_chunk;
+  if (g->units <= kMaxBlocks) {
+    long bpu = kMaxBlocks / g->units;
+    const long useful = (per_unit + 256 * kGatherUnroll - 1) / (256 * kGatherUnroll);
+    if (bpu > useful) bpu = useful;
+    if (bpu < 1) bpu = 1;
+    g->blocks_per_unit = (int)bpu;
+    g->n_blocks = (int)bpu * g->units;
+    g->unit_step = g->units;
+  } else {
+    g->blocks_per_unit = 1;
+    g->n_blocks = kMaxBlocks;
+    g->unit_step = kMaxBlocks;
+  }
+}
+
 }  // namespace skv

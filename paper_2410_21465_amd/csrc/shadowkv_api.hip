@@ -481,18 +481,35 @@ static int decode_impl(const shadowkv_params* params, const shadowkv_bf16* q, co
                             sh.units, sh.k, cache->slots, st);
     if (e != hipSuccess) return fail_hip("cache update", e);
   }
-  hipStream_t gs = st;
+  // With a side stream the gather is a launch of its own there; without one it is done by the first
+  // workgroups of the key-phase launch (no events between streams, and the step stays on one stream).
+  const int vec_per_chunk = sh.c * sh.d * sh.eb / 16;
   if (fork) {
     if ((e = hipEventRecord(ev_fork, st)) != hipSuccess) return fail_hip("hipEventRecord", e);
     if ((e = hipStreamWaitEvent(side, ev_fork, 0)) != hipSuccess) return fail_hip("hipStreamWaitEvent", e);
-    gs = side;
+  } else {
+    GatherArgs& g = t.gather;
+    g.store = static_cast<const uint4*>(value_store);
+    g.units = sh.units; g.k = sh.k; g.vec_per_chunk = vec_per_chunk; g.last_chunk = sh.s / sh.c - 1;
+    g.vec_per_unit_store = (size_t)sh.cap * sh.d * sh.eb / 16;
+    if (cache) {
+      g.dst = static_cast<uint4*>(cache->values); g.ids = cache->chunk_ids; g.miss_slots = miss_slots; g.n_miss = n_miss;
+      g.slots_per_unit = cache->slots;
+    } else {
+      g.dst = static_cast<uint4*>(v_sparse); g.ids = sel_ids; g.miss_slots = nullptr; g.n_miss = nullptr;
+      g.slots_per_unit = sh.k;
+    }
+    plan_gather(&g);
   }
+  e = hipSuccess;
   if (cache) {
-    e = launch_gather_missing(value_store, cache->chunk_ids, miss_slots, n_miss, cache->values, sh.eb, sh.units, sh.d,
-                              sh.s, sh.cap, sh.c, sh.k, cache->slots, gs);
+    if (fork)
+      e = launch_gather_missing(value_store, cache->chunk_ids, miss_slots, n_miss, cache->values, sh.eb, sh.units, sh.d,
+                                sh.s, sh.cap, sh.c, sh.k, cache->slots, side);
     t.v_sparse = cache->values; t.v_slots = sel_slots; t.v_unit_rows = cache->slots * sh.c;
   } else {
-    e = launch_gather_values(value_store, sel_ids, v_sparse, sh.eb, sh.units, sh.d, sh.s, sh.cap, sh.c, sh.k, gs);
+    if (fork)
+      e = launch_gather_values(value_store, sel_ids, v_sparse, sh.eb, sh.units, sh.d, sh.s, sh.cap, sh.c, sh.k, side);
     t.v_sparse = v_sparse;
   }
   if (e != hipSuccess) return fail_hip("gather values", e);

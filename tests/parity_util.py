@@ -112,7 +112,7 @@ def run_build_parity(wl: Workload, t: dict, device="cuda", kv_dtype: int = 0):
     return ref, got
 
 
-def run_decode_parity(wl: Workload, t: dict, ref_build: dict, qi: int = 0, side_stream: bool = True, flags: int = 0,
+def run_decode_parity(wl: Workload, t: dict, ref_build: dict, qi: int = 0, side_stream: bool = False, flags: int = 0,
                       inv_freq=None, softmax_scale: float = 0.0, pos_offset=None, device="cuda",
                       check_keys: bool = True, kv_dtype: int = 0):
     """shadowkv_decode_step against the oracle, both fed the ORACLE's landmarks and outliers."""

@@ -39,9 +39,9 @@ def _check_decode(wl, gp, op, q, t, g, ref_state, cache=None, ocache=None):
     args = (gp, q, g["A"], t["B"], g["landmarks"], g["ids"], g["k_outlier"], g["v_outlier"], t["k_local"],
             t["v_local"], g["v"])
     if cache is None:
-        out, ids, _ = S.decode_step(*args, t["pos_offset"], side_stream=torch.cuda.Stream())
+        out, ids, _ = S.decode_step(*args, t["pos_offset"])
     else:
-        out, ids, _ = S.decode_step_cached(*args, cache, t["pos_offset"], side_stream=torch.cuda.Stream())
+        out, ids, _ = S.decode_step_cached(*args, cache, t["pos_offset"])
     torch.cuda.synchronize()
     want = np.sort(ref["chunk_ids"].reshape(units, k), axis=1)
     np.testing.assert_array_equal(ids.cpu().numpy().reshape(units, k), want)

@@ -138,7 +138,8 @@ def test_reset_empties_the_cache():
     assert bool((cache.chunk_ids == -1).all()) and bool((cache.stamps == 0).all())
 
 
-def test_cached_step_in_a_hip_graph_replays_to_the_eager_sequence():
+@pytest.mark.parametrize("two_streams", [False, True])
+def test_cached_step_in_a_hip_graph_replays_to_the_eager_sequence(two_streams):
     """The cached step is stateful (the slots carry over).  A graph of one cached step, replayed over a query
     sequence with eager uncached work between the replays, must walk through exactly the states and outputs of
     the same sequence run eagerly."""
@@ -154,7 +155,7 @@ def test_cached_step_in_a_hip_graph_replays_to_the_eager_sequence():
     ws = S.alloc_workspace(S.decode_workspace_bytes(p))
     ws2 = S.alloc_workspace(S.decode_workspace_bytes(p))
     cache = S.ValueCache(p, slots=100)
-    side = torch.cuda.Stream()
+    side = torch.cuda.Stream() if two_streams else None
 
     def step():
         S.decode_step_cached(p, q, t["A"], t["B"], bl["landmarks"], bl["landmark_chunk_ids"], bl["k_outlier"],

@@ -25,6 +25,12 @@ def _run(name, n_queries=2):
         stats, ref_d, got = PU.run_decode_parity(wl, t, ref_b, qi=qi, check_keys=(qi == 0))
         print(f"[decode] {name} q{qi}: {stats}", flush=True)
         last = (stats, ref_d, got)
+    if wl.value_location == "host":
+        # the two-stream arrangement (gather as a launch of its own on a second stream) gives the same bits as
+        # the default, where the gather shares the launch of the key phase
+        _, _, two = PU.run_decode_parity(wl, t, ref_b, qi=n_queries - 1, check_keys=False, side_stream=True)
+        assert torch.equal(two[0], last[2][0]) and torch.equal(two[1], last[2][1])
+        print(f"[decode] {name}: two-stream run equals the single-launch run", flush=True)
     return wl, t, ref_b, last
 
 

@@ -102,10 +102,10 @@ def test_repeated_calls_are_deterministic():
     assert torch.equal(o1, o2) and torch.equal(i1, i2)
 
 
-@pytest.mark.parametrize("host_values", [False, True])
-def test_hip_graph_replays_match_eager(host_values):
-    """A captured decode step (with the side-stream fork when values are staged) replays to the eager result,
-    several times, with eager work and synchronisations between the replays."""
+@pytest.mark.parametrize("host_values,two_streams", [(False, False), (True, False), (True, True)])
+def test_hip_graph_replays_match_eager(host_values, two_streams):
+    """A captured decode step (gather inside the key-phase launch, or forked to a second stream) replays to the
+    eager result, several times, with eager work and synchronisations between the replays."""
     wl = small("graph", ctx_len=8192, topk_chunks=48, value_location="host" if host_values else "hbm", n_queries=3)
     t = PU.draw(wl)
     p = S.Params.from_workload(wl)
@@ -114,7 +114,7 @@ def test_hip_graph_replays_match_eager(host_values):
     q = t["q_pool"][0].clone()
     out = torch.empty(wl.batch, wl.n_q_heads, wl.head_dim, dtype=torch.bfloat16, device="cuda")
     ids = torch.empty(wl.batch, wl.n_kv_heads, wl.topk_chunks, dtype=torch.int32, device="cuda")
-    side = torch.cuda.Stream()
+    side = torch.cuda.Stream() if two_streams else None
 
     def step(stream_side):
         S.decode_step(p, q, t["A"], t["B"], bl["landmarks"], bl["landmark_chunk_ids"], bl["k_outlier"],

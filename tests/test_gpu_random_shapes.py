@@ -60,7 +60,8 @@ def test_random_shape(seed, kd):
              PU.to_bits(t["v"], kd), t["pos_offset"].cpu().numpy())
     for step in range(2):
         out, sel, _ = S.decode_step_cached(p, qs[step], t["A"], t["B"], lm, ids, ko, vo, t["k_local"], t["v_local"], t["v"],
-                                           cache, t["pos_offset"], side_stream=torch.cuda.Stream())
+                                           cache, t["pos_offset"],
+                                           side_stream=torch.cuda.Stream() if step == 1 else None)
         torch.cuda.synchronize()
         ref = O.decode_step(op, PU.to_bits(qs[step]), *fixed, diagnostics=True)
         g_ids = sel.cpu().numpy().reshape(units, k)
