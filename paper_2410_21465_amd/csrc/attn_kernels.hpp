@@ -665,43 +665,60 @@ __global__ __launch_bounds__(256) void sparse_values_kernel(AttnArgs a) {
 // Merge of the per-split states of one head: out = sum_s acc_s 2^(m_s - M) / sum_s l_s 2^(m_s - M).
 // A separate launch on purpose: a device-scope release inside the attention kernel would make every
 // workgroup write back its XCD's L2, which costs far more than this kernel.
+constexpr int kCombineNY = 4;
 template <int D>
-__global__ __launch_bounds__(D) void attn_combine_kernel(const float* __restrict__ part_acc,
-                                                         const float2* __restrict__ part_ml,
-                                                         bf16_t* __restrict__ out, int n_splits) {
+__global__ __launch_bounds__(D * kCombineNY) void attn_combine_kernel(const float* __restrict__ part_acc,
+                                                                      const float2* __restrict__ part_ml,
+                                                                      bf16_t* __restrict__ out, int n_splits) {
+  // thread (e, y): output column e, the y-th quarter of the partial states (long contexts with few units have
+  // dozens of them per head); eight loads are issued together, the folding order is fixed
+  __shared__ float sm_M[kCombineNY], sm_den[kCombineNY], sm_num[kCombineNY][D];
   const size_t head = blockIdx.x;
-  const int e = threadIdx.x;
+  const int e = threadIdx.x, y = threadIdx.y;
+  const int per = (n_splits + kCombineNY - 1) / kCombineNY;
+  const int s_begin = min(n_splits, y * per), s_end = min(n_splits, s_begin + per);
   const float2* ml = part_ml + head * n_splits;
   const float* pa = part_acc + head * n_splits * D + e;
-  // eight partial states at a time: their loads are issued together, the folding keeps the order of the splits
   float M = -INFINITY;
-  for (int s0 = 0; s0 < n_splits; s0 += 8) {
+  for (int s0 = s_begin; s0 < s_end; s0 += 8) {
     float mx[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) mx[u] = ml[min(s0 + u, n_splits - 1)].x;
+    for (int u = 0; u < 8; ++u) mx[u] = ml[min(s0 + u, s_end - 1)].x;
 #pragma unroll
     for (int u = 0; u < 8; ++u) M = fmaxf(M, mx[u]);
   }
+  if (e == 0) sm_M[y] = M;
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < kCombineNY; ++j) M = fmaxf(M, sm_M[j]);
   float num = 0.f, den = 0.f;
-  for (int s0 = 0; s0 < n_splits; s0 += 8) {
+  for (int s0 = s_begin; s0 < s_end; s0 += 8) {
     float2 st[8];
     float av[8];
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
-      const int sp = min(s0 + u, n_splits - 1);
+      const int sp = min(s0 + u, s_end - 1);
       st[u] = ml[sp];
       av[u] = pa[(size_t)sp * D];
     }
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
-      if (s0 + u < n_splits) {
+      if (s0 + u < s_end) {
         const float sc = (st[u].x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(st[u].x - M);
         num = fmaf(av[u], sc, num);
         den = fmaf(st[u].y, sc, den);
       }
     }
   }
-  out[head * D + e] = f32_to_bf16(num / den);
+  sm_num[y][e] = num;
+  if (e == 0) sm_den[y] = den;
+  __syncthreads();
+  if (y == 0) {
+    num = sm_num[0][e]; den = sm_den[0];
+#pragma unroll
+    for (int j = 1; j < kCombineNY; ++j) { num += sm_num[j][e]; den += sm_den[j]; }
+    out[head * D + e] = f32_to_bf16(num / den);
+  }
 }
 
 template <int D, int GH, int KSMAX, bool FAST4, bool KEYS_ONLY, int EB>
@@ -742,7 +759,7 @@ static hipError_t launch_keys_d(const AttnArgs& a, hipStream_t st) {
 
 template <int D>
 static hipError_t launch_combine_d(const AttnArgs& a, hipStream_t st) {
-  hipLaunchKernelGGL((attn_combine_kernel<D>), dim3(a.batch * a.hq), dim3(D), 0, st, a.part_acc, a.part_ml, a.out,
+  hipLaunchKernelGGL((attn_combine_kernel<D>), dim3(a.batch * a.hq), dim3(D, kCombineNY), 0, st, a.part_acc, a.part_ml, a.out,
                      a.n_part);
   return hipGetLastError();
 }
