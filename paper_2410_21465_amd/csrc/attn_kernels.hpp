@@ -133,7 +133,7 @@ struct OnlineSoftmax {
 // flight per thread; a fixed, small number of workgroups loops over the work, so that the rest of the chip
 // is left to the key phase that runs beside it.
 __device__ __forceinline__ void gather_chunks(const GatherArgs& g, int block) {
-  constexpr int U = 4;
+  constexpr int U = 4;  // loads in flight per thread
   const int vpc = g.vec_per_chunk;
   const int sub = block % g.blocks_per_unit;
   const int stride = g.blocks_per_unit * 256;
@@ -144,22 +144,23 @@ __device__ __forceinline__ void gather_chunks(const GatherArgs& g, int block) {
     const uint4* src_u = g.store + (size_t)unit * g.vec_per_unit_store;
     uint4* dst_u = g.dst + (size_t)unit * g.slots_per_unit * vpc;
     for (int v0 = sub * 256 + (int)threadIdx.x; v0 < total; v0 += stride * U) {
-      uint4 buf[U];
-      int at[U];
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
+      // every load is issued (positions past the end repeat the first one and are not stored); named
+      // variables rather than arrays, which the compiler kept in scratch memory here
+      auto fetch = [&](int u, uint4& buf, int& at) {
         const int v = v0 + u * stride;
-        at[u] = -1;
-        if (v < total) {
-          const int i = v / vpc, off = v - i * vpc;
-          const int slot = g.miss_slots ? min(max(g.miss_slots[(size_t)unit * g.k + i], 0), g.slots_per_unit - 1) : i;
-          buf[u] = src_u[(size_t)min(max(ids[slot], 0), g.last_chunk) * vpc + off];
-          at[u] = slot * vpc + off;
-        }
-      }
-#pragma unroll
-      for (int u = 0; u < U; ++u)
-        if (at[u] >= 0) dst_u[at[u]] = buf[u];
+        const int vc = v < total ? v : v0;
+        const int i = vc / vpc, off = vc - i * vpc;
+        const int slot = g.miss_slots ? min(max(g.miss_slots[(size_t)unit * g.k + i], 0), g.slots_per_unit - 1) : i;
+        buf = src_u[(size_t)min(max(ids[slot], 0), g.last_chunk) * vpc + off];
+        at = v < total ? slot * vpc + off : -1;
+      };
+      uint4 b0, b1, b2, b3;
+      int a0, a1, a2, a3;
+      fetch(0, b0, a0); fetch(1, b1, a1); fetch(2, b2, a2); fetch(3, b3, a3);
+      if (a0 >= 0) dst_u[a0] = b0;
+      if (a1 >= 0) dst_u[a1] = b1;
+      if (a2 >= 0) dst_u[a2] = b2;
+      if (a3 >= 0) dst_u[a3] = b3;
     }
   }
 }
