@@ -179,15 +179,17 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
   __shared__ float sm_acc[4][GH][D];
   __shared__ float sm_m[4][GH], sm_l[4][GH];
   // KEYS_ONLY: a flat grid, the gather's workgroups first (they are dispatched first), then (split, unit, head block)
-  int unit = blockIdx.y, split = blockIdx.x, g0 = blockIdx.z * GH;
+  // the unit is the fastest-varying index of the grid: workgroups go to the chip's eight XCDs in turn, so the
+  // splits of a unit (same B, same chunk ids) meet in one XCD's L2 when the unit count is a multiple of 8
+  int unit = blockIdx.x, split = blockIdx.y, g0 = blockIdx.z * GH;
   if constexpr (KEYS_ONLY) {
     if ((int)blockIdx.x < a.gather.n_blocks) {
       gather_chunks(a.gather, blockIdx.x);
       return;
     }
     const int idx = blockIdx.x - a.gather.n_blocks, units = a.batch * a.hkv;
-    split = idx % a.n_splits;
-    unit = (idx / a.n_splits) % units;
+    unit = idx % units;
+    split = (idx / units) % a.n_splits;
     g0 = idx / (a.n_splits * units) * GH;
   }
   const int G = a.hq / a.hkv, b = unit / a.hkv, h = unit % a.hkv;
@@ -749,7 +751,7 @@ static hipError_t launch_keys_d(const AttnArgs& a, hipStream_t st) {
   const int gh = attention_heads_per_group(G);
   // B^T (as bf16 whatever the storage), then the first token and the first value row of each chunk a split touches
   const size_t lds = (size_t)D * a.rp * sizeof(bf16_t) + 2 * ((size_t)a.sparse_split_len / a.c + 2) * sizeof(int);
-  dim3 grid(a.n_splits, a.batch * a.hkv, G / gh);
+  dim3 grid(a.batch * a.hkv, a.n_splits, G / gh);
   if (KEYS_ONLY) grid = dim3((unsigned)(a.gather.n_blocks + (long)a.n_splits * a.batch * a.hkv * (G / gh)));
   switch (gh) {
     case 4: return launch_sparse_ks<D, 4, KEYS_ONLY, EB>(a, grid, lds, st);
