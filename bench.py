@@ -53,7 +53,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="c3-hbm", help="c1 | c2 | c3-hbm | c3-host | c4 | c5")
+    ap.add_argument("--workload", default="c3-hbm", help="c1 | c2 | c3-hbm | c3-host | c4 | c5 (the benchmark's configurations), c3-g8")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU time budget of the oracle leg")
     ap.add_argument("--side-stream", action="store_true",
@@ -86,13 +86,13 @@ def main() -> int:
 
     import torch
     from paper_2410_21465_amd import shadowkv as S
-    from paper_2410_21465_amd.workloads import (CONFIGS, generate, generated_chunk, query_sequence, to_fp8_storage,
+    from paper_2410_21465_amd.workloads import (CONFIGS, EXTRA_CONFIGS, generate, generated_chunk, query_sequence, to_fp8_storage,
                                                 with_capacity)
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
-    wl = CONFIGS[args.workload]
+    wl = {**CONFIGS, **EXTRA_CONFIGS}[args.workload]
     dev = "cuda"
     t0 = time.time()
     print(f"[bench] drawing {wl.name}", file=sys.stderr, flush=True)

@@ -1,5 +1,6 @@
 // Landmark scoring: P = Q L^T * scale for every landmark slot (first line of the
-// decoding algorithm), streamed once from HBM for up to four heads of a KV group.
+// decoding algorithm), streamed once from HBM for the heads of a KV group (up to four here, up to 16 per pass in
+// score_kernel_g16 further down).
 //
 // The scores decide an index set that has to match a reference bit for bit: the logit
 // is defined as the exact dot product of the bf16 inputs rounded once to fp32, so the
@@ -135,7 +136,7 @@ __global__ __launch_bounds__(256) void score_kernel(const bf16_t* __restrict__ q
   }
 }
 
-// Groups of 16 query heads per KV head (or a multiple): the 16x16x4 form of the fp64 matrix instruction takes all
+// Groups of more than 4 query heads per KV head: the 16x16x4 form of the fp64 matrix instruction takes up to
 // 16 heads at once (A lane l = (head l % 16, k-slot l / 16), B lane l = (row l % 16, k-slot l / 16), result register j
 // of lane l = (head 4 j + l / 16, row l % 16); measured on gfx950), so every landmark element is loaded and widened
 // once instead of once per four heads.  Same tiles, same logits (exact sum, one rounding) and partials as above.
@@ -175,9 +176,10 @@ __global__ __launch_bounds__(256) void score_kernel_g16(const bf16_t* __restrict
       }
     }
   }
-  double qa[NI][PE];  // head g0 + rl, the elements this lane's k-slot meets
+  double qa[NI][PE];  // head g0 + rl, the elements this lane's k-slot meets (zero for heads past the group)
+  const bool hv = g0 + rl < G;
   {
-    const bf16_t* qp = q + (head0 + rl) * D + PE * kq;
+    const bf16_t* qp = q + (head0 + (hv ? rl : 0)) * D + PE * kq;
 #pragma unroll
     for (int i = 0; i < NI; ++i)
 #pragma unroll
@@ -185,37 +187,50 @@ __global__ __launch_bounds__(256) void score_kernel_g16(const bf16_t* __restrict
         float x[8];
         load_bf16_row<8>(qp + 4 * PE * i + 8 * e8, x);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) qa[i][8 * e8 + e] = (double)x[e];
+        for (int e = 0; e < 8; ++e) qa[i][8 * e8 + e] = hv ? (double)x[e] : 0.0;
       }
   }
   double m[4], s[4];   // heads g0 + 4 j + kq
 #pragma unroll
   for (int j = 0; j < 4; ++j) { m[j] = -INFINITY; s[j] = 0.0; }
+  // the four 16-row tiles of the wave take turns on the matrix pipe: consecutive instructions are independent,
+  // a tile's own chain comes round every fourth one
+  f64x4_t acc[4];
+#pragma unroll
+  for (int t = 0; t < 4; ++t) acc[t] = f64x4_t{0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+  for (int i = 0; i < NI; ++i)
+#pragma unroll
+    for (int x = 0; x < PW; ++x) {
+      if constexpr (EB == 2) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+          acc[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(qa[i][2 * x], (double)bf16_lo(w[t][i][x]), acc[t], 0, 0, 0);
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+          acc[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(qa[i][2 * x + 1], (double)bf16_hi(w[t][i][x]), acc[t], 0, 0, 0);
+      } else {
+        float f[4][4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) e5m2x4_to_f32(w[t][i][x], f[t]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+          for (int t = 0; t < 4; ++t)
+            acc[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(qa[i][4 * x + e], (double)f[t][e], acc[t], 0, 0, 0);
+      }
+    }
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
-    f64x4_t acc = {0.0, 0.0, 0.0, 0.0};
-#pragma unroll
-    for (int i = 0; i < NI; ++i)
-#pragma unroll
-      for (int x = 0; x < PW; ++x) {
-        if constexpr (EB == 2) {
-          acc = __builtin_amdgcn_mfma_f64_16x16x4f64(qa[i][2 * x], (double)bf16_lo(w[t][i][x]), acc, 0, 0, 0);
-          acc = __builtin_amdgcn_mfma_f64_16x16x4f64(qa[i][2 * x + 1], (double)bf16_hi(w[t][i][x]), acc, 0, 0, 0);
-        } else {
-          float f[4];
-          e5m2x4_to_f32(w[t][i][x], f);
-#pragma unroll
-          for (int e = 0; e < 4; ++e)
-            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(qa[i][4 * x + e], (double)f[e], acc, 0, 0, 0);
-        }
-      }
     const int r = row0 + t * 16 + rl;
     if (r < n_c) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        const float p32 = (float)(acc[j] * scale);   // the logit: exact dot product, rounded once to fp32
-        logits[(head0 + 4 * j + kq) * n_c + r] = p32;
-        lse_merge(m[j], s[j], (double)p32, 1.0);
+        if (g0 + 4 * j + kq < G) {
+          const float p32 = (float)(acc[t][j] * scale);   // the logit: exact dot product, rounded once to fp32
+          logits[(head0 + 4 * j + kq) * n_c + r] = p32;
+          lse_merge(m[j], s[j], (double)p32, 1.0);
+        }
       }
     }
   }
@@ -226,7 +241,7 @@ __global__ __launch_bounds__(256) void score_kernel_g16(const bf16_t* __restrict
     if (rl == 0) wred[wave][4 * j + kq] = make_double2(m[j], s[j]);
   }
   __syncthreads();
-  if (threadIdx.x < 16) {
+  if (threadIdx.x < 16 && g0 + (int)threadIdx.x < G) {
     const int g = threadIdx.x;
     double M = -INFINITY, S = 0.0;
 #pragma unroll
@@ -239,8 +254,10 @@ hipError_t launch_score(const bf16_t* q, const void* landmarks, int kv_bytes, fl
                         int batch, int hq, int hkv, int d, int n_c, int nc_stride, double scale, hipStream_t st) {
   const int G = hq / hkv;
   const int n_tiles = (n_c + kScoreTile - 1) / kScoreTile;
-  const bool g16 = G % 16 == 0;
-  dim3 grid(n_tiles, batch * hkv, g16 ? G / 16 : (G + 3) / 4), block(256);
+  // more than four heads per KV head: one pass per 16 heads on the 16x16x4 instruction (heads past the group are
+  // zero rows of its operand) instead of one pass over the landmarks per four heads
+  const bool g16 = G > 4;
+  dim3 grid(n_tiles, batch * hkv, g16 ? (G + 15) / 16 : 1), block(256);
   const uint8_t* L = static_cast<const uint8_t*>(landmarks);
 #define SKV_SCORE(D_, EB_)                                                                                            \
   do {                                                                                                                \

@@ -85,6 +85,12 @@ CONFIGS: Dict[str, Workload] = {
     "c5": Workload("c5", 8, 32, 32, 96, 131072, rope_theta=1e4, seed=4, value_location="hbm"),
 }
 
+# Further shapes bench.py accepts by name; not part of the benchmark's five.
+EXTRA_CONFIGS: Dict[str, Workload] = {
+    # c3-hbm with eight query heads per KV head (the grouping of 70B-class models)
+    "c3-g8": Workload("c3-g8", 16, 64, 8, 128, 131072, seed=2, value_location="hbm", plant="outliers"),
+}
+
 _LATENT = 320          # latent width; singular values beyond are far below the noise floor
 _NOISE = 0.02
 _TARGET_STD = 3.0      # per-element std of K_pre: makes q.k/sqrt(d) have std ~3 (peaked softmax)

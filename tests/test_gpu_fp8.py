@@ -29,6 +29,7 @@ CASES = [
     small("fp8-d96-mha", n_q_heads=4, n_kv_heads=4, head_dim=96, ctx_len=2048, rank=40, topk_chunks=17,
           n_outlier_chunks=2, rope_theta=1e4),
     small("fp8-g16", batch=1, n_q_heads=32, n_kv_heads=2, ctx_len=8192, rank=64, topk_chunks=40),
+    small("fp8-g8", batch=1, n_q_heads=16, n_kv_heads=2, ctx_len=8192, rank=64, topk_chunks=40),
     small("fp8-g3-odd", batch=1, n_q_heads=6, n_kv_heads=2, head_dim=64, ctx_len=1536, chunk_size=6, rank=24,
           topk_chunks=9, n_outlier_chunks=1, local_len=1),
     small("fp8-d96-c3", batch=1, n_q_heads=2, n_kv_heads=2, head_dim=96, ctx_len=999, chunk_size=3, rank=8,

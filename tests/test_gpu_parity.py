@@ -25,6 +25,10 @@ CASES = [
     small("d96-mha", n_q_heads=4, n_kv_heads=4, head_dim=96, ctx_len=2048, rank=40, topk_chunks=17,
           n_outlier_chunks=2, rope_theta=1e4),
     small("g16", batch=1, n_q_heads=32, n_kv_heads=2, ctx_len=8192, rank=64, topk_chunks=40),
+    small("g8", batch=1, n_q_heads=16, n_kv_heads=2, ctx_len=8192, rank=64, topk_chunks=40),      # 70B-class grouping
+    small("g12-d96", batch=1, n_q_heads=24, n_kv_heads=2, head_dim=96, ctx_len=4096, rank=48, topk_chunks=21),
+    small("g24-d64", batch=1, n_q_heads=24, n_kv_heads=1, head_dim=64, ctx_len=3000, chunk_size=3, rank=24,
+          topk_chunks=30, n_outlier_chunks=2),                                                     # two passes, the second half full
     small("g3-odd", batch=1, n_q_heads=6, n_kv_heads=2, head_dim=64, ctx_len=1536, chunk_size=6, rank=24,
           topk_chunks=9, n_outlier_chunks=1, local_len=1),
     small("no-outliers-no-local", n_outlier_chunks=0, local_len=0, ctx_len=1024, topk_chunks=7),
