@@ -39,7 +39,11 @@ __device__ __forceinline__ void lse_merge(double& m, double& s, double m2, doubl
 
 // EB = bytes per landmark element: 2 (bf16) or 1 (FP8 E5M2 storage; a row is then d bytes and a lane's
 // piece holds twice as many elements, or the same number in 8 bytes when d is not a multiple of 64).
-template <int D, int EB>
+// HG = groups of four heads per landmark element: 1, or 2 for 5 to 8 query heads per KV head.  With HG = 2 every
+// widened landmark element feeds two instructions (heads 0-3, heads 4-7; two accumulators per tile), so the
+// landmarks are read and converted once for all eight heads; the queries then live in LDS as fp64 (two groups of
+// them would not fit the registers beside the landmark rows).
+template <int D, int EB, int HG>
 __global__ __launch_bounds__(256) void score_kernel(const bf16_t* __restrict__ q, const uint8_t* __restrict__ L,
                                                     float* __restrict__ logits, double2* __restrict__ partials,
                                                     int hq, int hkv, int G, int n_c, int nc_stride, int n_tiles, double scale) {
@@ -47,8 +51,11 @@ __global__ __launch_bounds__(256) void score_kernel(const bf16_t* __restrict__ q
   constexpr int PE = PB / EB;                             // elements per piece
   constexpr int NI = D / (4 * PE);                        // pieces per lane per row
   constexpr int PW = PB / 4;                              // 32-bit words per piece
-  __shared__ double2 wred[4][4];
-  const int unit = blockIdx.y, tile = blockIdx.x, g0 = blockIdx.z * 4;
+  __shared__ double2 wred[4][4 * HG];
+  // HG = 2: q of the eight heads as fp64; rows padded so that the four heads a block column reads at once fall
+  // into different banks
+  __shared__ double qs[HG == 2 ? 8 : 1][HG == 2 ? D + 2 : 1];
+  const int unit = blockIdx.y, tile = blockIdx.x, g0 = blockIdx.z * 4 * HG;
   const int b = unit / hkv, h = unit % hkv;
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int kq = lane >> 4, blk = (lane >> 2) & 3, ij = lane & 3;
@@ -78,8 +85,14 @@ __global__ __launch_bounds__(256) void score_kernel(const bf16_t* __restrict__ q
   }
 
   // A operand: q of head g0 + ij, the elements this lane's k-slot meets, as fp64
-  double qa[NI][PE];
-  {
+  double qa[HG == 1 ? NI : 1][HG == 1 ? PE : 1];
+  if constexpr (HG == 2) {
+    for (int idx = threadIdx.x; idx < 8 * D; idx += 256) {
+      const int hh = idx / D, e = idx - hh * D;
+      qs[hh][e] = g0 + hh < G ? (double)bf16_to_f32(q[(head0 + hh) * D + e]) : 0.0;
+    }
+    __syncthreads();
+  } else {
     const bool hv = g0 + ij < G;
     const bf16_t* qp = q + (head0 + (hv ? ij : 0)) * D + PE * kq;
 #pragma unroll
@@ -93,41 +106,60 @@ __global__ __launch_bounds__(256) void score_kernel(const bf16_t* __restrict__ q
       }
   }
 
-  const int hd = g0 + (lane >> 4);  // head of this lane's results
-  double m = -INFINITY, s = 0.0;
+  double m[HG], s[HG];   // heads g0 + 4 hg + lane / 16
+#pragma unroll
+  for (int hg = 0; hg < HG; ++hg) { m[hg] = -INFINITY; s[hg] = 0.0; }
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
-    double acc = 0.0;
+    double acc[HG];
+#pragma unroll
+    for (int hg = 0; hg < HG; ++hg) acc[hg] = 0.0;
+    // one widened landmark element against the matching q element of each head group
+    auto step = [&](int i, int el, double lv) {
+      if constexpr (HG == 1) {
+        acc[0] = __builtin_amdgcn_mfma_f64_4x4x4f64(qa[i][el], lv, acc[0], 0, 0, 0);
+      } else {
+        const int col = 4 * PE * i + PE * kq + el;
+        acc[0] = __builtin_amdgcn_mfma_f64_4x4x4f64(qs[ij][col], lv, acc[0], 0, 0, 0);
+        acc[1] = __builtin_amdgcn_mfma_f64_4x4x4f64(qs[4 + ij][col], lv, acc[1], 0, 0, 0);
+      }
+    };
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
 #pragma unroll
       for (int x = 0; x < PW; ++x) {
         if constexpr (EB == 2) {
-          acc = __builtin_amdgcn_mfma_f64_4x4x4f64(qa[i][2 * x], (double)bf16_lo(w[t][i][x]), acc, 0, 0, 0);
-          acc = __builtin_amdgcn_mfma_f64_4x4x4f64(qa[i][2 * x + 1], (double)bf16_hi(w[t][i][x]), acc, 0, 0, 0);
+          step(i, 2 * x, (double)bf16_lo(w[t][i][x]));
+          step(i, 2 * x + 1, (double)bf16_hi(w[t][i][x]));
         } else {
           float f[4];
           e5m2x4_to_f32(w[t][i][x], f);
 #pragma unroll
-          for (int e = 0; e < 4; ++e)
-            acc = __builtin_amdgcn_mfma_f64_4x4x4f64(qa[i][4 * x + e], (double)f[e], acc, 0, 0, 0);
+          for (int e = 0; e < 4; ++e) step(i, 4 * x + e, (double)f[e]);
         }
       }
     }
     const int r = row0 + t * 16 + (lane & 15);
-    if (r < n_c && hd < G) {
-      const float p32 = (float)(acc * scale);   // THE logit: exact dot product, rounded once to fp32
-      logits[(head0 + (lane >> 4)) * n_c + r] = p32;
-      lse_merge(m, s, (double)p32, 1.0);
+#pragma unroll
+    for (int hg = 0; hg < HG; ++hg) {
+      const int hl = 4 * hg + (lane >> 4);   // head of this lane's result, inside the workgroup's heads
+      if (r < n_c && g0 + hl < G) {
+        const float p32 = (float)(acc[hg] * scale);   // THE logit: exact dot product, rounded once to fp32
+        logits[(head0 + hl) * n_c + r] = p32;
+        lse_merge(m[hg], s[hg], (double)p32, 1.0);
+      }
     }
   }
 
   // (max, sum) of each head over the workgroup's 256 rows
 #pragma unroll
-  for (int x = 8; x >= 1; x >>= 1) lse_merge(m, s, shfl_xor_f64(m, x), shfl_xor_f64(s, x));
-  if ((lane & 15) == 0) wred[wave][lane >> 4] = make_double2(m, s);
+  for (int hg = 0; hg < HG; ++hg) {
+#pragma unroll
+    for (int x = 8; x >= 1; x >>= 1) lse_merge(m[hg], s[hg], shfl_xor_f64(m[hg], x), shfl_xor_f64(s[hg], x));
+    if ((lane & 15) == 0) wred[wave][4 * hg + (lane >> 4)] = make_double2(m[hg], s[hg]);
+  }
   __syncthreads();
-  if (threadIdx.x < 4 && g0 + (int)threadIdx.x < G) {
+  if (threadIdx.x < 4 * HG && g0 + (int)threadIdx.x < G) {
     const int g = threadIdx.x;
     double M = -INFINITY, S = 0.0;
 #pragma unroll
@@ -254,16 +286,18 @@ hipError_t launch_score(const bf16_t* q, const void* landmarks, int kv_bytes, fl
                         int batch, int hq, int hkv, int d, int n_c, int nc_stride, double scale, hipStream_t st) {
   const int G = hq / hkv;
   const int n_tiles = (n_c + kScoreTile - 1) / kScoreTile;
-  // more than four heads per KV head: one pass per 16 heads on the 16x16x4 instruction (heads past the group are
-  // zero rows of its operand) instead of one pass over the landmarks per four heads
-  const bool g16 = G > 4;
+  // up to four heads per KV head: score_kernel<.., 1>; five to eight: score_kernel<.., 2>; more: one pass per 16
+  // heads on the 16x16x4 instruction (heads past the group are zero rows of its operand)
+  const bool g16 = G > 8;
   dim3 grid(n_tiles, batch * hkv, g16 ? (G + 15) / 16 : 1), block(256);
   const uint8_t* L = static_cast<const uint8_t*>(landmarks);
 #define SKV_SCORE(D_, EB_)                                                                                            \
   do {                                                                                                                \
     if (g16) hipLaunchKernelGGL((score_kernel_g16<D_, EB_>), grid, block, 0, st, q, L, logits, partials, hq, hkv, G,   \
                                 n_c, nc_stride, n_tiles, scale);                                                      \
-    else hipLaunchKernelGGL((score_kernel<D_, EB_>), grid, block, 0, st, q, L, logits, partials, hq, hkv, G, n_c,      \
+    else if (G > 4) hipLaunchKernelGGL((score_kernel<D_, EB_, 2>), grid, block, 0, st, q, L, logits, partials, hq,     \
+                                       hkv, G, n_c, nc_stride, n_tiles, scale);                                      \
+    else hipLaunchKernelGGL((score_kernel<D_, EB_, 1>), grid, block, 0, st, q, L, logits, partials, hq, hkv, G, n_c,   \
                             nc_stride, n_tiles, scale);                                                               \
   } while (0)
   switch (d * 4 + kv_bytes) {
