@@ -41,8 +41,7 @@ __device__ __forceinline__ void lse_merge(double& m, double& s, double m2, doubl
 // piece holds twice as many elements, or the same number in 8 bytes when d is not a multiple of 64).
 // HG = groups of four heads per landmark element: 1, or 2 for 5 to 8 query heads per KV head.  With HG = 2 every
 // widened landmark element feeds two instructions (heads 0-3, heads 4-7; two accumulators per tile), so the
-// landmarks are read and converted once for all eight heads; the queries then live in LDS as fp64 (two groups of
-// them would not fit the registers beside the landmark rows).
+// landmarks are read and converted once for all eight heads.  The queries live in LDS as fp64.
 template <int D, int EB, int HG>
 __global__ __launch_bounds__(256) void score_kernel(const bf16_t* __restrict__ q, const uint8_t* __restrict__ L,
                                                     float* __restrict__ logits, double2* __restrict__ partials,
@@ -52,9 +51,9 @@ __global__ __launch_bounds__(256) void score_kernel(const bf16_t* __restrict__ q
   constexpr int NI = D / (4 * PE);                        // pieces per lane per row
   constexpr int PW = PB / 4;                              // 32-bit words per piece
   __shared__ double2 wred[4][4 * HG];
-  // HG = 2: q of the eight heads as fp64; rows padded so that the four heads a block column reads at once fall
+  // q of the workgroup's heads as fp64; rows padded so that the four heads a block column reads at once fall
   // into different banks
-  __shared__ double qs[HG == 2 ? 8 : 1][HG == 2 ? D + 2 : 1];
+  __shared__ double qs[4 * HG][D + 2];
   const int unit = blockIdx.y, tile = blockIdx.x, g0 = blockIdx.z * 4 * HG;
   const int b = unit / hkv, h = unit % hkv;
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
@@ -84,27 +83,13 @@ __global__ __launch_bounds__(256) void score_kernel(const bf16_t* __restrict__ q
     }
   }
 
-  // A operand: q of head g0 + ij, the elements this lane's k-slot meets, as fp64
-  double qa[HG == 1 ? NI : 1][HG == 1 ? PE : 1];
-  if constexpr (HG == 2) {
-    for (int idx = threadIdx.x; idx < 8 * D; idx += 256) {
-      const int hh = idx / D, e = idx - hh * D;
-      qs[hh][e] = g0 + hh < G ? (double)bf16_to_f32(q[(head0 + hh) * D + e]) : 0.0;
-    }
-    __syncthreads();
-  } else {
-    const bool hv = g0 + ij < G;
-    const bf16_t* qp = q + (head0 + (hv ? ij : 0)) * D + PE * kq;
-#pragma unroll
-    for (int i = 0; i < NI; ++i)
-#pragma unroll
-      for (int e8 = 0; e8 < PE / 8; ++e8) {
-        float x[8];
-        load_bf16_row<8>(qp + 4 * PE * i + 8 * e8, x);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) qa[i][8 * e8 + e] = hv ? (double)x[e] : 0.0;
-      }
+  // A operand: q of the workgroup's heads as fp64, in LDS (registers are better spent on landmark rows in
+  // flight); a lane reads head 4 hg + ij, the elements its k-slot meets
+  for (int idx = threadIdx.x; idx < 4 * HG * D; idx += 256) {
+    const int hh = idx / D, e = idx - hh * D;
+    qs[hh][e] = g0 + hh < G ? (double)bf16_to_f32(q[(head0 + hh) * D + e]) : 0.0;
   }
+  __syncthreads();
 
   double m[HG], s[HG];   // heads g0 + 4 hg + lane / 16
 #pragma unroll
@@ -116,13 +101,10 @@ __global__ __launch_bounds__(256) void score_kernel(const bf16_t* __restrict__ q
     for (int hg = 0; hg < HG; ++hg) acc[hg] = 0.0;
     // one widened landmark element against the matching q element of each head group
     auto step = [&](int i, int el, double lv) {
-      if constexpr (HG == 1) {
-        acc[0] = __builtin_amdgcn_mfma_f64_4x4x4f64(qa[i][el], lv, acc[0], 0, 0, 0);
-      } else {
-        const int col = 4 * PE * i + PE * kq + el;
-        acc[0] = __builtin_amdgcn_mfma_f64_4x4x4f64(qs[ij][col], lv, acc[0], 0, 0, 0);
-        acc[1] = __builtin_amdgcn_mfma_f64_4x4x4f64(qs[4 + ij][col], lv, acc[1], 0, 0, 0);
-      }
+      const int col = 4 * PE * i + PE * kq + el;
+#pragma unroll
+      for (int hg = 0; hg < HG; ++hg)
+        acc[hg] = __builtin_amdgcn_mfma_f64_4x4x4f64(qs[4 * hg + ij][col], lv, acc[hg], 0, 0, 0);
     };
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
