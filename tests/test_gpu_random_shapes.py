@@ -14,6 +14,8 @@ pytestmark = pytest.mark.gpu
 
 
 def draw_shape(seed: int) -> Workload:
+    if seed >= 100:
+        return draw_shape_large_group(seed)
     rng = np.random.default_rng(1000 + seed)
     d = int(rng.choice([64, 96, 128]))
     hkv = int(rng.choice([1, 2, 3, 4]))
@@ -30,8 +32,27 @@ def draw_shape(seed: int) -> Workload:
                     value_location=str(rng.choice(["hbm", "host"])), n_queries=2)
 
 
+def draw_shape_large_group(seed: int) -> Workload:
+    """Shapes with 5 to 20 query heads per KV head (the scoring kernels for large groups, several head blocks per
+    unit in the attention)."""
+    rng = np.random.default_rng(5000 + seed)
+    d = int(rng.choice([64, 96, 128]))
+    hkv = int(rng.choice([1, 2, 3]))
+    G = int(rng.choice([5, 6, 7, 8, 9, 12, 16, 20]))
+    c = int(rng.choice([1, 2, 3, 4, 5, 8, 8, 8, 12, 16]))
+    n_ch = int(rng.integers(40, 900))
+    o = int(rng.integers(0, min(12, n_ch // 4)))
+    k = int(rng.integers(1, min(n_ch - o, 96)))
+    r = int(min(hkv * d, 8 * rng.integers(1, 25)))
+    return Workload(name=f"rand{seed}", batch=int(rng.choice([1, 2, 3])), n_q_heads=hkv * G, n_kv_heads=hkv, head_dim=d,
+                    ctx_len=n_ch * c, chunk_size=c, rank=r, n_outlier_chunks=o, topk_chunks=k,
+                    local_len=int(rng.integers(0, 40)), rope_theta=float(rng.choice([1e4, 5e5])), seed=300 + seed,
+                    value_location=str(rng.choice(["hbm", "host"])), n_queries=2)
+
+
 # every shape with bf16 storage of the KV cache; every other one also with FP8 E5M2 storage (seeds 100 + ...)
-@pytest.mark.parametrize("seed,kd", [(s, 0) for s in range(14)] + [(s, 1) for s in range(0, 14, 2)] + [(s, 1) for s in range(14, 20)],
+@pytest.mark.parametrize("seed,kd", [(s, 0) for s in range(14)] + [(s, 1) for s in range(0, 14, 2)] + [(s, 1) for s in range(14, 20)]
+                         + [(100 + s, s % 2) for s in range(8)],   # large head groups, alternating storage,
                          ids=lambda v: str(v))
 def test_random_shape(seed, kd):
     wl = draw_shape(seed)
