@@ -106,11 +106,14 @@ def test_repeated_calls_are_deterministic():
     assert torch.equal(o1, o2) and torch.equal(i1, i2)
 
 
-@pytest.mark.parametrize("host_values,two_streams", [(False, False), (True, False), (True, True)])
-def test_hip_graph_replays_match_eager(host_values, two_streams):
+@pytest.mark.parametrize("host_values,two_streams,rank", [(False, False, 32), (True, False, 32), (True, True, 32),
+                                                         (False, False, 256), (True, False, 256)])
+def test_hip_graph_replays_match_eager(host_values, two_streams, rank):
     """A captured decode step (gather inside the key-phase launch, or forked to a second stream) replays to the
     eager result, several times, with eager work and synchronisations between the replays."""
-    wl = small("graph", ctx_len=8192, topk_chunks=48, value_location="host" if host_values else "hbm", n_queries=3)
+    # rank 256: the attention kernel's LDS request goes above the default limit and is raised at launch time
+    wl = small("graph", ctx_len=8192, topk_chunks=48, value_location="host" if host_values else "hbm", n_queries=3,
+               rank=rank)
     t = PU.draw(wl)
     p = S.Params.from_workload(wl)
     bl = S.build_landmarks(p, t["k_rope"], t["v"])
