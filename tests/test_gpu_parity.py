@@ -97,6 +97,29 @@ def test_positions_beyond_one_million_and_inv_freq_override():
     print(f"[decode] inv_freq override: {stats}", flush=True)
 
 
+def test_optional_arguments_may_be_null():
+    """NULL `pos_offset` means position 0 for every sequence, NULL `out_chunk_ids` only drops that copy of the ids:
+    the raw C entry point with both NULL gives the output of the call with explicit zeros."""
+    import ctypes as C
+    wl = small("null-args", ctx_len=2048, topk_chunks=16)
+    t = PU.draw(wl)
+    p = S.Params.from_workload(wl)
+    bl = S.build_landmarks(p, t["k_rope"], t["v"])
+    zeros = torch.zeros(wl.batch, dtype=torch.int32, device="cuda")
+    args = (t["q_pool"][0], t["A"], t["B"], bl["landmarks"], bl["landmark_chunk_ids"], bl["k_outlier"], bl["v_outlier"],
+            t["k_local"], t["v_local"], t["v"])
+    want, _, _ = S.decode_step(p, *args, zeros)
+    torch.cuda.synchronize()
+    st = p.c_struct()
+    ws = S.alloc_workspace(S.decode_workspace_bytes(p))
+    out = torch.zeros_like(want)
+    rc = S.lib().shadowkv_decode_step(C.addressof(st), *[x.data_ptr() for x in args], None, out.data_ptr(), None,
+                                      ws.data_ptr(), ws.numel(), torch.cuda.current_stream().cuda_stream, None)
+    assert rc == S.OK, S.last_error()
+    torch.cuda.synchronize()
+    assert torch.equal(out, want)
+
+
 def test_repeated_calls_are_deterministic():
     wl = small("determinism")
     t = PU.draw(wl)
