@@ -59,6 +59,9 @@ def main() -> int:
     ap.add_argument("--side-stream", action="store_true",
                     help="run the value gather as a launch of its own on a second stream (default: it shares the "
                          "launch of the attention's key phase)")
+    ap.add_argument("--copies", type=int, default=1,
+                    help="copies of the layer's tensors used in turn (defeats reuse of the previous step's data in "
+                         "the last-level cache; default 1 = the one layer the configurations name)")
     ap.add_argument("--no-graph", action="store_true", help="enqueue the timed steps eagerly instead of replaying a HIP graph")
     ap.add_argument("--force-graph", action="store_true",
                     help="replay a HIP graph also where the default is eager (--side-stream)")
@@ -135,14 +138,28 @@ def main() -> int:
         pool = query_sequence(wl, 64, args.rho_q, device=dev)   # a ring: replaying it has no jump at the wrap
         cache = S.ValueCache(p, slots=args.cache_slots or None, device=dev)
 
+    # --copies N: N copies of the layer's device tensors, used in turn, so that no step finds the previous step's
+    # data in the 256 MB last-level cache (what a model with many layers would see); the default is the single
+    # layer the benchmark configurations name.
+    def layer_copy():
+        def dup(x):
+            return x.clone() if x.device.type == "cuda" else x      # a pinned host store is shared: it is not cached
+        return ({k: dup(t[k]) for k in ("A", "B", "k_local", "v_local", "v")},
+                {k: dup(bl[k]) for k in ("landmarks", "landmark_chunk_ids", "k_outlier", "v_outlier")})
+    layers = [(t, bl)] + [layer_copy() for _ in range(max(args.copies, 1) - 1)]
+    if len(layers) > 1 and (args.chunk_cache or args.append):
+        print("bench.py: --copies is for the plain decode step only", file=sys.stderr)
+        return 2
+
     def step(i: int):
         if cache is not None:
             S.decode_step_cached(p, pool[i % pool.shape[0]], t["A"], t["B"], bl["landmarks"], bl["landmark_chunk_ids"],
                                  bl["k_outlier"], bl["v_outlier"], t["k_local"], t["v_local"], t["v"], cache,
                                  t["pos_offset"], out=out, out_chunk_ids=ids, workspace=ws, side_stream=side)
             return
-        S.decode_step(p, pool[i % pool.shape[0]], t["A"], t["B"], bl["landmarks"], bl["landmark_chunk_ids"],
-                      bl["k_outlier"], bl["v_outlier"], t["k_local"], t["v_local"], t["v"], t["pos_offset"],
+        lt, lb = layers[i % len(layers)]
+        S.decode_step(p, pool[i % pool.shape[0]], lt["A"], lt["B"], lb["landmarks"], lb["landmark_chunk_ids"],
+                      lb["k_outlier"], lb["v_outlier"], lt["k_local"], lt["v_local"], lt["v"], t["pos_offset"],
                       out=out, out_chunk_ids=ids, workspace=ws, side_stream=side)
 
     for i in range(args.warmup):
@@ -275,7 +292,7 @@ def main() -> int:
                                f"heads, d={wl.head_dim}, c={wl.chunk_size}, r={wl.rank}, k={wl.topk_chunks}, "
                                f"o={wl.n_outlier_chunks}, w={wl.local_len}, values in {wl.value_location}"
                                + (", KV cache stored as FP8 E5M2" if fp8 else ""),
-                   "layers": 1, "side_stream": side is not None, "kv_storage": "fp8_e5m2" if fp8 else "bf16"},
+                   "layers": 1, "tensor_copies": len(layers), "side_stream": side is not None, "kv_storage": "fp8_e5m2" if fp8 else "bf16"},
         "roofline": {"kernel": "score_kernel (landmark scoring, P = Q L^T)", "bound": "hbm", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
                      "algorithmic_bytes_per_launch": score_bytes, "avg_launch_ms": score_ms,
