@@ -112,7 +112,7 @@ AttnPlan plan_attention(const Shape& sh) {
   const long kc = (long)sh.k * sh.c, n_res = (long)sh.o * sh.c + sh.w;
   // the largest split (fewest B^T stagings) that still gives >= 512 workgroups
   long len = 32;
-  for (long cand : {512l, 256l, 128l, 64l}) if (kc * groups / cand >= 512) { len = cand; break; }
+  for (long cand : {1024l, 512l, 256l, 128l, 64l}) if (kc * groups / cand >= 512) { len = cand; break; }
   // tuning override: rows per split (read once)
   static const long forced = [] { const char* ov = std::getenv("SHADOWKV_SPARSE_SPLIT"); return ov ? std::atol(ov) : 0l; }();
   if (forced >= 32 && forced <= 1024 && forced % 32 == 0) len = forced;
