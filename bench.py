@@ -53,7 +53,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="c3-hbm", help="c1 | c2 | c3-hbm | c3-host | c4 | c5 (the benchmark's configurations), c3-g8")
+    ap.add_argument("--workload", default="c3-hbm", help="c1 | c2 | c3-hbm | c3-host | c4 | c5 (the benchmark's configurations), c3-g7, c3-g8")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU time budget of the oracle leg")
     ap.add_argument("--side-stream", action="store_true",

@@ -194,6 +194,8 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
   }
   const int G = a.hq / a.hkv, b = unit / a.hkv, h = unit % a.hkv;
   const size_t head0 = (size_t)b * a.hq + (size_t)h * G + g0;
+  const int nv = min(GH, G - g0);   // heads of this block that exist (the last block of a group may be partly empty:
+                                    // its surplus heads repeat the last real one and are never written)
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform: keeps the row loops scalar
   const int sub = lane & 15, rg = lane >> 4;
@@ -335,7 +337,7 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
 #pragma unroll
     for (int g = 0; g < GH; ++g) {
       float x[EPL];
-      load_bf16_row<EPL>(a.q + (head0 + g) * D + sub * EPL, x);
+      load_bf16_row<EPL>(a.q + (head0 + min(g, nv - 1)) * D + sub * EPL, x);
 #pragma unroll
       for (int e = 0; e < EPL; ++e) qv[g][e] = x[e] * a.scale_log2;
     }
@@ -406,7 +408,8 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
 #pragma unroll
     for (int g = 0; g < GH; ++g)
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb) qc[g][nb] = bf16_to_f32(a.q[(head0 + g) * D + nb * 16 + sub]) * a.scale_log2;
+      for (int nb = 0; nb < NB; ++nb)
+        qc[g][nb] = bf16_to_f32(a.q[(head0 + min(g, nv - 1)) * D + nb * 16 + sub]) * a.scale_log2;
     double frev[HB];
 #pragma unroll
     for (int nb = 0; nb < HB; ++nb) {
@@ -499,7 +502,7 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
               float v = lg[0][g];
 #pragma unroll
               for (int j = 1; j < 4; ++j) v = sub == j ? lg[j][g] : v;
-              a.logit_buf[(head0 + g) * (size_t)kc + i] = v;
+              if (g < nv) a.logit_buf[(head0 + g) * (size_t)kc + i] = v;
             }
           }
         }
@@ -547,7 +550,7 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
     if (lane == 0) { sm_m[wave][g] = mt; sm_l[wave][g] = lv; }
   }
   __syncthreads();
-  for (int idx = threadIdx.x; idx < GH * D; idx += 256) {
+  for (int idx = threadIdx.x; idx < nv * D; idx += 256) {
     const int g = idx / D, e = idx - g * D;
     float M = -INFINITY;
 #pragma unroll
@@ -580,6 +583,7 @@ __global__ __launch_bounds__(256) void sparse_values_kernel(AttnArgs a) {
   const int unit = blockIdx.y, split = blockIdx.x, g0 = blockIdx.z * GH;
   const int G = a.hq / a.hkv, b = unit / a.hkv, h = unit % a.hkv;
   const size_t head0 = (size_t)b * a.hq + (size_t)h * G + g0;
+  const int nv = min(GH, G - g0);   // heads of this block that exist; surplus ones repeat the last real one
   const int sub = threadIdx.x & 15, grp = threadIdx.x >> 4;
   const int kc = a.k * a.c;
   const int r_begin = split * a.pv_split_len, r_end = min(kc, r_begin + a.pv_split_len);
@@ -593,7 +597,7 @@ __global__ __launch_bounds__(256) void sparse_values_kernel(AttnArgs a) {
   for (int g = 0; g < GH; ++g) mx[g] = -INFINITY;
   for (int i = r_begin + threadIdx.x; i < r_end; i += 256)
 #pragma unroll
-    for (int g = 0; g < GH; ++g) mx[g] = fmaxf(mx[g], lg[(size_t)g * kc + i]);
+    for (int g = 0; g < GH; ++g) mx[g] = fmaxf(mx[g], lg[(size_t)min(g, nv - 1) * kc + i]);
 #pragma unroll
   for (int g = 0; g < GH; ++g) {
 #pragma unroll
@@ -627,7 +631,7 @@ __global__ __launch_bounds__(256) void sparse_values_kernel(AttnArgs a) {
       const int slot = a.v_slots ? a.v_slots[(size_t)unit * a.k + ch] : ch;
       load_raw<EPL, EB>(vbase + (((size_t)min(max(slot, 0), last_slot) * a.c + t) * D + sub * EPL) * EB, vraw[x]);
 #pragma unroll
-      for (int g = 0; g < GH; ++g) p[x][g] = i < r_end ? lg[(size_t)g * kc + ic] : -INFINITY;
+      for (int g = 0; g < GH; ++g) p[x][g] = i < r_end ? lg[(size_t)min(g, nv - 1) * kc + ic] : -INFINITY;
     }
 #pragma unroll
     for (int x = 0; x < 4; ++x) {
@@ -649,7 +653,7 @@ __global__ __launch_bounds__(256) void sparse_values_kernel(AttnArgs a) {
     for (int e = 0; e < EPL; ++e) sm_acc[grp][g][sub * EPL + e] = acc[g][e];
   }
   __syncthreads();
-  for (int idx = threadIdx.x; idx < GH * D; idx += 256) {
+  for (int idx = threadIdx.x; idx < nv * D; idx += 256) {
     const int g = idx / D, e = idx - g * D;
     float num = 0.f, den = 0.f;
 #pragma unroll
@@ -751,8 +755,9 @@ static hipError_t launch_keys_d(const AttnArgs& a, hipStream_t st) {
   const int gh = attention_heads_per_group(G);
   // B^T (as bf16 whatever the storage), then the first token and the first value row of each chunk a split touches
   const size_t lds = (size_t)D * a.rp * sizeof(bf16_t) + 2 * ((size_t)a.sparse_split_len / a.c + 2) * sizeof(int);
-  dim3 grid(a.batch * a.hkv, a.n_splits, G / gh);
-  if (KEYS_ONLY) grid = dim3((unsigned)(a.gather.n_blocks + (long)a.n_splits * a.batch * a.hkv * (G / gh)));
+  const int zb = (G + gh - 1) / gh;   // head blocks per unit (the last one may be partly empty)
+  dim3 grid(a.batch * a.hkv, a.n_splits, zb);
+  if (KEYS_ONLY) grid = dim3((unsigned)(a.gather.n_blocks + (long)a.n_splits * a.batch * a.hkv * zb));
   switch (gh) {
     case 4: return launch_sparse_ks<D, 4, KEYS_ONLY, EB>(a, grid, lds, st);
     case 2: return launch_sparse_ks<D, 2, KEYS_ONLY, EB>(a, grid, lds, st);
@@ -770,8 +775,8 @@ static hipError_t launch_combine_d(const AttnArgs& a, hipStream_t st) {
 template <int D, int EB>
 static hipError_t launch_values_d(const AttnArgs& a, hipStream_t st) {
   const int G = a.hq / a.hkv;
-  const int gh = G % 4 == 0 ? 4 : attention_heads_per_group(G);
-  dim3 grid(a.n_pv_splits, a.batch * a.hkv, G / gh);
+  const int gh = attention_heads_per_group(G);
+  dim3 grid(a.n_pv_splits, a.batch * a.hkv, (G + gh - 1) / gh);
   switch (gh) {
     case 4: hipLaunchKernelGGL((sparse_values_kernel<D, 4, EB>), grid, dim3(256), 0, st, a); break;
     case 2: hipLaunchKernelGGL((sparse_values_kernel<D, 2, EB>), grid, dim3(256), 0, st, a); break;

@@ -120,7 +120,9 @@ struct AttnArgs {
   RopeFreqs freqs;
   GatherArgs gather;        // key phase of the two-phase path only: value gather done by the same launch
 };
-inline int attention_heads_per_group(int G) { return (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1; }
+// Query heads per attention workgroup: four wherever the group has at least three heads (a group of 3, 5, 6 or 7
+// leaves part of its last block empty, which costs less than rebuilding the keys once more per head or pair).
+inline int attention_heads_per_group(int G) { return G >= 3 ? 4 : G; }
 hipError_t launch_attention(const AttnArgs& a, hipStream_t st);         // values readable now: one fused kernel
 hipError_t launch_attention_keys(const AttnArgs& a, hipStream_t st);    // two-phase path, before the values arrive
 hipError_t launch_attention_values(const AttnArgs& a, hipStream_t st);  // two-phase path, after

@@ -107,7 +107,7 @@ struct AttnPlan {
 };
 AttnPlan plan_attention(const Shape& sh) {
   AttnPlan ap;
-  ap.z = sh.G / attention_heads_per_group(sh.G);
+  ap.z = (sh.G + attention_heads_per_group(sh.G) - 1) / attention_heads_per_group(sh.G);
   const long groups = (long)sh.units * ap.z;
   const long kc = (long)sh.k * sh.c, n_res = (long)sh.o * sh.c + sh.w;
   // the largest split (fewest B^T stagings) that still gives >= 512 workgroups

@@ -88,6 +88,8 @@ CONFIGS: Dict[str, Workload] = {
 # Further shapes bench.py accepts by name; not part of the benchmark's five.
 EXTRA_CONFIGS: Dict[str, Workload] = {
     # c3-hbm with eight query heads per KV head (the grouping of 70B-class models)
+    # 28 query / 4 KV heads (seven per group: the last four-head block of a group is partly empty)
+    "c3-g7": Workload("c3-g7", 16, 28, 4, 128, 131072, rank=160, seed=2, value_location="hbm", plant="outliers"),
     "c3-g8": Workload("c3-g8", 16, 64, 8, 128, 131072, seed=2, value_location="hbm", plant="outliers"),
 }
 
