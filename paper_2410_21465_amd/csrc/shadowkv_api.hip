@@ -116,6 +116,7 @@ AttnPlan plan_attention(const Shape& sh) {
   // tuning override: rows per split (read once)
   static const long forced = [] { const char* ov = std::getenv("SHADOWKV_SPARSE_SPLIT"); return ov ? std::atol(ov) : 0l; }();
   if (forced >= 32 && forced <= 1024 && forced % 32 == 0) len = forced;
+  while ((kc + len - 1) / len > 65535) len *= 2;   // the splits are a grid dimension
   ap.sparse_split_len = (int)len;
   ap.n_splits = (int)((kc + len - 1) / len);
   ap.res_split_len = (int)((n_res + ap.n_splits - 1) / ap.n_splits);
