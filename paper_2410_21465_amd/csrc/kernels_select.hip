@@ -51,9 +51,9 @@ __device__ void unit_lse(const double2* __restrict__ part, int n_tiles, int G, d
   __syncthreads();
 }
 
-// WIDE: the variant for more than 4 query heads per KV head or more than 64 score tiles per head (it spends
+// WIDE > 0: the variants for more than 4 query heads per KV head or more than 64 score tiles per head (they spend
 // registers on loads in flight that the common case does not need).
-template <int E, int SRC, bool WIDE>
+template <int E, int SRC, int WIDE>
 __global__ __launch_bounds__(kSelNT) void select_slices(SelectArgs a) {
   __shared__ SelectSmem<kSelNT> sm;
   __shared__ double lse_sm[64];
@@ -76,7 +76,7 @@ __global__ __launch_bounds__(kSelNT) void select_slices(SelectArgs a) {
 #pragma unroll
       for (int e = 0; e < E; ++e) pre[g][e] = row[min(j0 + e, a.n - 1)];
     }
-    unit_lse<WIDE ? 4 : 1>(a.partials + (size_t)unit * a.G * a.n_tiles, a.n_tiles, a.G, lse_sm);
+    unit_lse<WIDE == 0 ? 1 : WIDE == 1 ? 4 : 8>(a.partials + (size_t)unit * a.G * a.n_tiles, a.n_tiles, a.G, lse_sm);
 #pragma unroll
     for (int e = 0; e < E; ++e) key[e] = 0ull;
 #pragma unroll
@@ -93,7 +93,7 @@ __global__ __launch_bounds__(kSelNT) void select_slices(SelectArgs a) {
     }
     // the remaining heads of a large group: with few keys per thread a batch of 32 logits is requested
     // before it is used; the wide variants have no registers to spare and take one head at a time
-    constexpr int GB = !WIDE ? 1 : E <= 4 ? 8 : E <= 8 ? 4 : 1;
+    constexpr int GB = WIDE == 0 ? 1 : E <= 4 ? (WIDE == 1 ? 4 : 12) : E <= 8 ? 4 : 1;
     for (int gb = GP; gb < a.G; gb += GB) {
       float more[GB][E];
 #pragma unroll
@@ -244,7 +244,7 @@ bool plan_select(int n, int k, SelectPlan* plan) {
   return false;
 }
 
-template <int SRC, bool WIDE>
+template <int SRC, int WIDE>
 static hipError_t launch_slices_w(const SelectArgs& a, int e, int units, hipStream_t st) {
   dim3 grid(a.n_slices, units), block(kSelNT);
   switch (e) {
@@ -258,8 +258,10 @@ static hipError_t launch_slices_w(const SelectArgs& a, int e, int units, hipStre
 }
 template <int SRC>
 static hipError_t launch_slices(const SelectArgs& a, int e, int units, hipStream_t st) {
-  if (SRC == kSrcLogits && (a.G > 4 || a.n_tiles > 64)) return launch_slices_w<SRC, true>(a, e, units, st);
-  return launch_slices_w<SRC, false>(a, e, units, st);
+  // 0: the common case; 1: 5 to 8 heads per KV head or more than 64 score tiles per head; 2: more than 8 heads
+  if (SRC == kSrcLogits && a.G > 8) return launch_slices_w<SRC, 2>(a, e, units, st);
+  if (SRC == kSrcLogits && (a.G > 4 || a.n_tiles > 64)) return launch_slices_w<SRC, 1>(a, e, units, st);
+  return launch_slices_w<SRC, 0>(a, e, units, st);
 }
 
 template <bool MID>
