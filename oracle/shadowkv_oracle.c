@@ -14,9 +14,7 @@
  *   - inputs are the same bit patterns the GPU gets (bf16, or FP8 E5M2 bytes for
  *     the KV-cache tensors in the FP8 storage mode), widened exactly to
  *     fp64; every sum, norm, exponential and angle is fp64; nothing is rounded
- *     on the way except the chunk logits of the decode step (once, to fp32:
- *     the paper forms them in bf16) and the bf16 outputs (round-to-nearest-even
- *     from fp64);
+ *     on the way to the bf16 outputs (round-to-nearest-even from fp64);
  *   - the steps run in the paper's order with its notation, no blocking and
  *     no fusion, so it can be checked against the paper by eye;
  *   - only tests, the smoke check and the benchmark's cpu_baseline leg may
@@ -333,12 +331,6 @@ int oracle_decode_step(const oracle_params *p, const uint16_t *q,
     if (!P || !z2 || !Kt || !Vt || !a) {
       fail = 1; free(P); free(z2); free(Kt); free(Vt); free(a); continue;
     }
-    /* Precision of the chunk logits: the paper runs this GEMM in the model's bf16 (section
-     * "Precision Sensitivity": BF16 for weights and KV cache).  Here the dot product is formed
-     * exactly (bf16 products, fp64 sum) and rounded ONCE to fp32 -- sixteen more bits than the
-     * paper's -- and that fp32 value is the logit everything downstream sees (normaliser, group
-     * maximum, ranking).  Logits that agree to fp32 precision are ties (lower slot wins).
-     * Everything after the logit stays fp64. */
     /* P <- Q L^T, scaled by 1/sqrt(d); S <- Softmax over the landmarks.
      * Kept in the log domain: log S = P - logsumexp(P) per query head.
      * (The sum over the s_q query positions is the identity for s_q = 1.) */
@@ -348,7 +340,7 @@ int oracle_decode_step(const oracle_params *p, const uint16_t *q,
       for (int64_t j = 0; j < n_c; ++j) {
         double dot = 0.0;
         for (int x = 0; x < d; ++x) dot += bf16_to_f64(qg[x]) * kv_get(p, landmarks, L0 + j * d + x);
-        P[g * n_c + j] = (double)(float)(dot * scale); /* the chunk logit, kept in fp32 (see above) */
+        P[g * n_c + j] = dot * scale;
         if (P[g * n_c + j] > mx) mx = P[g * n_c + j];
       }
       double se = 0.0;

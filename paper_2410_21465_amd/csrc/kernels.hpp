@@ -17,11 +17,11 @@ struct RopeFreqs {
 };
 
 // ---- landmark scoring (decoding algorithm, P = Q L^T / sqrt(d)) ----------------
-// logits [b*h_q, n_c] fp32 (exact dot product rounded once); partials [b*h_q, n_tiles] (max, sum exp(p - max))
+// logits [b*h_q, n_c] fp64; partials [b*h_q, n_tiles] (max, sum exp(p - max))
 // per tile, fp64.
 // landmarks [units, nc_stride, d]: n_c valid rows per unit.
 // kv_bytes (here and below): bytes per element of the KV-cache tensors, 2 = bf16, 1 = FP8 E5M2.
-hipError_t launch_score(const bf16_t* q, const void* landmarks, int kv_bytes, float* logits, double2* partials,
+hipError_t launch_score(const bf16_t* q, const void* landmarks, int kv_bytes, double* logits, double2* partials,
                         int batch, int hq, int hkv, int d, int n_c, int nc_stride, double scale, hipStream_t st);
 
 // ---- ArgTopK -------------------------------------------------------------------
@@ -29,7 +29,7 @@ constexpr int kSrcLogits = 0;  // key = max over the group of (logit - lse)
 constexpr int kSrcArray = 1;   // key = sign * scores[unit, j]
 
 struct SelectArgs {
-  const float* logits;      // kSrcLogits: [units*G, n]
+  const double* logits;     // kSrcLogits: [units*G, n]
   const double2* partials;  //             [units*G, n_tiles]
   int n_tiles, G;
   const double* scores;     // kSrcArray: [units, n]

@@ -2,13 +2,13 @@
 // decoding algorithm), streamed once from HBM for the heads of a KV group (up to four here, up to 16 per pass in
 // score_kernel_g16 further down).
 //
-// The scores decide an index set that has to match a reference bit for bit: the logit
-// is defined as the exact dot product of the bf16 inputs rounded once to fp32, so the
-// inputs are widened to fp64 and contracted on the fp64 matrix pipe
-// (v_mfma_f64_4x4x4f64: four independent 4x4x4 blocks per wave, 256 FMAs per issue, no
-// cross-lane reduction needed) and the sum is rounded at the end -- an fp32 accumulation
-// would make the stored value depend on the order of summation.  The vector ALU only
-// unpacks and converts, which leaves the kernel bound by the HBM read of L.
+// The scores decide an index set that has to match an fp64 reference: the logit is the
+// plain dot product of the bf16 inputs, so the inputs are widened to fp64 and contracted on
+// the fp64 matrix pipe (v_mfma_f64_4x4x4f64: four independent 4x4x4 blocks per wave, 256 FMAs
+// per issue, no cross-lane reduction needed); the products are exact and the fp64 sum does
+// not depend on the order of summation beyond its last bit.  The logits are stored as fp64:
+// nothing is rounded between the contraction and the ranking.  The vector ALU only unpacks
+// and converts, which leaves the kernel bound by the HBM read of L.
 //
 // Operand layout of the instruction, as measured on gfx950: input lane
 // = 16*k + 4*block + (i for A | j for B), result lane = 16*i + 4*block + j.
@@ -16,7 +16,7 @@
 // k = which 16-byte piece of each 64-byte row segment the lane loads.  A wave covers
 // 64 rows (four 16-row tiles, all loads issued before the first MFMA), a workgroup 256.
 // Result lane 16*i + r holds the logit of head i, row r of the tile: it stores it
-// (16 consecutive floats per head) and folds it into its running (max, sum exp),
+// (16 consecutive doubles per head) and folds it into its running (max, sum exp),
 // from which the selection kernel forms each head's log-sum-exp.
 #include "kernels.hpp"
 
@@ -44,7 +44,7 @@ __device__ __forceinline__ void lse_merge(double& m, double& s, double m2, doubl
 // landmarks are read and converted once for all eight heads.  The queries live in LDS as fp64.
 template <int D, int EB, int HG>
 __global__ __launch_bounds__(256) void score_kernel(const bf16_t* __restrict__ q, const uint8_t* __restrict__ L,
-                                                    float* __restrict__ logits, double2* __restrict__ partials,
+                                                    double* __restrict__ logits, double2* __restrict__ partials,
                                                     int hq, int hkv, int G, int n_c, int nc_stride, int n_tiles, double scale) {
   constexpr int PB = (EB == 2 || D % 64 == 0) ? 16 : 8;  // bytes per piece
   constexpr int PE = PB / EB;                             // elements per piece
@@ -126,9 +126,9 @@ __global__ __launch_bounds__(256) void score_kernel(const bf16_t* __restrict__ q
     for (int hg = 0; hg < HG; ++hg) {
       const int hl = 4 * hg + (lane >> 4);   // head of this lane's result, inside the workgroup's heads
       if (r < n_c && g0 + hl < G) {
-        const float p32 = (float)(acc[hg] * scale);   // THE logit: exact dot product, rounded once to fp32
-        logits[(head0 + hl) * n_c + r] = p32;
-        lse_merge(m[hg], s[hg], (double)p32, 1.0);
+        const double p = acc[hg] * scale;   // the logit: exact products, fp64 sum
+        logits[(head0 + hl) * n_c + r] = p;
+        lse_merge(m[hg], s[hg], p, 1.0);
       }
     }
   }
@@ -153,11 +153,11 @@ __global__ __launch_bounds__(256) void score_kernel(const bf16_t* __restrict__ q
 // Groups of more than 4 query heads per KV head: the 16x16x4 form of the fp64 matrix instruction takes up to
 // 16 heads at once (A lane l = (head l % 16, k-slot l / 16), B lane l = (row l % 16, k-slot l / 16), result register j
 // of lane l = (head 4 j + l / 16, row l % 16); measured on gfx950), so every landmark element is loaded and widened
-// once instead of once per four heads.  Same tiles, same logits (exact sum, one rounding) and partials as above.
+// once instead of once per four heads.  Same tiles, same logits (exact products, fp64 sum) and partials as above.
 typedef double f64x4_t __attribute__((ext_vector_type(4)));
 template <int D, int EB>
 __global__ __launch_bounds__(256) void score_kernel_g16(const bf16_t* __restrict__ q, const uint8_t* __restrict__ L,
-                                                        float* __restrict__ logits, double2* __restrict__ partials,
+                                                        double* __restrict__ logits, double2* __restrict__ partials,
                                                         int hq, int hkv, int G, int n_c, int nc_stride, int n_tiles,
                                                         double scale) {
   constexpr int PB = (EB == 2 || D % 64 == 0) ? 16 : 8;
@@ -241,9 +241,9 @@ __global__ __launch_bounds__(256) void score_kernel_g16(const bf16_t* __restrict
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         if (g0 + 4 * j + kq < G) {
-          const float p32 = (float)(acc[t][j] * scale);   // the logit: exact dot product, rounded once to fp32
-          logits[(head0 + 4 * j + kq) * n_c + r] = p32;
-          lse_merge(m[j], s[j], (double)p32, 1.0);
+          const double p = acc[t][j] * scale;   // the logit: exact products, fp64 sum
+          logits[(head0 + 4 * j + kq) * n_c + r] = p;
+          lse_merge(m[j], s[j], p, 1.0);
         }
       }
     }
@@ -264,7 +264,7 @@ __global__ __launch_bounds__(256) void score_kernel_g16(const bf16_t* __restrict
   }
 }
 
-hipError_t launch_score(const bf16_t* q, const void* landmarks, int kv_bytes, float* logits, double2* partials,
+hipError_t launch_score(const bf16_t* q, const void* landmarks, int kv_bytes, double* logits, double2* partials,
                         int batch, int hq, int hkv, int d, int n_c, int nc_stride, double scale, hipStream_t st) {
   const int G = hq / hkv;
   const int n_tiles = (n_c + kScoreTile - 1) / kScoreTile;

@@ -67,12 +67,12 @@ __global__ __launch_bounds__(kSelNT) void select_slices(SelectArgs a) {
     // the logits of the first heads are requested before the normalisers are formed (the two do not
     // depend on each other), the remaining heads of a large group afterwards
     constexpr int GP = 4;
-    const float* lg = a.logits + (size_t)unit * a.G * a.n;
+    const double* lg = a.logits + (size_t)unit * a.G * a.n;
     const int j0 = base + threadIdx.x * E;
-    float pre[GP][E];
+    double pre[GP][E];
 #pragma unroll
     for (int g = 0; g < GP; ++g) {
-      const float* row = lg + (size_t)min(g, a.G - 1) * a.n;
+      const double* row = lg + (size_t)min(g, a.G - 1) * a.n;
 #pragma unroll
       for (int e = 0; e < E; ++e) pre[g][e] = row[min(j0 + e, a.n - 1)];
     }
@@ -86,7 +86,7 @@ __global__ __launch_bounds__(kSelNT) void select_slices(SelectArgs a) {
 #pragma unroll
         for (int e = 0; e < E; ++e)
           if (j0 + e < a.n) {
-            const uint64_t kk = f64_key((double)pre[g][e] - l);
+            const uint64_t kk = f64_key(pre[g][e] - l);
             key[e] = kk > key[e] ? kk : key[e];   // max over the heads of the group
           }
       }
@@ -95,12 +95,12 @@ __global__ __launch_bounds__(kSelNT) void select_slices(SelectArgs a) {
     // before it is used; the wide variants have no registers to spare and take one head at a time
     constexpr int GB = WIDE == 0 ? 1 : E <= 4 ? (WIDE == 1 ? 4 : 12) : E <= 8 ? 4 : 1;
     for (int gb = GP; gb < a.G; gb += GB) {
-      float more[GB][E];
+      double more[GB][E];
 #pragma unroll
       for (int g = 0; g < GB; ++g) {
-        const float* row = lg + (size_t)min(gb + g, a.G - 1) * a.n;
+        const double* row = lg + (size_t)min(gb + g, a.G - 1) * a.n;
 #pragma unroll
-        for (int e = 0; e < E; ++e) more[g][e] = GB > 1 ? row[min(j0 + e, a.n - 1)] : (j0 + e < a.n ? row[j0 + e] : 0.f);
+        for (int e = 0; e < E; ++e) more[g][e] = GB > 1 ? row[min(j0 + e, a.n - 1)] : (j0 + e < a.n ? row[j0 + e] : 0.0);
       }
 #pragma unroll
       for (int g = 0; g < GB; ++g) {
@@ -109,7 +109,7 @@ __global__ __launch_bounds__(kSelNT) void select_slices(SelectArgs a) {
 #pragma unroll
           for (int e = 0; e < E; ++e)
             if (j0 + e < a.n) {
-              const uint64_t kk = f64_key((double)more[g][e] - l);
+              const uint64_t kk = f64_key(more[g][e] - l);
               key[e] = kk > key[e] ? kk : key[e];
             }
         }

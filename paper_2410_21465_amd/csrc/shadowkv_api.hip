@@ -138,7 +138,7 @@ DecodeLayout decode_layout(const Shape& sh) {
   L.n_tiles = (sh.n_c + kScoreTile - 1) / kScoreTile;
   const size_t heads = (size_t)sh.b * sh.hq, rows = (size_t)sh.units * sh.k * sh.c;
   size_t off = 0;
-  L.logits = off; off += up(heads * sh.n_c * sizeof(float));
+  L.logits = off; off += up(heads * sh.n_c * sizeof(double));
   L.partials = off; off += up(heads * L.n_tiles * sizeof(double2));
   L.cand_key = off; off += up((size_t)sh.units * L.sel.cand_stride * sizeof(uint64_t));
   L.cand_idx = off; off += up((size_t)sh.units * L.sel.cand_stride * sizeof(int32_t));
@@ -403,7 +403,7 @@ static int decode_impl(const shadowkv_params* params, const shadowkv_bf16* q, co
   hipStream_t side = static_cast<hipStream_t>(side_stream);
   const bool fork = (sh.stage || cache) && side && side != st;
   char* ws = static_cast<char*>(workspace);
-  float* logits = reinterpret_cast<float*>(ws + L.logits);
+  double* logits = reinterpret_cast<double*>(ws + L.logits);
   double2* partials = reinterpret_cast<double2*>(ws + L.partials);
   int32_t* sel_ids = reinterpret_cast<int32_t*>(ws + L.sel_ids);
   void* v_sparse = sh.stage ? ws + L.v_sparse : nullptr;

@@ -4,8 +4,10 @@ One seeded workload is drawn once (on the GPU when there is one), the identical
 bits go to the CPU oracle and to the HIP library, and the results are compared:
 
 * chunk / outlier index sets: equal, except that an id present on one side only
-  is accepted when its oracle score lies within 1e-6 (relative, floor 1) of the
-  oracle's boundary score -- the tie rule;
+  is accepted when its oracle score lies within 1e-6 of the oracle's boundary
+  score -- the tie rule.  For the selected chunks the score is the log of the
+  softmax entry, so an absolute 1e-6 there is 1e-6 relative on the softmax entry;
+  for the outliers it is the minimum cosine, which lies in [-1, 1];
 * landmarks, gathered outlier rows: bit-exact;
 * decode output: max-abs <= 2e-2 and mean-abs <= 2e-3 against the oracle's bf16
   output (the stated acceptance bar), plus a tighter check of the rebuilt keys.
@@ -21,7 +23,7 @@ from paper_2410_21465_amd.workloads import Workload, generate
 
 OUT_MAX_ABS = 2e-2
 OUT_MEAN_ABS = 2e-3
-TIE_REL = 1e-6
+TIE_TOL = 1e-6
 # rebuilt keys: fp32 MFMA accumulation over r <= 256 exact bf16 products plus an fp32 rotation;
 # error <= ~r * 2^-24 * sum|a||b| -- a few 1e-5 of the key scale.  Bound used: 2e-4 * max|K|.
 KSPARSE_REL = 2e-4
@@ -63,7 +65,7 @@ def check_index_sets(got: np.ndarray, want_best_first: np.ndarray, score_of_id, 
         if g == w:
             continue
         boundary = float(score_of_id(u, want_best_first[u][-1:])[0])
-        tol = TIE_REL * max(1.0, abs(boundary))
+        tol = TIE_TOL
         odd = np.array(sorted(g ^ w))
         sc = score_of_id(u, odd)
         assert np.all(np.abs(sc - boundary) <= tol), (

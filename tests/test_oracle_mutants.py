@@ -15,8 +15,8 @@ MUTANTS = [
     ("rope-sign", "x[i] = x0 * cs - x1 * sn;", "x[i] = x0 * cs + x1 * sn;"),
     ("rope-frequency", "-2.0 * (double)i / (double)p->head_dim", "-1.0 * (double)i / (double)p->head_dim"),
     ("rope-pairing", "double x0 = x[i], x1 = x[i + half];", "double x0 = x[i], x1 = x[(i + 1) % half + half];"),
-    ("score-scale-dropped", "P[g * n_c + j] = (double)(float)(dot * scale);", "P[g * n_c + j] = (double)(float)(dot);"),
-    ("logit-not-rounded-to-fp32", "P[g * n_c + j] = (double)(float)(dot * scale);", "P[g * n_c + j] = (dot * scale);"),
+    ("score-scale-dropped", "P[g * n_c + j] = dot * scale;", "P[g * n_c + j] = dot;"),
+    ("logit-rounded-to-fp32", "P[g * n_c + j] = dot * scale;", "P[g * n_c + j] = (double)(float)(dot * scale);"),
     ("group-max-is-min", "if (P[g * n_c + j] > best) best = P[g * n_c + j];",
      "if (best == -INFINITY || P[g * n_c + j] < best) best = P[g * n_c + j];"),
     ("normaliser-dropped", "double lse = mx + log(se);", "double lse = 0.0 * se;"),

@@ -108,7 +108,6 @@ def brute_decode(p, t, L_bits, L_ids, Ko_bits, Vo_bits):
             S = np.zeros((G, n_c))
             for g in range(G):
                 P = np.array([np.dot(q[bi, hi * G + g], L[bi, hi, j]) for j in range(n_c)]) / math.sqrt(d)
-                P = P.astype(np.float32).astype(np.float64)      # the chunk logits are kept in fp32
                 e = np.exp(P - P.max())
                 S[g] = e / e.sum()
             S2 = S.max(axis=0)
@@ -376,25 +375,30 @@ def test_g1_group_max_uses_each_heads_own_normaliser():
     assert abs(dec["z2"][0, 0, 0] - math.log(math.exp(2.0) / (math.exp(2.0) + 4 * math.exp(l19) + 1.0))) < 1e-12
 
 
-def test_chunk_logits_are_fp32_and_closer_ones_tie():
-    """Slot 1's exact logit is 1 + 2^-30, slot 0's is 1: in fp32 they are equal, so the lower slot wins the
-    single place in the budget (an fp64 ranking would pick slot 1).  A gap of 2^-20 is kept."""
+def test_chunk_logits_are_not_rounded_on_the_way_to_the_ranking():
+    """P = Q L^T is the plain product (decoding algorithm, first line): slot 1's logit is 1 + 2^-30, slot 0's is 1.
+    The two differ far below fp32 (and bf16) resolution, and the single place in the budget still goes to slot 1;
+    with the operands swapped it goes to slot 0.  Any rounding of the logit below fp64 would tie them and hand the
+    place to the lower slot both times."""
     d, n_ch = 4, 3
     p = O.OracleParams(1, 1, 1, d, n_ch, 1, 1, 0, 1, 0, softmax_scale=1.0)
     q = np.zeros((1, 1, d)); q[0, 0, 0] = 1.0; q[0, 0, 1] = 2.0 ** -15
     zeros_kv = np.zeros((1, 1, 0, d), np.uint16)
 
-    def best(l1_second):
-        L = np.zeros((1, 1, n_ch, d)); L[0, 0, :, 0] = [1.0, 1.0, 0.5]; L[0, 0, 1, 1] = l1_second
+    def best(second):
+        L = np.zeros((1, 1, n_ch, d)); L[0, 0, :, 0] = [1.0, 1.0, 0.5]; L[0, 0, :, 1] = second
         dec = O.decode_step(p, bf16_bits(q), bf16_bits(np.zeros((1, n_ch, 1))), bf16_bits(np.zeros((1, 1, 1, d))),
                             bf16_bits(L), np.arange(n_ch, dtype=np.int32).reshape(1, 1, n_ch), zeros_kv, zeros_kv,
                             zeros_kv, zeros_kv, bf16_bits(np.ones((1, 1, n_ch, d))))
         return int(dec["chunk_ids"][0, 0, 0]), dec["z2"][0, 0]
 
-    slot, z2 = best(2.0 ** -15)           # exact logit of slot 1: 1 + 2^-30
-    assert slot == 0 and z2[0] == z2[1]
-    slot, z2 = best(2.0 ** -5)            # 1 + 2^-20: representable in fp32, slot 1 is ahead
+    slot, z2 = best([0.0, 2.0 ** -15, 0.0])     # exact logits 1, 1 + 2^-30, 0.5
     assert slot == 1 and z2[1] > z2[0]
+    assert abs((z2[1] - z2[0]) - 2.0 ** -30) < 2.0 ** -50    # the gap survives the normaliser (same for both slots)
+    slot, z2 = best([2.0 ** -15, 0.0, 0.0])     # 1 + 2^-30, 1, 0.5
+    assert slot == 0 and z2[0] > z2[1]
+    slot, z2 = best([0.0, 0.0, 0.0])            # an exact tie: lower slot
+    assert slot == 0 and z2[0] == z2[1]
 
 
 # ----------------------------------------------------------------------------- T7 invariants
