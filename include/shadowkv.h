@@ -168,6 +168,28 @@ int shadowkv_decode_step(const shadowkv_params *params, const shadowkv_bf16 *q,
                          size_t workspace_bytes, void *stream, void *side_stream);
 
 /*
+ * shadowkv_decode_step for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and
+ * same results (bit for bit) as shadowkv_decode_step without `workspace`, `workspace_bytes` and
+ * `side_stream`: the intermediates live in a scratch array inside the library's device image,
+ * shadowkv_static_scratch_bytes() bytes (96 MiB) per GPU the library is loaded on, held until the process
+ * ends.  A shape whose shadowkv_decode_workspace_bytes() exceeds that is rejected with SHADOWKV_EWORKSPACE
+ * before anything is enqueued (all five benchmark shapes fit).  The call allocates nothing (no hipMalloc,
+ * no events); its first use on a device looks up the array's address there.  Nothing in the scratch has to
+ * start at zero and nothing is cleared; it keeps the last call's intermediates.  All calls on one GPU share
+ * the one array: calls whose work overlaps on that GPU (different streams, or another thread) race -- order
+ * them on one stream.  A value gather, where the shape needs one, runs inside the key-phase launch.
+ */
+int shadowkv_decode_step_static(const shadowkv_params *params, const shadowkv_bf16 *q,
+                                const shadowkv_kv *A, const shadowkv_kv *B,
+                                const shadowkv_kv *landmarks, const int32_t *landmark_chunk_ids,
+                                const shadowkv_kv *k_outlier, const shadowkv_kv *v_outlier,
+                                const shadowkv_kv *k_local, const shadowkv_kv *v_local,
+                                const shadowkv_kv *value_store, const int32_t *pos_offset,
+                                shadowkv_bf16 *out, int32_t *out_chunk_ids, void *stream);
+size_t shadowkv_static_scratch_bytes(void);
+
+/*
  * The same decode step with a chunk cache of the value store (section "High-throughput Decoding":
  * the chunks selected by adjacent steps repeat to a large part; an index scan finds the missing ones
  * and only those are fetched -- the (1 - alpha) term of the equivalent-bandwidth formula in section

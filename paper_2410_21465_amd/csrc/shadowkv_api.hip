@@ -15,6 +15,12 @@
 
 using namespace skv;
 
+// Scratch memory of shadowkv_decode_step_static: what the other decode entry points take as `workspace`.
+// One copy per GPU the library is loaded on, held until the process ends.  In host code this name is only a
+// handle for hipGetSymbolAddress; the device address it yields (per device) is what the kernels are given.
+constexpr size_t kStaticScratchBytes = (size_t)96 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
 
 thread_local char g_err[512] = "";
@@ -198,6 +204,31 @@ int get_events(hipEvent_t* fork, hipEvent_t* join) {
     g_have[dev] = true;
   }
   *fork = g_fork[dev]; *join = g_join[dev];
+  return SHADOWKV_OK;
+}
+
+// Device address of `scratch` on the current device, looked up once per device.
+void* g_scratch_ptr[kMaxDev] = {};
+bool g_scratch_have[kMaxDev] = {};
+
+int static_scratch(void** ptr) {
+  std::lock_guard<std::mutex> lk(g_mu);
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail_hip("hipGetDevice", e);
+  if (dev < 0 || dev >= kMaxDev) return fail_inval("device index %d out of range", dev);
+  if (!g_scratch_have[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return fail_hip("hipGetSymbolAddress(scratch)", e);
+    if (!p || reinterpret_cast<uintptr_t>(p) % kAlign) {
+      set_err("static scratch has no usable device address");
+      return SHADOWKV_EHIP;
+    }
+    g_scratch_ptr[dev] = p;
+    g_scratch_have[dev] = true;
+  }
+  *ptr = g_scratch_ptr[dev];
   return SHADOWKV_OK;
 }
 
@@ -539,6 +570,31 @@ int shadowkv_decode_step(const shadowkv_params* params, const shadowkv_bf16* q, 
   return decode_impl(params, q, A, B, landmarks, landmark_chunk_ids, k_outlier, v_outlier, k_local, v_local,
                      value_store, pos_offset, nullptr, out, out_chunk_ids, workspace, workspace_bytes, stream,
                      side_stream);
+}
+
+size_t shadowkv_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int shadowkv_decode_step_static(const shadowkv_params* params, const shadowkv_bf16* q, const shadowkv_kv* A,
+                                const shadowkv_kv* B, const shadowkv_kv* landmarks, const int32_t* landmark_chunk_ids,
+                                const shadowkv_kv* k_outlier, const shadowkv_kv* v_outlier,
+                                const shadowkv_kv* k_local, const shadowkv_kv* v_local,
+                                const shadowkv_kv* value_store, const int32_t* pos_offset, shadowkv_bf16* out,
+                                int32_t* out_chunk_ids, void* stream) {
+  // the size check comes first: a shape that does not fit is rejected before anything touches the GPU
+  Shape sh;
+  int rc = check_params(params, true, &sh);
+  if (rc != SHADOWKV_OK) return rc;
+  const size_t need = decode_layout(sh).total;
+  if (need > kStaticScratchBytes) {
+    set_err("shape needs %zu bytes of scratch, the static scratch holds %zu: use shadowkv_decode_step with a workspace",
+            need, kStaticScratchBytes);
+    return SHADOWKV_EWORKSPACE;
+  }
+  void* ws = nullptr;
+  rc = static_scratch(&ws);
+  if (rc != SHADOWKV_OK) return rc;
+  return decode_impl(params, q, A, B, landmarks, landmark_chunk_ids, k_outlier, v_outlier, k_local, v_local,
+                     value_store, pos_offset, nullptr, out, out_chunk_ids, ws, kStaticScratchBytes, stream, nullptr);
 }
 
 int shadowkv_decode_step_cached(const shadowkv_params* params, const shadowkv_bf16* q, const shadowkv_kv* A,

@@ -28,7 +28,8 @@ EXPORTS = (
     "shadowkv_status_string", "shadowkv_last_error", "shadowkv_version", "shadowkv_shutdown",
     "shadowkv_profile_begin", "shadowkv_profile_end", "shadowkv_decode_step_cached", "shadowkv_value_cache_bytes",
     "shadowkv_value_cache_reset", "shadowkv_append_chunk", "shadowkv_argtopk", "shadowkv_argtopk_workspace_bytes",
-    "shadowkv_factorize_keys", "shadowkv_factorize_workspace_bytes",
+    "shadowkv_factorize_keys", "shadowkv_factorize_workspace_bytes", "shadowkv_decode_step_static",
+    "shadowkv_static_scratch_bytes",
 )
 STAGES = ("score", "select", "gather_values", "attention")
 
@@ -68,6 +69,10 @@ def lib() -> C.CDLL:
         L.shadowkv_build_landmarks.argtypes = [vp] * 9 + [sz, vp]
         L.shadowkv_decode_step.restype = i32
         L.shadowkv_decode_step.argtypes = [vp] * 15 + [sz, vp, vp]
+        L.shadowkv_decode_step_static.restype = i32
+        L.shadowkv_decode_step_static.argtypes = [vp] * 15
+        L.shadowkv_static_scratch_bytes.restype = sz
+        L.shadowkv_static_scratch_bytes.argtypes = []
         L.shadowkv_decode_step_cached.restype = i32
         L.shadowkv_decode_step_cached.argtypes = [vp] * 12 + [i32] + [vp] * 7 + [sz, vp, vp]
         L.shadowkv_value_cache_bytes.restype = sz
@@ -282,6 +287,21 @@ def decode_step(p: Params, q, A, B, landmarks, landmark_chunk_ids, k_outlier, v_
                                     None if side_stream is None else _stream_ptr(side_stream))
     _check(rc)
     return out, out_chunk_ids, workspace
+
+
+def static_scratch_bytes() -> int:
+    return int(lib().shadowkv_static_scratch_bytes())
+
+
+def decode_step_static(p: Params, q, A, B, landmarks, landmark_chunk_ids, k_outlier, v_outlier, k_local, v_local,
+                       value_store, pos_offset, out, out_chunk_ids, stream=None) -> None:
+    """``decode_step`` on the library's static scratch: nothing is allocated, ``out`` and ``out_chunk_ids`` are
+    the caller's."""
+    st = p.c_struct()
+    _check(lib().shadowkv_decode_step_static(C.addressof(st), _ptr(q), _ptr(A), _ptr(B), _ptr(landmarks),
+                                             _ptr(landmark_chunk_ids), _ptr(k_outlier), _ptr(v_outlier),
+                                             _ptr(k_local), _ptr(v_local), _ptr(value_store), _ptr(pos_offset),
+                                             _ptr(out), _ptr(out_chunk_ids), _stream_ptr(stream)))
 
 
 def append_chunk(p: Params, k_pre, k_rope, v, B, A, landmarks, landmark_chunk_ids, value_store, stream=None) -> None:
