@@ -155,8 +155,9 @@ int shadowkv_build_landmarks(const shadowkv_params *params, const shadowkv_kv *k
  *
  * Scores are ranked in the log domain: score(slot) = max over the group's heads of
  * (logit_g(slot) - logsumexp_g), which orders slots exactly like softmax-then-max.  The logit is
- * scale * <q_g, L_slot> in fp64 (exact bf16 products, fp64 sum), never rounded below that; normaliser
- * and comparison are fp64; ties go to the lower slot.
+ * scale * <q_g, L_slot> in fp64 (exact bf16 products, fp64 sum); the normaliser is formed from the fp64
+ * logits; the ranking is the one of the fp64 scores (the search runs on fp32 copies of the logits and
+ * settles its boundary on fp64 scores formed again from q and the landmarks); ties go to the lower slot.
  */
 int shadowkv_decode_step(const shadowkv_params *params, const shadowkv_bf16 *q,
                          const shadowkv_kv *A, const shadowkv_kv *B,
@@ -308,7 +309,8 @@ int shadowkv_validate_params(const shadowkv_params *params, int for_decode);
  *            (only with SHADOWKV_FLAG_KEEP_REBUILT_KEYS; the keys normally live in registers only);
  *        1 = staged values Gather(V_store, I), bf16 [b, h_kv, k*c, d] (NULL when the gather did not run);
  *        2 = selected true chunk ids, int32 [b, h_kv, k];
- *        3 = scaled landmark logits P / sqrt(d), fp64 [b, h_q, n_c];
+ *        3 = scaled landmark logits P / sqrt(d) as stored for the search, fp32 [b, h_q, ld], ld = n_c rounded up
+ *            to a multiple of 4 (the first n_c of a row are valid);
  *        4 = slots filled by the last cached step, int32 [b, h_kv, k] (first out_miss_count entries per unit);
  *        5 = slot of every selected chunk after the last cached step, int32 [b, h_kv, k].
  * Returns a pointer into `workspace`, or NULL.

@@ -108,6 +108,54 @@ __device__ __forceinline__ float sum16_f32(float v) {
   v += __shfl_xor(v, 1, kWave);
   return v;
 }
+
+// ---- wave-wide scans and reductions on the DPP path (data-parallel primitives: a VALU operand taken from another
+// lane, no LDS round trip as with the shuffle builtins).  Pattern: inclusive scan inside each row of 16 lanes with
+// row_shr 1, 2, 4, 8 (lanes without a source take the identity), then lane 15 of rows 0 and 2 into rows 1 and 3
+// (row_bcast:15), then lane 31 into rows 2 and 3 (row_bcast:31).  Lane 63 ends with the reduction over the wave.
+template <int CTRL, int ROW_MASK = 0xf>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t identity, uint32_t x) {
+  return (uint32_t)__builtin_amdgcn_update_dpp((int)identity, (int)x, CTRL, ROW_MASK, 0xf, false);
+}
+template <int CTRL, int ROW_MASK = 0xf>
+__device__ __forceinline__ double dpp_f64(double identity, double x) {
+  const int lo = __builtin_amdgcn_update_dpp(__double2loint(identity), __double2loint(x), CTRL, ROW_MASK, 0xf, false);
+  const int hi = __builtin_amdgcn_update_dpp(__double2hiint(identity), __double2hiint(x), CTRL, ROW_MASK, 0xf, false);
+  return __hiloint2double(hi, lo);
+}
+#define SKV_WAVE_SCAN(T, DPP, OP, ID)                                        \
+  x = OP(x, DPP<0x111>(ID, x)); x = OP(x, DPP<0x112>(ID, x));                \
+  x = OP(x, DPP<0x114>(ID, x)); x = OP(x, DPP<0x118>(ID, x));                \
+  x = OP(x, DPP<0x142, 0xa>(ID, x)); x = OP(x, DPP<0x143, 0xc>(ID, x));
+__device__ __forceinline__ uint32_t op_add(uint32_t a, uint32_t b) { return a + b; }
+__device__ __forceinline__ uint32_t op_min(uint32_t a, uint32_t b) { return a < b ? a : b; }
+__device__ __forceinline__ uint32_t op_max(uint32_t a, uint32_t b) { return a > b ? a : b; }
+__device__ __forceinline__ uint32_t op_and(uint32_t a, uint32_t b) { return a & b; }
+__device__ __forceinline__ uint32_t op_or(uint32_t a, uint32_t b) { return a | b; }
+__device__ __forceinline__ uint32_t last_lane_u32(uint32_t x) { return (uint32_t)__builtin_amdgcn_readlane((int)x, kWave - 1); }
+// inclusive prefix sum over the wave's lanes
+__device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t x) { SKV_WAVE_SCAN(uint32_t, dpp_u32, op_add, 0u) return x; }
+// reductions over the wave, result in every lane (through a scalar register)
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t x) { SKV_WAVE_SCAN(uint32_t, dpp_u32, op_min, 0xffffffffu) return last_lane_u32(x); }
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t x) { SKV_WAVE_SCAN(uint32_t, dpp_u32, op_max, 0u) return last_lane_u32(x); }
+__device__ __forceinline__ uint32_t wave_and_u32(uint32_t x) { SKV_WAVE_SCAN(uint32_t, dpp_u32, op_and, 0xffffffffu) return last_lane_u32(x); }
+__device__ __forceinline__ uint32_t wave_or_u32(uint32_t x) { SKV_WAVE_SCAN(uint32_t, dpp_u32, op_or, 0u) return last_lane_u32(x); }
+__device__ __forceinline__ double last_lane_f64(double x) {
+  return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(x), kWave - 1),
+                          __builtin_amdgcn_readlane(__double2loint(x), kWave - 1));
+}
+__device__ __forceinline__ double wave_max_f64_dpp(double x) {
+  SKV_WAVE_SCAN(double, dpp_f64, fmax, -INFINITY)
+  return last_lane_f64(x);
+}
+// (the order of the additions is fixed by the pattern: the same inputs give the same bits on every run)
+__device__ __forceinline__ double op_addd(double a, double b) { return a + b; }
+__device__ __forceinline__ double wave_sum_f64_dpp(double x) {
+  SKV_WAVE_SCAN(double, dpp_f64, op_addd, 0.0)
+  return last_lane_f64(x);
+}
+#undef SKV_WAVE_SCAN
+// the same two through the shuffle path (butterfly order)
 __device__ __forceinline__ double wave_max_f64(double v) {
 #pragma unroll
   for (int m = 32; m >= 1; m >>= 1) v = fmax(v, shfl_xor_f64(v, m));

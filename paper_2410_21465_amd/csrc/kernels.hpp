@@ -17,11 +17,11 @@ struct RopeFreqs {
 };
 
 // ---- landmark scoring (decoding algorithm, P = Q L^T / sqrt(d)) ----------------
-// logits [b*h_q, n_c] fp64; partials [b*h_q, n_tiles] (max, sum exp(p - max))
+// logits [b*h_q, ld] fp32 (the fp64 sum rounded once; ld = n_c rounded up to a multiple of 4); partials [b*h_q, n_tiles] (max, sum exp(p - max))
 // per tile, fp64.
 // landmarks [units, nc_stride, d]: n_c valid rows per unit.
 // kv_bytes (here and below): bytes per element of the KV-cache tensors, 2 = bf16, 1 = FP8 E5M2.
-hipError_t launch_score(const bf16_t* q, const void* landmarks, int kv_bytes, double* logits, double2* partials,
+hipError_t launch_score(const bf16_t* q, const void* landmarks, int kv_bytes, float* logits, int ld, double2* partials,
                         int batch, int hq, int hkv, int d, int n_c, int nc_stride, double scale, hipStream_t st);
 
 // ---- ArgTopK -------------------------------------------------------------------
@@ -29,28 +29,37 @@ constexpr int kSrcLogits = 0;  // key = max over the group of (logit - lse)
 constexpr int kSrcArray = 1;   // key = sign * scores[unit, j]
 
 struct SelectArgs {
-  const double* logits;     // kSrcLogits: [units*G, n]
+  const float* logits;      // kSrcLogits: [units*G, ld] stored logits (fp32 roundings of the fp64 sums), ld % 4 == 0
   const double2* partials;  //             [units*G, n_tiles]
-  int n_tiles, G;
+  int n_tiles, G, ld;
+  // kSrcLogits, for exact scores at the selection boundary: the operands of the logits and a place for the
+  // heads' log-sum-exp (written by the first level, read by the later ones)
+  const bf16_t* q;          // [units*G, d]
+  const void* landmarks;    // [units, nc_stride, d]
+  int d, kv_bytes, nc_stride;
+  double scale;
+  double* lse_out;          // [units*G]
+  uint32_t* key_top_out;    // [units] search key no slot of the unit exceeds
   const double* scores;     // kSrcArray: [units, n]
   double sign;
   int n, k, slice_len, n_slices, cand_stride;
   int group_cands, n_groups, cand2_off;  // middle level (0 groups = none): see SelectPlan
-  uint64_t* cand_key;       // [units, cand_stride] survivors of the slices
+  uint64_t* cand_key;       // [units, cand_stride] survivors of the slices (kSrcLogits: 32-bit keys in the same space)
   int32_t* cand_idx;
   const int32_t* id_map;    // optional [units, id_stride]: index -> reported id
   int id_stride;
   int32_t* out_ids;         // [units, k], ascending index order
   int32_t* out_ids2;        // optional copy
 };
-// Survivors of the slices are ranked by one workgroup per unit when there are at most 4096 of them;
-// otherwise groups of them (group_cands each) are first cut down to k per group by a middle level whose
-// output lives behind the slices' survivors in the same arrays (offset cand2_off inside a unit's stride).
+// Survivors of the slices are ranked by one workgroup per unit when it can hold them; otherwise groups of them
+// (group_cands each) are first cut down to k per group by a middle level whose output lives behind the slices'
+// survivors in the same arrays (offset cand2_off inside a unit's stride).  nt / e: threads per workgroup and
+// keys per thread of each level.
 struct SelectPlan {
-  int e, slice_len, n_slices, cand_stride, merge_e;
-  int group_cands, n_groups, cand2_off, mid_e;
+  int nt, e, slice_len, n_slices, cand_stride, merge_nt, merge_e;
+  int group_cands, n_groups, cand2_off, mid_nt, mid_e;
 };
-bool plan_select(int n, int k, SelectPlan* plan);
+bool plan_select(int n, int k, int src, int units, SelectPlan* plan);
 hipError_t launch_select(const SelectArgs& a, const SelectPlan& plan, int src, int units, hipStream_t st);
 
 // ---- value chunk gather (V_sparse = Gather(V_store, I)) -----------------------------

@@ -6,8 +6,10 @@
 // plain dot product of the bf16 inputs, so the inputs are widened to fp64 and contracted on
 // the fp64 matrix pipe (v_mfma_f64_4x4x4f64: four independent 4x4x4 blocks per wave, 256 FMAs
 // per issue, no cross-lane reduction needed); the products are exact and the fp64 sum does
-// not depend on the order of summation beyond its last bit.  The logits are stored as fp64:
-// nothing is rounded between the contraction and the ranking.  The vector ALU only unpacks
+// not depend on the order of summation beyond its last bit.  The per-tile softmax statistics
+// are formed from the fp64 logits.  What is stored for the selection is the logit rounded once
+// to fp32 (half the bytes): the selection searches on those and settles its boundary on logits
+// it forms again in fp64, so the rounding never decides a rank.  The vector ALU only unpacks
 // and converts, which leaves the kernel bound by the HBM read of L.
 //
 // Operand layout of the instruction, as measured on gfx950: input lane
@@ -16,7 +18,7 @@
 // k = which 16-byte piece of each 64-byte row segment the lane loads.  A wave covers
 // 64 rows (four 16-row tiles, all loads issued before the first MFMA), a workgroup 256.
 // Result lane 16*i + r holds the logit of head i, row r of the tile: it stores it
-// (16 consecutive doubles per head) and folds it into its running (max, sum exp),
+// (16 consecutive floats per head) and folds the fp64 value into its running (max, sum exp),
 // from which the selection kernel forms each head's log-sum-exp.
 #include "kernels.hpp"
 
@@ -44,8 +46,9 @@ __device__ __forceinline__ void lse_merge(double& m, double& s, double m2, doubl
 // landmarks are read and converted once for all eight heads.  The queries live in LDS as fp64.
 template <int D, int EB, int HG>
 __global__ __launch_bounds__(256) void score_kernel(const bf16_t* __restrict__ q, const uint8_t* __restrict__ L,
-                                                    double* __restrict__ logits, double2* __restrict__ partials,
-                                                    int hq, int hkv, int G, int n_c, int nc_stride, int n_tiles, double scale) {
+                                                    float* __restrict__ logits, double2* __restrict__ partials,
+                                                    int hq, int hkv, int G, int n_c, int ld, int nc_stride, int n_tiles,
+                                                    double scale) {
   constexpr int PB = (EB == 2 || D % 64 == 0) ? 16 : 8;  // bytes per piece
   constexpr int PE = PB / EB;                             // elements per piece
   constexpr int NI = D / (4 * PE);                        // pieces per lane per row
@@ -127,7 +130,7 @@ __global__ __launch_bounds__(256) void score_kernel(const bf16_t* __restrict__ q
       const int hl = 4 * hg + (lane >> 4);   // head of this lane's result, inside the workgroup's heads
       if (r < n_c && g0 + hl < G) {
         const double p = acc[hg] * scale;   // the logit: exact products, fp64 sum
-        logits[(head0 + hl) * n_c + r] = p;
+        logits[(head0 + hl) * ld + r] = (float)p;
         lse_merge(m[hg], s[hg], p, 1.0);
       }
     }
@@ -157,9 +160,9 @@ __global__ __launch_bounds__(256) void score_kernel(const bf16_t* __restrict__ q
 typedef double f64x4_t __attribute__((ext_vector_type(4)));
 template <int D, int EB>
 __global__ __launch_bounds__(256) void score_kernel_g16(const bf16_t* __restrict__ q, const uint8_t* __restrict__ L,
-                                                        double* __restrict__ logits, double2* __restrict__ partials,
-                                                        int hq, int hkv, int G, int n_c, int nc_stride, int n_tiles,
-                                                        double scale) {
+                                                        float* __restrict__ logits, double2* __restrict__ partials,
+                                                        int hq, int hkv, int G, int n_c, int ld, int nc_stride,
+                                                        int n_tiles, double scale) {
   constexpr int PB = (EB == 2 || D % 64 == 0) ? 16 : 8;
   constexpr int PE = PB / EB, NI = D / (4 * PE), PW = PB / 4;
   __shared__ double2 wred[4][16];
@@ -242,7 +245,7 @@ __global__ __launch_bounds__(256) void score_kernel_g16(const bf16_t* __restrict
       for (int j = 0; j < 4; ++j) {
         if (g0 + 4 * j + kq < G) {
           const double p = acc[t][j] * scale;   // the logit: exact products, fp64 sum
-          logits[(head0 + 4 * j + kq) * n_c + r] = p;
+          logits[(head0 + 4 * j + kq) * ld + r] = (float)p;
           lse_merge(m[j], s[j], p, 1.0);
         }
       }
@@ -264,7 +267,7 @@ __global__ __launch_bounds__(256) void score_kernel_g16(const bf16_t* __restrict
   }
 }
 
-hipError_t launch_score(const bf16_t* q, const void* landmarks, int kv_bytes, double* logits, double2* partials,
+hipError_t launch_score(const bf16_t* q, const void* landmarks, int kv_bytes, float* logits, int ld, double2* partials,
                         int batch, int hq, int hkv, int d, int n_c, int nc_stride, double scale, hipStream_t st) {
   const int G = hq / hkv;
   const int n_tiles = (n_c + kScoreTile - 1) / kScoreTile;
@@ -276,11 +279,11 @@ hipError_t launch_score(const bf16_t* q, const void* landmarks, int kv_bytes, do
 #define SKV_SCORE(D_, EB_)                                                                                            \
   do {                                                                                                                \
     if (g16) hipLaunchKernelGGL((score_kernel_g16<D_, EB_>), grid, block, 0, st, q, L, logits, partials, hq, hkv, G,   \
-                                n_c, nc_stride, n_tiles, scale);                                                      \
+                                n_c, ld, nc_stride, n_tiles, scale);                                                  \
     else if (G > 4) hipLaunchKernelGGL((score_kernel<D_, EB_, 2>), grid, block, 0, st, q, L, logits, partials, hq,     \
-                                       hkv, G, n_c, nc_stride, n_tiles, scale);                                      \
+                                       hkv, G, n_c, ld, nc_stride, n_tiles, scale);                                  \
     else hipLaunchKernelGGL((score_kernel<D_, EB_, 1>), grid, block, 0, st, q, L, logits, partials, hq, hkv, G, n_c,   \
-                            nc_stride, n_tiles, scale);                                                               \
+                            ld, nc_stride, n_tiles, scale);                                                           \
   } while (0)
   switch (d * 4 + kv_bytes) {
     case 64 * 4 + 2: SKV_SCORE(64, 2); break;

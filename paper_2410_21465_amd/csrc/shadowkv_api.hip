@@ -99,7 +99,7 @@ int check_params(const shadowkv_params* p, bool decode, Shape* sh) {
   if (!p->inv_freq && !(p->rope_theta > 0.0 && std::isfinite(p->rope_theta)))
     return fail_inval("rope_theta must be finite and > 0 when inv_freq is NULL");
   SelectPlan plan;
-  if (!plan_select(sh->n_c, sh->k, &plan))
+  if (!plan_select(sh->n_c, sh->k, kSrcLogits, sh->units, &plan))
     return fail_inval("topk_chunks / landmark count combination exceeds the selection kernels' capacity");
   return SHADOWKV_OK;
 }
@@ -132,20 +132,24 @@ AttnPlan plan_attention(const Shape& sh) {
 }
 
 struct DecodeLayout {
-  size_t logits, partials, cand_key, cand_idx, sel_ids, miss_slots, sel_slots, n_miss, logit_buf, k_sparse, v_sparse, part_acc, part_ml, total;
+  size_t logits, partials, lse, key_top, cand_key, cand_idx, sel_ids, miss_slots, sel_slots, n_miss, logit_buf, k_sparse, v_sparse, part_acc, part_ml, total;
   SelectPlan sel;
   AttnPlan attn;
-  int n_tiles;
+  int n_tiles, ld;   // score tiles per head; floats per row of the logits (n_c rounded up to a multiple of 4)
 };
 DecodeLayout decode_layout(const Shape& sh) {
   DecodeLayout L{};
-  plan_select(sh.n_c, sh.k, &L.sel);
+  plan_select(sh.n_c, sh.k, kSrcLogits, sh.units, &L.sel);
   L.attn = plan_attention(sh);
   L.n_tiles = (sh.n_c + kScoreTile - 1) / kScoreTile;
   const size_t heads = (size_t)sh.b * sh.hq, rows = (size_t)sh.units * sh.k * sh.c;
   size_t off = 0;
-  L.logits = off; off += up(heads * sh.n_c * sizeof(double));
+  L.ld = (sh.n_c + 3) / 4 * 4;
+  // (+ one slice of padding: the selection reads whole slices without bounds checks)
+  L.logits = off; off += up((heads * L.ld + (size_t)L.sel.slice_len) * sizeof(float));
   L.partials = off; off += up(heads * L.n_tiles * sizeof(double2));
+  L.lse = off; off += up(heads * sizeof(double));
+  L.key_top = off; off += up((size_t)sh.units * sizeof(uint32_t));
   L.cand_key = off; off += up((size_t)sh.units * L.sel.cand_stride * sizeof(uint64_t));
   L.cand_idx = off; off += up((size_t)sh.units * L.sel.cand_stride * sizeof(int32_t));
   L.sel_ids = off; off += up((size_t)sh.units * sh.k * sizeof(int32_t));
@@ -168,7 +172,7 @@ struct BuildLayout {
 };
 bool build_layout(const Shape& sh, BuildLayout* L) {
   *L = BuildLayout{};
-  if (sh.o > 0 && !plan_select(sh.n_ch, sh.o, &L->sel)) return false;
+  if (sh.o > 0 && !plan_select(sh.n_ch, sh.o, kSrcArray, sh.units, &L->sel)) return false;
   size_t off = 0;
   L->chunk_mean = off; off += up((size_t)sh.units * sh.n_ch * sh.d * sh.eb);
   L->min_cos = off; off += up((size_t)sh.units * sh.n_ch * sizeof(double));
@@ -434,7 +438,7 @@ static int decode_impl(const shadowkv_params* params, const shadowkv_bf16* q, co
   hipStream_t side = static_cast<hipStream_t>(side_stream);
   const bool fork = (sh.stage || cache) && side && side != st;
   char* ws = static_cast<char*>(workspace);
-  double* logits = reinterpret_cast<double*>(ws + L.logits);
+  float* logits = reinterpret_cast<float*>(ws + L.logits);
   double2* partials = reinterpret_cast<double2*>(ws + L.partials);
   int32_t* sel_ids = reinterpret_cast<int32_t*>(ws + L.sel_ids);
   void* v_sparse = sh.stage ? ws + L.v_sparse : nullptr;
@@ -455,12 +459,15 @@ static int decode_impl(const shadowkv_params* params, const shadowkv_bf16* q, co
   const int pstep = (g_prof.on && g_prof.n_steps < g_prof.max_steps) ? g_prof.n_steps++ : -1;
   prof_mark(st, pstep, 0);
   // 1. P = Q L^T / sqrt(d), per-tile softmax statistics
-  hipError_t e = launch_score(q, landmarks, sh.eb, logits, partials, sh.b, sh.hq, sh.hkv, sh.d, sh.n_c, sh.nc_cap, scale, st);
+  hipError_t e = launch_score(q, landmarks, sh.eb, logits, L.ld, partials, sh.b, sh.hq, sh.hkv, sh.d, sh.n_c, sh.nc_cap, scale, st);
   if (e != hipSuccess) return fail_hip("score", e);
   prof_mark(st, pstep, 1);
   // 2. softmax normaliser per head, max over the group, ArgTopK -> true chunk ids
   SelectArgs a{};
-  a.logits = logits; a.partials = partials; a.n_tiles = L.n_tiles; a.G = sh.G;
+  a.logits = logits; a.partials = partials; a.n_tiles = L.n_tiles; a.G = sh.G; a.ld = L.ld;
+  a.q = q; a.landmarks = landmarks; a.d = sh.d; a.kv_bytes = sh.eb; a.nc_stride = sh.nc_cap; a.scale = scale;
+  a.lse_out = reinterpret_cast<double*>(ws + L.lse);
+  a.key_top_out = reinterpret_cast<uint32_t*>(ws + L.key_top);
   a.n = sh.n_c; a.k = sh.k;
   a.slice_len = L.sel.slice_len; a.n_slices = L.sel.n_slices; a.cand_stride = L.sel.cand_stride;
   a.cand_key = reinterpret_cast<uint64_t*>(ws + L.cand_key);
@@ -668,7 +675,7 @@ int shadowkv_factorize_keys(const shadowkv_params* params, const shadowkv_kv* k_
 
 size_t shadowkv_argtopk_workspace_bytes(int32_t units, int32_t n, int32_t k) {
   SelectPlan plan;
-  if (units < 1 || units > 65535 || n < 1 || k < 1 || k > n || !plan_select(n, k, &plan)) return 0;
+  if (units < 1 || units > 65535 || n < 1 || k < 1 || k > n || !plan_select(n, k, kSrcArray, units, &plan)) return 0;
   const size_t bytes = up((size_t)units * plan.cand_stride * sizeof(uint64_t)) +
                        up((size_t)units * plan.cand_stride * sizeof(int32_t));
   return bytes ? bytes : kAlign;
@@ -680,7 +687,7 @@ int shadowkv_argtopk(const double* scores, int32_t units, int32_t n, int32_t k, 
   if (units < 1 || units > 65535 || n < 1 || k < 1 || k > n) return fail_inval("need 1 <= k <= n and 1 <= units <= 65535");
   if (sign != 1.0 && sign != -1.0) return fail_inval("sign must be +1 or -1");
   SelectPlan plan;
-  if (!plan_select(n, k, &plan)) return fail_inval("n / k combination exceeds the selection kernels' capacity");
+  if (!plan_select(n, k, kSrcArray, units, &plan)) return fail_inval("n / k combination exceeds the selection kernels' capacity");
   int rc = check_workspace(workspace, workspace_bytes, shadowkv_argtopk_workspace_bytes(units, n, k));
   if (rc != SHADOWKV_OK) return rc;
   char* ws = static_cast<char*>(workspace);

@@ -404,7 +404,7 @@ def decode_step_cached(p: Params, q, A, B, landmarks, landmark_chunk_ids, k_outl
 def workspace_view(p: Params, workspace: torch.Tensor, which: str) -> Optional[torch.Tensor]:
     """Intermediate of the last decode step as a tensor aliasing ``workspace``.
 
-    ``"k_sparse"`` fp32 [b,h_kv,k*c,d]; ``"v_sparse"`` in the KV storage type (staged runs only); ``"logits"`` fp64 [b,h_q,n_c].
+    ``"k_sparse"`` fp32 [b,h_kv,k*c,d]; ``"v_sparse"`` in the KV storage type (staged runs only); ``"logits"`` fp32 [b,h_q,n_c] (the copies the search runs on).
     """
     code = {"k_sparse": 0, "v_sparse": 1, "sel_ids": 2, "logits": 3, "miss_slots": 4, "sel_slots": 5}[which]
     st = p.c_struct()
@@ -422,5 +422,6 @@ def workspace_view(p: Params, workspace: torch.Tensor, which: str) -> Optional[t
     if which in ("sel_ids", "miss_slots", "sel_slots"):
         n = p.batch * p.n_kv_heads * p.topk_chunks
         return workspace[off:off + 4 * n].view(torch.int32).view(p.batch, p.n_kv_heads, p.topk_chunks)
-    n = p.batch * p.n_q_heads * p.n_landmarks
-    return workspace[off:off + 8 * n].view(torch.float64).view(p.batch, p.n_q_heads, p.n_landmarks)
+    ld = (p.n_landmarks + 3) // 4 * 4
+    n = p.batch * p.n_q_heads * ld
+    return workspace[off:off + 4 * n].view(torch.float32).view(p.batch, p.n_q_heads, ld)[:, :, :p.n_landmarks]
