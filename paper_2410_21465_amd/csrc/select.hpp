@@ -254,11 +254,23 @@ __device__ __forceinline__ uint32_t hist_bin(uint32_t key, uint32_t key_top) {
   return (uint32_t)(kHistBins / 2) - 1u - c;
 }
 
+// smallest key that falls into `bin` (inverse of hist_bin at the bin's lower edge; 0 when the edge is below every key)
+__device__ __forceinline__ uint32_t hist_bin_floor(uint32_t bin, uint32_t key_top) {
+  const uint32_t fine = (uint32_t)(kHistBins / 2) << kFineShift;
+  uint64_t d_max;   // largest distance below the top that still maps to `bin`
+  if (bin >= (uint32_t)(kHistBins / 2)) d_max = (((uint64_t)kHistBins - bin) << kFineShift) - 1u;
+  else d_max = (uint64_t)fine + ((((uint64_t)(kHistBins / 2) - bin)) << kCoarseShift) - 1u;
+  return d_max >= key_top ? 0u : key_top - (uint32_t)d_max;
+}
+
 // On return: `gt` = elements certainly among the k largest keys, `eq` = elements of which the first `need` in order
 // index are also in.  Returns false when `eq` holds more than `need` elements (identical keys; fallback path only).
+// When the boundary bin holds at most 64 keys (the usual case) every wave ranks them in its own registers and
+// `tu_known` is set: t_key = smallest key taken, u_key = largest key left out, or an upper bound on it (the
+// largest key that can lie below the boundary bin) when nothing of the bin is left out; 0 = nothing below.
 template <int NT, int E>
 __device__ bool threshold32(const uint32_t (&key)[E], uint32_t k, uint32_t key_top, Select32Smem<NT>& sm, uint32_t& gt,
-                            uint32_t& eq, uint32_t& need) {
+                            uint32_t& eq, uint32_t& need, bool& tu_known, uint32_t& t_key, uint32_t& u_key) {
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   uint32_t bins[E];
 #pragma unroll
@@ -300,7 +312,8 @@ __device__ bool threshold32(const uint32_t (&key)[E], uint32_t k, uint32_t key_t
     gt |= (uint32_t)(present & (bins[e] > bin)) << e;
     cand |= (uint32_t)(present & (bins[e] == bin)) << e;
   }
-  if (cnt == need) { eq = cand; return true; }      // the whole bin is wanted
+  tu_known = false;
+  if (cnt > (uint32_t)kWave && cnt == need) { eq = cand; return true; }      // the whole bin is wanted
   if (cnt <= (uint32_t)kListCap) {
 #pragma unroll
     for (int e = 0; e < E; ++e)
@@ -310,8 +323,35 @@ __device__ bool threshold32(const uint32_t (&key)[E], uint32_t k, uint32_t key_t
         sm.list_ord[slot] = threadIdx.x * E + e;
       }
     __syncthreads();
-    // every thread walks the list once (broadcast reads) and counts, for each of its own candidates, the entries
-    // ahead of it.  Equal keys on both sides of the boundary are ranked by order index here; the caller sees them
+    if (cnt <= (uint32_t)kWave) {
+      // every wave ranks the list in its registers: lane i holds entry i and counts the entries ahead of it
+      const uint32_t kv = (uint32_t)lane < cnt ? sm.list_key[lane] : 0u, ov = (uint32_t)lane < cnt ? sm.list_ord[lane] : 0xffffffffu;
+      uint32_t ahead = 0;
+      for (uint32_t j = 0; j < cnt; ++j) {
+        const uint32_t kj = (uint32_t)__builtin_amdgcn_readlane((int)kv, (int)j), oj = (uint32_t)__builtin_amdgcn_readlane((int)ov, (int)j);
+        ahead += (kj > kv) | ((kj == kv) & (oj < ov));
+      }
+      const int it = __ffsll((unsigned long long)__ballot((uint32_t)lane < cnt && ahead == need - 1u)) - 1;   // last one taken
+      t_key = (uint32_t)__builtin_amdgcn_readlane((int)kv, it);
+      const uint32_t t_ord = (uint32_t)__builtin_amdgcn_readlane((int)ov, it);
+      if (cnt > need) {
+        const int iu = __ffsll((unsigned long long)__ballot((uint32_t)lane < cnt && ahead == need)) - 1;      // first one left out
+        u_key = (uint32_t)__builtin_amdgcn_readlane((int)kv, iu);
+      } else {
+        const uint32_t fl = hist_bin_floor(bin, key_top);
+        u_key = fl > 1u ? fl - 1u : 0u;
+      }
+      tu_known = true;
+#pragma unroll
+      for (int e = 0; e < E; ++e) {
+        const bool in = (key[e] > t_key) | ((key[e] == t_key) & (threadIdx.x * E + e <= t_ord));
+        gt |= (uint32_t)(((cand >> e) & 1u) & in) << e;
+      }
+      need = 0;
+      return true;
+    }
+    // a longer list: every thread walks it once (broadcast reads) and counts, for each of its own candidates, the
+    // entries ahead of it.  Equal keys on both sides of the boundary are ranked by order index here; the caller sees them
     // as a taken and a left-out element with the same key and settles them on exact scores.
     if (__builtin_amdgcn_readfirstlane(__any(cand != 0u))) {
       uint32_t ahead[E];
@@ -360,25 +400,28 @@ __device__ void banded_select_topk(const uint32_t (&key)[E], int k, uint32_t key
                                    Early early, uint32_t& sel_mask, int& out_pos) {
   constexpr int NW = NT / kWave;
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-  uint32_t gt, eq, need;
-  const bool decided = threshold32<NT, E>(key, (uint32_t)k, key_top, sm, gt, eq, need);
-  // smallest key taken, largest key left out (when `decided`, every element of eq is taken)
-  uint32_t kmin = 0xffffffffu, kmax = 0u;
+  uint32_t gt, eq, need, kmin, kmax;
+  bool tu_known;
+  const bool decided = threshold32<NT, E>(key, (uint32_t)k, key_top, sm, gt, eq, need, tu_known, kmin, kmax);
+  if (!tu_known) {
+    // smallest key taken, largest key left out (when `decided`, every element of eq is taken)
+    kmin = 0xffffffffu; kmax = 0u;
 #pragma unroll
-  for (int e = 0; e < E; ++e) {
-    const bool taken = ((gt | eq) >> e) & 1u;
-    const uint32_t lo = taken ? key[e] : 0xffffffffu, hi = taken ? 0u : key[e];   // absent keys are 0: never taken
-    kmin = lo < kmin ? lo : kmin;
-    kmax = hi > kmax ? hi : kmax;
-  }
-  kmin = wave_min_u32(kmin);
-  kmax = wave_max_u32(kmax);
-  if (lane == 0) { sm.red[wave] = kmin; sm.red[NW + wave] = kmax; }
-  __syncthreads();
+    for (int e = 0; e < E; ++e) {
+      const bool taken = ((gt | eq) >> e) & 1u;
+      const uint32_t lo = taken ? key[e] : 0xffffffffu, hi = taken ? 0u : key[e];   // absent keys are 0: never taken
+      kmin = lo < kmin ? lo : kmin;
+      kmax = hi > kmax ? hi : kmax;
+    }
+    kmin = wave_min_u32(kmin);
+    kmax = wave_max_u32(kmax);
+    if (lane == 0) { sm.red[wave] = kmin; sm.red[NW + wave] = kmax; }
+    __syncthreads();
 #pragma unroll
-  for (int w = 0; w < NW; ++w) {
-    const uint32_t a = sm.red[w], b = sm.red[NW + w];
-    kmin = a < kmin ? a : kmin; kmax = b > kmax ? b : kmax;
+    for (int w = 0; w < NW; ++w) {
+      const uint32_t a = sm.red[w], b = sm.red[NW + w];
+      kmin = a < kmin ? a : kmin; kmax = b > kmax ? b : kmax;
+    }
   }
   const double T = score_from_key32(kmin);
   double band = 2.0 * (u_rel * (fabs(T) + 1.0 + lmax) + 2.0 / kKeyScale);
