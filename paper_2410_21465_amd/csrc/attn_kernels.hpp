@@ -40,6 +40,7 @@ namespace skv {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short bf16x4;
 
 // Sum over the 16 lanes of a DPP row, result in every lane: four rotate-and-add steps, each a
 // single VALU instruction with a DPP operand (row_ror:n), no LDS traffic.
@@ -162,6 +163,107 @@ __device__ __forceinline__ void gather_chunks(const GatherArgs& g, int block) {
       if (a2 >= 0) dst_u[a2] = b2;
       if (a3 >= 0) dst_u[a3] = b3;
     }
+  }
+}
+
+// Attention of four query heads of one unit over the unit's resident rows [outliers ; recent] alone, by a whole
+// workgroup of NT threads: the part of the decode step's attention that needs no selected chunk.  It can therefore
+// run beside the selection (the first level of the selection rides a launch that leaves half the chip idle, and the
+// extra workgroups of that launch call this), after which the attention kernel proper skips these rows.  Writes one
+// partial state (m, l, acc[d]) per head at index `part_slot` of the head's n_part states.
+// Heads past the group repeat its last head and are not written.  16 lanes share a row (d/16 columns each), a wave
+// takes eight rows per step.
+template <int D, int EB, int NT>
+__device__ void resident_rows_attention(const ResidentArgs& r, int unit, int g0) {
+  constexpr int GH = 4, EPL = D / 16, RW = RawWords<EPL, EB>::n, NW = NT / kWave;
+  __shared__ float sm_acc[NW][GH][D];
+  __shared__ float sm_m[NW][GH], sm_l[NW][GH];
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int sub = lane & 15, rg = lane >> 4;
+  const int G = r.hq / r.hkv, b = unit / r.hkv, h = unit % r.hkv;
+  const size_t head0 = (size_t)b * r.hq + (size_t)h * G + g0;
+  const int nv = min(GH, G - g0);
+  const int n_res = r.oc + r.w;
+  OnlineSoftmax<GH, EPL, EB> st;
+  st.init();
+  float qv[GH][EPL];
+#pragma unroll
+  for (int g = 0; g < GH; ++g) {
+    float x[EPL];
+    load_bf16_row<EPL>(r.q + (head0 + min(g, nv - 1)) * D + sub * EPL, x);
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) qv[g][e] = x[e] * r.scale_log2;
+  }
+  for (int i0 = wave * 8; i0 < n_res; i0 += NW * 8) {
+    uint32_t kraw[2][RW], vraw[2][RW];
+    bool ok[2];
+#pragma unroll
+    for (int x = 0; x < 2; ++x) {
+      const int i = i0 + 4 * x + rg;
+      ok[x] = i < n_res;
+      const int ic = min(i, n_res - 1);
+      const uint8_t *kp, *vp;
+      if (ic < r.oc) {
+        kp = static_cast<const uint8_t*>(r.k_outlier) + ((size_t)unit * r.oc + ic) * D * EB;
+        vp = static_cast<const uint8_t*>(r.v_outlier) + ((size_t)unit * r.oc + ic) * D * EB;
+      } else {
+        kp = static_cast<const uint8_t*>(r.k_local) + ((size_t)unit * r.w + (ic - r.oc)) * D * EB;
+        vp = static_cast<const uint8_t*>(r.v_local) + ((size_t)unit * r.w + (ic - r.oc)) * D * EB;
+      }
+      load_raw<EPL, EB>(kp + sub * EPL * EB, kraw[x]);
+      load_raw<EPL, EB>(vp + sub * EPL * EB, vraw[x]);
+    }
+    float lg[2][GH];
+#pragma unroll
+    for (int x = 0; x < 2; ++x) {
+      float kx[EPL], dot[GH];
+      unpack_kv<EPL, EB>(kraw[x], kx);
+#pragma unroll
+      for (int g = 0; g < GH; ++g) {
+        dot[g] = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) dot[g] = fmaf(kx[e], qv[g][e], dot[g]);
+      }
+      allsum16_vec<GH>(dot);
+#pragma unroll
+      for (int g = 0; g < GH; ++g) lg[x][g] = ok[x] ? dot[g] : -INFINITY;
+    }
+    st.template fold<2>(lg, vraw);
+  }
+  // merge: row groups of the wave, then the waves of the workgroup
+#pragma unroll
+  for (int g = 0; g < GH; ++g) {
+    float mt = fmaxf(st.m[g], __shfl_xor(st.m[g], 16, kWave));
+    mt = fmaxf(mt, __shfl_xor(mt, 32, kWave));
+    const float sc = (st.m[g] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(st.m[g] - mt);
+    float lv = st.l[g] * sc;
+    lv += __shfl_xor(lv, 16, kWave);
+    lv += __shfl_xor(lv, 32, kWave);
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+      float v = st.acc[g][e] * sc;
+      v += __shfl_xor(v, 16, kWave);
+      v += __shfl_xor(v, 32, kWave);
+      if (rg == 0) sm_acc[wave][g][sub * EPL + e] = v;
+    }
+    if (lane == 0) { sm_m[wave][g] = mt; sm_l[wave][g] = lv; }
+  }
+  __syncthreads();
+  for (int idx = threadIdx.x; idx < nv * D; idx += NT) {
+    const int g = idx / D, e = idx - g * D;
+    float M = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) M = fmaxf(M, sm_m[w][g]);
+    float num = 0.f, den = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+      const float sc = (sm_m[w][g] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(sm_m[w][g] - M);
+      num = fmaf(sm_acc[w][g][e], sc, num);
+      den = fmaf(sm_l[w][g], sc, den);
+    }
+    const size_t pidx = (head0 + g) * r.n_part + r.part_slot;
+    r.part_acc[pidx * D + e] = num;
+    if (e == 0) r.part_ml[pidx] = make_float2(M, den);
   }
 }
 
@@ -341,7 +443,7 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
 #pragma unroll
       for (int e = 0; e < EPL; ++e) qv[g][e] = x[e] * a.scale_log2;
     }
-    const int n_res = oc + a.w;
+    const int n_res = a.skip_resident ? 0 : oc + a.w;   // (skipped: another launch has attended over them)
     const int i_begin = min(n_res, split * a.res_split_len);
     const int i_end = min(n_res, i_begin + a.res_split_len);
     // two rows per lane group and step: rows i0 + rg and i0 + 4 + rg; the next step's rows are loaded
@@ -568,6 +670,445 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
   }
 }
 
+// The fused kernel again, with the work of a block of selected rows divided between two kinds of waves (512
+// threads: waves 0-3 rebuild keys, waves 4-7 attend), for groups of four query heads and chunk sizes that are
+// multiples of four.  The single-role kernel above keeps per lane the A fragments, the MFMA accumulators, the
+// rotation state, the queries, the value rows AND the online-softmax state of four heads: 242 registers, two waves
+// per SIMD, and with so few waves the scattered 2-2.5 KB pieces of A and V come in at 3.1-3.7 TB/s where the same
+// gather pattern reaches 5.5 TB/s once every SIMD holds four waves with loads in flight.  Here
+//   * a key wave owns 16 rows per step: A rows -> MFMA (B^T in LDS) -> RoPE in place -> q.K (queries from LDS, two
+//     heads at a time) -> the 16 x 4 logits into a two-deep ring in LDS; the A rows of its next block are requested
+//     before it starts on the current one (two sets of fragments);
+//   * a value wave owns the 16 rows the key wave of the same index produced one step earlier: logits from the ring,
+//     value rows requested two blocks ahead (they depend on nothing but the selection), online softmax, P.V;
+//     it also takes this split's share of the resident rows first, when no other launch has done them;
+//   * one barrier per step orders the ring.
+// Each role fits 128 registers, so two such workgroups (16 waves) share a compute unit.
+template <int D, int KSMAX, int EB, int ABUF>
+__global__ __launch_bounds__(512, 4) void sparse_attn_roles_kernel(AttnArgs a) {
+  constexpr int GH = 4, EPL = D / 16, NB = D / 16, HB = NB / 2;
+  constexpr int RW = RawWords<EPL, EB>::n;
+  extern __shared__ __align__(16) bf16_t Bt[];  // [D][rp], element (n, kk) = B[kk][n]; then int tokb[], vrowb[]
+  __shared__ __align__(16) float lgs[2][64][GH];  // logits (log2 units) of the rows of one step, -inf past the end
+  __shared__ __align__(16) float qs[GH][D];       // the block's queries, scaled to log2 units
+  __shared__ double frev_s[D / 2];                // rotary frequencies in revolutions per position
+  __shared__ float cd_s[D / 2], sd_s[D / 2];      // cos / sin of one position step
+  __shared__ float sm_acc[4][GH][D];
+  __shared__ float sm_m[4][GH], sm_l[4][GH];
+  const int unit = blockIdx.x, split = blockIdx.y, g0 = blockIdx.z * GH;
+  const int G = a.hq / a.hkv, b = unit / a.hkv, h = unit % a.hkv;
+  const size_t head0 = (size_t)b * a.hq + (size_t)h * G + g0;
+  const int nv = min(GH, G - g0);
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const int sub = lane & 15, rg = lane >> 4;
+  const int oc = a.o * a.c, kc = a.k * a.c;
+  const int r = a.r, rp = a.rp, r32 = a.r32;
+  const int s_begin = split * a.sparse_split_len;
+  const int s_end = min(kc, s_begin + a.sparse_split_len);
+  const int cshift = a.c_shift;
+  auto chunk_of = [&](int i) { return cshift >= 0 ? i >> cshift : i / a.c; };
+  const int ch_begin = chunk_of(s_begin);
+  const int n_it = (s_end - s_begin + 63) / 64;
+
+  int* tokb = reinterpret_cast<int*>(Bt + (size_t)D * rp);
+  int* vrowb = tokb + (a.sparse_split_len / a.c + 2);
+  const uint8_t* vbase = a.v_sparse ? static_cast<const uint8_t*>(a.v_sparse) + (size_t)unit * a.v_unit_rows * D * EB
+                                    : static_cast<const uint8_t*>(a.v_store) + (size_t)unit * a.s_cap * D * EB;
+  if (s_begin < s_end) {
+    const int last_chunk = a.s / a.c - 1;
+    const int32_t* ids = a.sel_ids + (size_t)unit * a.k;
+    const int n_ch = chunk_of(s_end - 1) - ch_begin + 1;
+    const int last_slot = a.v_unit_rows / a.c - 1;
+    for (int idx = threadIdx.x; idx < n_ch; idx += 512) {
+      const int tb = min(max(ids[ch_begin + idx], 0), last_chunk) * a.c;
+      tokb[idx] = tb;
+      int vb = tb;
+      if (a.v_sparse) {
+        const int slot = a.v_slots ? a.v_slots[(size_t)unit * a.k + ch_begin + idx] : ch_begin + idx;
+        vb = min(max(slot, 0), last_slot) * a.c;
+      }
+      vrowb[idx] = vb;
+    }
+  }
+  for (int idx = threadIdx.x; idx < GH * D; idx += 512) {
+    const int g = idx / D, e = idx - g * D;
+    qs[g][e] = bf16_to_f32(a.q[(head0 + min(g, nv - 1)) * D + e]) * a.scale_log2;
+  }
+  if (threadIdx.x < D / 2) {
+    double rv = a.inv_freq_dev ? (double)a.inv_freq_dev[threadIdx.x] * 0.15915494309189533577 : a.freqs.rev[threadIdx.x];
+    frev_s[threadIdx.x] = rv;
+    rv -= rint(rv);
+    cd_s[threadIdx.x] = __builtin_amdgcn_cosf((float)rv);
+    sd_s[threadIdx.x] = __builtin_amdgcn_sinf((float)rv);
+  }
+  // ---- B^T of this KV head into LDS (zero beyond rank r), by all eight waves
+  {
+    constexpr int NBI = (KSMAX * 32 * (D / 8) + 511) / 512;  // 16-byte pieces per thread
+    const uint8_t* Bu = static_cast<const uint8_t*>(a.B) + (size_t)unit * r * D * EB;
+    const int pieces = r32 * (D / 8);
+    uint4 bw[NBI];
+    int dst[NBI];
+#pragma unroll
+    for (int it = 0; it < NBI; ++it) {
+      const int idx = min((int)threadIdx.x + it * 512, pieces - 1);
+      const int n8 = (idx & 3) + 4 * (idx / (4 * r32)), kk = (idx >> 2) % r32;
+      const uint8_t* src = Bu + ((size_t)min(kk, r - 1) * D + n8 * 8) * EB;
+      if constexpr (EB == 2) {
+        bw[it] = *reinterpret_cast<const uint4*>(src);
+      } else {
+        const uint2 v = *reinterpret_cast<const uint2*>(src);
+        bw[it] = make_uint4(v.x, v.y, 0u, 0u);
+      }
+      dst[it] = kk < r ? n8 * 8 * rp + kk : -(n8 * 8 * rp + kk) - 1;  // negative: store zeros
+    }
+    if constexpr (EB == 1) {
+#pragma unroll
+      for (int it = 0; it < NBI; ++it)
+        bw[it] = make_uint4(e5m2x2_to_bf16x2<0>(bw[it].x), e5m2x2_to_bf16x2<1>(bw[it].x), e5m2x2_to_bf16x2<0>(bw[it].y),
+                            e5m2x2_to_bf16x2<1>(bw[it].y));
+    }
+#pragma unroll
+    for (int it = 0; it < NBI; ++it) {
+      const bool real = dst[it] >= 0;
+      const int at = real ? dst[it] : -(dst[it] + 1);
+      const uint32_t w4[4] = {real ? bw[it].x : 0u, real ? bw[it].y : 0u, real ? bw[it].z : 0u, real ? bw[it].w : 0u};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        Bt[at + (2 * i) * rp] = (bf16_t)(w4[i] & 0xffffu);
+        Bt[at + (2 * i + 1) * rp] = (bf16_t)(w4[i] >> 16);
+      }
+    }
+  }
+  __syncthreads();   // tables, queries and B^T are in place
+
+  if (wave < 4) {
+    // =========================== key waves ===========================
+    const int kw = wave;
+    const int ksteps = r32 / 32;
+    const double pos0 = a.pos_offset ? (double)a.pos_offset[b] : 0.0;
+    // two sets of A fragments: the rows of the next block are requested before the current block is worked on
+    AFrag<EB> afA[KSMAX], afB[KSMAX];
+    int tokA = 0, tokB = 0;
+    auto load_a = [&](int row0, AFrag<EB> (&af)[KSMAX], int& tok0) {
+      const int i = min(row0 + sub, s_end - 1);
+      const int ch = chunk_of(i);
+      const size_t n = (size_t)(tokb[ch - ch_begin] + (i - ch * a.c));
+      const uint8_t* arow = static_cast<const uint8_t*>(a.A) + ((size_t)b * a.s_cap + n) * r * EB;
+#pragma unroll
+      for (int ks = 0; ks < KSMAX; ++ks) af[ks].load(arow + (size_t)min(ks * 32 + rg * 8, r - 8) * EB);
+      const int ic = min(row0 + rg * 4, s_end - 4);   // first of this lane's four consecutive tokens
+      const int ch4 = chunk_of(ic);
+      tok0 = tokb[ch4 - ch_begin] + (ic - ch4 * a.c);
+    };
+    auto work = [&](int it, AFrag<EB> (&af)[KSMAX], int& tok_af) {
+      const int row0 = s_begin + it * 64 + kw * 16;
+      const int tok_cur = tok_af;
+      f32x4 acc[NB];
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) acc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < KSMAX; ++ks) {
+        if (ks < ksteps) {
+          const bf16x8 afrag = af[ks].operand(ks * 32 + rg * 8 >= r);
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb) {
+            const bf16x8 bfrag = *reinterpret_cast<const bf16x8*>(&Bt[(nb * 16 + sub) * rp + ks * 32 + rg * 8]);
+            acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afrag, bfrag, acc[nb], 0, 0, 0);
+          }
+        }
+      }
+      if (ABUF == 1 && it + 1 < n_it) load_a(row0 + 64, af, tok_af);   // one set of fragments: consumed, so reload
+      // RoPE in place: one accurate angle per frequency for the first of the lane's four tokens, stepped by
+      // one position for the others
+      {
+        float cs[HB], sn[HB];
+        const double pos = pos0 + (double)tok_cur;
+#pragma unroll
+        for (int nb = 0; nb < HB; ++nb) {
+          double rev = pos * frev_s[nb * 16 + sub];
+          rev -= rint(rev);
+          const float rv = (float)rev;
+          sn[nb] = __builtin_amdgcn_sinf(rv);
+          cs[nb] = __builtin_amdgcn_cosf(rv);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          if (j > 0) {
+#pragma unroll
+            for (int nb = 0; nb < HB; ++nb) {
+              const float cd = cd_s[nb * 16 + sub], sd = sd_s[nb * 16 + sub];
+              const float c1 = cs[nb] * cd - sn[nb] * sd;
+              sn[nb] = sn[nb] * cd + cs[nb] * sd;
+              cs[nb] = c1;
+            }
+          }
+#pragma unroll
+          for (int nb = 0; nb < HB; ++nb) {
+            const float x0 = acc[nb][j], x1 = acc[nb + HB][j];
+            acc[nb][j] = x0 * cs[nb] - x1 * sn[nb];
+            acc[nb + HB][j] = x1 * cs[nb] + x0 * sn[nb];
+          }
+        }
+      }
+      // q.K, two heads at a time; lane sub == 0 of a row group stores the logits of its four rows
+#pragma unroll
+      for (int hp = 0; hp < GH / 2; ++hp) {
+        float qv[2][NB];
+#pragma unroll
+        for (int g = 0; g < 2; ++g)
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb) qv[g][nb] = qs[2 * hp + g][nb * 16 + sub];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          float dot[2] = {0.f, 0.f};
+#pragma unroll
+          for (int g = 0; g < 2; ++g)
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) dot[g] = fmaf(acc[nb][j], qv[g][nb], dot[g]);
+          allsum16_vec<2>(dot);
+          if (sub == 0) {
+            const bool ok = row0 + rg * 4 + j < s_end;
+            float2 v = make_float2(dot[0], dot[1]);
+            if (!ok) v = make_float2(-INFINITY, -INFINITY);
+            *reinterpret_cast<float2*>(&lgs[it & 1][kw * 16 + rg * 4 + j][2 * hp]) = v;
+          }
+        }
+      }
+    };
+    if (n_it > 0) load_a(s_begin + kw * 16, afA, tokA);
+    if constexpr (ABUF == 1) {
+      for (int it = 0; it <= n_it; ++it) {
+        if (it < n_it) work(it, afA, tokA);
+        __syncthreads();
+      }
+    } else {
+      for (int it = 0; it <= n_it; it += 2) {
+        if (it < n_it) {
+          if (it + 1 < n_it) load_a(s_begin + (it + 1) * 64 + kw * 16, afB, tokB);
+          work(it, afA, tokA);
+        }
+        __syncthreads();
+        if (it + 1 <= n_it) {
+          if (it + 1 < n_it) {
+            if (it + 2 < n_it) load_a(s_begin + (it + 2) * 64 + kw * 16, afA, tokA);
+            work(it + 1, afB, tokB);
+          }
+          __syncthreads();
+        }
+      }
+    }
+    __syncthreads();   // (pairs with the value waves' barrier before the merge)
+    return;
+  }
+
+  // =========================== value waves ===========================
+  const int vw = wave - 4;
+  OnlineSoftmax<GH, EPL, EB> st;
+  st.init();
+  auto load_v = [&](int row0, uint32_t (&vraw)[4][RW]) {
+    const int ic = min(row0 + rg * 4, s_end - 4);
+    const int ch = chunk_of(ic);
+    const uint8_t* vp = vbase + ((size_t)(vrowb[ch - ch_begin] + (ic - ch * a.c)) * D + sub * EPL) * EB;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) load_raw<EPL, EB>(vp + (size_t)j * D * EB, vraw[j]);
+  };
+  // ---- this split's share of the resident rows [outliers ; recent], unless another launch has done them
+  if (!a.skip_resident) {
+    float qv[GH][EPL];
+#pragma unroll
+    for (int g = 0; g < GH; ++g)
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) qv[g][e] = qs[g][sub * EPL + e];
+    const int n_res = oc + a.w;
+    const int i_begin = min(n_res, split * a.res_split_len);
+    const int i_end = min(n_res, i_begin + a.res_split_len);
+    for (int i0 = i_begin + vw * 8; i0 < i_end; i0 += 32) {
+      uint32_t kraw[2][RW], vraw[2][RW];
+      bool ok[2];
+#pragma unroll
+      for (int x = 0; x < 2; ++x) {
+        const int i = i0 + 4 * x + rg;
+        ok[x] = i < i_end;
+        const int ic = min(i, i_end - 1);
+        const uint8_t *kp, *vp;
+        if (ic < oc) {
+          kp = static_cast<const uint8_t*>(a.k_outlier) + ((size_t)unit * oc + ic) * D * EB;
+          vp = static_cast<const uint8_t*>(a.v_outlier) + ((size_t)unit * oc + ic) * D * EB;
+        } else {
+          kp = static_cast<const uint8_t*>(a.k_local) + ((size_t)unit * a.w + (ic - oc)) * D * EB;
+          vp = static_cast<const uint8_t*>(a.v_local) + ((size_t)unit * a.w + (ic - oc)) * D * EB;
+        }
+        load_raw<EPL, EB>(kp + sub * EPL * EB, kraw[x]);
+        load_raw<EPL, EB>(vp + sub * EPL * EB, vraw[x]);
+      }
+      float lg[2][GH];
+#pragma unroll
+      for (int x = 0; x < 2; ++x) {
+        float kx[EPL], dot[GH];
+        unpack_kv<EPL, EB>(kraw[x], kx);
+#pragma unroll
+        for (int g = 0; g < GH; ++g) {
+          dot[g] = 0.f;
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) dot[g] = fmaf(kx[e], qv[g][e], dot[g]);
+        }
+        allsum16_vec<GH>(dot);
+#pragma unroll
+        for (int g = 0; g < GH; ++g) lg[x][g] = ok[x] ? dot[g] : -INFINITY;
+      }
+      st.template fold<2>(lg, vraw);
+    }
+  }
+  // ---- selected rows: softmax x V on the matrix cores.
+  // out[head][col] += sum_rows p[row][head] V[row][col] per block of 16 rows is a 16x16x16 product per output
+  // column block, with the heads (padded from 4 to 16) as the rows of the left operand: lane (sub, rg) supplies
+  // p of head sub for rows 4 rg .. 4 rg + 3 (only sub < 4 is real; the other lanes repeat head sub & 3 and feed
+  // output rows nobody reads) and V of rows 4 rg .. 4 rg + 3 at ONE column.  Which column an operand lane stands
+  // for is free as long as the output is read the same way: taking element e of the lane's EPL contiguous columns
+  // for product number e, the lane's row pieces are used as loaded (a byte permute gathers element e of the four
+  // rows), and lanes rg == 0 end up with out[head i][sub * EPL + e] in oacc[e][i] -- the columns they own in the
+  // vector form as well.  p is fed as two bf16 terms (the top 16 bits of the fp32 value, 2^-16 relative), V is
+  // bf16 as stored (E5M2 widens exactly).  The running maximum of every head is kept in every lane; the sum of p
+  // in the lanes sub < 4 for the rows they fed.
+  f32x4 oacc[EPL];
+  float mh[GH], lpart = 0.f;
+#pragma unroll
+  for (int g = 0; g < GH; ++g) {
+    // what the resident rows left in the vector form: common maximum, sums over the row groups
+    float mt = fmaxf(st.m[g], __shfl_xor(st.m[g], 16, kWave));
+    mt = fmaxf(mt, __shfl_xor(mt, 32, kWave));
+    const float sc = (st.m[g] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(st.m[g] - mt);
+    float lv = st.l[g] * sc;
+    lv += __shfl_xor(lv, 16, kWave);
+    lv += __shfl_xor(lv, 32, kWave);
+    mh[g] = mt;
+    if (rg == 0 && sub == g) lpart = lv;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+      float v = st.acc[g][e] * sc;
+      v += __shfl_xor(v, 16, kWave);
+      v += __shfl_xor(v, 32, kWave);
+      oacc[e][g] = rg == 0 ? v : 0.f;
+    }
+  }
+  {
+    uint32_t v0[4][RW], v1[4][RW];
+    const int rowv = s_begin + vw * 16;
+    const int hsel = sub & 3;   // the head whose weights this lane forms
+    if (n_it > 0) load_v(rowv, v0);
+    if (n_it > 1) load_v(rowv + 64, v1);
+    for (int it = 0; it <= n_it; ++it) {
+      if (it >= 1) {
+        const int blk = it - 1;   // the block whose logits the key waves finished in the previous step
+        float lgv[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) lgv[i] = lgs[blk & 1][vw * 16 + rg * 4 + i][hsel];
+        // maximum of each head over the block: the lane's four rows, the four row groups, then every head of the
+        // quad into every lane
+        float bm = fmaxf(fmaxf(lgv[0], lgv[1]), fmaxf(lgv[2], lgv[3]));
+        bm = fmaxf(bm, __shfl_xor(bm, 16, kWave));
+        bm = fmaxf(bm, __shfl_xor(bm, 32, kWave));
+        float corr[GH], m_own = -INFINITY, corr_own = 1.f;
+        bool moved = false;
+        const int bmi = __float_as_int(bm);
+        const float bq[GH] = {__int_as_float(__builtin_amdgcn_update_dpp(0, bmi, 0x00, 0xf, 0xf, false)),
+                              __int_as_float(__builtin_amdgcn_update_dpp(0, bmi, 0x55, 0xf, 0xf, false)),
+                              __int_as_float(__builtin_amdgcn_update_dpp(0, bmi, 0xaa, 0xf, 0xf, false)),
+                              __int_as_float(__builtin_amdgcn_update_dpp(0, bmi, 0xff, 0xf, 0xf, false))};
+#pragma unroll
+        for (int g = 0; g < GH; ++g) {
+          const float bg = bq[g];   // lane g of the quad, into every lane of the quad
+          const float mn = fmaxf(mh[g], bg);
+          corr[g] = (mn == mh[g]) ? 1.f : __builtin_amdgcn_exp2f(mh[g] - mn);   // (-inf -> value: 2^-inf = 0)
+          moved |= mn != mh[g];
+          mh[g] = mn;
+          if (hsel == g) { m_own = mn; corr_own = corr[g]; }
+        }
+        if (__any(moved)) {
+          lpart *= corr_own;
+#pragma unroll
+          for (int e = 0; e < EPL; ++e)
+#pragma unroll
+            for (int g = 0; g < GH; ++g) oacc[e][g] *= corr[g];
+        }
+        const float m_ref = m_own == -INFINITY ? 0.f : m_own;
+        uint32_t ph[4], pl[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float pv = __builtin_amdgcn_exp2f(lgv[i] - m_ref);   // rows past the end carry -inf: 0
+          lpart += pv;
+          ph[i] = __float_as_uint(pv) & 0xffff0000u;
+          pl[i] = __float_as_uint(pv - __uint_as_float(ph[i]));
+        }
+        bf16x4 a_hi, a_lo;
+        {
+          const uint32_t h01 = __builtin_amdgcn_perm(ph[1], ph[0], 0x07060302u), h23 = __builtin_amdgcn_perm(ph[3], ph[2], 0x07060302u);
+          const uint32_t l01 = __builtin_amdgcn_perm(pl[1], pl[0], 0x07060302u), l23 = __builtin_amdgcn_perm(pl[3], pl[2], 0x07060302u);
+          const uint2 hv = make_uint2(h01, h23), lv2 = make_uint2(l01, l23);
+          a_hi = *reinterpret_cast<const bf16x4*>(&hv);
+          a_lo = *reinterpret_cast<const bf16x4*>(&lv2);
+        }
+        uint32_t bw[4][EPL / 2];   // the four rows as bf16 pairs
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+#pragma unroll
+          for (int w = 0; w < EPL / 2; ++w) {
+            if constexpr (EB == 2) bw[j][w] = v0[j][w];
+            else bw[j][w] = (w & 1) ? e5m2x2_to_bf16x2<1>(v0[j][w / 2]) : e5m2x2_to_bf16x2<0>(v0[j][w / 2]);
+          }
+        }
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) {
+          const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;   // the upper / lower element of a pair
+          const uint2 bv = make_uint2(__builtin_amdgcn_perm(bw[1][e / 2], bw[0][e / 2], sel),
+                                      __builtin_amdgcn_perm(bw[3][e / 2], bw[2][e / 2], sel));
+          const bf16x4 bfrag = *reinterpret_cast<const bf16x4*>(&bv);
+          oacc[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a_hi, bfrag, oacc[e], 0, 0, 0);
+          oacc[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a_lo, bfrag, oacc[e], 0, 0, 0);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+          for (int e = 0; e < RW; ++e) v0[j][e] = v1[j][e];
+        if (blk + 2 < n_it) load_v(rowv + (blk + 2) * 64, v1);
+      }
+      __syncthreads();
+    }
+  }
+  // ---- merge: the four value waves through LDS
+  lpart += __shfl_xor(lpart, 16, kWave);
+  lpart += __shfl_xor(lpart, 32, kWave);
+  if (rg == 0) {
+#pragma unroll
+    for (int g = 0; g < GH; ++g)
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) sm_acc[vw][g][sub * EPL + e] = oacc[e][g];
+    if (sub < GH) { sm_l[vw][sub] = lpart; }
+  }
+  if (lane == 0) {
+#pragma unroll
+    for (int g = 0; g < GH; ++g) sm_m[vw][g] = mh[g];
+  }
+  __syncthreads();
+  for (int idx = threadIdx.x - 256; idx < nv * D; idx += 256) {
+    const int g = idx / D, e = idx - g * D;
+    float M = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) M = fmaxf(M, sm_m[w][g]);
+    float num = 0.f, den = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float sc = (sm_m[w][g] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(sm_m[w][g] - M);
+      num = fmaf(sm_acc[w][g][e], sc, num);
+      den = fmaf(sm_l[w][g], sc, den);
+    }
+    const size_t pidx = (head0 + g) * a.n_part + split;
+    a.part_acc[pidx * D + e] = num;
+    if (e == 0) a.part_ml[pidx] = make_float2(M, den);
+  }
+}
+
 // Second phase of the two-phase path: out-contribution of the selected rows from their stored logits
 // (log2 units) and their values.  A workgroup takes pv_split_len consecutive selected rows of a unit for
 // GH heads: 16 lanes share a row (d/16 columns each), 16 rows at a time; the maximum of each head over
@@ -749,6 +1290,17 @@ static hipError_t launch_sparse_ks(const AttnArgs& a, dim3 grid, size_t lds, hip
                : launch_sparse<D, GH, 8, false, KEYS_ONLY, EB>(a, grid, lds, st);
 }
 
+template <int D, int KSMAX, int EB>
+static hipError_t launch_roles(const AttnArgs& a, dim3 grid, size_t lds, hipStream_t st) {
+  if (lds > 32 * 1024) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sparse_attn_roles_kernel<D, KSMAX, EB, 1>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL((sparse_attn_roles_kernel<D, KSMAX, EB, 1>), grid, dim3(512), lds, st, a);
+  return hipGetLastError();
+}
+
 template <int D, bool KEYS_ONLY, int EB>
 static hipError_t launch_keys_d(const AttnArgs& a, hipStream_t st) {
   const int G = a.hq / a.hkv;
@@ -758,6 +1310,10 @@ static hipError_t launch_keys_d(const AttnArgs& a, hipStream_t st) {
   const int zb = (G + gh - 1) / gh;   // head blocks per unit (the last one may be partly empty)
   dim3 grid(a.batch * a.hkv, a.n_splits, zb);
   if (KEYS_ONLY) grid = dim3((unsigned)(a.gather.n_blocks + (long)a.n_splits * a.batch * a.hkv * zb));
+  // values readable now, four heads per block, chunks of a multiple of four tokens: the kernel with key waves and
+  // value waves
+  if (!KEYS_ONLY && gh == 4 && a.c % 4 == 0 && !a.k_sparse_out && a.k * a.c >= 4)
+    return a.r32 <= 160 ? launch_roles<D, 5, EB>(a, grid, lds, st) : launch_roles<D, 8, EB>(a, grid, lds, st);
   switch (gh) {
     case 4: return launch_sparse_ks<D, 4, KEYS_ONLY, EB>(a, grid, lds, st);
     case 2: return launch_sparse_ks<D, 2, KEYS_ONLY, EB>(a, grid, lds, st);

@@ -25,6 +25,21 @@ hipError_t launch_score(const bf16_t* q, const void* landmarks, int kv_bytes, fl
                         int batch, int hq, int hkv, int d, int n_c, int nc_stride, double scale, hipStream_t st);
 
 // ---- ArgTopK -------------------------------------------------------------------
+// Attention over the resident rows [outliers ; recent] of every unit, done by extra workgroups of the selection's
+// first launch (see resident_rows_attention in attn_kernels.hpp).
+struct ResidentArgs {
+  const bf16_t* q;          // [b, h_q, d]
+  const void* k_outlier;    // [units, o*c, d]
+  const void* v_outlier;
+  const void* k_local;      // [units, w, d]
+  const void* v_local;
+  float* part_acc;          // [b*h_q, n_part, d]
+  float2* part_ml;          // [b*h_q, n_part]
+  int hq, hkv, oc, w, n_part, part_slot;
+  int head_blocks;          // blocks of four heads per unit
+  int units;
+  float scale_log2;
+};
 constexpr int kSrcLogits = 0;  // key = max over the group of (logit - lse)
 constexpr int kSrcArray = 1;   // key = sign * scores[unit, j]
 
@@ -60,7 +75,10 @@ struct SelectPlan {
   int group_cands, n_groups, cand2_off, mid_nt, mid_e;
 };
 bool plan_select(int n, int k, int src, int units, SelectPlan* plan);
-hipError_t launch_select(const SelectArgs& a, const SelectPlan& plan, int src, int units, hipStream_t st);
+// res (may be NULL): resident-row attention to ride the first launch; only for shapes resident_fits() accepts
+hipError_t launch_select(const SelectArgs& a, const SelectPlan& plan, int src, int units, hipStream_t st,
+                         const ResidentArgs* res = nullptr, int d = 0, int kv_bytes = 2);
+bool resident_fits(const SelectPlan& plan, int units, int G, int d);
 
 // ---- value chunk gather (V_sparse = Gather(V_store, I)) -----------------------------
 // store [units, s_cap, d] of which s tokens are valid
@@ -123,7 +141,8 @@ struct AttnArgs {
   int res_split_len, sparse_split_len, n_splits;
   float* logit_buf;         // two-phase path: [b*h_q, k*c] logits of the selected rows (log2 units)
   int pv_split_len, n_pv_splits;  // two-phase path: selected rows per workgroup of the second phase
-  int n_part;               // partial states per head: n_splits (+ n_pv_splits on the two-phase path)
+  int n_part;               // partial states per head: n_splits (+ n_pv_splits on the two-phase path, + 1 with skip_resident)
+  int skip_resident;        // the resident rows [outliers ; recent] are attended over elsewhere (state at index n_part - 1)
   int c_shift;              // log2(c) when c is a power of two, else -1
   float scale_log2;         // softmax scale * log2(e)
   RopeFreqs freqs;

@@ -9,6 +9,7 @@
 // slices of a unit.  With a single slice the first kernel writes the final ids itself.
 #include "kernels.hpp"
 #include "select.hpp"
+#include "attn_kernels.hpp"
 #include <cstdlib>
 
 namespace skv {
@@ -125,12 +126,24 @@ __device__ __noinline__ double wave_group_score(ExactOperands a, int j, const do
 // One workgroup ranks NT*E slots of a unit (all of them when the unit has a single slice).  Thread t owns the
 // E consecutive slots from base + t*E: their logits come in as 16-byte pieces, GB heads at a time, the first
 // batch requested before the normalisers are formed.
-template <int NT, int E>
-__global__ __launch_bounds__(NT) void select_logits_kernel(SelectArgs a) {
+// RD != 0: workgroups past the slices attend over the resident rows of the unit (head dimension RD, REB bytes
+// per stored element), four query heads each: work that needs no selection, on compute units this launch would
+// leave idle.
+template <int NT, int E, int RD = 0, int REB = 2>
+__global__ __launch_bounds__(NT) void select_logits_kernel(SelectArgs a, ResidentArgs r) {
+  // RD != 0 (single slice per unit): a flat grid, the selection's workgroups first (they are dispatched first and
+  // are the longer ones), then (unit, head block) of the resident rows
+  if constexpr (RD != 0) {
+    if ((int)blockIdx.x >= r.units) {
+      const int idx = (int)blockIdx.x - r.units;
+      resident_rows_attention<RD, REB, NT>(r, idx % r.units, idx / r.units * 4);
+      return;
+    }
+  }
   constexpr int GB = E <= 4 ? 16 : E <= 8 ? 8 : E <= 16 ? 4 : 2;   // heads per batch: 64 logits in flight per thread
   __shared__ Select32Smem<NT> sm;
   __shared__ double lse_sm[64];
-  const int unit = blockIdx.y, slice = blockIdx.x;
+  const int unit = RD != 0 ? blockIdx.x : blockIdx.y, slice = RD != 0 ? 0 : blockIdx.x;
   const int base = slice * a.slice_len;
   const int n_here = min(a.slice_len, a.n - base);
   const int k_here = min(a.k, n_here);
@@ -531,9 +544,22 @@ static hipError_t launch_merge_array(const SelectArgs& a, int e, dim3 grid, hipS
     else return hipErrorInvalidValue;                                  \
   } while (0)
 
-static hipError_t launch_slices_logits(const SelectArgs& a, int nt, int e, int units, hipStream_t st) {
+// The resident rows ride the selection only where that costs nothing: a single slice per unit ranked by 1024
+// threads (one workgroup per compute unit), head dimension 128, and room on the chip for the extra workgroups.
+bool resident_fits(const SelectPlan& plan, int units, int G, int d) {
+  return plan.nt == 1024 && plan.e == 16 && plan.n_slices == 1 && d == 128 && (long)units * (1 + (G + 3) / 4) <= 256;
+}
+static hipError_t launch_slices_logits(const SelectArgs& a, int nt, int e, int units, hipStream_t st,
+                                       const ResidentArgs* res, int kv_bytes) {
+  if (res) {
+    dim3 grid(units * (1 + res->head_blocks));
+    if (kv_bytes == 1) hipLaunchKernelGGL((select_logits_kernel<1024, 16, 128, 1>), grid, dim3(1024), 0, st, a, *res);
+    else hipLaunchKernelGGL((select_logits_kernel<1024, 16, 128, 2>), grid, dim3(1024), 0, st, a, *res);
+    return hipGetLastError();
+  }
   dim3 grid(a.n_slices, units);
-#define SKV_L(NT_, E_) hipLaunchKernelGGL((select_logits_kernel<NT_, E_>), grid, dim3(NT_), 0, st, a)
+  const ResidentArgs none{};
+#define SKV_L(NT_, E_) hipLaunchKernelGGL((select_logits_kernel<NT_, E_>), grid, dim3(NT_), 0, st, a, none)
   SKV_FOR_SHAPE(nt, e, SKV_L);
 #undef SKV_L
   return hipGetLastError();
@@ -546,11 +572,13 @@ static hipError_t launch_merge_logits(const SelectArgs& a, int nt, int e, dim3 g
   return hipGetLastError();
 }
 
-hipError_t launch_select(const SelectArgs& a0, const SelectPlan& plan, int src, int units, hipStream_t st) {
+hipError_t launch_select(const SelectArgs& a0, const SelectPlan& plan, int src, int units, hipStream_t st,
+                         const ResidentArgs* res, int d, int kv_bytes) {
+  if (res && (src != kSrcLogits || !resident_fits(plan, units, a0.G, d))) return hipErrorInvalidValue;
   SelectArgs a = a0;
   a.group_cands = plan.group_cands; a.n_groups = plan.n_groups; a.cand2_off = plan.cand2_off;
   const bool lg = src == kSrcLogits;
-  hipError_t err = lg ? launch_slices_logits(a, plan.nt, plan.e, units, st) : launch_slices_array(a, plan.e, units, st);
+  hipError_t err = lg ? launch_slices_logits(a, plan.nt, plan.e, units, st, res, kv_bytes) : launch_slices_array(a, plan.e, units, st);
   if (err != hipSuccess || a.n_slices == 1) return err;
   if (plan.n_groups > 0) {
     err = lg ? launch_merge_logits<true>(a, plan.mid_nt, plan.mid_e, dim3(plan.n_groups, units), st)

@@ -444,7 +444,7 @@ __device__ void banded_select_topk(const uint32_t (&key)[E], int k, uint32_t key
     above |= (uint32_t)(present & hi) << e;
     near |= (uint32_t)(present & !hi & (z >= T - band)) << e;
   }
-  if (threadIdx.x == 0) sm.list_n = 0u;
+  if (threadIdx.x == 0) { sm.list_n = 0u; sm.above = 0u; }
   __syncthreads();
 #pragma unroll
   for (int e = 0; e < E; ++e)
@@ -452,8 +452,42 @@ __device__ void banded_select_topk(const uint32_t (&key)[E], int k, uint32_t key
       const uint32_t slot = atomicAdd(&sm.list_n, 1u);
       if (slot < (uint32_t)kListCap) { sm.list_ord[slot] = threadIdx.x * E + e; sm.list_key[slot] = (uint32_t)row_of(e); }
     }
+  {
+    const uint32_t n_mine = wave_incl_scan_u32((uint32_t)__popc(above));
+    if (lane == kWave - 1 && n_mine) atomicAdd(&sm.above, n_mine);
+  }
   __syncthreads();
-  const uint32_t n_near = sm.list_n;
+  const uint32_t n_near = sm.list_n, n_above = sm.above;
+  if (n_near <= (uint32_t)kWave) {
+    // the usual case, a handful of elements: one wave per row for the exact scores, then every wave ranks them in
+    // its registers (larger score first, equal scores by order index) and every thread decides its own elements
+    for (uint32_t i = wave; i < n_near; i += NW) {
+      const double ze = score_wave((int)sm.list_key[i]);
+      if (lane == 0) sm.list_z[i] = f64_key(ze);
+    }
+    __syncthreads();
+    const uint32_t want = (uint32_t)k - n_above;    // places left for the elements near the boundary (>= 1)
+    const uint64_t zv = (uint32_t)lane < n_near ? sm.list_z[lane] : 0ull;
+    const uint32_t ov = (uint32_t)lane < n_near ? sm.list_ord[lane] : 0xffffffffu;
+    uint32_t ahead = 0;
+    for (uint32_t j = 0; j < n_near; ++j) {
+      const uint64_t zj = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(zv >> 32), (int)j) << 32) |
+                          (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)zv, (int)j);
+      const uint32_t oj = (uint32_t)__builtin_amdgcn_readlane((int)ov, (int)j);
+      ahead += (zj > zv) | ((zj == zv) & (oj < ov));
+    }
+    const unsigned long long taken = __ballot((uint32_t)lane < n_near && ahead < want);
+    uint32_t gt2 = above;
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+      if (!(near & (1u << e))) continue;
+      const uint32_t ord = threadIdx.x * E + e;
+      for (uint32_t j = 0; j < n_near; ++j)
+        if ((uint32_t)__builtin_amdgcn_readlane((int)ov, (int)j) == ord && ((taken >> j) & 1ull)) gt2 |= 1u << e;
+    }
+    place_selected<NT, E>(gt2, 0u, 0u, sm.radix, sel_mask, out_pos);
+    return;
+  }
   uint64_t k2[E];
 #pragma unroll
   for (int e = 0; e < E; ++e) k2[e] = (above & (1u << e)) ? f64_key(1.0) : 0ull;   // in (exact scores never reach 1)

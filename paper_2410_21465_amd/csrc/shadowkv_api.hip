@@ -474,7 +474,21 @@ static int decode_impl(const shadowkv_params* params, const shadowkv_bf16* q, co
   a.cand_idx = reinterpret_cast<int32_t*>(ws + L.cand_idx);
   a.id_map = landmark_chunk_ids; a.id_stride = sh.nc_cap;
   a.out_ids = sel_ids; a.out_ids2 = out_chunk_ids;
-  e = launch_select(a, L.sel, kSrcLogits, sh.units, st);
+  // values readable in place: the attention over the resident rows [outliers ; recent] needs nothing of the
+  // selection and rides its launch where that launch leaves room (its state is the last of each head's partials)
+  const bool res_early = !cache && !sh.stage && !sh.keep_keys && sh.o * sh.c + sh.w > 0 &&
+                         resident_fits(L.sel, sh.units, sh.G, sh.d);
+  ResidentArgs ra{};
+  if (res_early) {
+    ra.q = q; ra.k_outlier = k_outlier; ra.v_outlier = v_outlier; ra.k_local = k_local; ra.v_local = v_local;
+    ra.part_acc = reinterpret_cast<float*>(ws + L.part_acc);
+    ra.part_ml = reinterpret_cast<float2*>(ws + L.part_ml);
+    ra.hq = sh.hq; ra.hkv = sh.hkv; ra.oc = sh.o * sh.c; ra.w = sh.w;
+    ra.n_part = L.attn.n_splits + 1; ra.part_slot = L.attn.n_splits;
+    ra.head_blocks = (sh.G + 3) / 4; ra.units = sh.units;
+    ra.scale_log2 = (float)(scale * 1.4426950408889634074);
+  }
+  e = launch_select(a, L.sel, kSrcLogits, sh.units, st, res_early ? &ra : nullptr, sh.d, sh.eb);
   if (e != hipSuccess) return fail_hip("select chunks", e);
   prof_mark(st, pstep, 2);
   AttnArgs t{};
@@ -502,7 +516,8 @@ static int decode_impl(const shadowkv_params* params, const shadowkv_bf16* q, co
     // 3./4. values readable in place: one fused kernel rebuilds and rotates the keys and attends over
     //       [outliers ; selected ; recent]
     prof_mark(st, pstep, 3);
-    t.n_part = t.n_splits;
+    t.n_part = t.n_splits + (res_early ? 1 : 0);
+    t.skip_resident = res_early ? 1 : 0;
     e = launch_attention(t, st);
     if (e != hipSuccess) return fail_hip("attention", e);
     prof_mark(st, pstep, 4);
