@@ -671,7 +671,7 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
 }
 
 // The fused kernel again, with the work of a block of selected rows divided between two kinds of waves (512
-// threads: waves 0-3 rebuild keys, waves 4-7 attend), for groups of four query heads and chunk sizes that are
+// threads: NKW waves rebuild keys, NVW waves attend), for groups of four query heads and chunk sizes that are
 // multiples of four.  The single-role kernel above keeps per lane the A fragments, the MFMA accumulators, the
 // rotation state, the queries, the value rows AND the online-softmax state of four heads: 242 registers, two waves
 // per SIMD, and with so few waves the scattered 2-2.5 KB pieces of A and V come in at 3.1-3.7 TB/s where the same
@@ -683,18 +683,22 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
 //     value rows requested two blocks ahead (they depend on nothing but the selection), online softmax, P.V;
 //     it also takes this split's share of the resident rows first, when no other launch has done them;
 //   * one barrier per step orders the ring.
-// Each role fits 128 registers, so two such workgroups (16 waves) share a compute unit.
-template <int D, int KSMAX, int EB, int ABUF>
-__global__ __launch_bounds__(512, 4) void sparse_attn_roles_kernel(AttnArgs a) {
+// Each role fits 128 registers, so 16 waves share a compute unit: 12 key + 4 value waves in one 1024-thread
+// workgroup per compute unit (with softmax x V on the matrix cores a value wave keeps up with three key waves;
+// waves i and i + 4 of a workgroup share a SIMD, so every SIMD gets three key waves and one value wave).
+template <int D, int KSMAX, int EB, int ABUF, int NKW, int NVW>
+__global__ __launch_bounds__(64 * (NKW + NVW), 4) void sparse_attn_roles_kernel(AttnArgs a) {
   constexpr int GH = 4, EPL = D / 16, NB = D / 16, HB = NB / 2;
   constexpr int RW = RawWords<EPL, EB>::n;
+  constexpr int NT = 64 * (NKW + NVW), RPS = 16 * NKW, BPV = NKW / NVW;   // threads; rows per step; blocks per value wave and step
+  static_assert(NKW % NVW == 0, "every value wave takes the same number of blocks per step");
   extern __shared__ __align__(16) bf16_t Bt[];  // [D][rp], element (n, kk) = B[kk][n]; then int tokb[], vrowb[]
-  __shared__ __align__(16) float lgs[2][64][GH];  // logits (log2 units) of the rows of one step, -inf past the end
+  __shared__ __align__(16) float lgs[2][RPS][GH]; // logits (log2 units) of the rows of one step, -inf past the end
   __shared__ __align__(16) float qs[GH][D];       // the block's queries, scaled to log2 units
   __shared__ double frev_s[D / 2];                // rotary frequencies in revolutions per position
   __shared__ float cd_s[D / 2], sd_s[D / 2];      // cos / sin of one position step
-  __shared__ float sm_acc[4][GH][D];
-  __shared__ float sm_m[4][GH], sm_l[4][GH];
+  __shared__ float sm_acc[NVW][GH][D];
+  __shared__ float sm_m[NVW][GH], sm_l[NVW][GH];
   const int unit = blockIdx.x, split = blockIdx.y, g0 = blockIdx.z * GH;
   const int G = a.hq / a.hkv, b = unit / a.hkv, h = unit % a.hkv;
   const size_t head0 = (size_t)b * a.hq + (size_t)h * G + g0;
@@ -709,7 +713,7 @@ __global__ __launch_bounds__(512, 4) void sparse_attn_roles_kernel(AttnArgs a) {
   const int cshift = a.c_shift;
   auto chunk_of = [&](int i) { return cshift >= 0 ? i >> cshift : i / a.c; };
   const int ch_begin = chunk_of(s_begin);
-  const int n_it = (s_end - s_begin + 63) / 64;
+  const int n_it = (s_end - s_begin + RPS - 1) / RPS;
 
   int* tokb = reinterpret_cast<int*>(Bt + (size_t)D * rp);
   int* vrowb = tokb + (a.sparse_split_len / a.c + 2);
@@ -720,7 +724,7 @@ __global__ __launch_bounds__(512, 4) void sparse_attn_roles_kernel(AttnArgs a) {
     const int32_t* ids = a.sel_ids + (size_t)unit * a.k;
     const int n_ch = chunk_of(s_end - 1) - ch_begin + 1;
     const int last_slot = a.v_unit_rows / a.c - 1;
-    for (int idx = threadIdx.x; idx < n_ch; idx += 512) {
+    for (int idx = threadIdx.x; idx < n_ch; idx += NT) {
       const int tb = min(max(ids[ch_begin + idx], 0), last_chunk) * a.c;
       tokb[idx] = tb;
       int vb = tb;
@@ -731,7 +735,7 @@ __global__ __launch_bounds__(512, 4) void sparse_attn_roles_kernel(AttnArgs a) {
       vrowb[idx] = vb;
     }
   }
-  for (int idx = threadIdx.x; idx < GH * D; idx += 512) {
+  for (int idx = threadIdx.x; idx < GH * D; idx += NT) {
     const int g = idx / D, e = idx - g * D;
     qs[g][e] = bf16_to_f32(a.q[(head0 + min(g, nv - 1)) * D + e]) * a.scale_log2;
   }
@@ -742,16 +746,16 @@ __global__ __launch_bounds__(512, 4) void sparse_attn_roles_kernel(AttnArgs a) {
     cd_s[threadIdx.x] = __builtin_amdgcn_cosf((float)rv);
     sd_s[threadIdx.x] = __builtin_amdgcn_sinf((float)rv);
   }
-  // ---- B^T of this KV head into LDS (zero beyond rank r), by all eight waves
+  // ---- B^T of this KV head into LDS (zero beyond rank r), by all the waves
   {
-    constexpr int NBI = (KSMAX * 32 * (D / 8) + 511) / 512;  // 16-byte pieces per thread
+    constexpr int NBI = (KSMAX * 32 * (D / 8) + NT - 1) / NT;  // 16-byte pieces per thread
     const uint8_t* Bu = static_cast<const uint8_t*>(a.B) + (size_t)unit * r * D * EB;
     const int pieces = r32 * (D / 8);
     uint4 bw[NBI];
     int dst[NBI];
 #pragma unroll
     for (int it = 0; it < NBI; ++it) {
-      const int idx = min((int)threadIdx.x + it * 512, pieces - 1);
+      const int idx = min((int)threadIdx.x + it * NT, pieces - 1);
       const int n8 = (idx & 3) + 4 * (idx / (4 * r32)), kk = (idx >> 2) % r32;
       const uint8_t* src = Bu + ((size_t)min(kk, r - 1) * D + n8 * 8) * EB;
       if constexpr (EB == 2) {
@@ -782,7 +786,7 @@ __global__ __launch_bounds__(512, 4) void sparse_attn_roles_kernel(AttnArgs a) {
   }
   __syncthreads();   // tables, queries and B^T are in place
 
-  if (wave < 4) {
+  if (wave < NKW) {
     // =========================== key waves ===========================
     const int kw = wave;
     const int ksteps = r32 / 32;
@@ -802,7 +806,7 @@ __global__ __launch_bounds__(512, 4) void sparse_attn_roles_kernel(AttnArgs a) {
       tok0 = tokb[ch4 - ch_begin] + (ic - ch4 * a.c);
     };
     auto work = [&](int it, AFrag<EB> (&af)[KSMAX], int& tok_af) {
-      const int row0 = s_begin + it * 64 + kw * 16;
+      const int row0 = s_begin + it * RPS + kw * 16;
       const int tok_cur = tok_af;
       f32x4 acc[NB];
 #pragma unroll
@@ -818,7 +822,7 @@ __global__ __launch_bounds__(512, 4) void sparse_attn_roles_kernel(AttnArgs a) {
           }
         }
       }
-      if (ABUF == 1 && it + 1 < n_it) load_a(row0 + 64, af, tok_af);   // one set of fragments: consumed, so reload
+      if (ABUF == 1 && it + 1 < n_it) load_a(row0 + RPS, af, tok_af);   // one set of fragments: consumed, so reload
       // RoPE in place: one accurate angle per frequency for the first of the lane's four tokens, stepped by
       // one position for the others
       {
@@ -876,23 +880,24 @@ __global__ __launch_bounds__(512, 4) void sparse_attn_roles_kernel(AttnArgs a) {
         }
       }
     };
+    // (blocks that start past the end of the split are skipped by both kinds of waves)
     if (n_it > 0) load_a(s_begin + kw * 16, afA, tokA);
     if constexpr (ABUF == 1) {
       for (int it = 0; it <= n_it; ++it) {
-        if (it < n_it) work(it, afA, tokA);
+        if (it < n_it && s_begin + it * RPS + kw * 16 < s_end) work(it, afA, tokA);
         __syncthreads();
       }
     } else {
       for (int it = 0; it <= n_it; it += 2) {
         if (it < n_it) {
-          if (it + 1 < n_it) load_a(s_begin + (it + 1) * 64 + kw * 16, afB, tokB);
-          work(it, afA, tokA);
+          if (it + 1 < n_it) load_a(s_begin + (it + 1) * RPS + kw * 16, afB, tokB);
+          if (s_begin + it * RPS + kw * 16 < s_end) work(it, afA, tokA);
         }
         __syncthreads();
         if (it + 1 <= n_it) {
           if (it + 1 < n_it) {
-            if (it + 2 < n_it) load_a(s_begin + (it + 2) * 64 + kw * 16, afA, tokA);
-            work(it + 1, afB, tokB);
+            if (it + 2 < n_it) load_a(s_begin + (it + 2) * RPS + kw * 16, afA, tokA);
+            if (s_begin + (it + 1) * RPS + kw * 16 < s_end) work(it + 1, afB, tokB);
           }
           __syncthreads();
         }
@@ -903,7 +908,7 @@ __global__ __launch_bounds__(512, 4) void sparse_attn_roles_kernel(AttnArgs a) {
   }
 
   // =========================== value waves ===========================
-  const int vw = wave - 4;
+  const int vw = wave - NKW;
   OnlineSoftmax<GH, EPL, EB> st;
   st.init();
   auto load_v = [&](int row0, uint32_t (&vraw)[4][RW]) {
@@ -923,7 +928,7 @@ __global__ __launch_bounds__(512, 4) void sparse_attn_roles_kernel(AttnArgs a) {
     const int n_res = oc + a.w;
     const int i_begin = min(n_res, split * a.res_split_len);
     const int i_end = min(n_res, i_begin + a.res_split_len);
-    for (int i0 = i_begin + vw * 8; i0 < i_end; i0 += 32) {
+    for (int i0 = i_begin + vw * 8; i0 < i_end; i0 += 8 * NVW) {
       uint32_t kraw[2][RW], vraw[2][RW];
       bool ok[2];
 #pragma unroll
@@ -994,16 +999,20 @@ __global__ __launch_bounds__(512, 4) void sparse_attn_roles_kernel(AttnArgs a) {
   }
   {
     uint32_t v0[4][RW], v1[4][RW];
-    const int rowv = s_begin + vw * 16;
     const int hsel = sub & 3;   // the head whose weights this lane forms
-    if (n_it > 0) load_v(rowv, v0);
-    if (n_it > 1) load_v(rowv + 64, v1);
+    // this wave's blocks in the order it meets them: number q is block vw + (q % BPV) * NVW of step q / BPV
+    const int n_q = n_it * BPV;
+    auto row_of_q = [&](int q) { return s_begin + (q / BPV) * RPS + (vw + (q % BPV) * NVW) * 16; };
+    if (n_q > 0) load_v(row_of_q(0), v0);
+    if (n_q > 1) load_v(row_of_q(1), v1);
     for (int it = 0; it <= n_it; ++it) {
-      if (it >= 1) {
-        const int blk = it - 1;   // the block whose logits the key waves finished in the previous step
+      for (int jj = 0; it >= 1 && jj < BPV; ++jj) {
+        const int q = (it - 1) * BPV + jj;   // logits finished by the key waves in the previous step
+        const int lrow = (vw + jj * NVW) * 16;
+        if (row_of_q(q) < s_end) {
         float lgv[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) lgv[i] = lgs[blk & 1][vw * 16 + rg * 4 + i][hsel];
+        for (int i = 0; i < 4; ++i) lgv[i] = lgs[(it - 1) & 1][lrow + rg * 4 + i][hsel];
         // maximum of each head over the block: the lane's four rows, the four row groups, then every head of the
         // quad into every lane
         float bm = fmaxf(fmaxf(lgv[0], lgv[1]), fmaxf(lgv[2], lgv[3]));
@@ -1067,16 +1076,17 @@ __global__ __launch_bounds__(512, 4) void sparse_attn_roles_kernel(AttnArgs a) {
           oacc[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a_hi, bfrag, oacc[e], 0, 0, 0);
           oacc[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a_lo, bfrag, oacc[e], 0, 0, 0);
         }
+        }
 #pragma unroll
         for (int j = 0; j < 4; ++j)
 #pragma unroll
           for (int e = 0; e < RW; ++e) v0[j][e] = v1[j][e];
-        if (blk + 2 < n_it) load_v(rowv + (blk + 2) * 64, v1);
+        if (q + 2 < n_q) load_v(row_of_q(q + 2), v1);   // (rows past the end are clamped inside)
       }
       __syncthreads();
     }
   }
-  // ---- merge: the four value waves through LDS
+  // ---- merge: the value waves through LDS
   lpart += __shfl_xor(lpart, 16, kWave);
   lpart += __shfl_xor(lpart, 32, kWave);
   if (rg == 0) {
@@ -1091,14 +1101,14 @@ __global__ __launch_bounds__(512, 4) void sparse_attn_roles_kernel(AttnArgs a) {
     for (int g = 0; g < GH; ++g) sm_m[vw][g] = mh[g];
   }
   __syncthreads();
-  for (int idx = threadIdx.x - 256; idx < nv * D; idx += 256) {
+  for (int idx = threadIdx.x - 64 * NKW; idx < nv * D; idx += 64 * NVW) {
     const int g = idx / D, e = idx - g * D;
     float M = -INFINITY;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) M = fmaxf(M, sm_m[w][g]);
+    for (int w = 0; w < NVW; ++w) M = fmaxf(M, sm_m[w][g]);
     float num = 0.f, den = 0.f;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
+    for (int w = 0; w < NVW; ++w) {
       const float sc = (sm_m[w][g] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(sm_m[w][g] - M);
       num = fmaf(sm_acc[w][g][e], sc, num);
       den = fmaf(sm_l[w][g], sc, den);
@@ -1292,12 +1302,13 @@ static hipError_t launch_sparse_ks(const AttnArgs& a, dim3 grid, size_t lds, hip
 
 template <int D, int KSMAX, int EB>
 static hipError_t launch_roles(const AttnArgs& a, dim3 grid, size_t lds, hipStream_t st) {
+  constexpr int NKW = 12, NVW = 4;
   if (lds > 32 * 1024) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sparse_attn_roles_kernel<D, KSMAX, EB, 1>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sparse_attn_roles_kernel<D, KSMAX, EB, 1, NKW, NVW>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL((sparse_attn_roles_kernel<D, KSMAX, EB, 1>), grid, dim3(512), lds, st, a);
+  hipLaunchKernelGGL((sparse_attn_roles_kernel<D, KSMAX, EB, 1, NKW, NVW>), grid, dim3(64 * (NKW + NVW)), lds, st, a);
   return hipGetLastError();
 }
 
@@ -1312,7 +1323,7 @@ static hipError_t launch_keys_d(const AttnArgs& a, hipStream_t st) {
   if (KEYS_ONLY) grid = dim3((unsigned)(a.gather.n_blocks + (long)a.n_splits * a.batch * a.hkv * zb));
   // values readable now, four heads per block, chunks of a multiple of four tokens: the kernel with key waves and
   // value waves
-  if (!KEYS_ONLY && gh == 4 && a.c % 4 == 0 && !a.k_sparse_out && a.k * a.c >= 4)
+  if (attention_has_roles(G, a.c, a.k, a.k_sparse_out != nullptr, KEYS_ONLY))
     return a.r32 <= 160 ? launch_roles<D, 5, EB>(a, grid, lds, st) : launch_roles<D, 8, EB>(a, grid, lds, st);
   switch (gh) {
     case 4: return launch_sparse_ks<D, 4, KEYS_ONLY, EB>(a, grid, lds, st);

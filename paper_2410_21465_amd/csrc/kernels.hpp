@@ -151,6 +151,11 @@ struct AttnArgs {
 // Query heads per attention workgroup: four wherever the group has at least three heads (a group of 3, 5, 6 or 7
 // leaves part of its last block empty, which costs less than rebuilding the keys once more per head or pair).
 inline int attention_heads_per_group(int G) { return G >= 3 ? 4 : G; }
+// Shapes the kernel with key waves and value waves takes: values readable in place, four heads per block, chunks
+// of a multiple of four tokens, no diagnostic copy of the keys.
+inline bool attention_has_roles(int G, int c, int k, bool keep_keys, bool keys_only) {
+  return !keys_only && attention_heads_per_group(G) == 4 && c % 4 == 0 && !keep_keys && (long)k * c >= 4;
+}
 hipError_t launch_attention(const AttnArgs& a, hipStream_t st);         // values readable now: one fused kernel
 hipError_t launch_attention_keys(const AttnArgs& a, hipStream_t st);    // two-phase path, before the values arrive
 hipError_t launch_attention_values(const AttnArgs& a, hipStream_t st);  // two-phase path, after

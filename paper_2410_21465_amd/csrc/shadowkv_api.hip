@@ -111,14 +111,17 @@ struct AttnPlan {
   int res_split_len, sparse_split_len, n_splits, z;
   int pv_split_len, n_pv_splits;  // second phase of the two-phase path (values gathered meanwhile)
 };
-AttnPlan plan_attention(const Shape& sh) {
+AttnPlan plan_attention(const Shape& sh, bool with_cache = false) {
   AttnPlan ap;
   ap.z = (sh.G + attention_heads_per_group(sh.G) - 1) / attention_heads_per_group(sh.G);
   const long groups = (long)sh.units * ap.z;
   const long kc = (long)sh.k * sh.c, n_res = (long)sh.o * sh.c + sh.w;
-  // the largest split (fewest B^T stagings) that still gives >= 512 workgroups
+  // the largest split (fewest B^T stagings) that still gives >= 512 workgroups; the kernel with key and value
+  // waves runs one 1024-thread workgroup per compute unit: 256 of them fill the chip
+  const bool roles = attention_has_roles(sh.G, sh.c, sh.k, sh.keep_keys, sh.stage || with_cache);
+  const long want = roles ? 256 : 512;
   long len = 32;
-  for (long cand : {1024l, 512l, 256l, 128l, 64l}) if (kc * groups / cand >= 512) { len = cand; break; }
+  for (long cand : {1024l, 512l, 256l, 128l, 64l}) if (kc * groups / cand >= want) { len = cand; break; }
   // tuning override: rows per split (read once)
   static const long forced = [] { const char* ov = std::getenv("SHADOWKV_SPARSE_SPLIT"); return ov ? std::atol(ov) : 0l; }();
   if (forced >= 32 && forced <= 1024 && forced % 32 == 0) len = forced;
@@ -159,7 +162,9 @@ DecodeLayout decode_layout(const Shape& sh) {
   L.logit_buf = off; off += up(heads * rows / sh.units * sizeof(float));  // two-phase path: [b*h_q, k*c]
   L.k_sparse = off; off += sh.keep_keys ? up(rows * sh.d * sizeof(float)) : 0;
   L.v_sparse = off; off += sh.stage ? up(rows * sh.d * sh.eb) : 0;
-  const size_t n_part = (size_t)L.attn.n_splits + L.attn.n_pv_splits;
+  // (a step with a value cache plans its splits for the two-phase kernels: room for whichever has more)
+  const AttnPlan cached = plan_attention(sh, true);
+  const size_t n_part = (size_t)std::max(L.attn.n_splits, cached.n_splits) + L.attn.n_pv_splits;
   L.part_acc = off; off += up(heads * n_part * sh.d * sizeof(float));
   L.part_ml = off; off += up(heads * n_part * sizeof(float2));
   L.total = off;
@@ -430,7 +435,8 @@ static int decode_impl(const shadowkv_params* params, const shadowkv_bf16* q, co
     if (cache->slots < sh.k || cache->slots > kMaxCacheSlots)
       return fail_inval("cache_slots %d must be in [topk_chunks = %d, %d]", cache->slots, sh.k, kMaxCacheSlots);
   }
-  const DecodeLayout L = decode_layout(sh);
+  DecodeLayout L = decode_layout(sh);
+  if (cache) L.attn = plan_attention(sh, true);
   rc = check_workspace(workspace, workspace_bytes, L.total);
   if (rc != SHADOWKV_OK) return rc;
 
@@ -503,7 +509,7 @@ static int decode_impl(const shadowkv_params* params, const shadowkv_bf16* q, co
   t.out = out;
   t.s_cap = sh.cap;
   t.batch = sh.b; t.hq = sh.hq; t.hkv = sh.hkv; t.d = sh.d; t.s = sh.s; t.c = sh.c; t.o = sh.o; t.k = sh.k; t.w = sh.w;
-  t.r = sh.r; t.r32 = (sh.r + 31) / 32 * 32; t.rp = t.r32 + 8;  // +8: 16-byte multiple that spreads LDS banks
+  t.r = sh.r; t.r32 = (sh.r + 31) / 32 * 32; t.rp = t.r32 + 16;  // row pitch = 16 mod 32 elements: the 16-byte operand reads of a wave then spread evenly over the LDS banks (measured: twice the rate of +8)
   t.res_split_len = L.attn.res_split_len; t.sparse_split_len = L.attn.sparse_split_len; t.n_splits = L.attn.n_splits;
   t.pv_split_len = L.attn.pv_split_len; t.n_pv_splits = L.attn.n_pv_splits;
   t.v_unit_rows = sh.k * sh.c;
