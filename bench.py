@@ -89,7 +89,7 @@ def main() -> int:
 
     import torch
     from paper_2410_21465_amd import shadowkv as S
-    from paper_2410_21465_amd.workloads import (CONFIGS, EXTRA_CONFIGS, generate, generated_chunk, query_sequence, to_fp8_storage,
+    from workloads import (CONFIGS, EXTRA_CONFIGS, generate, generated_chunk, query_sequence, to_fp8_storage,
                                                 with_capacity)
 
     if not torch.cuda.is_available():

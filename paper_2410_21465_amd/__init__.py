@@ -3,4 +3,4 @@
 ``shadowkv`` (the binding) loads ``libshadowkv.so`` lazily on first use and
 raises if it is missing; ``workloads`` draws the synthetic inputs.
 """
-__all__ = ["shadowkv", "workloads"]
+__all__ = ["shadowkv"]

@@ -19,7 +19,7 @@ import torch
 
 from oracle import shadowkv_oracle as O
 from paper_2410_21465_amd import shadowkv as S
-from paper_2410_21465_amd.workloads import Workload, generate
+from workloads import Workload, generate
 
 OUT_MAX_ABS = 2e-2
 OUT_MEAN_ABS = 2e-3

@@ -48,7 +48,7 @@ def test_valid_params_and_workspace_sizes():
     assert staged >= w + 2 * 8 * 16 * 128 * 2 * 2      # units * c * k * d bf16 values
     assert S.build_workspace_bytes(p) >= 2 * 2 * 512 * (128 * 2 + 8)
     # the five benchmark shapes are all accepted
-    from paper_2410_21465_amd.workloads import CONFIGS
+    from workloads import CONFIGS
     for wl in CONFIGS.values():
         assert S.validate_params(S.Params.from_workload(wl)) == S.OK, wl.name
 

@@ -32,7 +32,7 @@ def test_equivalent_bandwidth_reproduces_the_papers_example():
 
 def test_algorithmic_bytes_match_the_papers_traffic_terms():
     """Landmark and attended-row terms of the model, in bytes: M*S/C and 2*M*(K+O)*C with M = 2*d bytes per vector."""
-    from paper_2410_21465_amd.workloads import CONFIGS
+    from workloads import CONFIGS
     wl = CONFIGS["c3-hbm"]
     ab = bench.algorithmic_bytes(wl)
     M, u = 2 * wl.head_dim, wl.batch * wl.n_kv_heads

@@ -8,7 +8,7 @@ import torch
 
 from oracle import shadowkv_oracle as O
 from paper_2410_21465_amd import shadowkv as S
-from paper_2410_21465_amd.workloads import Workload, generate, generated_chunk, with_capacity
+from workloads import Workload, generate, generated_chunk, with_capacity
 from parity_util import OUT_MAX_ABS, OUT_MEAN_ABS, to_bits
 
 pytestmark = pytest.mark.gpu

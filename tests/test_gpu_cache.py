@@ -7,7 +7,7 @@ import torch
 
 from oracle import shadowkv_oracle as O
 from paper_2410_21465_amd import shadowkv as S
-from paper_2410_21465_amd.workloads import Workload, generate, query_sequence
+from workloads import Workload, generate, query_sequence
 from parity_util import OUT_MAX_ABS, OUT_MEAN_ABS, oracle_params, to_bits
 
 pytestmark = pytest.mark.gpu

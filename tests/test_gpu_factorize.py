@@ -8,7 +8,7 @@ import torch
 
 from oracle import shadowkv_oracle as O
 from paper_2410_21465_amd import shadowkv as S
-from paper_2410_21465_amd.workloads import Workload, generate
+from workloads import Workload, generate
 
 import parity_util as PU
 
@@ -114,7 +114,7 @@ def test_full_size_sequence_by_properties(name, kd):
     size is checked against fp64 numpy on the same keys: orthonormal right singular vectors, Ritz residuals at rounding level (K^T K psi = sigma^2 psi), the captured
     energy equal to the sum of the 160 largest eigenvalues of the Gram matrix (Eckart-Young), and sampled rows of A and
     all of B equal to the roundings of K psi and psi."""
-    from paper_2410_21465_amd.workloads import CONFIGS
+    from workloads import CONFIGS
     wl = CONFIGS[name].scaled(batch=1, n_queries=1, value_location="hbm")
     print(f"\n[case] kv_dtype {kd} {wl}", flush=True)
     t = generate(wl, device="cuda", want_prefill=False, want_k_pre=True)

@@ -8,7 +8,7 @@ import torch
 
 from oracle import shadowkv_oracle as O
 from paper_2410_21465_amd import shadowkv as S
-from paper_2410_21465_amd.workloads import Workload, generate, generated_chunk, to_fp8_storage, with_capacity
+from workloads import Workload, generate, generated_chunk, to_fp8_storage, with_capacity
 
 import parity_util as PU
 

@@ -6,7 +6,7 @@ import numpy as np
 import pytest
 import torch
 
-from paper_2410_21465_amd.workloads import CONFIGS
+from workloads import CONFIGS
 
 import parity_util as PU
 
@@ -69,7 +69,7 @@ def test_config5_mha_d96():
 
 # ---- the same configurations with the KV cache stored as FP8 E5M2 (section "Precision Sensitivity") ----
 def _run_fp8(name, n_queries=2, move_values_to=None):
-    from paper_2410_21465_amd.workloads import to_fp8_storage
+    from workloads import to_fp8_storage
     wl = CONFIGS[name]
     print(f"\n[config] fp8 {wl}", flush=True)
     t = to_fp8_storage(PU.draw(wl))

@@ -5,7 +5,7 @@ import pytest
 import torch
 
 from paper_2410_21465_amd import shadowkv as S
-from paper_2410_21465_amd.workloads import CONFIGS, Workload
+from workloads import CONFIGS, Workload
 
 import parity_util as PU
 

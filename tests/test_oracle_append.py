@@ -6,7 +6,7 @@ import scipy.linalg
 import torch
 
 from oracle import shadowkv_oracle as O
-from paper_2410_21465_amd.workloads import Workload, generate
+from workloads import Workload, generate
 
 
 def _bits(x: np.ndarray) -> np.ndarray:

@@ -7,7 +7,7 @@ import pytest
 import torch
 
 from paper_2410_21465_amd import shadowkv as S
-from paper_2410_21465_amd.workloads import Workload, to_fp8_storage
+from workloads import Workload, to_fp8_storage
 
 import parity_util as PU
 
