@@ -5,8 +5,11 @@ One "step" = one shadowkv_decode_step (landmark scoring, selection, key rebuild 
 value gather, attention) for the whole batch of a synthetic workload shaped like the
 paper's; the metric is decode tokens/s = batch / step time, inputs resident before the
 timed region.  Prints ONE JSON line (see the fields below) with a `roofline` object for
-the dominant kernel (landmark scoring, HBM-bound) and a `cpu_baseline` object (the CPU
-oracle timed on this host on a bounded sample).
+the dominant kernel (landmark scoring, HBM-bound), a `rooflines` list with one such object
+per memory-bound stage (scoring, attention + combine, the pre-filling call), and a
+`cpu_baseline` object (the CPU oracle timed on this host on a bounded sample, on all
+cores and on one thread).  `--workload all` runs the benchmark's configurations one after
+the other, each in a process of its own, and prints one such line per configuration.
 """
 from __future__ import annotations
 
@@ -86,6 +89,23 @@ def main() -> int:
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         return 2
+    if args.workload == "all":
+        # one child process per configuration (nothing in this process has touched the GPU), their lines passed on
+        import subprocess
+        rc = 0
+        for name in ("c1", "c2", "c3-host", "c3-hbm", "c4", "c5"):
+            argv = [sys.executable, os.path.abspath(__file__)]
+            skip = False
+            for a in sys.argv[1:]:
+                if skip:
+                    skip = False
+                elif a == "--workload":
+                    skip = True
+                elif not a.startswith("--workload="):
+                    argv.append(a)
+            r = subprocess.run(argv + ["--workload", name])
+            rc = rc or r.returncode
+        return rc
 
     import torch
     from paper_2410_21465_amd import shadowkv as S
@@ -188,16 +208,27 @@ def main() -> int:
         graph.replay()                      # one untimed replay
         torch.cuda.synchronize()
     n_rep, n_eager = (args.steps // n_pool, args.steps % n_pool) if graph is not None else (0, args.steps)
+    # exactly args.steps steps between two synchronisations; an event after every graph replay (one pass over the
+    # query pool) or eager step gives the distribution, and the median of those per-step times is what is reported
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(n_rep + n_eager + 1)]
+    torch.cuda.synchronize()
     t1 = time.perf_counter()
-    for _ in range(n_rep):
+    marks[0].record()
+    for j in range(n_rep):
         graph.replay()
+        marks[j + 1].record()
     for i in range(n_eager):
         step(i)
+        marks[n_rep + i + 1].record()
     torch.cuda.synchronize()
     t2 = time.perf_counter()
-    ms_per_step = (t2 - t1) * 1e3 / args.steps
+    ms_per_step_mean = (t2 - t1) * 1e3 / args.steps
+    import statistics
+    per_step = [marks[j].elapsed_time(marks[j + 1]) / (n_pool if j < n_rep else 1) for j in range(n_rep + n_eager)]
+    # (median over the replays when there are any: the few eager steps behind them carry host launch gaps)
+    ms_per_step = statistics.median(per_step[:n_rep]) if n_rep else statistics.median(per_step)
     value = wl.batch / (ms_per_step * 1e-3)
-    print(f"[bench] timed steps done ({ms_per_step:.4f} ms per step)", file=sys.stderr, flush=True)
+    print(f"[bench] timed steps done (median {ms_per_step:.4f} ms per step, mean {ms_per_step_mean:.4f})", file=sys.stderr, flush=True)
 
     # Per-stage times: the same number of steps again, eagerly, with HIP events at the stage boundaries.
     S.profile_begin(args.steps)
@@ -273,20 +304,58 @@ def main() -> int:
         h2d_gbps = 4 * hsrc.numel() / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
         del hsrc, ddst
 
-    ab = algorithmic_bytes(wl, 1 if fp8 else 2)
+    eb = 1 if fp8 else 2
+    ab = algorithmic_bytes(wl, eb)
     score_ms = prof["ms"]["score"]
     score_bytes = ab["landmarks"] + ab["q_out"] // 2
     achieved = score_bytes / (score_ms * 1e-3) / 1e9
-    traffic = None
+    # HBM bytes per launch by the chip's counters: a figure stored with the profiles (this run collects no
+    # counters), with the file and the commit it was collected at
     tag = wl.name + ("-fp8" if fp8 else "")
-    pmc = os.path.join(ROOT, "profiles", f"score_kernel_{tag}_traffic.txt")   # committed rocprofv3 --pmc summary
-    if os.path.exists(pmc):
-        for line in open(pmc):
-            if line.startswith("hbm_bytes_per_launch:"):
-                traffic = int(line.split(":")[1])
+
+    def stored_traffic(kernel):
+        path = os.path.join(ROOT, "profiles", f"{kernel}_{tag}_traffic.txt")   # committed rocprofv3 --pmc summary
+        val, commit = None, None
+        if os.path.exists(path):
+            for line in open(path):
+                if line.startswith("hbm_bytes_per_launch:"):
+                    val = int(line.split(":")[1])
+                if line.startswith("collected_at_commit:"):
+                    commit = line.split(":")[1].strip()
+        src = (f"profiles/{os.path.basename(path)}: rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE scaled by a copy kernel of known "
+               f"size, collected at commit {commit}; not measured by this run") if val is not None else None
+        return val, src
+    traffic, traffic_src = stored_traffic("score_kernel")
+    # the other memory-bound stages: attention + combine (gathered A rows and values, resident keys and values, B,
+    # queries, outputs) and the pre-filling call (every context key read once, every landmark written once)
+    plan = S.decode_plan(p)
+    # (where the resident rows are attended over by extra workgroups of the selection launch, their bytes are not
+    # the attention stage's)
+    res_in_select = plan["resident_rows_in_selection_launch"] and cache is None
+    attn_bytes = (ab["A_rows"] + ab["B"] + ab["q_out"] + (0 if res_in_select else ab["resident_kv"])
+                  + (ab["values"] if wl.value_location == "hbm" else 0))
+    attn_ms = prof["ms"]["attention"]
+    attn_traffic, attn_src = stored_traffic("attention")
+    build_bytes = wl.units * eb * wl.head_dim * (wl.ctx_len + wl.n_landmarks + 2 * 2 * wl.n_outlier_chunks * wl.chunk_size)
+    rooflines = [
+        {"kernel": "score_kernel (landmark scoring, P = Q L^T)", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS,
+         "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic, "traffic_source": traffic_src,
+         "algorithmic_bytes_per_launch": score_bytes, "avg_launch_ms": score_ms},
+        {"kernel": "sparse attention + combine (key rebuild, RoPE, softmax x V over selected and resident rows)"
+                   + ("; selected values arrive over PCIe and are not counted" if wl.value_location == "host" else ""),
+         "bound": "hbm", "achieved": attn_bytes / (attn_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+         "frac": attn_bytes / (attn_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, "traffic": attn_traffic, "traffic_source": attn_src,
+         "algorithmic_bytes_per_launch": attn_bytes, "avg_launch_ms": attn_ms},
+        {"kernel": "shadowkv_build_landmarks (chunk_stats_kernel + outlier selection + gathers; once per context)",
+         "bound": "hbm", "achieved": build_bytes / (build_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+         "frac": build_bytes / (build_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, "traffic": None, "traffic_source": None,
+         "algorithmic_bytes_per_launch": build_bytes, "avg_launch_ms": build_ms},
+    ]
     res = {
         "metric": "decode_tokens_per_s", "value": value, "unit": "tokens/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "ms_per_step_mean": ms_per_step_mean,
+        "ms_per_step_statistic": f"median over {n_rep} graph replays of {n_pool} steps" if n_rep else f"median over {n_eager} eager steps",
+        "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{wl.name}: batch {wl.batch} x context {wl.ctx_len}, {wl.n_q_heads}q/{wl.n_kv_heads}kv "
                                f"heads, d={wl.head_dim}, c={wl.chunk_size}, r={wl.rank}, k={wl.topk_chunks}, "
@@ -295,12 +364,15 @@ def main() -> int:
                    "layers": 1, "tensor_copies": len(layers), "side_stream": side is not None, "kv_storage": "fp8_e5m2" if fp8 else "bf16"},
         "roofline": {"kernel": "score_kernel (landmark scoring, P = Q L^T)", "bound": "hbm", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
+                     "traffic_source": traffic_src,
                      "algorithmic_bytes_per_launch": score_bytes, "avg_launch_ms": score_ms,
                      # the same launch priced on the fp64 matrix pipe it computes on (4 heads x d FMAs per landmark row
                      # and head group): what bounds it once the landmarks are one byte per element
                      "fp64_mfma_tflops": 2.0 * wl.units * ((wl.group + 3) // 4) * 4 * wl.n_landmarks * wl.head_dim
                                          / (score_ms * 1e-3) / 1e12,
                      "fp64_mfma_peak_tflops": 78.6},
+        "rooflines": rooflines,
+        "launch_plan": plan,
         "stage_ms": prof["ms"],
         "timed_region": "hip-graph replay" if graph is not None else "eager",
         "eager_ms_per_step_with_events": eager_ms_per_step,
@@ -356,28 +428,33 @@ def cpu_baseline(wl, t, budget_s: float, kv_dtype: int = 0) -> dict:
     a = (bits(t["A"]), bits(t["B"]), bl["landmarks"], bl["landmark_chunk_ids"], bl["k_outlier"], bl["v_outlier"],
          bits(t["k_local"]), bits(t["v_local"]), v, t["pos_offset"][:bs].cpu().numpy())
     pool = t["q_pool"]
-    reps, spent = 0, 0.0
-    while reps < 3 or (spent < budget_s and reps < 1000):
-        q = O.as_bits(pool[reps % pool.shape[0]][:bs].detach().cpu())
+    def one_step(i):
+        q = O.as_bits(pool[i % pool.shape[0]][:bs].detach().cpu())
         t0 = time.perf_counter()
         O.decode_step(op, q, *a, diagnostics=False)
-        spent += time.perf_counter() - t0
-        reps += 1
+        return time.perf_counter() - t0
+
+    # all cores: at least 5 steps, then until two thirds of the budget are spent
+    times = []
+    while len(times) < 5 or (sum(times) < budget_s * 2 / 3 and len(times) < 1000):
+        times.append(one_step(len(times)))
+    reps, spent = len(times), sum(times)
     res = {"value": bs * reps / spent, "unit": "tokens/s", "cores": O.num_threads(), "kind": "oracle",
-           "sample": f"first {bs} of {wl.batch} sequences of {sub.name}, {reps} decode steps, {spent:.1f} s",
-           "ms_per_step": spent / reps * 1e3}
-    # the same oracle held to one thread (two steps), for a per-core figure
+           "sample": f"first {bs} of {wl.batch} sequences of {sub.name}, {reps} decode steps on {O.num_threads()} threads, {spent:.1f} s",
+           "ms_per_step": spent / reps * 1e3, "ms_per_step_median": sorted(times)[reps // 2] * 1e3, "steps": reps,
+           "host_cores": os.cpu_count()}
+    # the same oracle held to one thread (at least 3 steps), for a per-core figure
     try:
         import ctypes
         gomp = ctypes.CDLL("libgomp.so.1")
         n_thr = O.num_threads()
         gomp.omp_set_num_threads(1)
-        t0 = time.perf_counter()
-        for i in range(2):
-            O.decode_step(op, O.as_bits(pool[i % pool.shape[0]][:bs].detach().cpu()), *a, diagnostics=False)
-        one = time.perf_counter() - t0
+        one = []
+        while len(one) < 3 or (sum(one) < budget_s / 3 and len(one) < 100):
+            one.append(one_step(len(one)))
         gomp.omp_set_num_threads(n_thr)
-        res["value_one_thread"] = bs * 2 / one
+        res["one_thread"] = {"value": bs * len(one) / sum(one), "unit": "tokens/s", "cores": 1, "steps": len(one),
+                             "ms_per_step": sum(one) / len(one) * 1e3}
     except OSError:
         pass
     return res

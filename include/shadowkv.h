@@ -318,6 +318,19 @@ int shadowkv_validate_params(const shadowkv_params *params, int for_decode);
 void *shadowkv_decode_workspace_view(const shadowkv_params *params, void *workspace, int which);
 
 /*
+ * How a plain shadowkv_decode_step (no value cache) of this shape is laid out on the GPU (measurement aid: lets
+ * a benchmark say which launch the bytes of a stage belong to).  Writes 8 values to `plan` (host):
+ *   [0] splits of the selected rows per (sequence, KV head); [1] rows per split;
+ *   [2] 1 if the rows resident in HBM (outliers, recent tokens) are attended over by extra workgroups of the
+ *       selection launch, 0 if by the attention launch;
+ *   [3] 1 if the attention launch is the kernel with key waves and value waves, 0 the single-role kernel;
+ *   [4] threads and [5] candidates per thread of the selection's first launch; [6] its launches (1 or 2, 3 with
+ *       a middle level); [7] floats per row of the stored logits.
+ * Returns SHADOWKV_OK or SHADOWKV_EINVAL (bad params / plan NULL).
+ */
+int shadowkv_decode_plan(const shadowkv_params *params, int32_t *plan);
+
+/*
  * Per-stage timing of decode steps with HIP events recorded on the caller's stream at the
  * stage boundaries (measurement aid, not part of the method).  Between begin and end every
  * decode step (up to max_steps) records 5 events; end synchronises, writes the summed

@@ -171,6 +171,11 @@ DecodeLayout decode_layout(const Shape& sh) {
   return L;
 }
 
+// Whether the resident rows (outliers, recent tokens) are attended over by extra workgroups of the selection launch.
+bool resident_rows_in_selection(const Shape& sh, const DecodeLayout& L, bool with_cache) {
+  return !with_cache && !sh.stage && !sh.keep_keys && sh.o * sh.c + sh.w > 0 && resident_fits(L.sel, sh.units, sh.G, sh.d);
+}
+
 struct BuildLayout {
   size_t chunk_mean, min_cos, cand_key, cand_idx, total;
   SelectPlan sel;
@@ -335,6 +340,23 @@ size_t shadowkv_decode_workspace_bytes(const shadowkv_params* params) {
   return decode_layout(sh).total;
 }
 
+int shadowkv_decode_plan(const shadowkv_params* params, int32_t* plan) {
+  Shape sh;
+  const int rc = check_params(params, true, &sh);
+  if (rc != SHADOWKV_OK) return rc;
+  if (!plan) return fail_inval("plan is NULL");
+  const DecodeLayout L = decode_layout(sh);
+  plan[0] = L.attn.n_splits;
+  plan[1] = L.attn.sparse_split_len;
+  plan[2] = resident_rows_in_selection(sh, L, false) ? 1 : 0;
+  plan[3] = attention_has_roles(sh.G, sh.c, sh.k, sh.keep_keys, sh.stage) ? 1 : 0;
+  plan[4] = L.sel.nt;
+  plan[5] = L.sel.e;
+  plan[6] = L.sel.n_slices == 1 ? 1 : (L.sel.n_groups > 0 ? 3 : 2);
+  plan[7] = L.ld;
+  return SHADOWKV_OK;
+}
+
 size_t shadowkv_build_workspace_bytes(const shadowkv_params* params) {
   Shape sh;
   BuildLayout L;
@@ -482,8 +504,7 @@ static int decode_impl(const shadowkv_params* params, const shadowkv_bf16* q, co
   a.out_ids = sel_ids; a.out_ids2 = out_chunk_ids;
   // values readable in place: the attention over the resident rows [outliers ; recent] needs nothing of the
   // selection and rides its launch where that launch leaves room (its state is the last of each head's partials)
-  const bool res_early = !cache && !sh.stage && !sh.keep_keys && sh.o * sh.c + sh.w > 0 &&
-                         resident_fits(L.sel, sh.units, sh.G, sh.d);
+  const bool res_early = resident_rows_in_selection(sh, L, cache != nullptr);
   ResidentArgs ra{};
   if (res_early) {
     ra.q = q; ra.k_outlier = k_outlier; ra.v_outlier = v_outlier; ra.k_local = k_local; ra.v_local = v_local;

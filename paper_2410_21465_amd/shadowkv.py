@@ -29,7 +29,7 @@ EXPORTS = (
     "shadowkv_profile_begin", "shadowkv_profile_end", "shadowkv_decode_step_cached", "shadowkv_value_cache_bytes",
     "shadowkv_value_cache_reset", "shadowkv_append_chunk", "shadowkv_argtopk", "shadowkv_argtopk_workspace_bytes",
     "shadowkv_factorize_keys", "shadowkv_factorize_workspace_bytes", "shadowkv_decode_step_static",
-    "shadowkv_static_scratch_bytes",
+    "shadowkv_static_scratch_bytes", "shadowkv_decode_plan",
 )
 STAGES = ("score", "select", "gather_values", "attention")
 
@@ -124,6 +124,16 @@ def version() -> int:
 
 def profile_begin(max_steps: int) -> None:
     _check(lib().shadowkv_profile_begin(int(max_steps)))
+
+
+def decode_plan(p: "Params") -> dict:
+    """shadowkv_decode_plan: how a plain decode step of this shape is laid out on the GPU."""
+    st = p.c_struct()
+    plan = (C.c_int32 * 8)()
+    _check(lib().shadowkv_decode_plan(C.byref(st), plan))
+    return {"splits": plan[0], "rows_per_split": plan[1], "resident_rows_in_selection_launch": bool(plan[2]),
+            "key_and_value_waves": bool(plan[3]), "selection_threads": plan[4], "selection_candidates_per_thread": plan[5],
+            "selection_launches": plan[6], "logit_row_floats": plan[7]}
 
 
 def profile_end() -> dict:
