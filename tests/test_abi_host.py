@@ -159,3 +159,25 @@ def test_append_chunk_rejects_a_full_context_and_bad_capacity():
     st = p.c_struct()
     assert lib.shadowkv_validate_params(C.addressof(st), 1) == S.OK
     assert lib.shadowkv_append_chunk(C.addressof(st), None, *([fake] * 7), None) == S.EINVAL   # NULL k_pre
+
+
+def test_decode_plan_of_the_benchmark_shapes():
+    """shadowkv_decode_plan is host logic: how the step of a shape is cut into launches, splits and roles."""
+    import ctypes as C
+    from workloads import CONFIGS
+    plan = S.decode_plan(S.Params.from_workload(CONFIGS["c3-hbm"]))
+    assert plan == {"splits": 2, "rows_per_split": 1024, "resident_rows_in_selection_launch": True,
+                    "key_and_value_waves": True, "selection_threads": 1024, "selection_candidates_per_thread": 16,
+                    "selection_launches": 1, "logit_row_floats": 16336}
+    # the splits cover the selected rows; one selection launch up to 32768 landmarks, more beyond
+    for wl in CONFIGS.values():
+        pl = S.decode_plan(S.Params.from_workload(wl))
+        assert pl["splits"] * pl["rows_per_split"] >= wl.topk_chunks * wl.chunk_size > (pl["splits"] - 1) * pl["rows_per_split"]
+        assert (pl["selection_launches"] == 1) == (wl.n_landmarks <= 32768)
+        assert pl["logit_row_floats"] >= wl.n_landmarks and pl["logit_row_floats"] % 4 == 0
+        # values that have to be gathered, or one or two heads per KV head, take the single-role kernels
+        assert pl["key_and_value_waves"] == (wl.value_location == "hbm" and wl.group >= 3 and wl.chunk_size % 4 == 0)
+    st = S.Params.from_workload(CONFIGS["c1"]).c_struct()
+    assert S.lib().shadowkv_decode_plan(C.byref(st), None) == S.EINVAL
+    bad = S.Params(**{**GOOD, "rank": 12}).c_struct()
+    assert S.lib().shadowkv_decode_plan(C.byref(bad), (C.c_int32 * 8)()) == S.EINVAL
