@@ -670,12 +670,12 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
   }
 }
 
-// The fused kernel again, with the work of a block of selected rows divided between two kinds of waves (512
-// threads: NKW waves rebuild keys, NVW waves attend), for groups of four query heads and chunk sizes that are
+// The fused kernel again, with the work of a block of selected rows divided between two kinds of waves (NKW waves
+// rebuild keys, NVW waves attend), for groups of four query heads and chunk sizes that are
 // multiples of four.  The single-role kernel above keeps per lane the A fragments, the MFMA accumulators, the
 // rotation state, the queries, the value rows AND the online-softmax state of four heads: 242 registers, two waves
-// per SIMD, and with so few waves the scattered 2-2.5 KB pieces of A and V come in at 3.1-3.7 TB/s where the same
-// gather pattern reaches 5.5 TB/s once every SIMD holds four waves with loads in flight.  Here
+// per SIMD, each going through all phases of a block in turn, and it moves the scattered 2-2.5 KB pieces of A and V
+// at 3.1-3.7 TB/s where the bare gather reaches 5.4 TB/s.  Here
 //   * a key wave owns 16 rows per step: A rows -> MFMA (B^T in LDS) -> RoPE in place -> q.K (queries from LDS, two
 //     heads at a time) -> the 16 x 4 logits into a two-deep ring in LDS; the A rows of its next block are requested
 //     before it starts on the current one (two sets of fragments);
