@@ -679,8 +679,9 @@ __global__ __launch_bounds__(256, 2) void sparse_attn_kernel(AttnArgs a) {
 //   * a key wave owns 16 rows per step: A rows -> MFMA (B^T in LDS) -> RoPE in place -> q.K (queries from LDS, two
 //     heads at a time) -> the 16 x 4 logits into a two-deep ring in LDS; the A rows of its next block are requested
 //     before it starts on the current one (two sets of fragments);
-//   * a value wave owns the 16 rows the key wave of the same index produced one step earlier: logits from the ring,
-//     value rows requested two blocks ahead (they depend on nothing but the selection), online softmax, P.V;
+//   * a value wave takes the blocks that key waves vw, vw + NVW, ... produced one step earlier: logits from the ring,
+//     value rows requested two blocks ahead (they depend on nothing but the selection), online softmax, P.V on the
+//     matrix cores;
 //     it also takes this split's share of the resident rows first, when no other launch has done them;
 //   * one barrier per step orders the ring.
 // Each role fits 128 registers, so 16 waves share a compute unit: 12 key + 4 value waves in one 1024-thread
